@@ -1,0 +1,70 @@
+"""Oracle: Algorithm 1 (SpeculativeDecodingStep) and the decoding loops.
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product path.
+
+A "scorer" is anything with score(prefix, k) -> logits rows [k, V] for the
+last k positions of prefix (oracle.transformer.CachedScorer, or the table
+models the tests use).  Uniforms for one step are laid out as
+[d_1..d_gamma | r_1..r_gamma | s]: draft draws, acceptance tests, final draw.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .sampling import accept_and_resample, icdf, standardise
+
+
+def speculative_decoding_step(mp, mq, prefix, gamma: int, temperature: float, uniforms):
+    """One run of Algorithm 1.  Returns (new_prefix, n, info).
+
+    1. for i = 1..gamma: q_i = Mq(prefix + x_<i), x_i ~ q_i        (serial)
+    2. p_1..p_{gamma+1} = Mp on prefix, prefix+[x_1], ..., prefix+[x_1..x_gamma]
+    3. n = number of guesses before the first r_i > p_i(x_i)/q_i(x_i)
+    4. t ~ p_{n+1}, replaced by norm(max(0, p_{n+1}-q_{n+1})) when n < gamma
+    5. return prefix + [x_1..x_n, t]
+    """
+    u = np.asarray(uniforms, dtype=np.float64)
+    if u.shape != (2 * gamma + 1,):
+        raise ValueError("need 2*gamma+1 uniforms")
+    if np.any(u <= 0) or np.any(u >= 1):
+        raise ValueError("uniforms must lie in the open interval (0,1)")
+    d, r, s = u[:gamma], u[gamma:2 * gamma], u[2 * gamma]
+    prefix = [int(t) for t in prefix]
+    x, q_rows, q_logits = [], [], []
+    for i in range(gamma):
+        zq = mq.score(prefix + x, 1)[0]
+        qi = standardise(zq, temperature)
+        x.append(icdf(qi, d[i]))
+        q_rows.append(qi)
+        q_logits.append(zq)
+    zp = mp.score(prefix + x, gamma + 1)
+    p_rows = np.stack([standardise(z, temperature) for z in zp])
+    n, t, info = accept_and_resample(p_rows, np.stack(q_rows), x, r, s)
+    info.update({"x": list(x), "p_logits": zp, "q_logits": np.stack(q_logits),
+                 "p_rows": p_rows, "q_rows": np.stack(q_rows)})
+    return prefix + x[:n] + [t], n, info
+
+
+def speculative_decode(mp, mq, prompt, n_new: int, gamma: int, temperature: float, uniform_rows):
+    """Repeat Algorithm 1 until n_new tokens exist; the surplus of the last
+    run is dropped.  uniform_rows yields one [2*gamma+1] row per run.
+    Returns (tokens, records) with one record (n, emitted tokens, info) per run."""
+    prefix = [int(t) for t in prompt]
+    target = len(prefix) + n_new
+    records = []
+    it = iter(uniform_rows)
+    while len(prefix) < target:
+        new_prefix, n, info = speculative_decoding_step(mp, mq, prefix, gamma, temperature, next(it))
+        records.append((n, new_prefix[len(prefix):], info))
+        prefix = new_prefix
+    return prefix[:target], records
+
+
+def plain_decode(mp, prompt, n_new: int, temperature: float, uniforms):
+    """Standard autoregressive decoding from Mp alone: one token per run."""
+    prefix = [int(t) for t in prompt]
+    it = iter(uniforms)
+    for _ in range(n_new):
+        z = mp.score(prefix, 1)[0]
+        prefix.append(icdf(standardise(z, temperature), float(next(it))))
+    return prefix

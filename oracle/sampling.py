@@ -1,0 +1,146 @@
+"""Oracle: standardised sampling and the accept / resample part of Algorithm 1.
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product path.
+
+Everything is float64 NumPy, written as the paper states it:
+
+* section 2.2 (standardised sampling): temperature and argmax are folded
+  into an ordinary probability vector;
+* section 2.3 (speculative sampling) and Algorithm 1: the acceptance test
+  r_i <= p_i(x_i)/q_i(x_i), n = index of the first rejection, the adjusted
+  distribution norm(max(0, p_{n+1} - q_{n+1})) and the final draw.
+
+Readings where the paper is silent:
+* a guess is accepted when r <= p/q (the algorithm rejects when r > p/q);
+  callers supply uniforms from the open interval (0, 1);
+* "x ~ dist" is realised by inverse-CDF sampling in vocabulary-index order
+  from a caller supplied uniform: the smallest k whose cumulative weight
+  exceeds u times the total weight;
+* argmax ties go to the lowest index;
+* if the residual max(0, p - q) has zero total weight in floating point, the
+  draw falls back to p_{n+1} itself.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def standardise(logits, temperature: float) -> np.ndarray:
+    """Section 2.2: turn one logits row into the distribution that is sampled.
+
+    temperature > 0: softmax(logits / temperature).
+    temperature == 0: argmax sampling, i.e. all mass on the (lowest-index)
+    maximum -- "zeroing out non-max elements and normalizing".
+    """
+    z = np.asarray(logits, dtype=np.float64)
+    if z.ndim != 1:
+        raise ValueError("standardise takes one logits row")
+    if temperature < 0:
+        raise ValueError("temperature must be >= 0")
+    if temperature == 0:
+        out = np.zeros_like(z)
+        out[int(np.argmax(z))] = 1.0          # np.argmax returns the first maximum
+        return out
+    y = z / float(temperature)
+    e = np.exp(y - np.max(y))
+    return e / np.sum(e)
+
+
+def icdf(weights, u: float) -> int:
+    """Inverse-CDF draw from unnormalised non-negative weights.
+
+    Returns the smallest index k with sum_{j<=k} w_j > u * sum_j w_j, sums
+    taken in index order.  If round-off leaves no such k, the last index with
+    a positive weight is returned.
+    """
+    w = np.asarray(weights, dtype=np.float64)
+    if np.any(w < 0):
+        raise ValueError("negative weight")
+    c = np.cumsum(w)
+    total = c[-1]
+    if not total > 0:
+        raise ValueError("weights sum to zero")
+    k = int(np.searchsorted(c, u * total, side="right"))
+    if k >= w.size:
+        k = int(np.nonzero(w > 0)[0][-1])
+    return k
+
+
+def beta(p, q) -> float:
+    """Acceptance probability of one guess: sum_x min(p(x), q(x)) (Theorem 3.5)."""
+    return float(np.sum(np.minimum(np.asarray(p, np.float64), np.asarray(q, np.float64))))
+
+
+def d_lk(p, q) -> float:
+    """Definition 3.2: sum_x |p(x) - M(x)| with M = (p + q)/2."""
+    p = np.asarray(p, np.float64)
+    q = np.asarray(q, np.float64)
+    m = 0.5 * (p + q)
+    return float(np.sum(np.abs(p - m)))
+
+
+def adjusted_distribution(p, q) -> np.ndarray:
+    """Unnormalised residual max(0, p - q) of section 2.3 / Algorithm 1."""
+    return np.maximum(0.0, np.asarray(p, np.float64) - np.asarray(q, np.float64))
+
+
+def accept_and_resample(p_rows, q_rows, x, r, s, lenience: float = 1.0):
+    """Second half of Algorithm 1, on explicit distributions.
+
+    p_rows : [gamma+1, V] target distributions p_1..p_{gamma+1}
+    q_rows : [gamma, V]   draft distributions q_1..q_gamma
+    x      : [gamma]      draft tokens x_i ~ q_i
+    r      : [gamma]      uniforms of the acceptance tests
+    s      : uniform of the final draw
+    lenience : the factor l of appendix A.5 (q is multiplied by l before the
+               comparison with p; 1 gives the exact algorithm).
+
+    Returns (n, t, info): n accepted guesses, the extra token t, and a dict
+    with the per-decision ratios p_i(x_i)/q_i(x_i), margins |r_i - ratio| and
+    whether the zero-residual fallback was taken.
+    """
+    p_rows = np.asarray(p_rows, np.float64)
+    q_rows = np.asarray(q_rows, np.float64)
+    gamma = q_rows.shape[0]
+    if p_rows.shape[0] != gamma + 1 or len(x) != gamma or len(r) != gamma:
+        raise ValueError("shape mismatch")
+    ratios = np.empty(gamma)
+    for i in range(gamma):
+        qi = q_rows[i, x[i]] * lenience
+        pi = p_rows[i, x[i]]
+        ratios[i] = np.inf if qi == 0 else pi / qi
+    n = gamma
+    for i in range(gamma):
+        if r[i] > ratios[i]:                   # first rejected guess
+            n = i
+            break
+    fallback = False
+    if n < gamma:
+        w = adjusted_distribution(p_rows[n], lenience * q_rows[n])
+        if not np.sum(w) > 0:
+            w = p_rows[n]
+            fallback = True
+    else:
+        w = p_rows[gamma]
+    t = icdf(w, s)
+    info = {"ratios": ratios, "margins": np.abs(np.asarray(r, np.float64) - ratios),
+            "fallback": fallback}
+    return n, t, info
+
+
+def accept_and_resample_from_logits(p_logits, q_logits, x, r, s, temperature: float):
+    """Same as accept_and_resample, starting from logits rows (section 2.2 first)."""
+    p_rows = np.stack([standardise(z, temperature) for z in p_logits])
+    q_rows = np.stack([standardise(z, temperature) for z in q_logits])
+    return accept_and_resample(p_rows, q_rows, x, r, s)
+
+
+def icdf_edge_distance(weights, u: float, k: int) -> float:
+    """Distance, in normalised CDF units, from u to the nearer edge of token k's
+    CDF interval.  Used by parity tests to recognise draws that a different
+    summation order may legitimately flip."""
+    w = np.asarray(weights, np.float64)
+    c = np.cumsum(w) / np.sum(w)
+    lo = 0.0 if k == 0 else c[k - 1]
+    hi = c[k]
+    return float(min(abs(u - lo), abs(u - hi)))

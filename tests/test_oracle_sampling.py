@@ -1,0 +1,236 @@
+"""Pins for oracle/sampling.py and oracle/decode.py (CPU only).
+
+The pins are facts the paper fixes, checked through the oracle's own entry
+points by exact enumeration: all uniforms run over midpoint grids chosen so
+that, for the dyadic distributions used, no grid point ever coincides with a
+decision threshold.  Counting grid points then gives exact probabilities.
+"""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+
+from oracle import analysis, decode, sampling
+
+
+def grid(n):
+    return [(k + 0.5) / n for k in range(n)]
+
+
+class TableScorer:
+    """Next-token distribution = table(prefix); logits = log(prob), so that at
+    temperature 1 the standardised distribution is the table row itself."""
+
+    def __init__(self, fn):
+        self.fn = fn
+
+    def score(self, prefix, k):
+        rows = []
+        for j in range(k):
+            ctx = prefix[: len(prefix) - k + 1 + j]
+            with np.errstate(divide="ignore"):
+                rows.append(np.log(np.asarray(self.fn(ctx), dtype=np.float64)))
+        return np.stack(rows)
+
+
+P1 = [3 / 16, 5 / 16, 1 / 16, 7 / 16]
+Q1 = [1 / 2, 1 / 4, 1 / 8, 1 / 8]
+# second-position tables, depending on the previous token
+P2 = {0: [1 / 4, 1 / 4, 1 / 4, 1 / 4], 1: [1 / 2, 0, 1 / 4, 1 / 4], 2: [0, 0, 1 / 2, 1 / 2], 3: [1 / 8, 3 / 8, 1 / 4, 1 / 4]}
+Q2 = {0: [1 / 2, 1 / 2, 0, 0], 1: [1 / 4, 1 / 4, 1 / 4, 1 / 4], 2: [1 / 2, 0, 0, 1 / 2], 3: [1 / 4, 1 / 8, 1 / 8, 1 / 2]}
+
+
+def table_models():
+    mp = TableScorer(lambda ctx: P1 if len(ctx) == 1 else P2[ctx[-1]])
+    mq = TableScorer(lambda ctx: Q1 if len(ctx) == 1 else Q2[ctx[-1]])
+    return mp, mq
+
+
+def test_standardise_matches_library_softmax_and_argmax():
+    rng = np.random.default_rng(0)
+    z = rng.normal(0, 3, size=50)
+    for T in (1.0, 0.7, 2.5):
+        np.testing.assert_allclose(sampling.standardise(z, T), scipy.special.softmax(z / T), rtol=1e-13)
+    z[7] = z[30] = z.max() + 1.0                     # tie -> lowest index
+    one = sampling.standardise(z, 0.0)
+    assert one[7] == 1.0 and one.sum() == 1.0
+
+
+def test_icdf_counts_equal_probabilities():
+    w = np.array([3, 0, 5, 1, 0, 7], dtype=float)    # total 16
+    counts = np.zeros(6, dtype=int)
+    for u in grid(32):
+        counts[sampling.icdf(w, u)] += 1
+    assert list(counts) == [6, 0, 10, 2, 0, 14]
+
+
+def test_single_token_speculative_sampling_is_distributed_as_p():
+    """Appendix A.1: P(x = x') = p(x'), by exact enumeration with gamma = 1; the
+    acceptance frequency equals sum min(p, q) (Theorem 3.5) and, given that
+    the guess is kept, the bonus token follows p_2(. | x_1)."""
+    mp, mq = table_models()
+    first = np.zeros(4, dtype=int)
+    accepted = 0
+    second = {a: np.zeros(4, dtype=int) for a in range(4)}
+    gd, gr, gs = grid(8), grid(16), grid(48)
+    for d, r, s in itertools.product(gd, gr, gs):
+        out, n, _ = decode.speculative_decoding_step(mp, mq, [0], 1, 1.0, [d, r, s])
+        first[out[1]] += 1
+        if n == 1:
+            accepted += 1
+            second[out[1]][out[2]] += 1
+        else:
+            assert len(out) == 2
+    total = len(gd) * len(gr) * len(gs)
+    assert [Fraction(int(c), total) for c in first] == [Fraction(p).limit_denominator(64) for p in P1]
+    assert Fraction(accepted, total) == Fraction(10, 16) == Fraction(sampling.beta(P1, Q1)).limit_denominator(64)
+    for a in range(4):
+        na = second[a].sum()
+        # P(first = a and kept) = min(p, q)(a)
+        assert Fraction(int(na), total) == Fraction(min(P1[a], Q1[a])).limit_denominator(64)
+        assert [Fraction(int(c), int(na)) for c in second[a]] == [Fraction(p).limit_denominator(64) for p in P2[a]]
+
+
+def test_two_guess_step_joint_distribution():
+    """gamma = 2 with context-dependent tables: first token ~ p_1; given the
+    first guess a is kept, the second token ~ p_2(.|a); given both kept, the
+    third ~ p_3 (here the uniform table)."""
+    mp0, mq0 = table_models()
+    P3 = [1 / 4, 1 / 4, 1 / 4, 1 / 4]
+    mp = TableScorer(lambda ctx: P3 if len(ctx) == 3 else mp0.fn(ctx))
+    mq = TableScorer(lambda ctx: P3 if len(ctx) == 3 else mq0.fn(ctx))
+    first = np.zeros(4, dtype=int)
+    pair = np.zeros((4, 4), dtype=int)
+    third = np.zeros(4, dtype=int)
+    gd, gr, gs = grid(8), grid(8), grid(12)
+    total = 0
+    for d1, d2, r1, r2 in itertools.product(gd, gd, gr, gr):
+        for s in gs:
+            out, n, _ = decode.speculative_decoding_step(mp, mq, [0], 2, 1.0, [d1, d2, r1, r2, s])
+            total += 1
+            assert len(out) == 1 + n + 1 and 0 <= n <= 2
+            first[out[1]] += 1
+            if n >= 1:
+                pair[out[1], out[2]] += 1
+            if n == 2:
+                third[out[3]] += 1
+    np.testing.assert_allclose(first / total, P1, atol=1e-12)
+    for a in range(4):
+        np.testing.assert_allclose(pair[a] / total, min(P1[a], Q1[a]) * np.array(P2[a]), atol=1e-12)
+    np.testing.assert_allclose(third / third.sum(), P3, atol=1e-12)
+
+
+def test_tokens_per_run_is_the_capped_geometric_of_equation_1():
+    """Context-free tables (the i.i.d. assumption of section 3.1 holds exactly):
+    the distribution of n and its mean match the capped geometric / Equation 1."""
+    p, q = [3 / 4, 1 / 4], [1 / 2, 1 / 2]
+    alpha = sampling.beta(p, q)
+    assert alpha == 0.75
+    mp, mq = TableScorer(lambda ctx: p), TableScorer(lambda ctx: q)
+    gamma = 3
+    hist = np.zeros(gamma + 1, dtype=int)
+    g2 = grid(2)
+    for u in itertools.product(*([g2] * (2 * gamma)), grid(4)):
+        _, n, _ = decode.speculative_decoding_step(mp, mq, [0], gamma, 1.0, list(u))
+        hist[n] += 1
+    pmf = hist / hist.sum()
+    np.testing.assert_allclose(pmf, analysis.capped_geometric_pmf(alpha, gamma), atol=1e-12)
+    mean_tokens = float(np.sum((np.arange(gamma + 1) + 1) * pmf))
+    assert abs(mean_tokens - (1 - 0.75 ** 4) / (1 - 0.75)) < 1e-12
+    assert abs(mean_tokens - analysis.expected_tokens(alpha, gamma)) < 1e-12
+
+
+def test_monte_carlo_output_distribution_chi_square():
+    """Non-dyadic p, q on 8 tokens: tokens decoded by repeated runs of Algorithm 1
+    from a context-free pair follow p (chi-square, fixed seed)."""
+    rng = np.random.default_rng(5)
+    p = rng.dirichlet(np.ones(8))
+    q = rng.dirichlet(np.ones(8))
+    mp, mq = TableScorer(lambda ctx: p), TableScorer(lambda ctx: q)
+    gamma = 3
+    counts = np.zeros(8)
+    acc = tot = 0
+    for _ in range(6000):
+        u = (rng.integers(0, 1 << 24, size=2 * gamma + 1) + 0.5) / (1 << 24)
+        out, n, _ = decode.speculative_decoding_step(mp, mq, [0], gamma, 1.0, u)
+        for t in out[1:]:
+            counts[t] += 1
+        acc += n
+        tot += min(n + 1, gamma)                    # guesses actually tested
+    chi2, pval = scipy.stats.chisquare(counts, p * counts.sum())
+    assert pval > 1e-3
+    rate = acc / tot
+    b = sampling.beta(p, q)
+    assert abs(rate - b) < 4 * np.sqrt(b * (1 - b) / tot)
+
+
+def test_dlk_identities():
+    rng = np.random.default_rng(1)
+    for _ in range(20):
+        p, q = rng.dirichlet(np.ones(9)), rng.dirichlet(np.ones(9))
+        assert abs(sampling.d_lk(p, q) - (1 - sampling.beta(p, q))) < 1e-14      # Lemma 3.3
+        assert abs(sampling.d_lk(p, q) - sampling.d_lk(q, p)) < 1e-14
+        # normaliser of the adjusted distribution is 1 - beta (appendix A.1)
+        assert abs(sampling.adjusted_distribution(p, q).sum() - (1 - sampling.beta(p, q))) < 1e-14
+    assert sampling.d_lk([1, 0, 0], [0, .5, .5]) == 1.0 and sampling.d_lk([.2, .8], [.2, .8]) == 0.0
+
+
+def test_degenerate_cases():
+    rng = np.random.default_rng(2)
+    p = rng.dirichlet(np.ones(6), size=4)
+    x = [int(np.argmax(p[i])) for i in range(3)]
+    # q == p: every guess is kept whatever the uniforms (Corollary 3.4, D_LK = 0)
+    for r in ([0.999] * 3, [0.5] * 3):
+        n, t, info = sampling.accept_and_resample(p, p[:3], x, r, 0.3)
+        assert n == 3 and not info["fallback"] and t == sampling.icdf(p[3], 0.3)
+    # disjoint supports: first guess always rejected, t ~ p_1 unchanged
+    pp = np.array([[.5, .5, 0, 0], [.25, .75, 0, 0]])
+    qq = np.array([[0, 0, .5, .5]])
+    for s in grid(4):
+        n, t, _ = sampling.accept_and_resample(pp, qq, [2], [1e-7], s)
+        assert n == 0 and t == sampling.icdf(pp[0], s)
+    # rejected although p == q numerically impossible; zero residual -> fall back to p
+    n, t, info = sampling.accept_and_resample(pp, pp[:1] * 1.0, [0], [0.5], 0.9)
+    assert n == 1
+    same = np.array([[.5, .5], [.5, .5]])
+    bigger_q = np.array([[.5 + 1e-17, .5]])
+    n, t, info = sampling.accept_and_resample(same, bigger_q, [0], [0.5], 0.9)
+    assert n == 1                                     # ratio rounds to 1: kept
+    # a rejection whose residual vanishes in floating point falls back to p itself
+    q_eps = np.array([[.5 * (1 + 2.0 ** -52), .5]])
+    n, t, info = sampling.accept_and_resample(same, q_eps, [0], [1 - 2.0 ** -53], 0.75)
+    assert n == 0 and info["fallback"] and t == 1
+
+
+def test_temperature_zero_is_argmax_logic():
+    zp = np.array([[0., 2., 1.], [3., 0., 0.], [0., 0., 5.]])
+    zq = np.array([[0., 1., 0.5], [0., 4., 0.]])
+    # q argmaxes: 1, 1 ; p argmaxes: 1, 0, 2  -> first kept, second rejected, t = argmax p_2 = 0
+    n, t, _ = sampling.accept_and_resample_from_logits(zp, zq, [1, 1], [0.99, 0.01], 0.5, 0.0)
+    assert (n, t) == (1, 0)
+    n, t, _ = sampling.accept_and_resample_from_logits(zp, np.array([[0., 1., 0.], [9., 0., 0.]]), [1, 0], [0.99, 0.99], 0.5, 0.0)
+    assert (n, t) == (2, 2)
+
+
+def test_lenient_alpha_formula_against_enumeration():
+    """Appendix A.5: with lenience l the acceptance rate is sum min(p/l, q)."""
+    l = 0.5
+    acc = 0
+    gd, gr = grid(8), grid(32)
+    p_rows = np.array([P1, P1])
+    for d, r in itertools.product(gd, gr):
+        x = sampling.icdf(Q1, d)
+        n, _, _ = sampling.accept_and_resample(p_rows, np.array([Q1]), [x], [r], 0.5, lenience=l)
+        acc += n
+    assert abs(acc / (len(gd) * len(gr)) - analysis.lenient_alpha(P1, Q1, l)) < 1e-12
+
+
+def test_uniform_validation():
+    mp, mq = table_models()
+    with pytest.raises(ValueError):
+        decode.speculative_decoding_step(mp, mq, [0], 1, 1.0, [0.0, 0.5, 0.5])
+    with pytest.raises(ValueError):
+        decode.speculative_decoding_step(mp, mq, [0], 2, 1.0, [0.5, 0.5, 0.5])
