@@ -1,0 +1,203 @@
+/*
+ * sd.h -- C ABI of the MI355X speculative-decoding hot path.
+ *
+ * One iteration of Algorithm 1 (SpeculativeDecodingStep) of "Fast Inference
+ * from Transformers via Speculative Decoding": gamma serial draft steps of
+ * the approximation model Mq, one target-model (Mp) forward over the gamma+1
+ * draft positions, the acceptance test r_i <= p_i(x_i)/q_i(x_i), the draw from
+ * the adjusted distribution norm(max(0, p_{n+1} - q_{n+1})), and the roll-back
+ * of both KV caches.  Every step runs in HIP kernels for gfx950.
+ *
+ * Conventions
+ *  - "host" / "dev" in a comment says where a pointer must live.
+ *  - All calls are synchronous with respect to their host outputs: they
+ *    enqueue on the context's stream and wait for it before returning.
+ *  - A context is not thread-safe.  Calls on one context must not overlap.
+ *  - Errors are return codes only; a failed call leaves the decoding state
+ *    unchanged.  sd_last_error() gives a human-readable reason.
+ *  - The library never allocates device memory: everything it needs on the
+ *    device lives in the caller's workspace (sd_workspace_bytes()).
+ */
+#ifndef SD_H
+#define SD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sd_ctx sd_ctx;     /* opaque: one (Mp, Mq) pair plus decoding state */
+
+typedef enum {
+  SD_OK = 0,
+  SD_EINVAL = 1,   /* bad argument: gamma out of range, NULL pointer, unknown tensor, shape mismatch */
+  SD_ESTATE = 2,   /* call out of order (step before prefill), or prefix check failed */
+  SD_ERANGE = 3,   /* token id >= vocab, sequence would exceed max_len, uniform outside (0,1) */
+  SD_ENOMEM = 4,   /* workspace too small */
+  SD_EHIP   = 5    /* a HIP call failed */
+} sd_status;
+
+typedef enum { SD_F32 = 0, SD_BF16 = 1 } sd_dtype;
+
+enum { SD_ARCH_GPT = 0, SD_ARCH_T5DEC = 1, SD_ARCH_GQA = 2 };
+enum { SD_MAX_GAMMA = 15 };       /* a forward handles at most SD_MAX_GAMMA+1 rows */
+
+/* Flags of sd_runtime_cfg.flags */
+enum {
+  SD_FLAG_GRAPH   = 1,  /* replay each iteration as one hipGraph (draft loop, verify, accept) */
+  SD_FLAG_PROFILE = 2   /* record HIP events around the draft / verify / accept phases */
+};
+
+/*
+ * Model description.  The paper treats Mp and Mq as black boxes (section 2.1)
+ * and gives only sizes for its experiments (section 4); the block types are:
+ *   SD_ARCH_GPT    pre-LayerNorm (gain+bias), learned positions, biased linear
+ *                  layers, tanh-GELU MLP, attention scale 1/sqrt(d_head)
+ *   SD_ARCH_T5DEC  RMSNorm, no biases, unscaled attention + one shared
+ *                  relative-position bias table, cross-attention over a fixed
+ *                  encoder output, gated tanh-GELU MLP
+ *   SD_ARCH_GQA    RMSNorm, rotary on adjacent pairs, grouped KV heads, SwiGLU
+ * dtype is the storage type of weights, activations and KV cache (accumulation
+ * is always fp32; logits are fp32).
+ */
+typedef struct {
+  int32_t arch;
+  int32_t n_layers, d_model, n_heads, n_kv_heads, d_head, d_ff, vocab, max_len;
+  int32_t enc_len;                 /* T5DEC: rows of the encoder output, else 0 */
+  int32_t rel_buckets, rel_max_dist;
+  float   rope_theta;
+  float   logit_scale;             /* logits = logit_scale * (norm(x) @ head^T) */
+  float   norm_eps;
+  int32_t dtype;                   /* sd_dtype */
+} sd_model_cfg;
+
+/*
+ * One weight tensor.  dev: device pointer, row-major, dtype == model dtype.
+ * Linear weights are [out_features, in_features].  Names:
+ *   tok_emb [V,d]  head [V,d]  lnf.g [d]  (GPT: lnf.b, pos_emb [max_len,d])
+ *   (T5DEC: rel_bias [n_heads, rel_buckets])
+ *   per layer i, prefix "l<i>.":  ln1.g ln2.g  wq wk wv wo  w2
+ *     GPT   : ln1.b ln2.b bq bk bv bo  w1 b1 b2
+ *     T5DEC : wg wu  lnc.g cq ck cv co
+ *     GQA   : wg wu
+ * All tensors are copied (linear weights re-tiled) into the workspace during
+ * sd_load_models; the caller may release them when it returns.
+ */
+typedef struct {
+  const char* name;
+  const void* dev;
+  int32_t     ndim;
+  int64_t     shape[4];
+  int32_t     dtype;
+} sd_tensor;
+
+typedef struct {
+  int32_t batch;            /* sequences decoded together; only 1 is supported */
+  int32_t max_gamma;        /* largest gamma sd_step will be called with, 1..SD_MAX_GAMMA */
+  int32_t page_size;        /* KV-cache page, positions; power of two, >= 16 */
+  void*   workspace;        /* dev, 256-byte aligned, caller-owned, outlives the context */
+  size_t  workspace_bytes;
+  void*   stream;           /* hipStream_t, or NULL for the default stream */
+  int32_t flags;
+} sd_runtime_cfg;
+
+typedef struct {
+  double  draft_ms, verify_ms, accept_ms;   /* last sd_step, valid with SD_FLAG_PROFILE */
+  int64_t steps;                            /* sd_step calls since load / reset */
+  int64_t tokens;                           /* tokens they produced */
+  int64_t accepted;                         /* sum of n */
+  int64_t fallbacks;                        /* zero-residual fallbacks taken */
+} sd_stats;
+
+/* Device bytes sd_load_models needs for this pair (weights, KV caches,
+ * activations, logits).  Returns 0 for an invalid configuration. */
+size_t sd_workspace_bytes(const sd_model_cfg* p_cfg, const sd_model_cfg* q_cfg,
+                          const sd_runtime_cfg* rt);
+
+/* Section 2.1: bind the target model Mp and the approximation model Mq.
+ * out: host, receives the context.  p_w / q_w: host arrays of descriptors of
+ * device tensors.  Fails with SD_EINVAL on a missing / unknown / misshapen
+ * tensor, SD_ENOMEM if the workspace is too small. */
+sd_status sd_load_models(sd_ctx** out,
+                         const sd_model_cfg* p_cfg, const sd_tensor* p_w, int32_t n_p,
+                         const sd_model_cfg* q_cfg, const sd_tensor* q_w, int32_t n_q,
+                         const sd_runtime_cfg* rt);
+
+/* Condition both models on a prefix (the "prefix" input of Algorithm 1):
+ * fills both KV caches for prompt[0 .. prompt_len-2] and records the last
+ * token.  prompt: host, prompt_len >= 1 ids.  enc_out_p / enc_out_q: dev,
+ * [enc_len, d_model] of the respective model in its dtype (T5DEC), else NULL;
+ * their cross-attention keys / values are computed here, once.
+ * row must be 0.  Requires prompt_len + max_gamma + 1 <= max_len of both models. */
+sd_status sd_prefill(sd_ctx* ctx, int32_t row, const int32_t* prompt, int32_t prompt_len,
+                     const void* enc_out_p, const void* enc_out_q);
+
+/*
+ * Algorithm 1, one run.
+ *   prefix, prefix_len : host; optional consistency check of the committed
+ *       sequence (length must equal the internal length and the last token
+ *       must match, else SD_ESTATE).  prefix == NULL skips the check.
+ *   gamma       : number of guesses, 1..max_gamma.
+ *   temperature : section 2.2 standardisation; 0 = argmax sampling, > 0 =
+ *       softmax(logits / temperature); the same for Mp and Mq.
+ *   uniforms    : host, [2*gamma+1] floats strictly inside (0,1):
+ *       [0,gamma) draw x_i ~ q_i, [gamma,2*gamma) the acceptance tests r_i,
+ *       [2*gamma] the final draw t ~ p'.  All draws are inverse-CDF in
+ *       vocabulary order.  May be NULL iff temperature == 0.
+ *   out_tokens  : host, [gamma+1]; receives x_1..x_n, t, then -1 padding.
+ *   out_n       : host, receives n, the number of accepted guesses.
+ * On return the committed sequence is n+1 tokens longer and both KV caches
+ * are rolled back to it.
+ */
+sd_status sd_step(sd_ctx* ctx, const int32_t* prefix, int32_t prefix_len,
+                  int32_t gamma, float temperature, const float* uniforms,
+                  int32_t* out_tokens, int32_t* out_n);
+
+/* Standard decoding (section 1 / the denominator of Theorem 3.8): one Mp
+ * forward on the last token, one draw from p with uniforms[0] (host; may be
+ * NULL iff temperature == 0).  out_token: host.  Leaves Mq's cache behind:
+ * sd_step after sd_step_baseline needs sd_reset + sd_prefill first
+ * (SD_ESTATE otherwise). */
+sd_status sd_step_baseline(sd_ctx* ctx, float temperature, const float* uniforms,
+                           int32_t* out_token);
+
+/* Forget the sequence (row must be 0 or -1): KV lengths to zero, state EMPTY. */
+sd_status sd_reset(sd_ctx* ctx, int32_t row);
+
+void sd_free(sd_ctx* ctx);
+
+/* Reason of the last failure on this context (or of the last failed
+ * sd_load_models when ctx == NULL).  The string is owned by the library. */
+const char* sd_last_error(const sd_ctx* ctx);
+
+/* Measurement / test access.  which = 0: Mp logits of the last step,
+ * [gamma+1, vocab]; which = 1: Mq logits, [gamma, vocab]; which = 2 after
+ * sd_step_baseline: [1, vocab].  host_out: host, n floats (n <= rows*vocab). */
+sd_status sd_debug_logits(sd_ctx* ctx, int32_t which, float* host_out, size_t n);
+sd_status sd_get_stats(sd_ctx* ctx, sd_stats* out);
+
+/*
+ * The accept / resample part of Algorithm 1 on explicit logits, for `rows`
+ * independent sequences:  n = number of guesses before the first
+ * r_i > p_i(x_i)/q_i(x_i);  t ~ norm(max(0, p_{n+1} - q_{n+1})) if n < gamma
+ * else t ~ p_{gamma+1};  p_i, q_i = section-2.2 standardisation of the logits.
+ *   p_logits : dev, [rows, gamma+1, vocab] fp32      q_logits : dev, [rows, gamma, vocab] fp32
+ *   x        : dev, [rows, gamma] int32 guesses      r : dev, [rows, gamma] fp32
+ *   s        : dev, [rows] fp32                      out_n, out_t : dev, [rows] int32
+ *   scratch  : dev, sd_spec_sample_scratch_bytes(rows, gamma) bytes, zeroed
+ *              once by the caller before the first call.
+ * Asynchronous on `stream`; no host output.
+ */
+size_t    sd_spec_sample_scratch_bytes(int32_t rows, int32_t gamma);
+sd_status sd_spec_sample(const float* p_logits, const float* q_logits, const int32_t* x,
+                         const float* r, const float* s, int32_t rows, int32_t gamma,
+                         int32_t vocab, float temperature,
+                         int32_t* out_n, int32_t* out_t,
+                         void* scratch, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SD_H */

@@ -1,0 +1,238 @@
+"""Thin ctypes binding of libsd.so (argument marshalling only).
+
+Every step of the hot path runs in the HIP library; this module converts
+Python / torch arguments to the plain pointers and sizes of include/sd.h.
+PyTorch provides device memory and the stream, nothing else.  Importing this
+module fails loudly if the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsd.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2211_17192_amd.build` first")
+lib = C.CDLL(LIB_PATH)
+
+SD_OK, SD_EINVAL, SD_ESTATE, SD_ERANGE, SD_ENOMEM, SD_EHIP = range(6)
+SD_F32, SD_BF16 = 0, 1
+SD_MAX_GAMMA = 15
+SD_FLAG_GRAPH, SD_FLAG_PROFILE = 1, 2
+STATUS_NAMES = ["SD_OK", "SD_EINVAL", "SD_ESTATE", "SD_ERANGE", "SD_ENOMEM", "SD_EHIP"]
+
+
+class SdError(RuntimeError):
+    def __init__(self, status, msg=""):
+        self.status = status
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 6 else status}: {msg}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+lib.sd_spec_sample_scratch_bytes.restype = C.c_size_t
+lib.sd_spec_sample_scratch_bytes.argtypes = [C.c_int32, C.c_int32]
+lib.sd_spec_sample.restype = C.c_int
+lib.sd_spec_sample.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+
+
+def spec_sample_scratch(rows: int, gamma: int) -> torch.Tensor:
+    n = lib.sd_spec_sample_scratch_bytes(rows, gamma)
+    if n == 0:
+        raise SdError(SD_EINVAL, "rows / gamma out of range")
+    return torch.zeros(n, dtype=torch.uint8, device="cuda")
+
+
+def spec_sample(p_logits, q_logits, x, r, s, temperature: float, scratch=None, out_n=None, out_t=None):
+    """sd_spec_sample on cuda tensors: p_logits [rows, gamma+1, V] fp32, q_logits
+    [rows, gamma, V] fp32, x [rows, gamma] int32, r [rows, gamma] fp32, s [rows] fp32.
+    Returns device tensors (n [rows], t [rows]); asynchronous on the current stream."""
+    rows, g1, V = p_logits.shape
+    gamma = g1 - 1
+    for t_, dt in ((p_logits, torch.float32), (q_logits, torch.float32), (x, torch.int32)):
+        assert t_.is_cuda and t_.is_contiguous() and t_.dtype == dt
+    assert q_logits.shape == (rows, gamma, V) and x.shape == (rows, gamma)
+    if scratch is None:
+        scratch = spec_sample_scratch(rows, gamma)
+    if out_n is None:
+        out_n = torch.empty(rows, dtype=torch.int32, device="cuda")
+        out_t = torch.empty(rows, dtype=torch.int32, device="cuda")
+    st = lib.sd_spec_sample(_ptr(p_logits), _ptr(q_logits), _ptr(x), _ptr(r), _ptr(s), rows, gamma, V,
+                            float(temperature), _ptr(out_n), _ptr(out_t), _ptr(scratch), _stream())
+    if st != SD_OK:
+        raise SdError(st, "sd_spec_sample")
+    return out_n, out_t
+
+
+# --------------------------------------------------------------------------
+# the model API
+# --------------------------------------------------------------------------
+class _ModelCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("arch", "n_layers", "d_model", "n_heads", "n_kv_heads", "d_head",
+                                         "d_ff", "vocab", "max_len", "enc_len", "rel_buckets", "rel_max_dist")] + \
+               [("rope_theta", C.c_float), ("logit_scale", C.c_float), ("norm_eps", C.c_float), ("dtype", C.c_int32)]
+
+
+class _Tensor(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("dev", C.c_void_p), ("ndim", C.c_int32), ("shape", C.c_int64 * 4),
+                ("dtype", C.c_int32)]
+
+
+class _RuntimeCfg(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("max_gamma", C.c_int32), ("page_size", C.c_int32),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
+                ("flags", C.c_int32)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("draft_ms", C.c_double), ("verify_ms", C.c_double), ("accept_ms", C.c_double),
+                ("steps", C.c_int64), ("tokens", C.c_int64), ("accepted", C.c_int64), ("fallbacks", C.c_int64)]
+
+
+lib.sd_workspace_bytes.restype = C.c_size_t
+lib.sd_workspace_bytes.argtypes = [C.POINTER(_ModelCfg), C.POINTER(_ModelCfg), C.POINTER(_RuntimeCfg)]
+lib.sd_load_models.restype = C.c_int
+lib.sd_load_models.argtypes = [C.POINTER(C.c_void_p), C.POINTER(_ModelCfg), C.POINTER(_Tensor), C.c_int32,
+                               C.POINTER(_ModelCfg), C.POINTER(_Tensor), C.c_int32, C.POINTER(_RuntimeCfg)]
+lib.sd_prefill.restype = C.c_int
+lib.sd_prefill.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_void_p]
+lib.sd_step.restype = C.c_int
+lib.sd_step.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_float,
+                        C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+lib.sd_step_baseline.restype = C.c_int
+lib.sd_step_baseline.argtypes = [C.c_void_p, C.c_float, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+lib.sd_reset.restype = C.c_int
+lib.sd_reset.argtypes = [C.c_void_p, C.c_int32]
+lib.sd_free.restype = None
+lib.sd_free.argtypes = [C.c_void_p]
+lib.sd_last_error.restype = C.c_char_p
+lib.sd_last_error.argtypes = [C.c_void_p]
+lib.sd_debug_logits.restype = C.c_int
+lib.sd_debug_logits.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float), C.c_size_t]
+lib.sd_get_stats.restype = C.c_int
+lib.sd_get_stats.argtypes = [C.c_void_p, C.POINTER(_Stats)]
+
+
+def _cfg_struct(cfg: dict) -> _ModelCfg:
+    s = _ModelCfg()
+    for k in ("arch", "n_layers", "d_model", "n_heads", "n_kv_heads", "d_head", "d_ff", "vocab", "max_len",
+              "enc_len", "rel_buckets", "rel_max_dist"):
+        setattr(s, k, int(cfg[k]))
+    s.rope_theta = float(cfg["rope_theta"])
+    s.logit_scale = float(cfg["logit_scale"])
+    s.norm_eps = float(cfg["norm_eps"])
+    s.dtype = SD_BF16 if cfg["dtype"] == "bf16" else SD_F32
+    return s
+
+
+def _tensor_array(w: dict, keep: list):
+    arr = (_Tensor * len(w))()
+    for i, (name, t) in enumerate(w.items()):
+        assert t.is_cuda and t.is_contiguous(), name
+        nb = name.encode()
+        keep.append(nb)
+        arr[i].name = nb
+        arr[i].dev = t.data_ptr()
+        arr[i].ndim = t.dim()
+        for j, v in enumerate(t.shape):
+            arr[i].shape[j] = int(v)
+        arr[i].dtype = SD_BF16 if t.dtype == torch.bfloat16 else SD_F32
+    return arr
+
+
+class SpecDecoder:
+    """One (Mp, Mq) pair bound with sd_load_models.  Weights are dicts name -> cuda tensor."""
+
+    def __init__(self, cfg_p: dict, w_p: dict, cfg_q: dict, w_q: dict, max_gamma: int = 7,
+                 page_size: int = 16, flags: int = 0):
+        self._ctx = C.c_void_p()
+        self.cfg_p, self.cfg_q = cfg_p, cfg_q
+        cp, cq = _cfg_struct(cfg_p), _cfg_struct(cfg_q)
+        rt = _RuntimeCfg(batch=1, max_gamma=max_gamma, page_size=page_size, workspace=None,
+                         workspace_bytes=0, stream=None, flags=flags)
+        need = lib.sd_workspace_bytes(C.byref(cp), C.byref(cq), C.byref(rt))
+        if need == 0:
+            raise SdError(SD_EINVAL, "invalid model / runtime configuration")
+        self.workspace = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+        base = (self.workspace.data_ptr() + 255) // 256 * 256
+        rt.workspace, rt.workspace_bytes = base, need
+        keep = []
+        tp, tq = _tensor_array(w_p, keep), _tensor_array(w_q, keep)
+        torch.cuda.synchronize()                      # weights were produced on torch's streams
+        st = lib.sd_load_models(C.byref(self._ctx), C.byref(cp), tp, len(w_p), C.byref(cq), tq, len(w_q),
+                                C.byref(rt))
+        if st != SD_OK:
+            raise SdError(st, (lib.sd_last_error(None) or b"").decode())
+        self.vocab = int(cfg_p["vocab"])
+        self.workspace_bytes = need
+
+    def _check(self, st):
+        if st != SD_OK:
+            raise SdError(st, (lib.sd_last_error(self._ctx) or b"").decode())
+
+    def prefill(self, prompt, enc_p=None, enc_q=None):
+        p = np.ascontiguousarray(np.asarray(prompt, dtype=np.int32))
+        torch.cuda.synchronize()
+        self._check(lib.sd_prefill(self._ctx, 0, p.ctypes.data_as(C.POINTER(C.c_int32)), len(p),
+                                   _ptr(enc_p), _ptr(enc_q)))
+
+    def step(self, gamma: int, temperature: float, uniforms=None, prefix=None):
+        out = (C.c_int32 * (gamma + 1))()
+        n = C.c_int32()
+        u = None
+        if uniforms is not None:
+            ua = np.ascontiguousarray(np.asarray(uniforms, dtype=np.float32))
+            assert ua.shape == (2 * gamma + 1,)
+            u = ua.ctypes.data_as(C.POINTER(C.c_float))
+        pp, pl = None, 0
+        if prefix is not None:
+            pa = np.ascontiguousarray(np.asarray(prefix, dtype=np.int32))
+            pp, pl = pa.ctypes.data_as(C.POINTER(C.c_int32)), len(pa)
+        self._check(lib.sd_step(self._ctx, pp, pl, gamma, float(temperature), u, out, C.byref(n)))
+        return n.value, [out[i] for i in range(n.value + 1)]
+
+    def step_baseline(self, temperature: float, uniform=None) -> int:
+        tok = C.c_int32()
+        u = None
+        if uniform is not None:
+            ua = np.asarray([uniform], dtype=np.float32)
+            u = ua.ctypes.data_as(C.POINTER(C.c_float))
+        self._check(lib.sd_step_baseline(self._ctx, float(temperature), u, C.byref(tok)))
+        return tok.value
+
+    def logits(self, which: int, rows: int) -> np.ndarray:
+        out = np.empty((rows, self.vocab), dtype=np.float32)
+        self._check(lib.sd_debug_logits(self._ctx, which, out.ctypes.data_as(C.POINTER(C.c_float)), out.size))
+        return out
+
+    def stats(self) -> dict:
+        s = _Stats()
+        self._check(lib.sd_get_stats(self._ctx, C.byref(s)))
+        return {k: getattr(s, k) for k, _ in _Stats._fields_}
+
+    def reset(self):
+        self._check(lib.sd_reset(self._ctx, -1))
+
+    def close(self):
+        if self._ctx:
+            lib.sd_free(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,279 @@
+// Skinny GEMM for the (gamma+1)-row forward: Y[R,N] = X[R,K] * W[N,K]^T with
+// R <= 16 rows.  The path is HBM-bound on the weights (about R flop per byte),
+// so the kernel is organised around streaming W exactly once:
+//
+//  * W is re-tiled at load time into MFMA operand order
+//      Wt[N/16][K/32][64 lanes][8 elements],
+//    lane l of a tile holding W[n0 + l%16][k0 + (l/16)*8 .. +8], so a wavefront
+//    fetches one contiguous 1 KB (bf16) block per MFMA with 16-byte loads and
+//    its whole K-slice is one contiguous stream.
+//  * The weights sit on the MFMA "A" side (16 output features), the R
+//    activation rows on the 16-wide "B" side; fp32 accumulation.
+//  * One workgroup owns one 16-feature tile; its S wavefronts split K and the
+//    partial tiles are added through LDS in wave order 0..S-1.  S depends on
+//    (N, K) only, never on R, so a row's result is bit-identical whether it is
+//    computed alone or among gamma+1 rows.
+//  * Prologue: RMSNorm / LayerNorm of the fp32 residual rows (statistics
+//    reduced across the workgroup), rounded to the storage type.
+//  * Epilogues: bias, tanh-GELU, gated GELU / SwiGLU (two weight streams, one
+//    activation stream), residual add, rotary + scatter of q / k / v (k and v
+//    go straight into the paged KV cache), logit scaling.
+#pragma once
+#include "common.h"
+
+namespace sd {
+
+enum { PRO_NONE = 0, PRO_RMS = 1, PRO_LN = 2 };
+enum { EPI_STORE = 0, EPI_QKV = 1, EPI_RESID = 2, EPI_ACT = 3, EPI_GATED = 4, EPI_LOGITS = 5 };
+enum { ACT_GELU = 0, ACT_SILU = 1 };
+
+struct GemmArgs {
+  const void* W;          // tiled weights, N/16 tiles
+  const void* W2;         // EPI_GATED: the "up" weights, tiled alike
+  const void* X;          // PRO_NONE: T [R][K]; else float [R][K]
+  const void* gain;       // T [K]   (PRO_RMS / PRO_LN)
+  const void* beta;       // T [K]   (PRO_LN)
+  const void* bias;       // T [N] or nullptr
+  int R, K, N;
+  int ksteps_per_wave;    // ceil((K/32) / waves)
+  float eps;
+  void* out;              // STORE/ACT/GATED: T [R][ldo]; RESID, LOGITS: float [R][ldo]
+  int ldo;
+  float scale;            // EPI_LOGITS
+  int act;                // EPI_GATED
+  // EPI_QKV
+  void* q_out;            // T [R][nq]
+  int nq, nkv;            // features [0,nq) q, [nq,nq+nkv) k, [nq+nkv,nq+2nkv) v
+  void* kv_pool;          // this layer's pages: [page][2][n_kv_heads][page_size][d_head]
+  const int* page_table;
+  int page_size, n_kv_heads, d_head;
+  const int* row_pos;     // [R] position of each row; < 0: row is padding
+  const float* rope;      // [max_len][d_head/2][2] (cos, sin) or nullptr
+};
+
+template <typename T> struct Mma;
+template <> struct Mma<bf16> {
+  typedef bf16x8 Frag;
+  static __device__ __forceinline__ Frag load(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+  static __device__ __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f[e] = (bf16)0.0f; return f; }
+  static __device__ __forceinline__ Frag from_floats(const float (&v)[8]) {
+    Frag f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = (bf16)v[e];
+    return f;
+  }
+  static __device__ __forceinline__ f32x4 mma(const Frag& a, const Frag& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+};
+template <> struct Mma<float> {
+  struct Frag { float v[8]; };
+  static __device__ __forceinline__ Frag load(const float* p) { Frag f; load8<float>(p, f.v); return f; }
+  static __device__ __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f.v[e] = 0.0f; return f; }
+  static __device__ __forceinline__ Frag from_floats(const float (&v)[8]) {
+    Frag f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f.v[e] = v[e];
+    return f;
+  }
+  // eight 16x16x4 steps; step e contracts the k indices {kq*8 + e}, the same
+  // set on both operands
+  static __device__ __forceinline__ f32x4 mma(const Frag& a, const Frag& b, f32x4 c) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[e], b.v[e], c, 0, 0, 0);
+    return c;
+  }
+};
+
+__device__ __forceinline__ float gelu_tanh(float x) {
+  return 0.5f * x * (1.0f + tanhf(0.7978845608028654f * (x + 0.044715f * x * x * x)));
+}
+__device__ __forceinline__ float silu(float x) { return x / (1.0f + expf(-x)); }
+
+constexpr int GEMM_UNROLL = 8;
+
+template <typename T, int PRO, int EPI>
+static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
+  extern __shared__ float lds[];
+  constexpr int ND = (EPI == EPI_GATED) ? 2 : 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, S = blockDim.x >> 6;
+  const int tile = blockIdx.x;
+  const int j = lane & 15, kq = lane >> 4;           // B side: row j, k-quarter kq
+  const int KS = a.K >> 5;
+  const int ks0 = min(KS, wave * a.ksteps_per_wave), ks1 = min(KS, ks0 + a.ksteps_per_wave);
+  float* part = lds;                                 // [S][ND][256]
+  float* stat = lds + S * ND * 256;                  // [S][16]
+  float* ybuf = stat + S * 16;                       // [ND][256]
+  const bool row_ok = (j < a.R);
+
+  // ---- prologue statistics (normalisation of the residual rows) ----
+  float mu = 0.0f, rstd = 1.0f;
+  if (PRO != PRO_NONE) {
+    const float* x = static_cast<const float*>(a.X) + (size_t)j * a.K + kq * 8;
+    if (PRO == PRO_LN) {
+      float s = 0.0f;
+      if (row_ok) for (int ks = ks0; ks < ks1; ++ks) {
+        float v[8]; load8<float>(x + ks * 32, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += v[e];
+      }
+      s += __shfl_xor(s, 16, WAVE); s += __shfl_xor(s, 32, WAVE);
+      if (kq == 0) stat[wave * 16 + j] = s;
+      __syncthreads();
+      float t = 0.0f;
+      for (int w = 0; w < S; ++w) t += stat[w * 16 + j];
+      mu = t / (float)a.K;
+      __syncthreads();
+    }
+    float s2 = 0.0f;
+    if (row_ok) for (int ks = ks0; ks < ks1; ++ks) {
+      float v[8]; load8<float>(x + ks * 32, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float d = v[e] - mu; s2 += d * d; }
+    }
+    s2 += __shfl_xor(s2, 16, WAVE); s2 += __shfl_xor(s2, 32, WAVE);
+    if (kq == 0) stat[wave * 16 + j] = s2;
+    __syncthreads();
+    float t2 = 0.0f;
+    for (int w = 0; w < S; ++w) t2 += stat[w * 16 + j];
+    rstd = 1.0f / sqrtf(t2 / (float)a.K + a.eps);
+  }
+
+  // ---- main loop: stream this wave's K-slice of the tile ----
+  typedef typename Mma<T>::Frag Frag;
+  f32x4 acc[ND];
+#pragma unroll
+  for (int d = 0; d < ND; ++d) acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const T* w0 = static_cast<const T*>(a.W) + ((size_t)tile * KS) * 512 + lane * 8;
+  const T* w1 = (ND == 2) ? static_cast<const T*>(a.W2) + ((size_t)tile * KS) * 512 + lane * 8 : nullptr;
+
+  auto make_b = [&](int ks) -> Frag {
+    if (!row_ok) return Mma<T>::zero();
+    const int k = ks * 32 + kq * 8;
+    if (PRO == PRO_NONE) {
+      return Mma<T>::load(static_cast<const T*>(a.X) + (size_t)j * a.K + k);
+    } else {
+      float v[8], g[8];
+      load8<float>(static_cast<const float*>(a.X) + (size_t)j * a.K + k, v);
+      load8<T>(static_cast<const T*>(a.gain) + k, g);
+      if (PRO == PRO_LN) {
+        float bb[8];
+        load8<T>(static_cast<const T*>(a.beta) + k, bb);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (v[e] - mu) * rstd * g[e] + bb[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = v[e] * rstd * g[e];
+      }
+      return Mma<T>::from_floats(v);
+    }
+  };
+
+  int ks = ks0;
+  for (; ks + GEMM_UNROLL <= ks1; ks += GEMM_UNROLL) {
+    Frag fa[ND][GEMM_UNROLL], fb[GEMM_UNROLL];
+#pragma unroll
+    for (int u = 0; u < GEMM_UNROLL; ++u) {
+      fa[0][u] = Mma<T>::load(w0 + (size_t)(ks + u) * 512);
+      if (ND == 2) fa[ND - 1][u] = Mma<T>::load(w1 + (size_t)(ks + u) * 512);
+    }
+#pragma unroll
+    for (int u = 0; u < GEMM_UNROLL; ++u) fb[u] = make_b(ks + u);
+#pragma unroll
+    for (int u = 0; u < GEMM_UNROLL; ++u) {
+      acc[0] = Mma<T>::mma(fa[0][u], fb[u], acc[0]);
+      if (ND == 2) acc[ND - 1] = Mma<T>::mma(fa[ND - 1][u], fb[u], acc[ND - 1]);
+    }
+  }
+  for (; ks < ks1; ++ks) {
+    const Frag fb = make_b(ks);
+    acc[0] = Mma<T>::mma(Mma<T>::load(w0 + (size_t)ks * 512), fb, acc[0]);
+    if (ND == 2) acc[ND - 1] = Mma<T>::mma(Mma<T>::load(w1 + (size_t)ks * 512), fb, acc[ND - 1]);
+  }
+
+  // ---- combine the K-slices in wave order ----
+  // accumulator layout: lane holds features (lane/16)*4 + r, r = 0..3, of row lane%16
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      part[(wave * ND + d) * 256 + j * 16 + kq * 4 + r] = acc[d][r];
+  __syncthreads();
+
+  for (int t = tid; t < 256; t += blockDim.x) {
+    float y[ND];
+#pragma unroll
+    for (int d = 0; d < ND; ++d) {
+      float s = 0.0f;
+      for (int w = 0; w < S; ++w) s += part[(w * ND + d) * 256 + t];
+      y[d] = s;
+    }
+    const int row = t >> 4, f = t & 15, n = tile * 16 + f;
+    if (a.bias != nullptr) y[0] += Store<T>::ld(static_cast<const T*>(a.bias) + n);
+    if (EPI == EPI_QKV) {
+      ybuf[t] = y[0];
+    } else if (row < a.R) {
+      if (EPI == EPI_STORE) {
+        Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
+      } else if (EPI == EPI_RESID) {
+        float* o = static_cast<float*>(a.out) + (size_t)row * a.ldo + n;
+        *o = *o + y[0];
+      } else if (EPI == EPI_ACT) {
+        Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, gelu_tanh(y[0]));
+      } else if (EPI == EPI_GATED) {
+        const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
+        Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[ND - 1]);
+      } else if (EPI == EPI_LOGITS) {
+        static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = a.scale * y[0];
+      }
+    }
+  }
+
+  if (EPI == EPI_QKV) {
+    __syncthreads();
+    for (int t = tid; t < 256; t += blockDim.x) {
+      const int row = t >> 4, f = t & 15, n = tile * 16 + f;
+      if (row >= a.R) continue;
+      const int pos = a.row_pos[row];
+      float y = ybuf[t];
+      const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
+      const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
+      const int head = nn / a.d_head, d = nn % a.d_head;
+      if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
+        const float other = ybuf[t ^ 1];
+        const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
+        y = (d & 1) ? (other * cs[1] + y * cs[0]) : (y * cs[0] - other * cs[1]);
+      }
+      if (is_q) {
+        Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
+      } else if (pos >= 0) {
+        const int page = a.page_table[pos / a.page_size], slot = pos % a.page_size;
+        const size_t idx = ((((size_t)page * 2 + (is_k ? 0 : 1)) * a.n_kv_heads + head) * a.page_size + slot) *
+                               a.d_head + d;
+        Store<T>::st(static_cast<T*>(a.kv_pool) + idx, y);
+      }
+    }
+  }
+}
+
+// Re-tile a row-major [N][K] weight into MFMA operand order (see above).
+// One thread moves 8 consecutive K-elements.
+template <typename T>
+static __global__ void retile_kernel(const T* __restrict__ src, T* __restrict__ dst, int N, int K) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;     // index of an 8-element group
+  const size_t total = (size_t)N * K / 8;
+  if (i >= total) return;
+  const int KS = K >> 5;
+  const int lane = (int)(i & 63);
+  const size_t blk = i >> 6;                   // tile * KS + ks
+  const int ks = (int)(blk % KS);
+  const size_t tile = blk / KS;
+  const size_t n = tile * 16 + (lane & 15);
+  const size_t k = (size_t)ks * 32 + (lane >> 4) * 8;
+  const T* s = src + n * K + k;
+  T* d = dst + i * 8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) d[e] = s[e];
+}
+
+}  // namespace sd

@@ -1,0 +1,51 @@
+// Row set-up + embedding: decides which tokens a forward processes, from the
+// device-resident sequence state, and writes their embeddings into the fp32
+// residual stream.  Keeping this on the device lets one captured graph serve
+// every iteration.
+#pragma once
+#include "common.h"
+
+namespace sd {
+
+enum {
+  ROWS_VERIFY = 0,       // Mp scoring of Algorithm 1: [last token, x_1..x_gamma] at len-1 ..
+  ROWS_DRAFT_FIRST = 1,  // first Mq step: the last two committed tokens at len-2, len-1
+  ROWS_DRAFT_NEXT = 2,   // Mq step i >= 2: x_{i-1} at len-2+i
+  ROWS_BASELINE = 3,     // standard decoding: last token at len-1
+  ROWS_PREFILL = 4       // prompt[start .. start+R) at start ..
+};
+
+// grid = R workgroups.  row_pos[r] < 0 marks a padding row (first draft step of
+// a one-token sequence): it is embedded as token 0 at position 0 and ignored.
+template <typename T>
+static __global__ __launch_bounds__(256) void embed_kernel(
+    int mode, int step, const SeqState* __restrict__ st, const int* __restrict__ prompt, int start,
+    const T* __restrict__ tok_emb, const T* __restrict__ pos_emb, int d, int vocab,
+    float* __restrict__ x, int* __restrict__ row_pos) {
+  const int r = blockIdx.x;
+  int tok, pos;
+  switch (mode) {
+    case ROWS_VERIFY:      tok = (r == 0) ? st->last_tok : st->x[r - 1]; pos = st->len - 1 + r; break;
+    case ROWS_DRAFT_FIRST: tok = (r == 0) ? st->prev_tok : st->last_tok; pos = st->len - 2 + r; break;
+    case ROWS_DRAFT_NEXT:  tok = st->x[step - 1]; pos = st->len - 1 + step; break;
+    case ROWS_BASELINE:    tok = st->last_tok; pos = st->len - 1; break;
+    default:               tok = prompt[start + r]; pos = start + r; break;
+  }
+  if (threadIdx.x == 0) row_pos[r] = pos;
+  if (pos < 0) { tok = 0; pos = 0; }
+  tok = min(max(tok, 0), vocab - 1);
+  const T* e = tok_emb + (size_t)tok * d;
+  const T* p = pos_emb ? pos_emb + (size_t)pos * d : nullptr;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    float v = Store<T>::ld(e + i);
+    if (p) v += Store<T>::ld(p + i);
+    x[(size_t)r * d + i] = v;
+  }
+}
+
+static __global__ void fill_u32_kernel(unsigned int* p, unsigned int v, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+}  // namespace sd

@@ -1,0 +1,365 @@
+// Sampling kernels: section 2.2 standardisation (temperature softmax / argmax),
+// inverse-CDF draws from caller-supplied uniforms, and the accept / resample
+// part of Algorithm 1 fused into one launch (row statistics in parallel, then
+// the last-finishing workgroup of a sequence takes the decisions, draws the
+// extra token and commits / rolls back the sequence state).
+//
+// Arithmetic of a standardised row z at temperature T > 0:
+//   m = max_k z_k,  e_k = exp((z_k - m) / T)  (fp32 hardware exp2 path),
+//   S = sum_k e_k (fp64),  prob_k = e_k * (1/S) (fp64).
+// Sums and cumulative sums are carried in fp64, so the blocked summation order
+// differs from a sequential one only far below the resolution of the uniforms.
+// T == 0 uses integer argmax compares (ties to the lowest index).
+#pragma once
+#include <limits.h>
+#include "common.h"
+
+namespace sd {
+
+constexpr int SAMPLE_THREADS = 1024;
+constexpr int SAMPLE_CHUNK = 256;           // vocabulary entries per scan chunk (64 lanes x 4)
+constexpr int SAMPLE_MAX_CHUNKS = 1024;     // vocab <= 262144
+constexpr int SAMPLE_REG_F4 = 8;            // a row up to 32768 entries is held in registers
+
+struct RowStat {
+  float  m;      // max logit
+  int    arg;    // lowest index attaining it
+  double S;      // sum of e_k
+};
+
+struct SampleSmem {
+  float  redf[16];
+  double redd[16];
+  int    redi[16];
+  int    flag;
+  int    n;
+  int    chunk;          // scan: chunk that holds the threshold
+  int    token;
+  double before;         // scan: cumulative weight before that chunk
+  double total;
+  double ctot[SAMPLE_MAX_CHUNKS];
+};
+
+__device__ __forceinline__ float exp_scaled(float z, float m, float invT) {
+  return __expf((z - m) * invT);
+}
+
+// max / argmax / sum-of-exponentials of one logits row; every thread gets it.
+// Rows of up to 32768 entries are read from memory exactly once.
+__device__ __forceinline__ RowStat row_stats(const float* __restrict__ z, int V, float invT,
+                                             bool greedy, SampleSmem& sm) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  RowStat st; st.arg = 0; st.S = 0.0;
+  const bool vec = ((V & 3) == 0) && ((reinterpret_cast<uintptr_t>(z) & 15) == 0) &&
+                   (V <= SAMPLE_REG_F4 * 4 * nt);
+  if (vec) {
+    const float4* z4 = reinterpret_cast<const float4*>(z);
+    const int n4 = V >> 2;
+    float4 v[SAMPLE_REG_F4];
+#pragma unroll
+    for (int it = 0; it < SAMPLE_REG_F4; ++it) {
+      const int i = it * nt + tid;
+      v[it] = (i < n4) ? z4[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int it = 0; it < SAMPLE_REG_F4; ++it)
+      m = fmaxf(m, fmaxf(fmaxf(v[it].x, v[it].y), fmaxf(v[it].z, v[it].w)));
+    m = block_reduce(m, sm.redf, OpMaxF(), -INFINITY);
+    st.m = m;
+    if (greedy) {
+      int a = INT_MAX;
+#pragma unroll
+      for (int it = SAMPLE_REG_F4 - 1; it >= 0; --it) {
+        const int k = (it * nt + tid) * 4;
+        if (v[it].w == m) a = k + 3;
+        if (v[it].z == m) a = k + 2;
+        if (v[it].y == m) a = k + 1;
+        if (v[it].x == m) a = k;
+      }
+      st.arg = block_reduce(a, sm.redi, OpMinI(), INT_MAX);
+      return st;
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int it = 0; it < SAMPLE_REG_F4; ++it)       // exp(-inf) = 0 for the padding
+      s += (exp_scaled(v[it].x, m, invT) + exp_scaled(v[it].y, m, invT)) +
+           (exp_scaled(v[it].z, m, invT) + exp_scaled(v[it].w, m, invT));
+    st.S = block_reduce((double)s, sm.redd, OpSumD(), 0.0);
+    return st;
+  }
+  float m = -INFINITY;
+  for (int i = tid; i < V; i += nt) m = fmaxf(m, z[i]);
+  m = block_reduce(m, sm.redf, OpMaxF(), -INFINITY);
+  st.m = m;
+  if (greedy) {
+    int a = INT_MAX;
+    for (int i = tid; i < V; i += nt) if (z[i] == m) a = min(a, i);
+    st.arg = block_reduce(a, sm.redi, OpMinI(), INT_MAX);
+    return st;
+  }
+  double s = 0.0;
+  for (int i = tid; i < V; i += nt) s += (double)exp_scaled(z[i], m, invT);
+  st.S = block_reduce(s, sm.redd, OpSumD(), 0.0);
+  return st;
+}
+
+// The four weights of entries k..k+3: prob_p, minus prob_q clipped at zero when
+// a draft row is given (the unnormalised adjusted distribution of section 2.3).
+struct RowPair {
+  const float* zp; const float* zq;     // zq == nullptr: plain row
+  float mp, mq;
+  double invSp, invSq;
+  float invT;
+  int V;
+  bool vec;
+};
+
+__device__ __forceinline__ void weights4(const RowPair& rp, int k, double (&w)[4]) {
+  float zp[4], zq[4];
+  if (rp.vec && k + 3 < rp.V) {
+    const float4 a = *reinterpret_cast<const float4*>(rp.zp + k);
+    zp[0] = a.x; zp[1] = a.y; zp[2] = a.z; zp[3] = a.w;
+    if (rp.zq) {
+      const float4 b = *reinterpret_cast<const float4*>(rp.zq + k);
+      zq[0] = b.x; zq[1] = b.y; zq[2] = b.z; zq[3] = b.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      zp[e] = (k + e < rp.V) ? rp.zp[k + e] : -INFINITY;
+      zq[e] = (rp.zq && k + e < rp.V) ? rp.zq[k + e] : -INFINITY;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    double p = (k + e < rp.V) ? (double)exp_scaled(zp[e], rp.mp, rp.invT) * rp.invSp : 0.0;
+    if (rp.zq) {
+      const double q = (k + e < rp.V) ? (double)exp_scaled(zq[e], rp.mq, rp.invT) * rp.invSq : 0.0;
+      p -= q;
+      p = p > 0.0 ? p : 0.0;
+    }
+    w[e] = p;
+  }
+}
+
+// Inverse-CDF draw: smallest k with cumulative weight > u * total weight, in
+// vocabulary order.  Chunks of 256 consecutive entries are summed by one
+// wavefront each (coalesced 1 KB reads), the chunk totals are scanned, and only
+// the chunk that holds the threshold is scanned entry by entry.  Returns -1 in
+// every thread if the total weight is not positive (the caller then falls back
+// to the unadjusted row).
+__device__ __forceinline__ int icdf_row(const float* zp, const RowStat& sp, const float* zq,
+                                        const RowStat& sq, float invT, int V, float u,
+                                        SampleSmem& sm) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+  RowPair rp;
+  rp.zp = zp; rp.zq = zq; rp.mp = sp.m; rp.mq = sq.m;
+  rp.invSp = 1.0 / sp.S; rp.invSq = zq ? 1.0 / sq.S : 0.0;
+  rp.invT = invT; rp.V = V;
+  rp.vec = ((V & 3) == 0) && ((reinterpret_cast<uintptr_t>(zp) & 15) == 0) &&
+           (zq == nullptr || (reinterpret_cast<uintptr_t>(zq) & 15) == 0);
+  const int nchunks = (V + SAMPLE_CHUNK - 1) / SAMPLE_CHUNK;
+  __syncthreads();
+  for (int c = wave; c < nchunks; c += nw) {
+    double w[4];
+    weights4(rp, c * SAMPLE_CHUNK + lane * 4, w);
+    const double t = wave_sum((w[0] + w[1]) + (w[2] + w[3]));
+    if (lane == 0) sm.ctot[c] = t;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    // scan the chunk totals: lane l owns chunks [l*cpl, (l+1)*cpl)
+    const int cpl = (nchunks + 63) / 64;
+    const int c0 = min(nchunks, lane * cpl), c1 = min(nchunks, c0 + cpl);
+    double local = 0.0;
+    for (int c = c0; c < c1; ++c) local += sm.ctot[c];
+    double inc = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double t = __shfl_up(inc, o, WAVE);
+      if (lane >= o) inc += t;
+    }
+    const double total = __shfl(inc, 63, WAVE);
+    const double theta = (double)u * total;
+    double cum = inc - local;
+    int found = INT_MAX;
+    double before = 0.0;
+    for (int c = c0; c < c1; ++c) {
+      const double nx = cum + sm.ctot[c];
+      if (found == INT_MAX && nx > theta) { found = c; before = cum; }
+      cum = nx;
+    }
+    const int first = wave_min(found);
+    int lastpos = -1;                         // fallback: last chunk with positive weight
+    for (int c = c0; c < c1; ++c) if (sm.ctot[c] > 0.0) lastpos = c;
+    lastpos = wave_max(lastpos);
+    if (found == first && first != INT_MAX) { sm.chunk = first; sm.before = before; }
+    if (lane == 0) {
+      sm.total = total;
+      if (first == INT_MAX) { sm.chunk = -1 - lastpos; sm.before = 0.0; }
+    }
+  }
+  __syncthreads();
+  const double total = sm.total;
+  if (!(total > 0.0)) return -1;
+  const int chunk = sm.chunk;
+  if (wave == 0) {
+    const bool fallback = chunk < 0;          // threshold not reached by round-off
+    const int c = fallback ? (-1 - chunk) : chunk;
+    const int k = c * SAMPLE_CHUNK + lane * 4;
+    double w[4];
+    weights4(rp, k, w);
+    const double local = (w[0] + w[1]) + (w[2] + w[3]);
+    double inc = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double t = __shfl_up(inc, o, WAVE);
+      if (lane >= o) inc += t;
+    }
+    int cand = INT_MAX;
+    if (!fallback) {
+      const double theta = (double)u * total;
+      double cum = sm.before + (inc - local);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        cum += w[e];
+        if (cand == INT_MAX && cum > theta && k + e < V) cand = k + e;
+      }
+      cand = wave_min(cand);
+    }
+    if (cand == INT_MAX) {                    // last entry with positive weight
+      int lp = -1;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) if (w[e] > 0.0 && k + e < V) lp = k + e;
+      cand = wave_max(lp);
+    }
+    if (lane == 0) sm.token = cand;
+  }
+  __syncthreads();
+  return sm.token;
+}
+
+// ---------------------------------------------------------------------------
+// Draw one token from one logits row: x_i ~ q_i of the draft loop, or the
+// plain-decoding draw t ~ p.  One workgroup.
+//   mode 0: store the token as guess number `slot` (st->x[slot])
+//   mode 1: commit it (standard decoding): len += 1
+// ---------------------------------------------------------------------------
+static __global__ __launch_bounds__(SAMPLE_THREADS) void sample_row_kernel(
+    const float* __restrict__ logits, int V, const StepParams* __restrict__ prm, int uniform_idx,
+    SeqState* __restrict__ st, int mode, int slot) {
+  __shared__ SampleSmem sm;
+  const float T = prm->temperature;
+  const bool greedy = (T == 0.0f);
+  const float invT = greedy ? 1.0f : 1.0f / T;
+  const RowStat rs = row_stats(logits, V, invT, greedy, sm);
+  int tok;
+  if (greedy) tok = rs.arg;
+  else tok = icdf_row(logits, rs, nullptr, rs, invT, V, prm->uniforms[uniform_idx], sm);
+  if (threadIdx.x == 0) {
+    if (mode == 0) {
+      st->x[slot] = tok;
+    } else {
+      st->prev_tok = st->last_tok;
+      st->last_tok = tok;
+      st->len += 1;
+      st->n = 0;
+      st->out[0] = tok;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Accept / resample (Algorithm 1, second half).  grid = (2*gamma+1, rows):
+// block (j, b) computes the statistics of logits row j of sequence b (j <=
+// gamma: p_{j+1}; j > gamma: q_{j-gamma}); the last block of a sequence to
+// finish then
+//   * evaluates r_i <= p_i(x_i)/q_i(x_i) for all i in one wavefront and takes
+//     n = index of the first rejection from the ballot,
+//   * draws t from norm(max(0, p_{n+1} - q_{n+1})) (n < gamma) or p_{gamma+1},
+//   * writes n and t, and, when `st` is given, commits the sequence:
+//     out = x_1..x_n, t; len += n+1 (which is the KV roll-back: cache rows
+//     beyond the committed length are dead and get overwritten).
+// x, r, s: explicit arrays [rows, gamma] / [rows] or, when prm/st are given,
+// taken from the device-resident step parameters and state.
+// ---------------------------------------------------------------------------
+static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
+    const float* __restrict__ p_logits, const float* __restrict__ q_logits,
+    const int* __restrict__ x_in, const float* __restrict__ r_in, const float* __restrict__ s_in,
+    int gamma, int V, float temperature, const StepParams* __restrict__ prm,
+    RowStat* __restrict__ stats, unsigned int* __restrict__ counters,
+    int* __restrict__ out_n, int* __restrict__ out_t, SeqState* __restrict__ st) {
+  __shared__ SampleSmem sm;
+  __shared__ RowStat srow[2 * 15 + 1];
+  const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int nrows = 2 * gamma + 1;
+  const float T = prm ? prm->temperature : temperature;
+  const bool greedy = (T == 0.0f);
+  const float invT = greedy ? 1.0f : 1.0f / T;
+  const float* P = p_logits + (size_t)b * (gamma + 1) * V;
+  const float* Q = q_logits + (size_t)b * gamma * V;
+  RowStat* my_stats = stats + (size_t)b * nrows;
+
+  if (!(greedy && j > gamma)) {          // argmax sampling never looks at q rows
+    const float* z = (j <= gamma) ? P + (size_t)j * V : Q + (size_t)(j - gamma - 1) * V;
+    const RowStat rs = row_stats(z, V, invT, greedy, sm);
+    if (tid == 0) my_stats[j] = rs;
+  }
+  if (!last_block_arrives(counters + b, (unsigned)nrows, &sm.flag)) return;
+
+  // ---- tail: one workgroup per sequence ----
+  if (tid < nrows) srow[tid] = my_stats[tid];
+  __syncthreads();
+  const int* x = st ? st->x : x_in + (size_t)b * gamma;
+  const float* r = prm ? prm->uniforms + gamma : r_in + (size_t)b * gamma;
+  const float s = greedy ? 0.5f : (prm ? prm->uniforms[2 * gamma] : s_in[b]);
+
+  if (tid < WAVE) {                       // wavefront 0: one lane per guess
+    bool reject = false;
+    if (tid < gamma) {
+      const int xi = min(max(x[tid], 0), V - 1);
+      if (greedy) {
+        reject = (srow[tid].arg != xi);
+      } else {
+        const RowStat sp = srow[tid], sq = srow[gamma + 1 + tid];
+        const double p = (double)exp_scaled(P[(size_t)tid * V + xi], sp.m, invT) * (1.0 / sp.S);
+        const double q = (double)exp_scaled(Q[(size_t)tid * V + xi], sq.m, invT) * (1.0 / sq.S);
+        const double ratio = (q > 0.0) ? p / q : INFINITY;
+        reject = ((double)r[tid] > ratio);
+      }
+    }
+    const unsigned long long mask = __ballot(reject);
+    if (tid == 0) sm.n = mask ? (__ffsll((long long)mask) - 1) : gamma;
+  }
+  __syncthreads();
+  const int n = sm.n;
+  int t;
+  int fell_back = 0;
+  if (greedy) {
+    t = srow[n].arg;
+  } else {
+    const float* zp = P + (size_t)n * V;
+    if (n < gamma) {
+      t = icdf_row(zp, srow[n], Q + (size_t)n * V, srow[gamma + 1 + n], invT, V, s, sm);
+      if (t < 0) { fell_back = 1; t = icdf_row(zp, srow[n], nullptr, srow[n], invT, V, s, sm); }
+    } else {
+      t = icdf_row(zp, srow[n], nullptr, srow[n], invT, V, s, sm);
+    }
+  }
+  if (tid == 0) {
+    if (out_n) out_n[b] = n;
+    if (out_t) out_t[b] = t;
+    if (st) {
+      const int last = st->last_tok;
+      for (int i = 0; i < 16; ++i) st->out[i] = (i < n) ? x[i] : (i == n ? t : -1);
+      st->prev_tok = (n >= 1) ? x[n - 1] : last;
+      st->last_tok = t;
+      st->len += n + 1;
+      st->n = n;
+      st->fallbacks += fell_back;
+    }
+  }
+}
+
+}  // namespace sd

@@ -1,0 +1,704 @@
+// Host side of the speculative-decoding library: workspace layout, weight
+// loading / re-tiling, and the launch sequences of prefill, one run of
+// Algorithm 1 (sd_step) and one plain decoding step (sd_step_baseline).
+// The C ABI is declared and documented in include/sd.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/sd.h"
+#include "kernels_attn.h"
+#include "kernels_gemm.h"
+#include "kernels_misc.h"
+#include "kernels_sample.h"
+
+namespace {
+
+using namespace sd;
+
+thread_local std::string g_load_error;
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// Bump allocator over the caller's workspace; with base == nullptr it only sizes.
+struct Arena {
+  char* base;
+  size_t off = 0;
+  explicit Arena(void* b) : base(static_cast<char*>(b)) {}
+  void* take(size_t bytes) {
+    off = align_up(off);
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+struct LayerW {
+  void *ln1g = nullptr, *ln1b = nullptr, *wqkv = nullptr, *bqkv = nullptr, *wo = nullptr, *bo = nullptr;
+  void *lncg = nullptr, *cq = nullptr, *ck = nullptr, *cv = nullptr, *co = nullptr;
+  void *ln2g = nullptr, *ln2b = nullptr, *w1 = nullptr, *wu = nullptr, *b1 = nullptr, *w2 = nullptr, *b2 = nullptr;
+  void* kv = nullptr;                       // [page][2][Hkv][PS][dh]
+  void *cross_k = nullptr, *cross_v = nullptr;   // [enc_len][H*dh]
+};
+
+struct Model {
+  sd_model_cfg cfg{};
+  size_t esz = 4;
+  int nq = 0, nkv = 0, n_pages = 0, page_size = 0, nchunks = 0;
+  void *tok_emb = nullptr, *pos_emb = nullptr, *head = nullptr, *lnfg = nullptr, *lnfb = nullptr, *rel_bias = nullptr;
+  int* bucket_lut = nullptr;
+  float* rope = nullptr;
+  std::vector<LayerW> L;
+  int* page_table = nullptr;
+  float* x = nullptr;
+  void *qbuf = nullptr, *attn = nullptr, *ffn = nullptr;
+  int* row_pos = nullptr;
+  float *part_o = nullptr, *part_ml = nullptr;
+  unsigned int* attn_counters = nullptr;
+  int* prompt = nullptr;
+};
+
+bool cfg_ok(const sd_model_cfg& c, std::string& why) {
+  auto bad = [&](const char* m) { why = m; return false; };
+  if (c.arch < 0 || c.arch > 2) return bad("unknown arch");
+  if (c.dtype != SD_F32 && c.dtype != SD_BF16) return bad("unknown dtype");
+  if (c.n_layers < 1 || c.d_model < 32 || c.n_heads < 1 || c.n_kv_heads < 1 || c.d_ff < 32 ||
+      c.vocab < 16 || c.max_len < 2)
+    return bad("non-positive size");
+  if (c.d_head != 32 && c.d_head != 64 && c.d_head != 128) return bad("d_head must be 32, 64 or 128");
+  if (c.n_heads % c.n_kv_heads) return bad("n_heads must be a multiple of n_kv_heads");
+  if (c.arch != SD_ARCH_GQA && c.n_heads != c.n_kv_heads) return bad("grouped KV heads need SD_ARCH_GQA");
+  if (c.n_heads / c.n_kv_heads > 4) return bad("at most 4 query heads per KV head");
+  if (c.d_model % 32 || c.d_ff % 32 || (c.n_heads * c.d_head) % 32) return bad("dims must be multiples of 32");
+  if (c.vocab % 16) return bad("vocab must be a multiple of 16");
+  if (c.vocab > SAMPLE_CHUNK * SAMPLE_MAX_CHUNKS) return bad("vocab too large");
+  if (c.arch == SD_ARCH_T5DEC && (c.enc_len < 1 || c.rel_buckets < 2 || c.rel_buckets % 2 ||
+                                  c.rel_max_dist <= c.rel_buckets / 2))
+    return bad("T5DEC needs enc_len, rel_buckets, rel_max_dist");
+  if (c.arch != SD_ARCH_T5DEC && c.enc_len != 0) return bad("enc_len only for T5DEC");
+  if (!(c.norm_eps > 0.0f)) return bad("norm_eps must be positive");
+  return true;
+}
+
+// Lays a model out in the arena (or sizes it).
+void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size) {
+  m.cfg = c;
+  m.esz = (c.dtype == SD_BF16) ? 2 : 4;
+  const size_t e = m.esz, d = c.d_model, ff = c.d_ff, V = c.vocab;
+  m.nq = c.n_heads * c.d_head;
+  m.nkv = c.n_kv_heads * c.d_head;
+  m.page_size = page_size;
+  m.n_pages = (c.max_len + page_size - 1) / page_size;
+  const int longest = c.max_len > c.enc_len ? c.max_len : c.enc_len;
+  m.nchunks = (longest + ATTN_CHUNK - 1) / ATTN_CHUNK;
+  m.tok_emb = A.take(V * d * e);
+  m.head = A.take(V * d * e);
+  m.lnfg = A.take(d * e);
+  if (c.arch == SD_ARCH_GPT) { m.lnfb = A.take(d * e); m.pos_emb = A.take((size_t)c.max_len * d * e); }
+  if (c.arch == SD_ARCH_T5DEC) {
+    m.rel_bias = A.take((size_t)c.n_heads * c.rel_buckets * e);
+    m.bucket_lut = static_cast<int*>(A.take((size_t)c.max_len * sizeof(int)));
+  }
+  if (c.arch == SD_ARCH_GQA) m.rope = static_cast<float*>(A.take((size_t)c.max_len * c.d_head * sizeof(float)));
+  m.L.assign(c.n_layers, LayerW());
+  for (auto& l : m.L) {
+    l.ln1g = A.take(d * e); l.ln2g = A.take(d * e);
+    l.wqkv = A.take((size_t)(m.nq + 2 * m.nkv) * d * e);
+    l.wo = A.take(d * m.nq * e);
+    l.w2 = A.take(d * ff * e);
+    if (c.arch == SD_ARCH_GPT) {
+      l.ln1b = A.take(d * e); l.ln2b = A.take(d * e);
+      l.bqkv = A.take((size_t)(m.nq + 2 * m.nkv) * e);
+      l.bo = A.take(d * e); l.b1 = A.take(ff * e); l.b2 = A.take(d * e);
+      l.w1 = A.take(ff * d * e);
+    } else {
+      l.w1 = A.take(ff * d * e);            // gate
+      l.wu = A.take(ff * d * e);
+    }
+    if (c.arch == SD_ARCH_T5DEC) {
+      l.lncg = A.take(d * e);
+      l.cq = A.take(m.nq * d * e); l.ck = A.take(m.nq * d * e); l.cv = A.take(m.nq * d * e);
+      l.co = A.take(d * m.nq * e);
+      l.cross_k = A.take((size_t)c.enc_len * m.nq * e);
+      l.cross_v = A.take((size_t)c.enc_len * m.nq * e);
+    }
+    l.kv = A.take((size_t)m.n_pages * 2 * c.n_kv_heads * page_size * c.d_head * e);
+  }
+  m.page_table = static_cast<int*>(A.take((size_t)m.n_pages * sizeof(int)));
+  m.x = static_cast<float*>(A.take((size_t)MAX_ROWS * d * sizeof(float)));
+  m.qbuf = A.take((size_t)MAX_ROWS * m.nq * e);
+  m.attn = A.take((size_t)MAX_ROWS * m.nq * e);
+  m.ffn = A.take((size_t)MAX_ROWS * ff * e);
+  m.row_pos = static_cast<int*>(A.take(MAX_ROWS * sizeof(int)));
+  const size_t G = c.n_heads / c.n_kv_heads, RG = MAX_ROWS * G;
+  m.part_o = static_cast<float*>(A.take((size_t)c.n_kv_heads * m.nchunks * RG * c.d_head * sizeof(float)));
+  m.part_ml = static_cast<float*>(A.take((size_t)c.n_kv_heads * m.nchunks * RG * 2 * sizeof(float)));
+  m.attn_counters = static_cast<unsigned int*>(A.take((size_t)c.n_kv_heads * sizeof(unsigned int)));
+  m.prompt = static_cast<int*>(A.take((size_t)c.max_len * sizeof(int)));
+}
+
+}  // namespace
+
+struct sd_ctx {
+  Model p, q;
+  sd_runtime_cfg rt{};
+  hipStream_t stream = nullptr;
+  bool own_stream = false;
+  SeqState* d_state = nullptr;
+  StepParams* d_params = nullptr;
+  float *p_logits = nullptr, *q_logits = nullptr;
+  RowStat* d_stats = nullptr;
+  unsigned int* d_counter = nullptr;
+  SeqState* h_state = nullptr;       // pinned
+  StepParams* h_params = nullptr;    // pinned
+  // host mirror of the sequence
+  int state = 0;                     // 0 EMPTY, 1 READY, 2 Mq cache stale (after baseline steps)
+  int len = 0, last_tok = -1;
+  int last_gamma = 0, last_kind = -1;   // for sd_debug_logits
+  hipGraphExec_t graphs[SD_MAX_GAMMA + 1] = {};
+  hipGraphExec_t graph_baseline = nullptr;
+  hipEvent_t ev[4] = {};
+  sd_stats stats{};
+  std::string err;
+};
+
+namespace {
+
+void plan_ctx(Arena& A, sd_ctx& c, const sd_model_cfg& pc, const sd_model_cfg& qc, const sd_runtime_cfg& rt) {
+  plan_model(A, c.p, pc, rt.page_size);
+  plan_model(A, c.q, qc, rt.page_size);
+  c.d_state = static_cast<SeqState*>(A.take(sizeof(SeqState)));
+  c.d_params = static_cast<StepParams*>(A.take(sizeof(StepParams)));
+  c.p_logits = static_cast<float*>(A.take((size_t)MAX_ROWS * pc.vocab * sizeof(float)));
+  c.q_logits = static_cast<float*>(A.take((size_t)SD_MAX_GAMMA * pc.vocab * sizeof(float)));
+  c.d_stats = static_cast<RowStat*>(A.take((2 * SD_MAX_GAMMA + 1) * sizeof(RowStat)));
+  c.d_counter = static_cast<unsigned int*>(A.take(256));
+}
+
+bool rt_ok(const sd_runtime_cfg& rt, std::string& why) {
+  if (rt.batch != 1) { why = "only batch 1 is supported"; return false; }
+  if (rt.max_gamma < 1 || rt.max_gamma > SD_MAX_GAMMA) { why = "max_gamma out of range"; return false; }
+  if (rt.page_size < 16 || (rt.page_size & (rt.page_size - 1))) { why = "page_size must be a power of two >= 16"; return false; }
+  return true;
+}
+
+sd_status fail(sd_ctx* c, sd_status s, const std::string& msg) {
+  if (c) c->err = msg; else g_load_error = msg;
+  return s;
+}
+
+#define HIP_TRY(ctx, expr)                                                              \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess)                                                               \
+      return fail(ctx, SD_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_));     \
+  } while (0)
+
+// ------------------------------------------------------------------ launches
+int pick_waves(int tiles, int ksteps) {
+  int S = 1;
+  while (S < 8 && tiles * S < 4096 && ksteps / (S * 2) >= 4) S *= 2;
+  return S;
+}
+
+template <typename T, int PRO, int EPI>
+void launch_gemm_t(hipStream_t s, GemmArgs a) {
+  const int tiles = a.N / 16, KS = a.K / 32;
+  const int S = pick_waves(tiles, KS);
+  a.ksteps_per_wave = (KS + S - 1) / S;
+  const int ND = (EPI == EPI_GATED) ? 2 : 1;
+  const size_t lds = (size_t)(S * ND * 256 + S * 16 + ND * 256) * sizeof(float);
+  hipLaunchKernelGGL((gemm_kernel<T, PRO, EPI>), dim3(tiles), dim3(64 * S), lds, s, a);
+}
+
+template <typename T>
+void launch_gemm(hipStream_t s, int pro, int epi, const GemmArgs& a) {
+#define SD_CASE(P, E) if (pro == P && epi == E) return launch_gemm_t<T, P, E>(s, a)
+  SD_CASE(PRO_LN, EPI_QKV); SD_CASE(PRO_RMS, EPI_QKV);
+  SD_CASE(PRO_NONE, EPI_RESID); SD_CASE(PRO_NONE, EPI_STORE); SD_CASE(PRO_RMS, EPI_STORE);
+  SD_CASE(PRO_LN, EPI_ACT); SD_CASE(PRO_RMS, EPI_GATED);
+  SD_CASE(PRO_LN, EPI_LOGITS); SD_CASE(PRO_RMS, EPI_LOGITS);
+#undef SD_CASE
+}
+
+template <typename T>
+void launch_attn(hipStream_t s, const Model& m, const AttnArgs& a) {
+  const int G = a.H / a.Hkv, RG = a.R * G, DH = m.cfg.d_head;
+  const int NG = ATTN_THREADS / DH;
+  const size_t lds = (size_t)(RG * DH + RG * ATTN_CHUNK + NG * RG * DH + RG * 2) * sizeof(float);
+  const dim3 grid(m.nchunks, a.Hkv), block(ATTN_THREADS);
+  if (DH == 32) hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, lds, s, a);
+  else if (DH == 64) hipLaunchKernelGGL((attn_kernel<T, 64>), grid, block, lds, s, a);
+  else hipLaunchKernelGGL((attn_kernel<T, 128>), grid, block, lds, s, a);
+}
+
+// One forward of model m over R rows chosen by (mode, step); optionally the
+// LM head on rows [row0, row0+nrows) into `logits` (fp32 [nrows][vocab]).
+template <typename T>
+void forward(sd_ctx* c, Model& m, int mode, int step, int R, int start, int row0, int nrows, float* logits) {
+  hipStream_t s = c->stream;
+  const sd_model_cfg& f = m.cfg;
+  const int d = f.d_model;
+  const int pro = (f.arch == SD_ARCH_GPT) ? PRO_LN : PRO_RMS;
+  hipLaunchKernelGGL((embed_kernel<T>), dim3(R), dim3(256), 0, s, mode, step, c->d_state, m.prompt, start,
+                     static_cast<const T*>(m.tok_emb), static_cast<const T*>(m.pos_emb), d, f.vocab, m.x,
+                     m.row_pos);
+  for (const LayerW& l : m.L) {
+    GemmArgs g{};
+    g.R = R; g.eps = f.norm_eps;
+    // q, k, v projections (+ rotary) with k, v appended to the cache
+    g.W = l.wqkv; g.X = m.x; g.gain = l.ln1g; g.beta = l.ln1b; g.bias = l.bqkv;
+    g.K = d; g.N = m.nq + 2 * m.nkv;
+    g.q_out = m.qbuf; g.nq = m.nq; g.nkv = m.nkv; g.kv_pool = l.kv; g.page_table = m.page_table;
+    g.page_size = m.page_size; g.n_kv_heads = f.n_kv_heads; g.d_head = f.d_head; g.row_pos = m.row_pos;
+    g.rope = m.rope;
+    launch_gemm<T>(s, pro, EPI_QKV, g);
+    AttnArgs a{};
+    a.q = m.qbuf; a.out = m.attn; a.kv_pool = l.kv; a.page_table = m.page_table; a.page_size = m.page_size;
+    a.row_pos = m.row_pos; a.R = R; a.H = f.n_heads; a.Hkv = f.n_kv_heads; a.cross = 0; a.kv_len = 0;
+    a.scale = (f.arch == SD_ARCH_T5DEC) ? 1.0f : 1.0f / sqrtf((float)f.d_head);
+    a.rel_bias = m.rel_bias; a.bucket_lut = m.bucket_lut; a.rel_buckets = f.rel_buckets;
+    a.part_o = m.part_o; a.part_ml = m.part_ml; a.counters = m.attn_counters;
+    launch_attn<T>(s, m, a);
+    GemmArgs o{};
+    o.R = R; o.W = l.wo; o.X = m.attn; o.bias = l.bo; o.K = m.nq; o.N = d; o.out = m.x; o.ldo = d;
+    launch_gemm<T>(s, PRO_NONE, EPI_RESID, o);
+    if (f.arch == SD_ARCH_T5DEC) {
+      GemmArgs cq{};
+      cq.R = R; cq.eps = f.norm_eps; cq.W = l.cq; cq.X = m.x; cq.gain = l.lncg; cq.K = d; cq.N = m.nq;
+      cq.out = m.qbuf; cq.ldo = m.nq;
+      launch_gemm<T>(s, PRO_RMS, EPI_STORE, cq);
+      AttnArgs ca = a;
+      ca.cross = 1; ca.ck = l.cross_k; ca.cv = l.cross_v; ca.kv_len = f.enc_len; ca.scale = 1.0f;
+      ca.rel_bias = nullptr;
+      launch_attn<T>(s, m, ca);
+      GemmArgs co = o;
+      co.W = l.co;
+      launch_gemm<T>(s, PRO_NONE, EPI_RESID, co);
+    }
+    GemmArgs h{};
+    h.R = R; h.eps = f.norm_eps; h.X = m.x; h.gain = l.ln2g; h.beta = l.ln2b; h.K = d; h.N = f.d_ff;
+    h.out = m.ffn; h.ldo = f.d_ff; h.W = l.w1;
+    if (f.arch == SD_ARCH_GPT) {
+      h.bias = l.b1;
+      launch_gemm<T>(s, PRO_LN, EPI_ACT, h);
+    } else {
+      h.W2 = l.wu; h.act = (f.arch == SD_ARCH_T5DEC) ? ACT_GELU : ACT_SILU;
+      launch_gemm<T>(s, PRO_RMS, EPI_GATED, h);
+    }
+    GemmArgs w2{};
+    w2.R = R; w2.W = l.w2; w2.X = m.ffn; w2.bias = l.b2; w2.K = f.d_ff; w2.N = d; w2.out = m.x; w2.ldo = d;
+    launch_gemm<T>(s, PRO_NONE, EPI_RESID, w2);
+  }
+  if (logits != nullptr) {
+    GemmArgs g{};
+    g.R = nrows; g.eps = f.norm_eps; g.W = m.head; g.X = m.x + (size_t)row0 * d; g.gain = m.lnfg; g.beta = m.lnfb;
+    g.K = d; g.N = f.vocab; g.out = logits; g.ldo = f.vocab; g.scale = f.logit_scale;
+    launch_gemm<T>(s, pro, EPI_LOGITS, g);
+  }
+}
+
+void forward_any(sd_ctx* c, Model& m, int mode, int step, int R, int start, int row0, int nrows, float* logits) {
+  if (m.cfg.dtype == SD_BF16) forward<bf16>(c, m, mode, step, R, start, row0, nrows, logits);
+  else forward<float>(c, m, mode, step, R, start, row0, nrows, logits);
+}
+
+// Cross-attention keys / values of every layer from the encoder output.
+template <typename T>
+void cross_kv(sd_ctx* c, Model& m, const void* enc) {
+  const sd_model_cfg& f = m.cfg;
+  for (const LayerW& l : m.L)
+    for (int which = 0; which < 2; ++which)
+      for (int r0 = 0; r0 < f.enc_len; r0 += MAX_ROWS) {
+        GemmArgs g{};
+        g.R = std::min(MAX_ROWS, f.enc_len - r0);
+        g.W = which ? l.cv : l.ck;
+        g.X = static_cast<const char*>(enc) + (size_t)r0 * f.d_model * m.esz;
+        g.K = f.d_model; g.N = m.nq;
+        g.out = static_cast<char*>(which ? l.cross_v : l.cross_k) + (size_t)r0 * m.nq * m.esz;
+        g.ldo = m.nq;
+        launch_gemm<T>(c->stream, PRO_NONE, EPI_STORE, g);
+      }
+}
+
+// The launch sequence of one run of Algorithm 1 (everything between the
+// upload of the step parameters and the download of the state).
+void enqueue_step(sd_ctx* c, int gamma, bool profile) {
+  hipStream_t s = c->stream;
+  const int V = c->p.cfg.vocab;
+  if (profile) hipEventRecord(c->ev[0], s);
+  for (int i = 0; i < gamma; ++i) {              // q_i <- Mq(prefix + x_<i), x_i ~ q_i
+    float* qrow = c->q_logits + (size_t)i * V;
+    if (i == 0) forward_any(c, c->q, ROWS_DRAFT_FIRST, 0, 2, 0, 1, 1, qrow);
+    else forward_any(c, c->q, ROWS_DRAFT_NEXT, i, 1, 0, 0, 1, qrow);
+    hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, s, qrow, V, c->d_params, i,
+                       c->d_state, 0, i);
+  }
+  if (profile) hipEventRecord(c->ev[1], s);
+  // p_1..p_{gamma+1} in one forward
+  forward_any(c, c->p, ROWS_VERIFY, 0, gamma + 1, 0, 0, gamma + 1, c->p_logits);
+  if (profile) hipEventRecord(c->ev[2], s);
+  hipLaunchKernelGGL(spec_verify_kernel, dim3(2 * gamma + 1, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
+                     c->q_logits, (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V,
+                     0.0f, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr, c->d_state);
+  if (profile) hipEventRecord(c->ev[3], s);
+}
+
+void enqueue_baseline(sd_ctx* c) {
+  const int V = c->p.cfg.vocab;
+  forward_any(c, c->p, ROWS_BASELINE, 0, 1, 0, 0, 1, c->p_logits);
+  hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
+                     c->d_params, 0, c->d_state, 1, 0);
+}
+
+// ------------------------------------------------------------------ loading
+struct TensorMap {
+  std::map<std::string, const sd_tensor*> m;
+  TensorMap(const sd_tensor* t, int n) { for (int i = 0; i < n; ++i) if (t[i].name) m[t[i].name] = &t[i]; }
+};
+
+template <typename T>
+sd_status put(hipStream_t s, const TensorMap& tm, const Model& m, const std::string& name, void* dst,
+              int64_t rows, int64_t cols, bool tiled, std::string& err) {
+  auto it = tm.m.find(name);
+  if (it == tm.m.end()) { err = "missing tensor " + name; return SD_EINVAL; }
+  const sd_tensor* t = it->second;
+  const bool shape_ok = (cols == 0) ? (t->ndim == 1 && t->shape[0] == rows)
+                                    : (t->ndim == 2 && t->shape[0] == rows && t->shape[1] == cols);
+  if (!shape_ok || t->dtype != m.cfg.dtype || t->dev == nullptr) { err = "bad shape / dtype / pointer: " + name; return SD_EINVAL; }
+  const size_t n = (size_t)rows * (cols ? cols : 1);
+  if (tiled) {
+    const size_t groups = n / 8;
+    hipLaunchKernelGGL((retile_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s,
+                       static_cast<const T*>(t->dev), static_cast<T*>(dst), (int)rows, (int)cols);
+  } else if (hipMemcpyAsync(dst, t->dev, n * sizeof(T), hipMemcpyDeviceToDevice, s) != hipSuccess) {
+    err = "copy failed: " + name; return SD_EHIP;
+  }
+  return SD_OK;
+}
+
+template <typename T>
+sd_status load_model(hipStream_t s, Model& m, const sd_tensor* w, int n, std::string& err) {
+  const TensorMap tm(w, n);
+  const sd_model_cfg& f = m.cfg;
+  const int64_t d = f.d_model, ff = f.d_ff, V = f.vocab;
+  sd_status st;
+#define PUT(name, dst, r, cc, tiled) \
+  if ((st = put<T>(s, tm, m, name, dst, r, cc, tiled, err)) != SD_OK) return st
+  PUT("tok_emb", m.tok_emb, V, d, false);
+  PUT("head", m.head, V, d, true);
+  PUT("lnf.g", m.lnfg, d, 0, false);
+  if (f.arch == SD_ARCH_GPT) { PUT("lnf.b", m.lnfb, d, 0, false); PUT("pos_emb", m.pos_emb, f.max_len, d, false); }
+  if (f.arch == SD_ARCH_T5DEC) PUT("rel_bias", m.rel_bias, f.n_heads, f.rel_buckets, false);
+  for (int i = 0; i < f.n_layers; ++i) {
+    LayerW& l = m.L[i];
+    const std::string p = "l" + std::to_string(i) + ".";
+    char* qkv = static_cast<char*>(l.wqkv);
+    PUT(p + "ln1.g", l.ln1g, d, 0, false);
+    PUT(p + "ln2.g", l.ln2g, d, 0, false);
+    PUT(p + "wq", qkv, m.nq, d, true);
+    PUT(p + "wk", qkv + (size_t)m.nq * d * m.esz, m.nkv, d, true);
+    PUT(p + "wv", qkv + (size_t)(m.nq + m.nkv) * d * m.esz, m.nkv, d, true);
+    PUT(p + "wo", l.wo, d, m.nq, true);
+    PUT(p + "w2", l.w2, d, ff, true);
+    if (f.arch == SD_ARCH_GPT) {
+      char* b = static_cast<char*>(l.bqkv);
+      PUT(p + "ln1.b", l.ln1b, d, 0, false);
+      PUT(p + "ln2.b", l.ln2b, d, 0, false);
+      PUT(p + "bq", b, m.nq, 0, false);
+      PUT(p + "bk", b + (size_t)m.nq * m.esz, m.nkv, 0, false);
+      PUT(p + "bv", b + (size_t)(m.nq + m.nkv) * m.esz, m.nkv, 0, false);
+      PUT(p + "bo", l.bo, d, 0, false);
+      PUT(p + "w1", l.w1, ff, d, true);
+      PUT(p + "b1", l.b1, ff, 0, false);
+      PUT(p + "b2", l.b2, d, 0, false);
+    } else {
+      PUT(p + "wg", l.w1, ff, d, true);
+      PUT(p + "wu", l.wu, ff, d, true);
+    }
+    if (f.arch == SD_ARCH_T5DEC) {
+      PUT(p + "lnc.g", l.lncg, d, 0, false);
+      PUT(p + "cq", l.cq, m.nq, d, true);
+      PUT(p + "ck", l.ck, m.nq, d, true);
+      PUT(p + "cv", l.cv, m.nq, d, true);
+      PUT(p + "co", l.co, d, m.nq, true);
+    }
+  }
+#undef PUT
+  // host-built tables
+  std::vector<int> pt(m.n_pages);
+  for (int i = 0; i < m.n_pages; ++i) pt[i] = i;
+  if (hipMemcpy(m.page_table, pt.data(), pt.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess) { err = "page table upload"; return SD_EHIP; }
+  if (f.arch == SD_ARCH_T5DEC) {
+    // causal distance -> bucket: one distance per bucket in the first half,
+    // logarithmic spacing up to rel_max_dist in the second, then saturation
+    std::vector<int> lut(f.max_len);
+    const int half = f.rel_buckets / 2;
+    for (int rel = 0; rel < f.max_len; ++rel) {
+      int b = rel;
+      if (rel >= half) {
+        b = half + (int)std::floor(std::log((double)rel / half) / std::log((double)f.rel_max_dist / half) *
+                                   (f.rel_buckets - half));
+        if (b > f.rel_buckets - 1) b = f.rel_buckets - 1;
+      }
+      lut[rel] = b;
+    }
+    if (hipMemcpy(m.bucket_lut, lut.data(), lut.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess) { err = "bucket table upload"; return SD_EHIP; }
+  }
+  if (f.arch == SD_ARCH_GQA) {
+    std::vector<float> cs((size_t)f.max_len * f.d_head);
+    for (int pos = 0; pos < f.max_len; ++pos)
+      for (int i = 0; i < f.d_head / 2; ++i) {
+        const double ang = (double)pos * std::pow((double)f.rope_theta, -2.0 * i / f.d_head);
+        cs[((size_t)pos * (f.d_head / 2) + i) * 2] = (float)std::cos(ang);
+        cs[((size_t)pos * (f.d_head / 2) + i) * 2 + 1] = (float)std::sin(ang);
+      }
+    if (hipMemcpy(m.rope, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) { err = "rope table upload"; return SD_EHIP; }
+  }
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, s, m.attn_counters, 0u, (size_t)f.n_kv_heads);
+  return SD_OK;
+}
+
+sd_status sync_state_to_host(sd_ctx* c) {
+  HIP_TRY(c, hipMemcpyAsync(c->h_state, c->d_state, sizeof(SeqState), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return SD_OK;
+}
+
+}  // namespace
+
+// ====================================================================== C ABI
+extern "C" size_t sd_workspace_bytes(const sd_model_cfg* p_cfg, const sd_model_cfg* q_cfg,
+                                     const sd_runtime_cfg* rt) {
+  std::string why;
+  if (!p_cfg || !q_cfg || !rt || !cfg_ok(*p_cfg, why) || !cfg_ok(*q_cfg, why) || !rt_ok(*rt, why)) return 0;
+  if (p_cfg->vocab != q_cfg->vocab) return 0;
+  sd_ctx tmp;
+  Arena A(nullptr);
+  plan_ctx(A, tmp, *p_cfg, *q_cfg, *rt);
+  return align_up(A.off);
+}
+
+extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, const sd_tensor* p_w, int32_t n_p,
+                                    const sd_model_cfg* q_cfg, const sd_tensor* q_w, int32_t n_q,
+                                    const sd_runtime_cfg* rt) {
+  if (!out || !p_cfg || !q_cfg || !rt || !p_w || !q_w || n_p < 1 || n_q < 1) return fail(nullptr, SD_EINVAL, "null argument");
+  *out = nullptr;
+  std::string why;
+  if (!cfg_ok(*p_cfg, why)) return fail(nullptr, SD_EINVAL, "Mp config: " + why);
+  if (!cfg_ok(*q_cfg, why)) return fail(nullptr, SD_EINVAL, "Mq config: " + why);
+  if (!rt_ok(*rt, why)) return fail(nullptr, SD_EINVAL, "runtime config: " + why);
+  if (p_cfg->vocab != q_cfg->vocab) return fail(nullptr, SD_EINVAL, "Mp and Mq must share the vocabulary");
+  if (!rt->workspace || (reinterpret_cast<uintptr_t>(rt->workspace) & 255)) return fail(nullptr, SD_EINVAL, "workspace must be 256-byte aligned");
+  const size_t need = sd_workspace_bytes(p_cfg, q_cfg, rt);
+  if (rt->workspace_bytes < need) return fail(nullptr, SD_ENOMEM, "workspace too small: need " + std::to_string(need));
+  sd_ctx* c = new (std::nothrow) sd_ctx();
+  if (!c) return fail(nullptr, SD_ENOMEM, "host allocation failed");
+  c->rt = *rt;
+  Arena A(rt->workspace);
+  plan_ctx(A, *c, *p_cfg, *q_cfg, *rt);
+  auto bail = [&](sd_status s, const std::string& m) { sd_free(c); return fail(nullptr, s, m); };
+  if (rt->stream) c->stream = static_cast<hipStream_t>(rt->stream);
+  else {
+    if (hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking) != hipSuccess) return bail(SD_EHIP, "stream creation failed");
+    c->own_stream = true;
+  }
+  if (hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(SeqState), hipHostMallocDefault) != hipSuccess ||
+      hipHostMalloc(reinterpret_cast<void**>(&c->h_params), sizeof(StepParams), hipHostMallocDefault) != hipSuccess)
+    return bail(SD_EHIP, "pinned allocation failed");
+  for (auto& e : c->ev) if (hipEventCreate(&e) != hipSuccess) return bail(SD_EHIP, "event creation failed");
+  std::string err;
+  sd_status st = (p_cfg->dtype == SD_BF16) ? load_model<bf16>(c->stream, c->p, p_w, n_p, err)
+                                           : load_model<float>(c->stream, c->p, p_w, n_p, err);
+  if (st != SD_OK) return bail(st, "Mp: " + err);
+  st = (q_cfg->dtype == SD_BF16) ? load_model<bf16>(c->stream, c->q, q_w, n_q, err)
+                                 : load_model<float>(c->stream, c->q, q_w, n_q, err);
+  if (st != SD_OK) return bail(st, "Mq: " + err);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, c->d_counter, 0u, (size_t)64);
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) return bail(SD_EHIP, std::string("load: ") + hipGetErrorString(e));
+  *out = c;
+  return SD_OK;
+}
+
+extern "C" void sd_free(sd_ctx* c) {
+  if (!c) return;
+  if (c->stream) hipStreamSynchronize(c->stream);
+  for (auto& g : c->graphs) if (g) hipGraphExecDestroy(g);
+  if (c->graph_baseline) hipGraphExecDestroy(c->graph_baseline);
+  for (auto& e : c->ev) if (e) hipEventDestroy(e);
+  if (c->h_state) hipHostFree(c->h_state);
+  if (c->h_params) hipHostFree(c->h_params);
+  if (c->own_stream && c->stream) hipStreamDestroy(c->stream);
+  delete c;
+}
+
+extern "C" const char* sd_last_error(const sd_ctx* c) { return c ? c->err.c_str() : g_load_error.c_str(); }
+
+extern "C" sd_status sd_reset(sd_ctx* c, int32_t row) {
+  if (!c) return SD_EINVAL;
+  if (row != 0 && row != -1) return fail(c, SD_EINVAL, "row must be 0 or -1");
+  c->state = 0; c->len = 0; c->last_tok = -1;
+  c->stats = sd_stats{};
+  return SD_OK;
+}
+
+extern "C" sd_status sd_prefill(sd_ctx* c, int32_t row, const int32_t* prompt, int32_t n,
+                                const void* enc_p, const void* enc_q) {
+  if (!c) return SD_EINVAL;
+  if (row != 0 || !prompt || n < 1) return fail(c, SD_EINVAL, "row must be 0, prompt non-empty");
+  const sd_model_cfg &pc = c->p.cfg, &qc = c->q.cfg;
+  if ((pc.arch == SD_ARCH_T5DEC) != (enc_p != nullptr) || (qc.arch == SD_ARCH_T5DEC) != (enc_q != nullptr))
+    return fail(c, SD_EINVAL, "encoder output must be given exactly for T5DEC models");
+  const int room = std::min(pc.max_len, qc.max_len);
+  if (n + c->rt.max_gamma + 1 > room) return fail(c, SD_ERANGE, "prompt + max_gamma + 1 exceeds max_len");
+  for (int i = 0; i < n; ++i) if (prompt[i] < 0 || prompt[i] >= pc.vocab) return fail(c, SD_ERANGE, "token id out of range");
+  c->state = 0;
+  Model* ms[2] = {&c->p, &c->q};
+  const void* encs[2] = {enc_p, enc_q};
+  for (int k = 0; k < 2; ++k) {
+    Model& m = *ms[k];
+    HIP_TRY(c, hipMemcpyAsync(m.prompt, prompt, (size_t)n * sizeof(int), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (m.cfg.arch == SD_ARCH_T5DEC) {
+      if (m.cfg.dtype == SD_BF16) cross_kv<bf16>(c, m, encs[k]); else cross_kv<float>(c, m, encs[k]);
+    }
+    for (int s0 = 0; s0 < n - 1; s0 += MAX_ROWS)
+      forward_any(c, m, ROWS_PREFILL, 0, std::min(MAX_ROWS, n - 1 - s0), s0, 0, 0, nullptr);
+  }
+  SeqState st{};
+  st.len = n; st.last_tok = prompt[n - 1]; st.prev_tok = (n >= 2) ? prompt[n - 2] : 0;
+  for (int i = 0; i < 16; ++i) { st.x[i] = 0; st.out[i] = -1; }
+  *c->h_state = st;
+  HIP_TRY(c, hipMemcpyAsync(c->d_state, c->h_state, sizeof(SeqState), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipGetLastError());
+  c->state = 1; c->len = n; c->last_tok = prompt[n - 1];
+  return SD_OK;
+}
+
+static sd_status check_uniforms(sd_ctx* c, float temperature, const float* u, int n) {
+  if (!(temperature >= 0.0f) || !std::isfinite(temperature)) return fail(c, SD_EINVAL, "temperature must be finite and >= 0");
+  if (temperature > 0.0f && !u) return fail(c, SD_EINVAL, "uniforms required when temperature > 0");
+  if (u) for (int i = 0; i < n; ++i) if (!(u[i] > 0.0f && u[i] < 1.0f)) return fail(c, SD_ERANGE, "uniform outside (0,1)");
+  return SD_OK;
+}
+
+extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_len, int32_t gamma,
+                             float temperature, const float* uniforms, int32_t* out_tokens, int32_t* out_n) {
+  if (!c) return SD_EINVAL;
+  if (!out_tokens || !out_n) return fail(c, SD_EINVAL, "null output");
+  if (gamma < 1 || gamma > c->rt.max_gamma) return fail(c, SD_EINVAL, "gamma out of range");
+  if (c->state == 0) return fail(c, SD_ESTATE, "sd_step before sd_prefill");
+  if (c->state == 2) return fail(c, SD_ESTATE, "Mq cache is stale after sd_step_baseline: reset and prefill");
+  if (prefix && (prefix_len != c->len || prefix[prefix_len - 1] != c->last_tok))
+    return fail(c, SD_ESTATE, "prefix does not match the committed sequence");
+  sd_status st = check_uniforms(c, temperature, uniforms, 2 * gamma + 1);
+  if (st != SD_OK) return st;
+  if (c->len + gamma + 1 > std::min(c->p.cfg.max_len, c->q.cfg.max_len)) return fail(c, SD_ERANGE, "sequence would exceed max_len");
+
+  c->h_params->temperature = temperature;
+  for (int i = 0; i < 2 * gamma + 1; ++i) c->h_params->uniforms[i] = uniforms ? uniforms[i] : 0.5f;
+  const bool profile = (c->rt.flags & SD_FLAG_PROFILE) != 0;
+  const bool graph = (c->rt.flags & SD_FLAG_GRAPH) != 0 && !profile;
+  if (graph) {
+    if (!c->graphs[gamma]) {
+      hipGraph_t g = nullptr;
+      HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+      hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream);
+      enqueue_step(c, gamma, false);
+      hipMemcpyAsync(c->h_state, c->d_state, sizeof(SeqState), hipMemcpyDeviceToHost, c->stream);
+      HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
+      hipError_t e = hipGraphInstantiate(&c->graphs[gamma], g, nullptr, nullptr, 0);
+      hipGraphDestroy(g);
+      if (e != hipSuccess) { c->graphs[gamma] = nullptr; return fail(c, SD_EHIP, std::string("graph instantiate: ") + hipGetErrorString(e)); }
+    }
+    HIP_TRY(c, hipGraphLaunch(c->graphs[gamma], c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  } else {
+    HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream));
+    enqueue_step(c, gamma, profile);
+    if ((st = sync_state_to_host(c)) != SD_OK) return st;
+  }
+  HIP_TRY(c, hipGetLastError());
+  const SeqState& hs = *c->h_state;
+  if (hs.n < 0 || hs.n > gamma || hs.len != c->len + hs.n + 1) return fail(c, SD_EHIP, "device state inconsistent after step");
+  *out_n = hs.n;
+  for (int i = 0; i <= gamma; ++i) out_tokens[i] = (i <= hs.n) ? hs.out[i] : -1;
+  c->len = hs.len; c->last_tok = hs.last_tok;
+  c->last_gamma = gamma; c->last_kind = 0;
+  c->stats.steps += 1; c->stats.tokens += hs.n + 1; c->stats.accepted += hs.n; c->stats.fallbacks = hs.fallbacks;
+  if (profile) {
+    float a = 0, b = 0, d = 0;
+    hipEventElapsedTime(&a, c->ev[0], c->ev[1]); hipEventElapsedTime(&b, c->ev[1], c->ev[2]);
+    hipEventElapsedTime(&d, c->ev[2], c->ev[3]);
+    c->stats.draft_ms = a; c->stats.verify_ms = b; c->stats.accept_ms = d;
+  }
+  return SD_OK;
+}
+
+extern "C" sd_status sd_step_baseline(sd_ctx* c, float temperature, const float* uniforms, int32_t* out_token) {
+  if (!c) return SD_EINVAL;
+  if (!out_token) return fail(c, SD_EINVAL, "null output");
+  if (c->state == 0) return fail(c, SD_ESTATE, "sd_step_baseline before sd_prefill");
+  sd_status st = check_uniforms(c, temperature, uniforms, 1);
+  if (st != SD_OK) return st;
+  if (c->len + 1 > c->p.cfg.max_len) return fail(c, SD_ERANGE, "sequence would exceed max_len");
+  c->h_params->temperature = temperature;
+  c->h_params->uniforms[0] = uniforms ? uniforms[0] : 0.5f;
+  if ((c->rt.flags & SD_FLAG_GRAPH) != 0) {
+    if (!c->graph_baseline) {
+      hipGraph_t g = nullptr;
+      HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+      hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream);
+      enqueue_baseline(c);
+      hipMemcpyAsync(c->h_state, c->d_state, sizeof(SeqState), hipMemcpyDeviceToHost, c->stream);
+      HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
+      hipError_t e = hipGraphInstantiate(&c->graph_baseline, g, nullptr, nullptr, 0);
+      hipGraphDestroy(g);
+      if (e != hipSuccess) { c->graph_baseline = nullptr; return fail(c, SD_EHIP, std::string("graph instantiate: ") + hipGetErrorString(e)); }
+    }
+    HIP_TRY(c, hipGraphLaunch(c->graph_baseline, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  } else {
+    HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream));
+    enqueue_baseline(c);
+    if ((st = sync_state_to_host(c)) != SD_OK) return st;
+  }
+  HIP_TRY(c, hipGetLastError());
+  const SeqState& hs = *c->h_state;
+  if (hs.len != c->len + 1) return fail(c, SD_EHIP, "device state inconsistent after baseline step");
+  *out_token = hs.last_tok;
+  c->len = hs.len; c->last_tok = hs.last_tok; c->state = 2;
+  c->last_kind = 2;
+  return SD_OK;
+}
+
+extern "C" sd_status sd_debug_logits(sd_ctx* c, int32_t which, float* host_out, size_t n) {
+  if (!c || !host_out) return SD_EINVAL;
+  const size_t V = c->p.cfg.vocab;
+  const float* src = nullptr;
+  size_t rows = 0;
+  if (which == 0 && c->last_kind == 0) { src = c->p_logits; rows = c->last_gamma + 1; }
+  else if (which == 1 && c->last_kind == 0) { src = c->q_logits; rows = c->last_gamma; }
+  else if (which == 2 && c->last_kind == 2) { src = c->p_logits; rows = 1; }
+  else return fail(c, SD_ESTATE, "no such logits from the last call");
+  if (n > rows * V) return fail(c, SD_EINVAL, "more floats requested than the last call produced");
+  HIP_TRY(c, hipMemcpy(host_out, src, n * sizeof(float), hipMemcpyDeviceToHost));
+  return SD_OK;
+}
+
+extern "C" sd_status sd_get_stats(sd_ctx* c, sd_stats* out) {
+  if (!c || !out) return SD_EINVAL;
+  *out = c->stats;
+  return SD_OK;
+}
+
+#include "spec_sample_api.hip"

@@ -1,0 +1,35 @@
+// C-ABI entry points of the stand-alone accept / resample kernel (the second
+// half of Algorithm 1 on explicit logits).  See include/sd.h.
+#include <hip/hip_runtime.h>
+#include "../../include/sd.h"
+#include "kernels_sample.h"
+
+namespace {
+size_t scratch_align(size_t v, size_t a) { return (v + a - 1) / a * a; }
+}
+
+extern "C" size_t sd_spec_sample_scratch_bytes(int32_t rows, int32_t gamma) {
+  if (rows < 1 || gamma < 1 || gamma > SD_MAX_GAMMA) return 0;
+  return scratch_align((size_t)rows * sizeof(unsigned int), 256) +
+         (size_t)rows * (2 * gamma + 1) * sizeof(sd::RowStat);
+}
+
+extern "C" sd_status sd_spec_sample(const float* p_logits, const float* q_logits, const int32_t* x,
+                                    const float* r, const float* s, int32_t rows, int32_t gamma,
+                                    int32_t vocab, float temperature, int32_t* out_n,
+                                    int32_t* out_t, void* scratch, void* stream) {
+  if (!p_logits || !q_logits || !x || !out_n || !out_t || !scratch) return SD_EINVAL;
+  if (rows < 1 || rows > 65535 || gamma < 1 || gamma > SD_MAX_GAMMA || vocab < 1 ||
+      vocab > sd::SAMPLE_CHUNK * sd::SAMPLE_MAX_CHUNKS) return SD_EINVAL;
+  if (!(temperature >= 0.0f)) return SD_EINVAL;
+  if (temperature > 0.0f && (!r || !s)) return SD_EINVAL;
+  unsigned int* counters = static_cast<unsigned int*>(scratch);
+  sd::RowStat* stats = reinterpret_cast<sd::RowStat*>(
+      static_cast<char*>(scratch) + scratch_align((size_t)rows * sizeof(unsigned int), 256));
+  dim3 grid(2 * gamma + 1, rows);
+  hipLaunchKernelGGL(sd::spec_verify_kernel, grid, dim3(sd::SAMPLE_THREADS), 0,
+                     static_cast<hipStream_t>(stream), p_logits, q_logits, x, r, s, gamma, vocab,
+                     temperature, (const sd::StepParams*)nullptr, stats, counters, out_n, out_t,
+                     (sd::SeqState*)nullptr);
+  return hipGetLastError() == hipSuccess ? SD_OK : SD_EHIP;
+}

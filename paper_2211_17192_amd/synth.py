@@ -185,3 +185,21 @@ def to_numpy_weights(w: dict) -> dict:
         else:
             out[k] = t.numpy()
     return out
+
+
+def sampler_case(rows: int, gamma: int, vocab: int, sigma: float, seed: int):
+    """Inputs of the isolated accept / resample kernel: target logits
+    N(0, 3^2) [rows, gamma+1, V]; draft logits = target logits of the first gamma
+    positions + N(0, sigma^2); guesses x_i drawn from softmax(draft logits) with
+    numpy's categorical sampler; uniforms r [rows, gamma], s [rows].  numpy arrays."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    zp = (3.0 * g.standard_normal((rows, gamma + 1, vocab), dtype=np.float32)).astype(np.float32)
+    zq = (zp[:, :gamma] + sigma * g.standard_normal((rows, gamma, vocab), dtype=np.float32)).astype(np.float32)
+    x = np.zeros((rows, gamma), dtype=np.int32)
+    for b in range(rows):
+        for i in range(gamma):
+            z = zq[b, i].astype(np.float64)
+            q = np.exp(z - z.max())
+            x[b, i] = g.choice(vocab, p=q / q.sum())
+    u = uniform_stream(seed + 7919, rows * (gamma + 1)).reshape(rows, gamma + 1)
+    return zp, zq, x, np.ascontiguousarray(u[:, :gamma]), np.ascontiguousarray(u[:, gamma])

@@ -1,0 +1,230 @@
+"""GPU parity of the whole iteration (draft loop, verify forward, accept /
+resample, roll-back) against the CPU oracle, through the C ABI.
+
+Two levels, because sampling turns small logit differences into different
+tokens:
+  level M  same weights, same prefix, same guesses -> GPU logits vs oracle
+           logits, max |diff| / max |oracle| per row <= 1e-4 (fp32), 2e-2 (bf16);
+  level S  the oracle's Algorithm-1 arithmetic applied to the GPU's own logits
+           with the same uniforms must give the GPU's n and tokens, except
+           acceptance decisions with |r - p/q| < 1e-3 and draws whose uniform is
+           within 1e-5 (CDF units) of an edge of the chosen token's interval.
+For the fp32 pair the GPU token sequence is additionally compared with the
+independent oracle run end to end.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decode, sampling, transformer as T
+from paper_2211_17192_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def oracle_models(cfg_p, w_p, cfg_q, w_q, enc_p=None, enc_q=None):
+    mp = T.Transformer(T.ModelConfig(**cfg_p), synth.to_numpy_weights(w_p))
+    mq = T.Transformer(T.ModelConfig(**cfg_q), synth.to_numpy_weights(w_q))
+    if enc_p is not None:
+        mp.set_encoder_output(synth.to_numpy_weights({"e": enc_p})["e"])
+        mq.set_encoder_output(synth.to_numpy_weights({"e": enc_q})["e"])
+    return T.CachedScorer(mp), T.CachedScorer(mq)
+
+
+def rel_err(got, ref):
+    return float(np.max(np.abs(got - ref), axis=-1).max() / np.abs(ref).max())
+
+
+def level_s(zp, zq, u, gamma, temperature):
+    """Oracle sampling arithmetic on the GPU's logits -> (x, n, t, infos)."""
+    d, r, s = u[:gamma], u[gamma:2 * gamma], u[2 * gamma]
+    q_rows = [sampling.standardise(z, temperature) for z in zq]
+    x = [sampling.icdf(q_rows[i], d[i]) for i in range(gamma)]
+    p_rows = np.stack([sampling.standardise(z, temperature) for z in zp])
+    n, t, info = sampling.accept_and_resample(p_rows, np.stack(q_rows), x, r, s)
+    return x, n, t, info, p_rows, q_rows
+
+
+def run_pair(dec, sp, sq, prompt, n_new, gamma, temperature, useed, dtype, end_to_end):
+    """Decode n_new tokens on the GPU, checking every iteration.  Returns
+    (gpu tokens, counts of tolerated events, worst logit errors, mean accepted)."""
+    prefix = [int(t) for t in prompt]
+    target = len(prefix) + n_new
+    urows = synth.uniform_stream(useed, 400 * (2 * gamma + 1)).reshape(400, -1)
+    tolerated = {"accept": 0, "draw": 0, "e2e": 0}
+    worst = {"p": 0.0, "q": 0.0}
+    acc = []
+    it = 0
+    while len(prefix) < target:
+        u = urows[it]; it += 1
+        n_g, toks_g = dec.step(gamma, temperature, u, prefix=prefix)
+        zp = dec.logits(0, gamma + 1).astype(np.float64)
+        zq = dec.logits(1, gamma).astype(np.float64)
+        assert np.isfinite(zp).all() and np.isfinite(zq).all()
+        # ---- level S
+        x_s, n_s, t_s, info, p_rows, q_rows = level_s(zp, zq, u, gamma, temperature)
+        expect = x_s[:n_s] + [t_s]
+        if (n_g, toks_g) != (n_s, expect):
+            if temperature == 0:
+                raise AssertionError(f"argmax decoding must agree exactly: {n_g, toks_g} vs {n_s, expect}")
+            k = min(n_g, n_s)
+            if toks_g[:k] != x_s[:k]:               # a draft draw flipped: must be an edge case
+                j = next(i for i in range(k) if toks_g[i] != x_s[i])
+                assert sampling.icdf_edge_distance(q_rows[j], u[j], toks_g[j]) < 1e-5
+                tolerated["draw"] += 1
+            elif n_g != n_s:
+                assert info["margins"][k] < 1e-3, (it, n_g, n_s, info["margins"])
+                tolerated["accept"] += 1
+            else:
+                w = p_rows[n_s] if n_s == gamma else sampling.adjusted_distribution(p_rows[n_s], q_rows[n_s])
+                assert sampling.icdf_edge_distance(w, u[2 * gamma], toks_g[-1]) < 1e-5
+                tolerated["draw"] += 1
+        # ---- level M: oracle logits for the same prefix and the same guesses
+        zq_o = np.stack([sq.score(prefix + x_s[:i], 1)[0] for i in range(gamma)])
+        zp_o = sp.score(prefix + x_s, gamma + 1)
+        worst["q"] = max(worst["q"], rel_err(zq, zq_o))
+        worst["p"] = max(worst["p"], rel_err(zp, zp_o))
+        assert worst["q"] <= TOL[dtype] and worst["p"] <= TOL[dtype], (it, worst)
+        # ---- end to end against the independent oracle (fp32 only)
+        if end_to_end:
+            new_o, n_o, info_o = decode.speculative_decoding_step(sp, sq, prefix, gamma, temperature, u)
+            if new_o[len(prefix):] != toks_g:
+                assert temperature > 0
+                tolerated["e2e"] += 1
+        acc.append(n_g)
+        prefix = prefix + toks_g
+    return prefix[:target], tolerated, worst, float(np.mean(acc))
+
+
+def make_decoder(cfg_p, w_p, cfg_q, w_q, **kw):
+    from paper_2211_17192_amd import binding
+    dev = {k: v.cuda() for k, v in w_p.items()}, {k: v.cuda() for k, v in w_q.items()}
+    return binding.SpecDecoder(cfg_p, dev[0], cfg_q, dev[1], **kw)
+
+
+# ----------------------------------------------------------------------------
+# the tiny fp32 pair: 16-token prompt, 64 new tokens, gamma = 4
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("temperature", [1.0, 0.0])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_tiny_fp32_pair_matches_oracle(temperature, flags):
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    sp, sq = oracle_models(cfg_p, w_p, cfg_q, w_q)
+    prompt = synth.random_tokens(1, 16, cfg_p["vocab"])
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=4, flags=flags)
+    dec.prefill(prompt)
+    toks, tol, worst, mean_n = run_pair(dec, sp, sq, prompt, 64, 4, temperature, 2, "f32", True)
+    assert tol["accept"] + tol["draw"] + tol["e2e"] <= 1, tol
+    assert worst["p"] < 1e-4 and worst["q"] < 1e-4
+    assert 0.0 < mean_n < 4.0                       # guesses are sometimes kept, sometimes not
+    # independent oracle run end to end (same uniforms): identical tokens
+    urows = synth.uniform_stream(2, 400 * 9).reshape(400, -1)
+    ref, _ = decode.speculative_decode(*oracle_models(cfg_p, w_p, cfg_q, w_q), prompt, 64, 4, temperature, urows)
+    if tol["accept"] + tol["draw"] + tol["e2e"] == 0:
+        assert toks == ref
+    if temperature == 0:
+        greedy = decode.plain_decode(oracle_models(cfg_p, w_p, cfg_q, w_q)[0], prompt, 64, 0.0, [0.5] * 64)
+        assert toks == greedy
+    dec.close()
+
+
+def small_pair(arch, dtype, seed=3):
+    kw = dict(dtype=dtype, logit_scale=4.0)
+    if arch == T.GPT:
+        cfg = synth.model_cfg(T.GPT, 3, 64, 2, 128, 512, 160, **kw)
+    elif arch == T.T5DEC:
+        cfg = synth.model_cfg(T.T5DEC, 3, 64, 2, 96, 512, 160, enc_len=40, norm_eps=1e-6, **kw)
+    else:
+        cfg = synth.model_cfg(T.GQA, 3, 128, 4, 160, 512, 160, d_head=32, n_kv_heads=2, **kw)
+    w = synth.random_weights(cfg, seed, w_std=0.1)
+    cfg_q, w_q = synth.truncated_noisy_copy(cfg, w, 1, seed + 50, 0.02)
+    enc_p = enc_q = None
+    if arch == T.T5DEC:
+        enc_p = synth.counter_normal((cfg["enc_len"], cfg["d_model"]), 91, 1.0).to(w["head"].dtype)
+        enc_q = enc_p.clone()
+    return cfg, w, cfg_q, w_q, enc_p, enc_q
+
+
+@pytest.mark.parametrize("arch", [T.GPT, T.T5DEC, T.GQA])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_pairs_all_block_types(arch, dtype):
+    """Every block type in both storage types; the 70-token prompt spans two
+    attention chunks with a ragged tail, gamma = 5, graph replay on."""
+    cfg_p, w_p, cfg_q, w_q, enc_p, enc_q = small_pair(arch, dtype)
+    sp, sq = oracle_models(cfg_p, w_p, cfg_q, w_q, enc_p, enc_q)
+    prompt = synth.random_tokens(21, 70, cfg_p["vocab"])
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=7, flags=1)
+    dec.prefill(prompt, None if enc_p is None else enc_p.cuda(), None if enc_q is None else enc_q.cuda())
+    for temperature, gamma, useed in ((1.0, 5, 4), (0.0, 3, 5), (0.7, 7, 6)):
+        dec.reset()
+        dec.prefill(prompt, None if enc_p is None else enc_p.cuda(), None if enc_q is None else enc_q.cuda())
+        toks, tol, worst, mean_n = run_pair(dec, sp, sq, prompt, 24, gamma, temperature, useed, dtype, dtype == "f32")
+        assert tol["accept"] + tol["draw"] <= 1, tol
+    dec.close()
+
+
+def test_one_token_prefix_and_baseline_identity():
+    """Decoder that starts from a single start token (the encoder-decoder case):
+    the first draft step has a padding row.  Also: argmax speculative decoding
+    == the library's own plain argmax decoding, token for token."""
+    cfg_p, w_p, cfg_q, w_q, enc_p, enc_q = small_pair(T.T5DEC, "bf16")
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=7, flags=1)
+    sp, sq = oracle_models(cfg_p, w_p, cfg_q, w_q, enc_p, enc_q)
+    dec.prefill([0], enc_p.cuda(), enc_q.cuda())
+    toks, tol, worst, _ = run_pair(dec, sp, sq, [0], 20, 4, 1.0, 8, "bf16", False)
+    assert tol["accept"] + tol["draw"] <= 1
+    for gamma in (1, 3, 7):
+        dec.reset(); dec.prefill([0], enc_p.cuda(), enc_q.cuda())
+        spec = [0]
+        while len(spec) < 41:
+            n, t = dec.step(gamma, 0.0, None, prefix=spec)
+            spec += t
+        dec.reset(); dec.prefill([0], enc_p.cuda(), enc_q.cuda())
+        plain = [0] + [dec.step_baseline(0.0) for _ in range(40)]
+        assert spec[:41] == plain
+    dec.close()
+
+
+def test_error_paths():
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=4)
+    u = synth.uniform_stream(1, 9)
+    with pytest.raises(binding.SdError) as e:
+        dec.step(4, 1.0, u)
+    assert e.value.status == binding.SD_ESTATE                      # step before prefill
+    prompt = list(synth.random_tokens(1, 16, 256))
+    dec.prefill(prompt)
+    for bad, status in (((5, 1.0, synth.uniform_stream(1, 11)), binding.SD_EINVAL),   # gamma > max_gamma
+                        ((4, -1.0, u), binding.SD_EINVAL)):
+        with pytest.raises(binding.SdError) as e:
+            dec.step(*bad)
+        assert e.value.status == status
+    ub = u.copy(); ub[3] = 1.0
+    with pytest.raises(binding.SdError) as e:
+        dec.step(4, 1.0, ub)
+    assert e.value.status == binding.SD_ERANGE
+    with pytest.raises(binding.SdError) as e:
+        dec.step(4, 1.0, u, prefix=prompt[:-1] + [(prompt[-1] + 1) % 256])
+    assert e.value.status == binding.SD_ESTATE                      # prefix mismatch
+    n, t = dec.step(4, 1.0, u, prefix=prompt)                       # failed calls left the state intact
+    assert len(t) == n + 1
+    dec.step_baseline(1.0, 0.3)
+    with pytest.raises(binding.SdError) as e:
+        dec.step(4, 1.0, u)
+    assert e.value.status == binding.SD_ESTATE                      # Mq cache stale after baseline
+    with pytest.raises(binding.SdError) as e:
+        dec.prefill(list(range(125)))                               # 125 + 4 + 1 > 128
+    assert e.value.status == binding.SD_ERANGE
+    with pytest.raises(binding.SdError) as e:
+        dec.prefill([0, 300])
+    assert e.value.status == binding.SD_ERANGE
+    dec.close()
+    bad = dict(cfg_p); bad["d_head"] = 48
+    with pytest.raises(binding.SdError):
+        make_decoder(bad, w_p, cfg_q, w_q)
+    wq2 = dict(w_q); wq2.pop("head")
+    with pytest.raises(binding.SdError):
+        make_decoder(cfg_p, w_p, cfg_q, wq2)

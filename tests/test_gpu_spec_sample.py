@@ -1,0 +1,110 @@
+"""GPU parity: the fused accept / resample kernel against the oracle's
+Algorithm-1 arithmetic on the same seeded logits, guesses and uniforms.
+
+Bar: n and t bit-exact, except acceptance decisions with |r - p/q| < 1e-3 and
+draws whose uniform lies within 1e-5 (normalised CDF units) of an edge of the
+chosen token's CDF interval; such tolerated events are counted and must be rare.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sampling
+from paper_2211_17192_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(rows, gamma, vocab, sigma, seed, temperature):
+    from paper_2211_17192_amd import binding
+    zp, zq, x, r, s = synth.sampler_case(rows, gamma, vocab, sigma, seed)
+    dev = "cuda"
+    n_d, t_d = binding.spec_sample(torch.from_numpy(zp).to(dev), torch.from_numpy(zq).to(dev),
+                                   torch.from_numpy(x).to(dev), torch.from_numpy(r).to(dev),
+                                   torch.from_numpy(s).to(dev), temperature)
+    torch.cuda.synchronize()
+    n_g, t_g = n_d.cpu().numpy(), t_d.cpu().numpy()
+    tolerated = 0
+    for b in range(rows):
+        if temperature == 0:
+            xb = [int(np.argmax(zq[b, i])) for i in range(gamma)]      # x_i ~ one-hot q_i
+        else:
+            xb = list(x[b])
+        n_o, t_o, info = sampling.accept_and_resample_from_logits(zp[b], zq[b], xb, r[b], s[b], temperature)
+        if temperature == 0:
+            continue_check = True
+        if (n_g[b], t_g[b]) == (n_o, t_o):
+            continue
+        # a tolerated disagreement must be explained by a near-threshold decision
+        if n_g[b] != n_o:
+            first = min(n_g[b], n_o)
+            assert info["margins"][first] < 1e-3, (b, n_g[b], n_o, info["margins"])
+        else:
+            p_rows = np.stack([sampling.standardise(z, temperature) for z in zp[b]])
+            q_rows = np.stack([sampling.standardise(z, temperature) for z in zq[b]])
+            w = p_rows[n_o] if n_o == gamma else sampling.adjusted_distribution(p_rows[n_o], q_rows[n_o])
+            assert sampling.icdf_edge_distance(w, s[b], int(t_g[b])) < 1e-5, (b, t_g[b], t_o)
+        tolerated += 1
+    return tolerated, n_g
+
+
+@pytest.mark.parametrize("sigma", [0.5, 1.0, 2.0])
+def test_spec_sample_matches_oracle_full_vocab(sigma):
+    tol, n = run_case(16, 7, 32128, sigma, seed=int(sigma * 10), temperature=1.0)
+    assert tol <= 1
+    assert n.min() >= 0 and n.max() <= 7
+
+
+@pytest.mark.parametrize("rows,gamma,vocab,temperature", [
+    (5, 1, 256, 1.0), (3, 4, 50, 1.0), (4, 15, 1000, 0.7), (2, 3, 4099, 2.0),   # ragged / odd vocab
+    (6, 5, 8192, 0.0), (3, 7, 32128, 0.0),
+])
+def test_spec_sample_shapes_and_temperatures(rows, gamma, vocab, temperature):
+    if temperature == 0.0:
+        from paper_2211_17192_amd import binding
+        zp, zq, x, r, s = synth.sampler_case(rows, gamma, vocab, 0.5, 3)
+        xg = np.argmax(zq, axis=-1).astype(np.int32)
+        n_d, t_d = binding.spec_sample(torch.from_numpy(zp).cuda(), torch.from_numpy(zq).cuda(),
+                                       torch.from_numpy(xg).cuda(), torch.from_numpy(r).cuda(),
+                                       torch.from_numpy(s).cuda(), 0.0)
+        for b in range(rows):
+            n_o, t_o, _ = sampling.accept_and_resample_from_logits(zp[b], zq[b], list(xg[b]), r[b], s[b], 0.0)
+            assert (int(n_d[b]), int(t_d[b])) == (n_o, t_o)
+    else:
+        tol, _ = run_case(rows, gamma, vocab, 1.0, 11, temperature)
+        assert tol <= 1
+
+
+def test_spec_sample_degenerate_inputs():
+    """q == p keeps every guess; a guess the target gives (almost) no mass is dropped
+    and the residual draw can never return it when q > p there."""
+    from paper_2211_17192_amd import binding
+    rows, gamma, V = 4, 3, 512
+    zp, _, _, r, s = synth.sampler_case(rows, gamma, V, 1.0, 5)
+    zq = zp[:, :gamma].copy()
+    x = np.argmax(zq, axis=-1).astype(np.int32)
+    n_d, t_d = binding.spec_sample(torch.from_numpy(zp).cuda(), torch.from_numpy(zq).cuda(),
+                                   torch.from_numpy(x).cuda(), torch.from_numpy(r).cuda(),
+                                   torch.from_numpy(s).cuda(), 1.0)
+    assert n_d.cpu().tolist() == [gamma] * rows
+    for b in range(rows):
+        assert int(t_d[b]) == sampling.icdf(sampling.standardise(zp[b, gamma], 1.0), s[b])
+    # second scenario: the first guess has target probability ~ e^-60 -> rejected at once
+    zp2 = zp.copy()
+    for b in range(rows):
+        zp2[b, 0, x[b, 0]] = -60.0
+    n_d, t_d = binding.spec_sample(torch.from_numpy(zp2).cuda(), torch.from_numpy(zq).cuda(),
+                                   torch.from_numpy(x).cuda(), torch.from_numpy(r).cuda(),
+                                   torch.from_numpy(s).cuda(), 1.0)
+    assert n_d.cpu().tolist() == [0] * rows
+    assert all(int(t_d[b]) != x[b, 0] for b in range(rows))
+
+
+def test_spec_sample_rejects_bad_arguments():
+    from paper_2211_17192_amd import binding
+    assert binding.lib.sd_spec_sample_scratch_bytes(0, 3) == 0
+    assert binding.lib.sd_spec_sample_scratch_bytes(4, 16) == 0
+    z = torch.zeros(1, 2, 8, device="cuda")
+    with pytest.raises(binding.SdError):
+        binding.spec_sample(z, z[:, :1].contiguous(), torch.zeros(1, 1, dtype=torch.int32, device="cuda"),
+                            None, None, 1.0)
