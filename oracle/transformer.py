@@ -26,7 +26,9 @@ values.  dtype "bf16": weights are bf16 values; the residual stream and all
 accumulations stay wide, and a tensor is rounded to bf16 (nearest-even)
 exactly where the GPU path stores or feeds one in bf16: the normed GEMM
 input, q / k / v (after rotary), the attention output, the MLP hidden
-activation and the final normed row.
+activation and the final normed row.  For RMSNorm the rounded GEMM input is
+x * gain and the division by rms(x) is applied to the GEMM output rows (the
+same product; only the place of the rounding is fixed by this convention).
 """
 from __future__ import annotations
 
@@ -183,11 +185,16 @@ class Transformer:
             y = y + self.W(bname)
         return y
 
-    def norm(self, x, prefix):
+    def normed(self, x, prefix):
+        """(h, rs): the rows fed to the linear layers after a norm and the per-row
+        factor their outputs are multiplied by.  LayerNorm: h = R(LN(x)), rs = 1.
+        RMSNorm: h = R(x * gain), rs = 1 / sqrt(mean(x^2) + eps), so that
+        (h @ W^T) * rs = rms_norm(x) @ W^T up to the rounding R."""
         c = self.cfg
         if c.arch == GPT:
-            return layer_norm(x, self.W(prefix + ".g"), self.W(prefix + ".b"), c.norm_eps)
-        return rms_norm(x, self.W(prefix + ".g"), c.norm_eps)
+            return self.R(layer_norm(x, self.W(prefix + ".g"), self.W(prefix + ".b"), c.norm_eps)), 1.0
+        rs = 1.0 / np.sqrt((x ** 2).mean(axis=-1, keepdims=True) + c.norm_eps)
+        return self.R(x * self.W(prefix + ".g")), rs
 
     # -- encoder side (T5DEC) ------------------------------------------------
     def set_encoder_output(self, enc_out):
@@ -248,15 +255,15 @@ class Transformer:
             bias = tab[:, bucket]                           # [H, M, L]
         for l in range(c.n_layers):
             p = f"l{l}"
-            h = self.R(self.norm(x, p + ".ln1"))
+            h, rs = self.normed(x, p + ".ln1")
             if c.arch == GPT:
                 q = self.linear(h, p + ".wq", p + ".bq")
                 k = self.linear(h, p + ".wk", p + ".bk")
                 v = self.linear(h, p + ".wv", p + ".bv")
             else:
-                q = self.linear(h, p + ".wq")
-                k = self.linear(h, p + ".wk")
-                v = self.linear(h, p + ".wv")
+                q = self.linear(h, p + ".wq") * rs
+                k = self.linear(h, p + ".wk") * rs
+                v = self.linear(h, p + ".wv") * rs
             if c.arch == GQA:
                 q = q.reshape(M, c.n_heads, c.d_head)
                 k = k.reshape(M, c.n_kv_heads, c.d_head)
@@ -271,20 +278,20 @@ class Transformer:
             a = self.R(self._attend(q, cache.k[l, :L], cache.v[l, :L], scale, bias, pos))
             x = x + self.linear(a, p + ".wo", p + ".bo" if c.arch == GPT else None)
             if c.arch == T5DEC:
-                hc = self.R(self.norm(x, p + ".lnc"))
-                qc = self.R(self.linear(hc, p + ".cq"))
+                hc, rsc = self.normed(x, p + ".lnc")
+                qc = self.R(self.linear(hc, p + ".cq") * rsc)
                 ac = self.R(self._attend(qc, self.cross_k[l], self.cross_v[l], 1.0))
                 x = x + self.linear(ac, p + ".co")
-            h2 = self.R(self.norm(x, p + ".ln2"))
+            h2, rs2 = self.normed(x, p + ".ln2")
             if c.arch == GPT:
                 f = self.R(gelu_tanh(self.linear(h2, p + ".w1", p + ".b1")))
                 x = x + self.linear(f, p + ".w2", p + ".b2")
             else:
                 act = gelu_tanh if c.arch == T5DEC else silu
-                f = self.R(act(self.linear(h2, p + ".wg")) * self.linear(h2, p + ".wu"))
+                f = self.R(act(self.linear(h2, p + ".wg") * rs2) * (self.linear(h2, p + ".wu") * rs2))
                 x = x + self.linear(f, p + ".w2")
-        hf = self.R(self.norm(x, "lnf"))
-        return c.logit_scale * self.linear(hf, "head")
+        hf, rsf = self.normed(x, "lnf")
+        return c.logit_scale * (self.linear(hf, "head") * rsf)
 
 
 class CachedScorer:

@@ -13,8 +13,13 @@
 //    partial tiles are added through LDS in wave order 0..S-1.  S depends on
 //    (N, K) only, never on R, so a row's result is bit-identical whether it is
 //    computed alone or among gamma+1 rows.
-//  * Prologue: RMSNorm / LayerNorm of the fp32 residual rows (statistics
-//    reduced across the workgroup), rounded to the storage type.
+//  * RMSNorm is folded around the GEMM: the producer of the residual stream
+//    (embedding or a residual-add epilogue) also writes xg = x * gain of the
+//    next norm in the storage type and, per 16-feature tile, the partial sums
+//    of x^2; the consumer multiplies plain xg rows and scales its output rows
+//    by 1/rms, which it gets by adding the partials in tile order.  No pass
+//    over x, no barrier before the weight stream starts.
+//  * LayerNorm (mean subtraction) is applied as a prologue on the fp32 rows.
 //  * Epilogues: bias, tanh-GELU, gated GELU / SwiGLU (two weight streams, one
 //    activation stream), residual add, rotary + scatter of q / k / v (k and v
 //    go straight into the paged KV cache), logit scaling.
@@ -23,17 +28,19 @@
 
 namespace sd {
 
-enum { PRO_NONE = 0, PRO_RMS = 1, PRO_LN = 2 };
+enum { PRO_NONE = 0, PRO_POST = 1, PRO_LN = 2 };
 enum { EPI_STORE = 0, EPI_QKV = 1, EPI_RESID = 2, EPI_ACT = 3, EPI_GATED = 4, EPI_LOGITS = 5 };
 enum { ACT_GELU = 0, ACT_SILU = 1 };
 
 struct GemmArgs {
   const void* W;          // tiled weights, N/16 tiles
   const void* W2;         // EPI_GATED: the "up" weights, tiled alike
-  const void* X;          // PRO_NONE: T [R][K]; else float [R][K]
-  const void* gain;       // T [K]   (PRO_RMS / PRO_LN)
+  const void* X;          // PRO_NONE / PRO_POST: T [R][K]; PRO_LN: float [R][K]
+  const void* gain;       // T [K]   (PRO_LN)
   const void* beta;       // T [K]   (PRO_LN)
   const void* bias;       // T [N] or nullptr
+  const float* ss_in;     // PRO_POST: [n_part][16] partial sums of x^2 of the input rows
+  int n_part;
   int R, K, N;
   int ksteps_per_wave;    // ceil((K/32) / waves)
   float eps;
@@ -41,6 +48,10 @@ struct GemmArgs {
   int ldo;
   float scale;            // EPI_LOGITS
   int act;                // EPI_GATED
+  // EPI_RESID extras for a following RMSNorm (all optional)
+  void* xg_out;           // T [R][ldo]: (x + y) * gain_next
+  const void* gain_next;  // T [N]
+  float* ss_out;          // [N/16][16] partial sums of (x + y)^2 per tile and row
   // EPI_QKV
   void* q_out;            // T [R][nq]
   int nq, nkv;            // features [0,nq) q, [nq,nq+nkv) k, [nq+nkv,nq+2nkv) v
@@ -55,6 +66,9 @@ template <typename T> struct Mma;
 template <> struct Mma<bf16> {
   typedef bf16x8 Frag;
   static __device__ __forceinline__ Frag load(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+  static __device__ __forceinline__ Frag load_stream(const bf16* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p));
+  }
   static __device__ __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f[e] = (bf16)0.0f; return f; }
   static __device__ __forceinline__ Frag from_floats(const float (&v)[8]) {
     Frag f;
@@ -69,6 +83,7 @@ template <> struct Mma<bf16> {
 template <> struct Mma<float> {
   struct Frag { float v[8]; };
   static __device__ __forceinline__ Frag load(const float* p) { Frag f; load8<float>(p, f.v); return f; }
+  static __device__ __forceinline__ Frag load_stream(const float* p) { return load(p); }
   static __device__ __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f.v[e] = 0.0f; return f; }
   static __device__ __forceinline__ Frag from_floats(const float (&v)[8]) {
     Frag f;
@@ -91,6 +106,7 @@ __device__ __forceinline__ float gelu_tanh(float x) {
 __device__ __forceinline__ float silu(float x) { return x / (1.0f + expf(-x)); }
 
 constexpr int GEMM_UNROLL = 8;
+constexpr int GEMM_MAX_PART_LOADS = 64;     // n_part <= 16 * 64 (d_model <= 16384)
 
 template <typename T, int PRO, int EPI>
 static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
@@ -103,33 +119,45 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   const int ks0 = min(KS, wave * a.ksteps_per_wave), ks1 = min(KS, ks0 + a.ksteps_per_wave);
   float* part = lds;                                 // [S][ND][256]
   float* stat = lds + S * ND * 256;                  // [S][16]
-  float* ybuf = stat + S * 16;                       // [ND][256]
+  float* ybuf = stat + S * 16;                       // [256]
   const bool row_ok = (j < a.R);
 
-  // ---- prologue statistics (normalisation of the residual rows) ----
+  // ---- PRO_POST: start fetching the partial sums of x^2; used in the epilogue.
+  // Epilogue thread t = (row t/16, feature t%16) adds the partials p = t%16 (mod 16).
+  float ssq = 0.0f;
+  if (PRO == PRO_POST && tid < 256) {
+    const int row = tid >> 4, f = tid & 15;
+    for (int p = f; p < a.n_part; p += 16) ssq += a.ss_in[p * 16 + row];
+  }
+
+  // ---- PRO_LN: statistics of the fp32 rows, reduced across the workgroup ----
   float mu = 0.0f, rstd = 1.0f;
-  if (PRO != PRO_NONE) {
+  if (PRO == PRO_LN) {
     const float* x = static_cast<const float*>(a.X) + (size_t)j * a.K + kq * 8;
-    if (PRO == PRO_LN) {
-      float s = 0.0f;
-      if (row_ok) for (int ks = ks0; ks < ks1; ++ks) {
+    float s = 0.0f;
+    if (row_ok) {
+#pragma unroll 4
+      for (int ks = ks0; ks < ks1; ++ks) {
         float v[8]; load8<float>(x + ks * 32, v);
 #pragma unroll
         for (int e = 0; e < 8; ++e) s += v[e];
       }
-      s += __shfl_xor(s, 16, WAVE); s += __shfl_xor(s, 32, WAVE);
-      if (kq == 0) stat[wave * 16 + j] = s;
-      __syncthreads();
-      float t = 0.0f;
-      for (int w = 0; w < S; ++w) t += stat[w * 16 + j];
-      mu = t / (float)a.K;
-      __syncthreads();
     }
+    s += __shfl_xor(s, 16, WAVE); s += __shfl_xor(s, 32, WAVE);
+    if (kq == 0) stat[wave * 16 + j] = s;
+    __syncthreads();
+    float t = 0.0f;
+    for (int w = 0; w < S; ++w) t += stat[w * 16 + j];
+    mu = t / (float)a.K;
+    __syncthreads();
     float s2 = 0.0f;
-    if (row_ok) for (int ks = ks0; ks < ks1; ++ks) {
-      float v[8]; load8<float>(x + ks * 32, v);
+    if (row_ok) {
+#pragma unroll 4
+      for (int ks = ks0; ks < ks1; ++ks) {
+        float v[8]; load8<float>(x + ks * 32, v);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { const float d = v[e] - mu; s2 += d * d; }
+        for (int e = 0; e < 8; ++e) { const float d = v[e] - mu; s2 += d * d; }
+      }
     }
     s2 += __shfl_xor(s2, 16, WAVE); s2 += __shfl_xor(s2, 32, WAVE);
     if (kq == 0) stat[wave * 16 + j] = s2;
@@ -150,21 +178,15 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   auto make_b = [&](int ks) -> Frag {
     if (!row_ok) return Mma<T>::zero();
     const int k = ks * 32 + kq * 8;
-    if (PRO == PRO_NONE) {
+    if (PRO != PRO_LN) {
       return Mma<T>::load(static_cast<const T*>(a.X) + (size_t)j * a.K + k);
     } else {
-      float v[8], g[8];
+      float v[8], g[8], bb[8];
       load8<float>(static_cast<const float*>(a.X) + (size_t)j * a.K + k, v);
       load8<T>(static_cast<const T*>(a.gain) + k, g);
-      if (PRO == PRO_LN) {
-        float bb[8];
-        load8<T>(static_cast<const T*>(a.beta) + k, bb);
+      load8<T>(static_cast<const T*>(a.beta) + k, bb);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = (v[e] - mu) * rstd * g[e] + bb[e];
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = v[e] * rstd * g[e];
-      }
+      for (int e = 0; e < 8; ++e) v[e] = (v[e] - mu) * rstd * g[e] + bb[e];
       return Mma<T>::from_floats(v);
     }
   };
@@ -174,8 +196,8 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     Frag fa[ND][GEMM_UNROLL], fb[GEMM_UNROLL];
 #pragma unroll
     for (int u = 0; u < GEMM_UNROLL; ++u) {
-      fa[0][u] = Mma<T>::load(w0 + (size_t)(ks + u) * 512);
-      if (ND == 2) fa[ND - 1][u] = Mma<T>::load(w1 + (size_t)(ks + u) * 512);
+      fa[0][u] = Mma<T>::load_stream(w0 + (size_t)(ks + u) * 512);
+      if (ND == 2) fa[ND - 1][u] = Mma<T>::load_stream(w1 + (size_t)(ks + u) * 512);
     }
 #pragma unroll
     for (int u = 0; u < GEMM_UNROLL; ++u) fb[u] = make_b(ks + u);
@@ -187,8 +209,8 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   }
   for (; ks < ks1; ++ks) {
     const Frag fb = make_b(ks);
-    acc[0] = Mma<T>::mma(Mma<T>::load(w0 + (size_t)ks * 512), fb, acc[0]);
-    if (ND == 2) acc[ND - 1] = Mma<T>::mma(Mma<T>::load(w1 + (size_t)ks * 512), fb, acc[ND - 1]);
+    acc[0] = Mma<T>::mma(Mma<T>::load_stream(w0 + (size_t)ks * 512), fb, acc[0]);
+    if (ND == 2) acc[ND - 1] = Mma<T>::mma(Mma<T>::load_stream(w1 + (size_t)ks * 512), fb, acc[ND - 1]);
   }
 
   // ---- combine the K-slices in wave order ----
@@ -200,6 +222,8 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
       part[(wave * ND + d) * 256 + j * 16 + kq * 4 + r] = acc[d][r];
   __syncthreads();
 
+  // Epilogue threads: t = row * 16 + feature, t < 256 (the first four wavefronts,
+  // or a loop when the workgroup is smaller).
   for (int t = tid; t < 256; t += blockDim.x) {
     float y[ND];
 #pragma unroll
@@ -209,15 +233,40 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
       y[d] = s;
     }
     const int row = t >> 4, f = t & 15, n = tile * 16 + f;
+    if (PRO == PRO_POST) {
+      float q = ssq;
+      if (blockDim.x < 256) {                       // small workgroup: this thread serves several t
+        q = 0.0f;
+        for (int p = f; p < a.n_part; p += 16) q += a.ss_in[p * 16 + row];
+      }
+      q += __shfl_xor(q, 1, WAVE); q += __shfl_xor(q, 2, WAVE);
+      q += __shfl_xor(q, 4, WAVE); q += __shfl_xor(q, 8, WAVE);
+      const float rs = 1.0f / sqrtf(q / (float)a.K + a.eps);
+#pragma unroll
+      for (int d = 0; d < ND; ++d) y[d] *= rs;
+    }
     if (a.bias != nullptr) y[0] += Store<T>::ld(static_cast<const T*>(a.bias) + n);
     if (EPI == EPI_QKV) {
       ybuf[t] = y[0];
+    } else if (EPI == EPI_RESID) {
+      float xn = 0.0f;
+      if (row < a.R) {
+        float* o = static_cast<float*>(a.out) + (size_t)row * a.ldo + n;
+        xn = *o + y[0];
+        *o = xn;
+        if (a.xg_out != nullptr)
+          Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n,
+                       xn * Store<T>::ld(static_cast<const T*>(a.gain_next) + n));
+      }
+      if (a.ss_out != nullptr) {
+        float q = xn * xn;
+        q += __shfl_xor(q, 1, WAVE); q += __shfl_xor(q, 2, WAVE);
+        q += __shfl_xor(q, 4, WAVE); q += __shfl_xor(q, 8, WAVE);
+        if (f == 0) a.ss_out[tile * 16 + row] = q;
+      }
     } else if (row < a.R) {
       if (EPI == EPI_STORE) {
         Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
-      } else if (EPI == EPI_RESID) {
-        float* o = static_cast<float*>(a.out) + (size_t)row * a.ldo + n;
-        *o = *o + y[0];
       } else if (EPI == EPI_ACT) {
         Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, gelu_tanh(y[0]));
       } else if (EPI == EPI_GATED) {

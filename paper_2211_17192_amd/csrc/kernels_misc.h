@@ -17,11 +17,15 @@ enum {
 
 // grid = R workgroups.  row_pos[r] < 0 marks a padding row (first draft step of
 // a one-token sequence): it is embedded as token 0 at position 0 and ignored.
+// For RMSNorm models the kernel also writes xg = x * gain of the first norm in
+// the storage type and the row's sum of squares (one partial: ss[0][r]).
 template <typename T>
 static __global__ __launch_bounds__(256) void embed_kernel(
     int mode, int step, const SeqState* __restrict__ st, const int* __restrict__ prompt, int start,
     const T* __restrict__ tok_emb, const T* __restrict__ pos_emb, int d, int vocab,
-    float* __restrict__ x, int* __restrict__ row_pos) {
+    float* __restrict__ x, int* __restrict__ row_pos, const T* __restrict__ gain_next,
+    T* __restrict__ xg, float* __restrict__ ss) {
+  __shared__ float red[16];
   const int r = blockIdx.x;
   int tok, pos;
   switch (mode) {
@@ -36,10 +40,17 @@ static __global__ __launch_bounds__(256) void embed_kernel(
   tok = min(max(tok, 0), vocab - 1);
   const T* e = tok_emb + (size_t)tok * d;
   const T* p = pos_emb ? pos_emb + (size_t)pos * d : nullptr;
+  float q = 0.0f;
   for (int i = threadIdx.x; i < d; i += blockDim.x) {
     float v = Store<T>::ld(e + i);
     if (p) v += Store<T>::ld(p + i);
     x[(size_t)r * d + i] = v;
+    if (xg) Store<T>::st(xg + (size_t)r * d + i, v * Store<T>::ld(gain_next + i));
+    q += v * v;
+  }
+  if (ss) {
+    q = block_reduce(q, red, OpSumF(), 0.0f);
+    if (threadIdx.x == 0) ss[r] = q;
   }
 }
 

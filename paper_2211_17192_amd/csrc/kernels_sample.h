@@ -19,6 +19,7 @@ namespace sd {
 constexpr int SAMPLE_THREADS = 1024;
 constexpr int SAMPLE_CHUNK = 256;           // vocabulary entries per scan chunk (64 lanes x 4)
 constexpr int SAMPLE_MAX_CHUNKS = 1024;     // vocab <= 262144
+constexpr int SAMPLE_COUNTER_STRIDE = 64;    // uint32 elements between the tickets of two sequences
 constexpr int SAMPLE_REG_F4 = 8;            // a row up to 32768 entries is held in registers
 
 struct RowStat {
@@ -306,7 +307,9 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
     const RowStat rs = row_stats(z, V, invT, greedy, sm);
     if (tid == 0) my_stats[j] = rs;
   }
-  if (!last_block_arrives(counters + b, (unsigned)nrows, &sm.flag)) return;
+  // one counter per sequence, 256 bytes apart: device-scope atomics that queue on
+  // one cache line serialise at roughly 0.2 us each
+  if (!last_block_arrives(counters + (size_t)b * SAMPLE_COUNTER_STRIDE, (unsigned)nrows, &sm.flag)) return;
 
   // ---- tail: one workgroup per sequence ----
   if (tid < nrows) srow[tid] = my_stats[tid];

@@ -50,17 +50,17 @@ struct LayerW {
 struct Model {
   sd_model_cfg cfg{};
   size_t esz = 4;
-  int nq = 0, nkv = 0, n_pages = 0, page_size = 0, nchunks = 0;
+  int nq = 0, nkv = 0, n_pages = 0, page_size = 0;
   void *tok_emb = nullptr, *pos_emb = nullptr, *head = nullptr, *lnfg = nullptr, *lnfb = nullptr, *rel_bias = nullptr;
   int* bucket_lut = nullptr;
   float* rope = nullptr;
   std::vector<LayerW> L;
   int* page_table = nullptr;
   float* x = nullptr;
+  void* xg = nullptr;          // x * gain of the next RMSNorm, storage type
+  float* ss = nullptr;         // [d_model/16][16] partial sums of x^2
   void *qbuf = nullptr, *attn = nullptr, *ffn = nullptr;
   int* row_pos = nullptr;
-  float *part_o = nullptr, *part_ml = nullptr;
-  unsigned int* attn_counters = nullptr;
   int* prompt = nullptr;
 };
 
@@ -95,8 +95,6 @@ void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size) {
   m.nkv = c.n_kv_heads * c.d_head;
   m.page_size = page_size;
   m.n_pages = (c.max_len + page_size - 1) / page_size;
-  const int longest = c.max_len > c.enc_len ? c.max_len : c.enc_len;
-  m.nchunks = (longest + ATTN_CHUNK - 1) / ATTN_CHUNK;
   m.tok_emb = A.take(V * d * e);
   m.head = A.take(V * d * e);
   m.lnfg = A.take(d * e);
@@ -132,14 +130,12 @@ void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size) {
   }
   m.page_table = static_cast<int*>(A.take((size_t)m.n_pages * sizeof(int)));
   m.x = static_cast<float*>(A.take((size_t)MAX_ROWS * d * sizeof(float)));
+  m.xg = A.take((size_t)MAX_ROWS * d * e);
+  m.ss = static_cast<float*>(A.take((size_t)(d / 16) * 16 * sizeof(float)));
   m.qbuf = A.take((size_t)MAX_ROWS * m.nq * e);
   m.attn = A.take((size_t)MAX_ROWS * m.nq * e);
   m.ffn = A.take((size_t)MAX_ROWS * ff * e);
   m.row_pos = static_cast<int*>(A.take(MAX_ROWS * sizeof(int)));
-  const size_t G = c.n_heads / c.n_kv_heads, RG = MAX_ROWS * G;
-  m.part_o = static_cast<float*>(A.take((size_t)c.n_kv_heads * m.nchunks * RG * c.d_head * sizeof(float)));
-  m.part_ml = static_cast<float*>(A.take((size_t)c.n_kv_heads * m.nchunks * RG * 2 * sizeof(float)));
-  m.attn_counters = static_cast<unsigned int*>(A.take((size_t)c.n_kv_heads * sizeof(unsigned int)));
   m.prompt = static_cast<int*>(A.take((size_t)c.max_len * sizeof(int)));
 }
 
@@ -220,23 +216,40 @@ void launch_gemm_t(hipStream_t s, GemmArgs a) {
 template <typename T>
 void launch_gemm(hipStream_t s, int pro, int epi, const GemmArgs& a) {
 #define SD_CASE(P, E) if (pro == P && epi == E) return launch_gemm_t<T, P, E>(s, a)
-  SD_CASE(PRO_LN, EPI_QKV); SD_CASE(PRO_RMS, EPI_QKV);
-  SD_CASE(PRO_NONE, EPI_RESID); SD_CASE(PRO_NONE, EPI_STORE); SD_CASE(PRO_RMS, EPI_STORE);
-  SD_CASE(PRO_LN, EPI_ACT); SD_CASE(PRO_RMS, EPI_GATED);
-  SD_CASE(PRO_LN, EPI_LOGITS); SD_CASE(PRO_RMS, EPI_LOGITS);
+  SD_CASE(PRO_LN, EPI_QKV); SD_CASE(PRO_POST, EPI_QKV);
+  SD_CASE(PRO_NONE, EPI_RESID); SD_CASE(PRO_NONE, EPI_STORE); SD_CASE(PRO_POST, EPI_STORE);
+  SD_CASE(PRO_LN, EPI_ACT); SD_CASE(PRO_POST, EPI_GATED);
+  SD_CASE(PRO_LN, EPI_LOGITS); SD_CASE(PRO_POST, EPI_LOGITS);
 #undef SD_CASE
+}
+
+size_t attn_lds_bytes(int RG, int DH) {
+  const int NG = ATTN_THREADS / DH;
+  return (size_t)(RG * DH + RG * ATTN_BLOCK + NG * MAX_ROWS * DH + 3 * RG + RG * DH) * sizeof(float);
 }
 
 template <typename T>
 void launch_attn(hipStream_t s, const Model& m, const AttnArgs& a) {
   const int G = a.H / a.Hkv, RG = a.R * G, DH = m.cfg.d_head;
-  const int NG = ATTN_THREADS / DH;
-  const size_t lds = (size_t)(RG * DH + RG * ATTN_CHUNK + NG * RG * DH + RG * 2) * sizeof(float);
-  const dim3 grid(m.nchunks, a.Hkv), block(ATTN_THREADS);
+  const size_t lds = attn_lds_bytes(RG, DH);
+  const dim3 grid(a.Hkv), block(ATTN_THREADS);
   if (DH == 32) hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, lds, s, a);
   else if (DH == 64) hipLaunchKernelGGL((attn_kernel<T, 64>), grid, block, lds, s, a);
   else hipLaunchKernelGGL((attn_kernel<T, 128>), grid, block, lds, s, a);
 }
+
+// The attention kernel keeps up to ATTN_MAX_RG query rows in more than 64 KB of LDS.
+template <typename T>
+hipError_t allow_big_lds() {
+  const int bytes = (int)attn_lds_bytes(ATTN_MAX_RG, 128);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, 32>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, 128>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  return e;
+}
+
+// Rows one prefill pass may carry so that rows x (query heads per kv head) fits the attention kernel.
+int prefill_rows(const sd_model_cfg& c) { return std::min(MAX_ROWS, ATTN_MAX_RG / (c.n_heads / c.n_kv_heads)); }
 
 // One forward of model m over R rows chosen by (mode, step); optionally the
 // LM head on rows [row0, row0+nrows) into `logits` (fp32 [nrows][vocab]).
@@ -245,16 +258,35 @@ void forward(sd_ctx* c, Model& m, int mode, int step, int R, int start, int row0
   hipStream_t s = c->stream;
   const sd_model_cfg& f = m.cfg;
   const int d = f.d_model;
-  const int pro = (f.arch == SD_ARCH_GPT) ? PRO_LN : PRO_RMS;
+  const bool rms = (f.arch != SD_ARCH_GPT);
+  const int pro = rms ? PRO_POST : PRO_LN;
+  const int n_layers = (int)m.L.size();
   hipLaunchKernelGGL((embed_kernel<T>), dim3(R), dim3(256), 0, s, mode, step, c->d_state, m.prompt, start,
                      static_cast<const T*>(m.tok_emb), static_cast<const T*>(m.pos_emb), d, f.vocab, m.x,
-                     m.row_pos);
-  for (const LayerW& l : m.L) {
+                     m.row_pos, static_cast<const T*>(rms ? m.L[0].ln1g : nullptr),
+                     static_cast<T*>(rms ? m.xg : nullptr), rms ? m.ss : nullptr);
+  int n_part = 1;                                   // partial sums of x^2 the next norm has to add
+  // input of a normed GEMM: LayerNorm reads the fp32 rows, RMSNorm the pre-scaled rows + partials
+  auto normed = [&](GemmArgs& g, const void* gain, const void* beta) {
+    g.eps = f.norm_eps;
+    if (rms) { g.X = m.xg; g.ss_in = m.ss; g.n_part = n_part; }
+    else { g.X = m.x; g.gain = gain; g.beta = beta; }
+  };
+  // residual add that also prepares the input of the next norm
+  auto resid = [&](const void* W, const void* X, const void* bias, int K, const void* gain_next) {
+    GemmArgs o{};
+    o.R = R; o.W = W; o.X = X; o.bias = bias; o.K = K; o.N = d; o.out = m.x; o.ldo = d;
+    if (rms) { o.xg_out = m.xg; o.gain_next = gain_next; o.ss_out = m.ss; }
+    launch_gemm<T>(s, PRO_NONE, EPI_RESID, o);
+    n_part = d / 16;
+  };
+  for (int li = 0; li < n_layers; ++li) {
+    const LayerW& l = m.L[li];
     GemmArgs g{};
-    g.R = R; g.eps = f.norm_eps;
+    g.R = R;
+    normed(g, l.ln1g, l.ln1b);
     // q, k, v projections (+ rotary) with k, v appended to the cache
-    g.W = l.wqkv; g.X = m.x; g.gain = l.ln1g; g.beta = l.ln1b; g.bias = l.bqkv;
-    g.K = d; g.N = m.nq + 2 * m.nkv;
+    g.W = l.wqkv; g.bias = l.bqkv; g.K = d; g.N = m.nq + 2 * m.nkv;
     g.q_out = m.qbuf; g.nq = m.nq; g.nkv = m.nkv; g.kv_pool = l.kv; g.page_table = m.page_table;
     g.page_size = m.page_size; g.n_kv_heads = f.n_kv_heads; g.d_head = f.d_head; g.row_pos = m.row_pos;
     g.rope = m.rope;
@@ -264,42 +296,40 @@ void forward(sd_ctx* c, Model& m, int mode, int step, int R, int start, int row0
     a.row_pos = m.row_pos; a.R = R; a.H = f.n_heads; a.Hkv = f.n_kv_heads; a.cross = 0; a.kv_len = 0;
     a.scale = (f.arch == SD_ARCH_T5DEC) ? 1.0f : 1.0f / sqrtf((float)f.d_head);
     a.rel_bias = m.rel_bias; a.bucket_lut = m.bucket_lut; a.rel_buckets = f.rel_buckets;
-    a.part_o = m.part_o; a.part_ml = m.part_ml; a.counters = m.attn_counters;
     launch_attn<T>(s, m, a);
-    GemmArgs o{};
-    o.R = R; o.W = l.wo; o.X = m.attn; o.bias = l.bo; o.K = m.nq; o.N = d; o.out = m.x; o.ldo = d;
-    launch_gemm<T>(s, PRO_NONE, EPI_RESID, o);
+    resid(l.wo, m.attn, l.bo, m.nq, (f.arch == SD_ARCH_T5DEC) ? l.lncg : l.ln2g);
     if (f.arch == SD_ARCH_T5DEC) {
       GemmArgs cq{};
-      cq.R = R; cq.eps = f.norm_eps; cq.W = l.cq; cq.X = m.x; cq.gain = l.lncg; cq.K = d; cq.N = m.nq;
-      cq.out = m.qbuf; cq.ldo = m.nq;
-      launch_gemm<T>(s, PRO_RMS, EPI_STORE, cq);
+      cq.R = R;
+      normed(cq, l.lncg, nullptr);
+      cq.W = l.cq; cq.K = d; cq.N = m.nq; cq.out = m.qbuf; cq.ldo = m.nq;
+      launch_gemm<T>(s, PRO_POST, EPI_STORE, cq);
       AttnArgs ca = a;
       ca.cross = 1; ca.ck = l.cross_k; ca.cv = l.cross_v; ca.kv_len = f.enc_len; ca.scale = 1.0f;
       ca.rel_bias = nullptr;
       launch_attn<T>(s, m, ca);
-      GemmArgs co = o;
-      co.W = l.co;
-      launch_gemm<T>(s, PRO_NONE, EPI_RESID, co);
+      resid(l.co, m.attn, nullptr, m.nq, l.ln2g);
     }
     GemmArgs h{};
-    h.R = R; h.eps = f.norm_eps; h.X = m.x; h.gain = l.ln2g; h.beta = l.ln2b; h.K = d; h.N = f.d_ff;
-    h.out = m.ffn; h.ldo = f.d_ff; h.W = l.w1;
+    h.R = R;
+    normed(h, l.ln2g, l.ln2b);
+    h.K = d; h.N = f.d_ff; h.out = m.ffn; h.ldo = f.d_ff; h.W = l.w1;
     if (f.arch == SD_ARCH_GPT) {
       h.bias = l.b1;
       launch_gemm<T>(s, PRO_LN, EPI_ACT, h);
     } else {
       h.W2 = l.wu; h.act = (f.arch == SD_ARCH_T5DEC) ? ACT_GELU : ACT_SILU;
-      launch_gemm<T>(s, PRO_RMS, EPI_GATED, h);
+      launch_gemm<T>(s, PRO_POST, EPI_GATED, h);
     }
-    GemmArgs w2{};
-    w2.R = R; w2.W = l.w2; w2.X = m.ffn; w2.bias = l.b2; w2.K = f.d_ff; w2.N = d; w2.out = m.x; w2.ldo = d;
-    launch_gemm<T>(s, PRO_NONE, EPI_RESID, w2);
+    resid(l.w2, m.ffn, l.b2, f.d_ff, (li + 1 < n_layers) ? m.L[li + 1].ln1g : m.lnfg);
   }
   if (logits != nullptr) {
     GemmArgs g{};
-    g.R = nrows; g.eps = f.norm_eps; g.W = m.head; g.X = m.x + (size_t)row0 * d; g.gain = m.lnfg; g.beta = m.lnfb;
-    g.K = d; g.N = f.vocab; g.out = logits; g.ldo = f.vocab; g.scale = f.logit_scale;
+    g.R = nrows;
+    normed(g, m.lnfg, m.lnfb);
+    g.X = static_cast<const char*>(g.X) + (size_t)row0 * d * (rms ? m.esz : sizeof(float));
+    if (rms) g.ss_in = m.ss + row0;
+    g.W = m.head; g.K = d; g.N = f.vocab; g.out = logits; g.ldo = f.vocab; g.scale = f.logit_scale;
     launch_gemm<T>(s, pro, EPI_LOGITS, g);
   }
 }
@@ -461,7 +491,6 @@ sd_status load_model(hipStream_t s, Model& m, const sd_tensor* w, int n, std::st
       }
     if (hipMemcpy(m.rope, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) { err = "rope table upload"; return SD_EHIP; }
   }
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, s, m.attn_counters, 0u, (size_t)f.n_kv_heads);
   return SD_OK;
 }
 
@@ -495,6 +524,9 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
   if (!cfg_ok(*q_cfg, why)) return fail(nullptr, SD_EINVAL, "Mq config: " + why);
   if (!rt_ok(*rt, why)) return fail(nullptr, SD_EINVAL, "runtime config: " + why);
   if (p_cfg->vocab != q_cfg->vocab) return fail(nullptr, SD_EINVAL, "Mp and Mq must share the vocabulary");
+  if ((rt->max_gamma + 1) * (p_cfg->n_heads / p_cfg->n_kv_heads) > ATTN_MAX_RG ||
+      2 * (q_cfg->n_heads / q_cfg->n_kv_heads) > ATTN_MAX_RG)
+    return fail(nullptr, SD_EINVAL, "(max_gamma+1) x (query heads per kv head) exceeds the attention kernel's limit");
   if (!rt->workspace || (reinterpret_cast<uintptr_t>(rt->workspace) & 255)) return fail(nullptr, SD_EINVAL, "workspace must be 256-byte aligned");
   const size_t need = sd_workspace_bytes(p_cfg, q_cfg, rt);
   if (rt->workspace_bytes < need) return fail(nullptr, SD_ENOMEM, "workspace too small: need " + std::to_string(need));
@@ -513,6 +545,7 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
       hipHostMalloc(reinterpret_cast<void**>(&c->h_params), sizeof(StepParams), hipHostMallocDefault) != hipSuccess)
     return bail(SD_EHIP, "pinned allocation failed");
   for (auto& e : c->ev) if (hipEventCreate(&e) != hipSuccess) return bail(SD_EHIP, "event creation failed");
+  if (allow_big_lds<bf16>() != hipSuccess || allow_big_lds<float>() != hipSuccess) return bail(SD_EHIP, "cannot raise the LDS limit");
   std::string err;
   sd_status st = (p_cfg->dtype == SD_BF16) ? load_model<bf16>(c->stream, c->p, p_w, n_p, err)
                                            : load_model<float>(c->stream, c->p, p_w, n_p, err);
@@ -570,8 +603,9 @@ extern "C" sd_status sd_prefill(sd_ctx* c, int32_t row, const int32_t* prompt, i
     if (m.cfg.arch == SD_ARCH_T5DEC) {
       if (m.cfg.dtype == SD_BF16) cross_kv<bf16>(c, m, encs[k]); else cross_kv<float>(c, m, encs[k]);
     }
-    for (int s0 = 0; s0 < n - 1; s0 += MAX_ROWS)
-      forward_any(c, m, ROWS_PREFILL, 0, std::min(MAX_ROWS, n - 1 - s0), s0, 0, 0, nullptr);
+    const int step = prefill_rows(m.cfg);
+    for (int s0 = 0; s0 < n - 1; s0 += step)
+      forward_any(c, m, ROWS_PREFILL, 0, std::min(step, n - 1 - s0), s0, 0, 0, nullptr);
   }
   SeqState st{};
   st.len = n; st.last_tok = prompt[n - 1]; st.prev_tok = (n >= 2) ? prompt[n - 2] : 0;

@@ -10,7 +10,7 @@ size_t scratch_align(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 extern "C" size_t sd_spec_sample_scratch_bytes(int32_t rows, int32_t gamma) {
   if (rows < 1 || gamma < 1 || gamma > SD_MAX_GAMMA) return 0;
-  return scratch_align((size_t)rows * sizeof(unsigned int), 256) +
+  return scratch_align((size_t)rows * sd::SAMPLE_COUNTER_STRIDE * sizeof(unsigned int), 256) +
          (size_t)rows * (2 * gamma + 1) * sizeof(sd::RowStat);
 }
 
@@ -25,7 +25,7 @@ extern "C" sd_status sd_spec_sample(const float* p_logits, const float* q_logits
   if (temperature > 0.0f && (!r || !s)) return SD_EINVAL;
   unsigned int* counters = static_cast<unsigned int*>(scratch);
   sd::RowStat* stats = reinterpret_cast<sd::RowStat*>(
-      static_cast<char*>(scratch) + scratch_align((size_t)rows * sizeof(unsigned int), 256));
+      static_cast<char*>(scratch) + scratch_align((size_t)rows * sd::SAMPLE_COUNTER_STRIDE * sizeof(unsigned int), 256));
   dim3 grid(2 * gamma + 1, rows);
   hipLaunchKernelGGL(sd::spec_verify_kernel, grid, dim3(sd::SAMPLE_THREADS), 0,
                      static_cast<hipStream_t>(stream), p_logits, q_logits, x, r, s, gamma, vocab,

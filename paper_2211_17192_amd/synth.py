@@ -203,3 +203,73 @@ def sampler_case(rows: int, gamma: int, vocab: int, sigma: float, seed: int):
             x[b, i] = g.choice(vocab, p=q / q.sum())
     u = uniform_stream(seed + 7919, rows * (gamma + 1)).reshape(rows, gamma + 1)
     return zp, zq, x, np.ascontiguousarray(u[:, :gamma]), np.ascontiguousarray(u[:, gamma])
+
+
+def correlated_pair(cfg_p: dict, cfg_q: dict, seed: int, device="cpu", emb_rms: float = 1.0,
+                    head_std: float = 0.02, w_std: float = 0.02, q_logit_gain: float = 1.0):
+    """Random-init (Mp, Mq) whose next-token distributions agree to a tunable
+    degree, standing in for a trained target / draft pair.
+
+    Both models share a token table E [V, d_q] and an output table H [V, d_q];
+    Mq uses them directly, Mp sees them through a random rotation P (d_q
+    orthonormal rows in d_p dimensions): tok_emb_p = a E P, head_p = H P.  On
+    the embedding -> head skip path the two models then give the same logits;
+    the randomly initialised layers perturb them differently, so a larger
+    emb_rms (embedding magnitude relative to the layers' output) gives a higher
+    acceptance rate.  Iteration time does not depend on these values."""
+    d_p, d_q, V = cfg_p["d_model"], cfg_q["d_model"], cfg_p["vocab"]
+    assert cfg_q["vocab"] == V and d_q <= d_p
+    cfg_q = dict(cfg_q)
+    w_p = random_weights(cfg_p, seed, device, w_std)
+    w_q = random_weights(cfg_q, seed + 1, device, w_std)
+    E = counter_normal((V, d_q), seed * 7 + 1, 1.0, 0.0, device)
+    H = counter_normal((V, d_q), seed * 7 + 2, head_std, 0.0, device)
+    G = counter_normal((d_p, d_q), seed * 7 + 3, 1.0, 0.0, device)
+    P = torch.linalg.qr(G)[0].T.contiguous()                 # [d_q, d_p], orthonormal rows
+    dt = _tdtype(cfg_p)
+    w_p["tok_emb"] = (emb_rms * math.sqrt(d_p / d_q) * (E @ P)).to(dt)
+    w_p["head"] = (H @ P).to(dt)
+    w_q["tok_emb"] = (emb_rms * E).to(dt)
+    w_q["head"] = H.to(dt)
+    cfg_q["logit_scale"] = cfg_p["logit_scale"] * math.sqrt(d_p / d_q) * q_logit_gain
+    return w_p, cfg_q, w_q
+
+
+def t5xxl_pair(device="cuda", seed: int = 4, gen_len: int = 128, emb_rms: float = 4.0,
+               head_std: float = 0.02, logit_scale: float = 1.0, q_logit_gain: float = 1.0):
+    """T5-XXL-shaped decoder (24 layers, d_model 4096, 64 heads x 64, d_ff 10240
+    gated-GELU, vocab 32128, 512 encoder positions) with a T5-small-shaped draft
+    (6 layers, d_model 512, 8 heads x 64, d_ff 2048), bf16, random init.  The
+    encoder stack is not run: encoder outputs are N(0,1) tensors."""
+    max_len = (gen_len + 1 + 16 + 15) // 16 * 16
+    cfg_p = model_cfg(T5DEC, 24, 4096, 64, 10240, 32128, max_len, d_head=64, enc_len=512,
+                      norm_eps=1e-6, dtype="bf16", logit_scale=logit_scale)
+    cfg_q = model_cfg(T5DEC, 6, 512, 8, 2048, 32128, max_len, d_head=64, enc_len=512,
+                      norm_eps=1e-6, dtype="bf16", logit_scale=logit_scale)
+    w_p, cfg_q, w_q = correlated_pair(cfg_p, cfg_q, seed, device, emb_rms, head_std, 0.02, q_logit_gain)
+    enc_p = counter_normal((512, 4096), seed * 7 + 5, 1.0, 0.0, device).to(torch.bfloat16)
+    enc_q = counter_normal((512, 512), seed * 7 + 6, 1.0, 0.0, device).to(torch.bfloat16)
+    return cfg_p, w_p, cfg_q, w_q, enc_p, enc_q
+
+
+def gpt_pair(device="cuda", seed: int = 2, emb_rms: float = 1.0, head_std: float = 0.02,
+             logit_scale: float = 1.0, q_logit_gain: float = 1.0):
+    """GPT-like pair in bf16: Mp 12 layers, d_model 768, 12 heads, d_ff 3072,
+    vocab 8192 (~97M parameters); Mq 2 layers, d_model 256, 4 heads, d_ff 1024
+    (~6M).  Room for a 128-token prompt plus 256 generated tokens."""
+    cfg_p = model_cfg(GPT, 12, 768, 12, 3072, 8192, 416, dtype="bf16", logit_scale=logit_scale)
+    cfg_q = model_cfg(GPT, 2, 256, 4, 1024, 8192, 416, dtype="bf16", logit_scale=logit_scale)
+    w_p, cfg_q, w_q = correlated_pair(cfg_p, cfg_q, seed, device, emb_rms, head_std, 0.02, q_logit_gain)
+    return cfg_p, w_p, cfg_q, w_q
+
+
+def model_bytes(cfg: dict) -> dict:
+    """Bytes one forward has to read: layer + head weights (every row of them),
+    and per cached position the self-attention keys / values."""
+    e = 2 if cfg["dtype"] == "bf16" else 4
+    shapes = weight_shapes(cfg)
+    w = sum(int(np.prod(s)) for n, (s, k) in shapes.items()
+            if k == "w" and n not in ("tok_emb", "pos_emb") and not n.endswith((".ck", ".cv")))
+    cross = 2 * cfg["n_layers"] * cfg["enc_len"] * cfg["n_heads"] * cfg["d_head"] * e
+    kv_per_pos = 2 * cfg["n_layers"] * cfg["n_kv_heads"] * cfg["d_head"] * e
+    return {"weights": w * e, "cross_kv": cross, "kv_per_pos": kv_per_pos}
