@@ -63,46 +63,71 @@ template <> __device__ __forceinline__ void load8<bf16>(const bf16* p, float (&o
   for (int e = 0; e < 8; ++e) o[e] = (float)v[e];
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-  return v;
+// ---------------------------------------------------------------------------
+// Cross-lane combines that stay in the vector ALU: DPP quad permutes and row
+// rotations inside a row of 16 lanes, and the gfx950 half-swap instructions
+// across rows.  (ds_bpermute-based shuffles go through the LDS pipe, which the
+// attention and sampling kernels need for data.)  lane_combine<OFF>(v, op)
+// returns op(v, v of the partner lane) in every lane; the partner is lane^OFF
+// for OFF in {1, 2, 8, 16, 32} and lane+4 (mod 16, same row) for OFF == 4.
+// ---------------------------------------------------------------------------
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+template <int OFF> __device__ __forceinline__ unsigned dpp_partner(unsigned v) {
+  constexpr int ctrl = (OFF == 1) ? 0xB1 : (OFF == 2) ? 0x4E : (OFF == 4) ? 0x124 : 0x128;
+  return (unsigned)__builtin_amdgcn_mov_dpp((int)v, ctrl, 0xf, 0xf, true);
 }
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
-  return v;
-}
-__device__ __forceinline__ int wave_min(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, WAVE));
-  return v;
-}
-__device__ __forceinline__ int wave_max(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, WAVE));
-  return v;
+template <int OFF> __device__ __forceinline__ u32x2 half_swap(unsigned v) {
+  if (OFF == 16) return __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return __builtin_amdgcn_permlane32_swap(v, v, false, false);
 }
 
-// Workgroup-wide reductions over up to 16 waves.  `red` is LDS scratch of at
-// least 16 elements of the value type; every thread gets the result.  The
-// combine order is fixed (wave 0..n-1), so results are run-to-run identical.
-template <typename V, typename Op>
-__device__ __forceinline__ V block_reduce(V v, V* red, Op op, V identity) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+template <typename V> struct Words;
+template <> struct Words<float> {
+  static constexpr int N = 1;
+  static __device__ __forceinline__ void split(float v, unsigned (&w)[2]) { w[0] = __float_as_uint(v); w[1] = 0; }
+  static __device__ __forceinline__ float join(const unsigned (&w)[2]) { return __uint_as_float(w[0]); }
+};
+template <> struct Words<int> {
+  static constexpr int N = 1;
+  static __device__ __forceinline__ void split(int v, unsigned (&w)[2]) { w[0] = (unsigned)v; w[1] = 0; }
+  static __device__ __forceinline__ int join(const unsigned (&w)[2]) { return (int)w[0]; }
+};
+template <> struct Words<double> {
+  static constexpr int N = 2;
+  static __device__ __forceinline__ void split(double v, unsigned (&w)[2]) {
+    const unsigned long long u = (unsigned long long)__double_as_longlong(v);
+    w[0] = (unsigned)u; w[1] = (unsigned)(u >> 32);
+  }
+  static __device__ __forceinline__ double join(const unsigned (&w)[2]) {
+    return __longlong_as_double((long long)(((unsigned long long)w[1] << 32) | w[0]));
+  }
+};
+
+template <int OFF, typename V, typename Op>
+__device__ __forceinline__ V lane_combine(V v, Op op) {
+  unsigned w[2];
+  Words<V>::split(v, w);
+  if (OFF < 16) {
+    unsigned o[2] = {0, 0};
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = op(v, __shfl_xor(v, o, WAVE));
-  __syncthreads();                       // protect `red` from the previous use
-  if (lane == 0) red[wave] = v;
-  __syncthreads();
-  V r = identity;
-  for (int w = 0; w < nw; ++w) r = op(r, red[w]);
-  return r;
+    for (int i = 0; i < Words<V>::N; ++i) o[i] = dpp_partner<OFF>(w[i]);
+    return op(v, Words<V>::join(o));
+  } else {
+    unsigned x[2] = {0, 0}, y[2] = {0, 0};     // {own, partner} in an order that depends on the lane
+#pragma unroll
+    for (int i = 0; i < Words<V>::N; ++i) { const u32x2 r = half_swap<OFF>(w[i]); x[i] = r.x; y[i] = r.y; }
+    return op(Words<V>::join(x), Words<V>::join(y));
+  }
+}
+
+// All 64 lanes get op over the wavefront (op must be commutative; the
+// association order is fixed per lane, so results are run-to-run identical).
+template <typename V, typename Op>
+__device__ __forceinline__ V wave_allreduce(V v, Op op) {
+  v = lane_combine<1>(v, op); v = lane_combine<2>(v, op); v = lane_combine<4>(v, op);
+  v = lane_combine<8>(v, op); v = lane_combine<16>(v, op); v = lane_combine<32>(v, op);
+  return v;
 }
 
 struct OpSumF { __device__ float operator()(float a, float b) const { return a + b; } };
@@ -110,6 +135,27 @@ struct OpSumD { __device__ double operator()(double a, double b) const { return 
 struct OpMaxF { __device__ float operator()(float a, float b) const { return fmaxf(a, b); } };
 struct OpMinI { __device__ int operator()(int a, int b) const { return min(a, b); } };
 struct OpMaxI { __device__ int operator()(int a, int b) const { return max(a, b); } };
+
+__device__ __forceinline__ float wave_sum(float v) { return wave_allreduce(v, OpSumF()); }
+__device__ __forceinline__ double wave_sum(double v) { return wave_allreduce(v, OpSumD()); }
+__device__ __forceinline__ float wave_max(float v) { return wave_allreduce(v, OpMaxF()); }
+__device__ __forceinline__ int wave_min(int v) { return wave_allreduce(v, OpMinI()); }
+__device__ __forceinline__ int wave_max(int v) { return wave_allreduce(v, OpMaxI()); }
+
+// Workgroup-wide reductions over up to 16 waves.  `red` is LDS scratch of at
+// least 16 elements of the value type; every thread gets the result.  The
+// combine order is fixed (wave 0..n-1), so results are run-to-run identical.
+template <typename V, typename Op>
+__device__ __forceinline__ V block_reduce(V v, V* red, Op op, V identity) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  v = wave_allreduce(v, op);
+  __syncthreads();                       // protect `red` from the previous use
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  V r = identity;
+  for (int w = 0; w < nw; ++w) r = op(r, red[w]);
+  return r;
+}
 
 // Ticket: returns true in every thread of exactly one workgroup, the one that
 // arrives last among `expected`; that workgroup sees all global writes the

@@ -6,64 +6,109 @@
 // (cross-attention).
 //
 // One workgroup of 1024 threads owns one kv head and walks its keys in blocks
-// of 512 with an online softmax (running max m, denominator l, unnormalised
-// output O per row).  There is no split over workgroups and therefore no
-// cross-workgroup merge: device-scope atomics cost about a quarter of a
-// microsecond each on this chip when they queue on one address, which is more
-// than the whole kernel should take.  Per block of keys:
-//   scores  2 lanes per key, each holding half of the head dimension of its key
-//           in registers and dotting it with every query row (rows in LDS);
-//   softmax one wavefront per row over the 512 scores;
-//   P*V     thread = (key group, head-dim element); coalesced V rows; the 16
-//           (8 for d_head 128) key groups are added in fixed order through LDS.
+// (512 keys, 256 for d_head 128) with an online softmax (running max m,
+// denominator l, unnormalised output O per row).  There is no split over
+// workgroups and therefore no cross-workgroup merge: device-scope atomics cost
+// about a quarter of a microsecond each on this chip when they queue on one
+// address, which is more than the whole kernel should take.  The kernel is
+// latency-bound, so every thread issues all its K and V loads of a key block
+// up front with 16-byte loads and no branches (they do not depend on the
+// scores), and the rest runs out of registers and LDS:
+//   scores  LPK lanes per key, each holding a slice of the head dimension of
+//           its key in registers and dotting it with every query row (in LDS);
+//   softmax one wavefront per row over the block's scores;
+//   P*V     thread = (group of KPT consecutive keys, 8 head-dim elements); the
+//           groups of a wavefront are added by lane shuffles, the wavefronts in
+//           fixed order through LDS.
 // Key blocks sit at absolute positions and all reduction orders are fixed, so
 // a row's result does not depend on R or on the other rows: a row computed
 // alone (plain decoding) is bit-identical to the same row among gamma+1.
 // KV layout per layer: [page][K|V][kv_head][slot][d_head]; a (kv head, page)
-// is a contiguous page_size * d_head block, so key reads are coalesced.
+// is a contiguous page_size * d_head block.  Cross keys / values: [head][key][d_head].
 #pragma once
 #include "common.h"
 
 namespace sd {
 
+#ifdef SD_KTIME
+// Build-time instrumentation (off by default): block 0 accumulates the time it
+// spends in each phase, in ticks of the constant 100 MHz clock.
+__device__ unsigned long long g_ktime[64];
+#define SD_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) { const unsigned long long t_ = wall_clock64(); \
+    atomicAdd(&g_ktime[kt_base + (i)], t_ - kt_last); kt_last = t_; } } while (0)
+#else
+#define SD_STAMP(i) do { } while (0)
+#endif
+
 constexpr int ATTN_THREADS = 1024;
-constexpr int ATTN_BLOCK = 512;            // keys per pass
+constexpr int ATTN_LDS_PAGES = 1024;       // page-table entries cached in LDS
+constexpr int ATTN_LDS_DIST = 4096;        // causal distances whose bias bucket is cached in LDS
 constexpr int ATTN_MAX_RG = 24;            // query rows x heads per kv head that fit in LDS
+
+// KB keys per block; LPK lanes per key and DP head-dim elements per lane in the
+// score phase; KPT consecutive keys per thread in the P*V phase; RPP rows per
+// P*V pass (bounds the LDS reduction buffer [16 waves][RPP][DH] to 64 KB).
+template <int DH> struct AttnShape;
+template <> struct AttnShape<32>  { static constexpr int KB = 512, LPK = 2, DP = 16, KPT = 2, RPP = 16; };
+template <> struct AttnShape<64>  { static constexpr int KB = 512, LPK = 2, DP = 32, KPT = 4, RPP = 16; };
+template <> struct AttnShape<128> { static constexpr int KB = 256, LPK = 4, DP = 32, KPT = 4, RPP = 8; };
+constexpr int attn_block_keys(int dh) { return dh == 128 ? 256 : 512; }
+constexpr int attn_rows_per_pass(int dh) { return dh == 128 ? 8 : 16; }
 
 struct AttnArgs {
   const void* q;            // T [R][H*dh]
   void* out;                // T [R][H*dh]
   const void* kv_pool;      // self: this layer's pages
-  const void* ck; const void* cv;   // cross: T [kv_len][H*dh] each
+  const void* ck; const void* cv;   // cross: T [H][kv_len][dh] each
   const int* page_table;
-  int page_size;
+  int page_size, n_pages;   // page_size a power of two, n_pages <= ATTN_LDS_PAGES
   const int* row_pos;       // [R]; self: causal limit of each row, < 0 = padding row
   int R, H, Hkv;
   int cross;                // 1: cross-attention over kv_len keys, no mask, no bias
   int kv_len;
   float scale;
   const void* rel_bias;     // T [H][rel_buckets] or nullptr
-  const int* bucket_lut;    // [max_len] bucket of each causal distance
+  const int* bucket_lut;    // [n_pages * page_size <= ATTN_LDS_DIST] bucket of each causal distance
   int rel_buckets;
 };
 
-// dynamic LDS (floats): q [RG][DH] | s [RG][512] | o [NG][16][DH] | m, l, f [3][RG] | acc [RG][DH]
+// dynamic LDS (floats): q [RG][DH] | s [RG][KB] | o [16][RPP][DH] | m, l, f [3][RG] | acc [RG][DH]
 template <typename T, int DH>
 static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArgs a) {
   extern __shared__ float lds[];
   __shared__ int s_pos[MAX_ROWS];
-  constexpr int DP = DH / 2;                       // head-dim elements per lane in the score phase
-  constexpr int NG = ATTN_THREADS / DH;            // key groups in the P*V phase
+  __shared__ int s_pt[ATTN_LDS_PAGES];
+  __shared__ float s_bias[4 * 64];                 // rel_bias rows of this kv head's query heads
+  __shared__ unsigned char s_bucket[ATTN_LDS_DIST];
+  typedef AttnShape<DH> SH;
+  constexpr int KB = SH::KB, LPK = SH::LPK, DP = SH::DP, KPT = SH::KPT, RPP = SH::RPP;
+  constexpr int OCT = DH / 8;                      // 8-element slices of a V row
   constexpr int NW = ATTN_THREADS / 64;
+  static_assert((ATTN_THREADS / OCT) * KPT == KB, "P*V mapping must cover the key block");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int hkv = blockIdx.x;
   const int G = a.H / a.Hkv, RG = a.R * G;
+#ifdef SD_KTIME
+  const int kt_base = (a.cross ? 8 : 0) + (a.R > 1 ? 16 : 0) + (a.Hkv > 8 ? 32 : 0);
+  unsigned long long kt_last = wall_clock64();
+  if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&g_ktime[kt_base + 7], 1ull);
+#endif
 
   if (tid < MAX_ROWS) s_pos[tid] = (tid < a.R) ? (a.cross ? 0 : a.row_pos[tid]) : -1;
+  if (!a.cross) for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += ATTN_THREADS) s_pt[i] = a.page_table[i];
+  // relative-position bias: table rows and distance -> bucket map into LDS, so
+  // the score loop has no global loads
+  const bool use_bias = !a.cross && a.rel_bias != nullptr;
+  if (use_bias) {
+    for (int i = tid; i < G * a.rel_buckets; i += ATTN_THREADS)
+      s_bias[i] = Store<T>::ld(static_cast<const T*>(a.rel_bias) + (size_t)(hkv * G) * a.rel_buckets + i);
+    const int n_dist = min(ATTN_LDS_DIST, a.n_pages * a.page_size);
+    for (int i = tid; i < n_dist; i += ATTN_THREADS) s_bucket[i] = (unsigned char)a.bucket_lut[i];
+  }
   float* q_s = lds;                                // [RG][DH]
-  float* s_s = q_s + RG * DH;                      // [RG][512]
-  float* o_s = s_s + RG * ATTN_BLOCK;              // [NG][16][DH]
-  float* m_s = o_s + NG * MAX_ROWS * DH;           // [RG] running max
+  float* s_s = q_s + RG * DH;                      // [RG][KB]
+  float* o_s = s_s + RG * KB;                      // [16][RPP][DH]
+  float* m_s = o_s + NW * RPP * DH;                // [RG] running max
   float* l_s = m_s + RG;                           // [RG] running denominator
   float* f_s = l_s + RG;                           // [RG] rescale factor of this pass
   float* acc_s = f_s + RG;                         // [RG][DH] running output
@@ -76,77 +121,89 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   }
   if (tid < RG) { m_s[tid] = -INFINITY; l_s[tid] = 0.0f; }
   __syncthreads();
+  SD_STAMP(0);
   int kv_len = a.kv_len;
   if (!a.cross) {
     int mx = -1;
     for (int r = 0; r < a.R; ++r) mx = max(mx, s_pos[r]);
     kv_len = mx + 1;
   }
+  const int page_shift = __ffs(a.page_size) - 1, page_mask = a.page_size - 1;
+  const T* cross_k = a.cross ? static_cast<const T*>(a.ck) + (size_t)hkv * a.kv_len * DH : nullptr;
+  const T* cross_v = a.cross ? static_cast<const T*>(a.cv) + (size_t)hkv * a.kv_len * DH : nullptr;
+  auto row_ptr = [&](int key, int which) -> const T* {   // which: 0 = K, 1 = V
+    if (a.cross) return (which ? cross_v : cross_k) + (size_t)key * DH;
+    const int page = s_pt[key >> page_shift], slot = key & page_mask;
+    return static_cast<const T*>(a.kv_pool) +
+           ((((size_t)page * 2 + which) * a.Hkv + hkv) * a.page_size + slot) * DH;
+  };
+  const int kl_s = tid / LPK, part = tid % LPK;    // score phase: key within block, slice
+  const int oct = tid % OCT, grp = tid / OCT;      // P*V phase: V slice, key group (KPT keys)
 
-  for (int k0 = 0; k0 < kv_len; k0 += ATTN_BLOCK) {
-    // ---- scores: 2 lanes per key ----
+  for (int k0 = 0; k0 < kv_len; k0 += KB) {
+    const int nkeys = min(KB, kv_len - k0);
+    // ---- issue every global load of this block.  Loads are unconditional
+    //      (out-of-range keys re-read the last valid one and get probability 0):
+    //      a branch per load would serialise them. ----
+    float kreg[DP];
+    const bool key_ok = kl_s < nkeys;
     {
-      const int kl = tid >> 1, part = tid & 1;
-      const int key = k0 + kl;
-      const bool key_ok = key < kv_len;
-      float kreg[DP];
-      if (key_ok) {
-        const T* kp;
-        if (a.cross) {
-          kp = static_cast<const T*>(a.ck) + (size_t)key * a.H * DH + hkv * DH;
-        } else {
-          const int page = a.page_table[key / a.page_size], slot = key % a.page_size;
-          kp = static_cast<const T*>(a.kv_pool) +
-               ((((size_t)page * 2 + 0) * a.Hkv + hkv) * a.page_size + slot) * DH;
-        }
+      const T* kp = row_ptr(k0 + min(kl_s, nkeys - 1), 0) + part * DP;
 #pragma unroll
-        for (int e = 0; e < DP; e += 8) {
-          float v[8];
-          load8<T>(kp + part * DP + e, v);
+      for (int e = 0; e < DP; e += 8) {
+        float v[8];
+        load8<T>(kp + e, v);
 #pragma unroll
-          for (int f = 0; f < 8; ++f) kreg[e + f] = v[f];
-        }
-      } else {
-#pragma unroll
-        for (int e = 0; e < DP; ++e) kreg[e] = 0.0f;
-      }
-      for (int rg = 0; rg < RG; ++rg) {
-        const float* qr = q_s + rg * DH + part * DP;
-        float dot = 0.0f;
-#pragma unroll
-        for (int e = 0; e < DP; ++e) dot += qr[e] * kreg[e];
-        dot += __shfl_xor(dot, 1, WAVE);
-        if (part == 0) {
-          const int r = rg / G, pos = s_pos[r];
-          float sc = -INFINITY;
-          if (key_ok && pos >= 0 && (a.cross || key <= pos)) {
-            sc = a.scale * dot;
-            if (a.rel_bias != nullptr) {
-              const int h = hkv * G + rg % G;
-              sc += Store<T>::ld(static_cast<const T*>(a.rel_bias) + h * a.rel_buckets +
-                                 a.bucket_lut[pos - key]);
-            }
-          }
-          s_s[rg * ATTN_BLOCK + kl] = sc;
-        }
+        for (int f = 0; f < 8; ++f) kreg[e + f] = v[f];
       }
     }
-    __syncthreads();
+    float vreg[KPT][8];                            // keys grp * KPT + u
+#pragma unroll
+    for (int u = 0; u < KPT; ++u)
+      load8<T>(row_ptr(k0 + min(grp * KPT + u, nkeys - 1), 1) + oct * 8, vreg[u]);
 
-    // ---- online softmax: one wavefront per row, 8 scores per lane ----
+    // ---- scores ----
+    for (int rg = 0; rg < RG; ++rg) {
+      const float4* qr = reinterpret_cast<const float4*>(q_s + rg * DH + part * DP);
+      float4 q4[DP / 4];
+#pragma unroll
+      for (int e = 0; e < DP / 4; ++e) q4[e] = qr[e];
+      float dot = 0.0f;
+#pragma unroll
+      for (int e = 0; e < DP / 4; ++e) {
+        dot += q4[e].x * kreg[4 * e]; dot += q4[e].y * kreg[4 * e + 1];
+        dot += q4[e].z * kreg[4 * e + 2]; dot += q4[e].w * kreg[4 * e + 3];
+      }
+      dot = lane_combine<1>(dot, OpSumF());
+      if (LPK == 4) dot = lane_combine<2>(dot, OpSumF());
+      if (part == 0) {
+        const int r = rg / G, pos = s_pos[r], key = k0 + kl_s;
+        float sc = -INFINITY;
+        if (key_ok && pos >= 0 && (a.cross || key <= pos)) {
+          sc = a.scale * dot;
+          if (use_bias) sc += s_bias[(rg % G) * a.rel_buckets + (int)s_bucket[pos - key]];
+        }
+        s_s[rg * KB + kl_s] = sc;
+      }
+    }
+    SD_STAMP(1);
+    __syncthreads();
+    SD_STAMP(2);
+
+    // ---- online softmax: one wavefront per row ----
     for (int rg = wave; rg < RG; rg += NW) {
-      float sc[ATTN_BLOCK / 64];
+      float sc[KB / 64];
       float mx = -INFINITY;
 #pragma unroll
-      for (int i = 0; i < ATTN_BLOCK / 64; ++i) { sc[i] = s_s[rg * ATTN_BLOCK + i * 64 + lane]; mx = fmaxf(mx, sc[i]); }
+      for (int i = 0; i < KB / 64; ++i) { sc[i] = s_s[rg * KB + i * 64 + lane]; mx = fmaxf(mx, sc[i]); }
       mx = wave_max(mx);
       const float m_old = m_s[rg];
       const float m_new = fmaxf(m_old, mx);
       float sum = 0.0f;
 #pragma unroll
-      for (int i = 0; i < ATTN_BLOCK / 64; ++i) {
+      for (int i = 0; i < KB / 64; ++i) {
         const float p = (sc[i] == -INFINITY) ? 0.0f : __expf(sc[i] - m_new);
-        s_s[rg * ATTN_BLOCK + i * 64 + lane] = p;
+        s_s[rg * KB + i * 64 + lane] = p;
         sum += p;
       }
       sum = wave_sum(sum);
@@ -158,45 +215,52 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
       }
     }
     __syncthreads();
+    SD_STAMP(3);
 
-    // ---- P * V: thread = (key group, head-dim element), 16 rows at a time ----
-    {
-      const int d = tid % DH, g = tid / DH;
-      const int nkeys = min(ATTN_BLOCK, kv_len - k0);
-      for (int rb = 0; rb < RG; rb += MAX_ROWS) {
-        float acc[MAX_ROWS];
-#pragma unroll
-        for (int i = 0; i < MAX_ROWS; ++i) acc[i] = 0.0f;
-        const int nr = min(MAX_ROWS, RG - rb);
-        for (int kl = g; kl < nkeys; kl += NG) {
-          const int key = k0 + kl;
-          const T* vp;
-          if (a.cross) {
-            vp = static_cast<const T*>(a.cv) + (size_t)key * a.H * DH + hkv * DH;
-          } else {
-            const int page = a.page_table[key / a.page_size], slot = key % a.page_size;
-            vp = static_cast<const T*>(a.kv_pool) +
-                 ((((size_t)page * 2 + 1) * a.Hkv + hkv) * a.page_size + slot) * DH;
-          }
-          const float v = Store<T>::ld(vp + d);
-#pragma unroll
-          for (int i = 0; i < MAX_ROWS; ++i)
-            if (i < nr) acc[i] += s_s[(rb + i) * ATTN_BLOCK + kl] * v;
+    // ---- P * V out of registers, RPP rows per pass ----
+    for (int rb = 0; rb < RG; rb += RPP) {
+      const int nr = min(RPP, RG - rb);
+      for (int i = 0; i < nr; ++i) {
+        float pk[KPT];
+        if (KPT == 4) {
+          const float4 p4 = *reinterpret_cast<const float4*>(s_s + (rb + i) * KB + grp * KPT);
+          pk[0] = p4.x; pk[1] = p4.y; pk[KPT - 2] = p4.z; pk[KPT - 1] = p4.w;
+        } else {
+          const float2 p2 = *reinterpret_cast<const float2*>(s_s + (rb + i) * KB + grp * KPT);
+          pk[0] = p2.x; pk[KPT - 1] = p2.y;
         }
+        float t[8];
 #pragma unroll
-        for (int i = 0; i < MAX_ROWS; ++i)
-          if (i < nr) o_s[(g * MAX_ROWS + i) * DH + d] = acc[i];
-        __syncthreads();
-        for (int i = tid; i < nr * DH; i += ATTN_THREADS) {      // key groups in fixed order
-          float t = 0.0f;
+        for (int e = 0; e < 8; ++e) t[e] = 0.0f;
 #pragma unroll
-          for (int gg = 0; gg < NG; ++gg) t += o_s[gg * MAX_ROWS * DH + i];
-          const int idx = rb * DH + i;
-          acc_s[idx] = acc_s[idx] * f_s[idx / DH] + t;
+        for (int u = 0; u < KPT; ++u)              // keys in ascending order
+#pragma unroll
+          for (int e = 0; e < 8; ++e) t[e] += pk[u] * vreg[u][e];
+        // add the key groups of this wavefront (ascending lane distance: fixed order)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (OCT <= 4) t[e] = lane_combine<4>(t[e], OpSumF());
+          if (OCT <= 8) t[e] = lane_combine<8>(t[e], OpSumF());
+          t[e] = lane_combine<16>(t[e], OpSumF());
+          t[e] = lane_combine<32>(t[e], OpSumF());
         }
-        __syncthreads();
+        if (lane < OCT) {
+          float* o = o_s + ((size_t)wave * RPP + i) * DH + oct * 8;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = t[e];
+        }
       }
+      __syncthreads();
+      for (int i = tid; i < nr * DH; i += ATTN_THREADS) {      // wavefronts = key ranges, ascending
+        float t = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) t += o_s[w * RPP * DH + i];
+        const int idx = rb * DH + i;
+        acc_s[idx] = acc_s[idx] * f_s[idx / DH] + t;
+      }
+      __syncthreads();
     }
+    SD_STAMP(4);
   }
 
   T* og = static_cast<T*>(a.out);
@@ -205,6 +269,7 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
     const float L = l_s[rg];
     Store<T>::st(og + (size_t)r * a.H * DH + h * DH + d, (L > 0.0f) ? acc_s[i] / L : 0.0f);
   }
+  SD_STAMP(5);
 }
 
 }  // namespace sd

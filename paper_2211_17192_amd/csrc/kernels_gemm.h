@@ -9,7 +9,10 @@
 //    its whole K-slice is one contiguous stream.
 //  * The weights sit on the MFMA "A" side (16 output features), the R
 //    activation rows on the 16-wide "B" side; fp32 accumulation.
-//  * One workgroup owns one 16-feature tile; its S wavefronts split K and the
+//  * A workgroup works through 16-feature tiles (tile = block, block + grid,
+//    ...) with a two-stage software pipeline: the loads of the next chunk, or of
+//    the next tile's first chunk, are in flight while the current one is
+//    multiplied, reduced and written out.  Its S wavefronts split K and the
 //    partial tiles are added through LDS in wave order 0..S-1.  S depends on
 //    (N, K) only, never on R, so a row's result is bit-identical whether it is
 //    computed alone or among gamma+1 rows.
@@ -48,6 +51,7 @@ struct GemmArgs {
   int ldo;
   float scale;            // EPI_LOGITS
   int act;                // EPI_GATED
+  int hm_rows, hm_row0;   // EPI_STORE: > 0 selects the head-major layout (uses d_head)
   // EPI_RESID extras for a following RMSNorm (all optional)
   void* xg_out;           // T [R][ldo]: (x + y) * gain_next
   const void* gain_next;  // T [N]
@@ -105,20 +109,26 @@ __device__ __forceinline__ float gelu_tanh(float x) {
 }
 __device__ __forceinline__ float silu(float x) { return x / (1.0f + expf(-x)); }
 
-constexpr int GEMM_UNROLL = 8;
+#ifndef SD_EXP_UNROLL
+#define SD_EXP_UNROLL 8
+#endif
+constexpr int GEMM_UNROLL = SD_EXP_UNROLL;
 constexpr int GEMM_MAX_PART_LOADS = 64;     // n_part <= 16 * 64 (d_model <= 16384)
 
 template <typename T, int PRO, int EPI>
 static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   extern __shared__ float lds[];
   constexpr int ND = (EPI == EPI_GATED) ? 2 : 1;
+  constexpr int U = GEMM_UNROLL;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, S = blockDim.x >> 6;
-  const int tile = blockIdx.x;
   const int j = lane & 15, kq = lane >> 4;           // B side: row j, k-quarter kq
   const int KS = a.K >> 5;
   const int ks0 = min(KS, wave * a.ksteps_per_wave), ks1 = min(KS, ks0 + a.ksteps_per_wave);
-  float* part = lds;                                 // [S][ND][256]
-  float* stat = lds + S * ND * 256;                  // [S][16]
+  const int nchunks = (a.ksteps_per_wave + U - 1) / U;          // same for every wave
+  const int ntiles = a.N >> 4;
+  const int my_tiles = (ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+  float* part = lds;                                 // [2][S][ND][256], double-buffered per tile
+  float* stat = lds + 2 * S * ND * 256;              // [S][16]
   float* ybuf = stat + S * 16;                       // [256]
   const bool row_ok = (j < a.R);
 
@@ -167,13 +177,8 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     rstd = 1.0f / sqrtf(t2 / (float)a.K + a.eps);
   }
 
-  // ---- main loop: stream this wave's K-slice of the tile ----
   typedef typename Mma<T>::Frag Frag;
-  f32x4 acc[ND];
-#pragma unroll
-  for (int d = 0; d < ND; ++d) acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const T* w0 = static_cast<const T*>(a.W) + ((size_t)tile * KS) * 512 + lane * 8;
-  const T* w1 = (ND == 2) ? static_cast<const T*>(a.W2) + ((size_t)tile * KS) * 512 + lane * 8 : nullptr;
+  struct Buf { Frag fa[ND][U]; Frag fb[U]; };
 
   auto make_b = [&](int ks) -> Frag {
     if (!row_ok) return Mma<T>::zero();
@@ -191,117 +196,150 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     }
   };
 
-  int ks = ks0;
-  for (; ks + GEMM_UNROLL <= ks1; ks += GEMM_UNROLL) {
-    Frag fa[ND][GEMM_UNROLL], fb[GEMM_UNROLL];
+  // chunk g of this workgroup's work list: tile blockIdx.x + (g / nchunks) * gridDim.x,
+  // k-steps ks0 + (g % nchunks) * U ... of this wave's K-slice
+  auto load_chunk = [&](Buf& b, int g) {
+    const int ti = g / nchunks, c = g - ti * nchunks;
+    const size_t tile = (size_t)blockIdx.x + (size_t)ti * gridDim.x;
+    const T* w0 = static_cast<const T*>(a.W) + (tile * KS) * 512 + lane * 8;
+    const T* w1 = (ND == 2) ? static_cast<const T*>(a.W2) + (tile * KS) * 512 + lane * 8 : nullptr;
 #pragma unroll
-    for (int u = 0; u < GEMM_UNROLL; ++u) {
-      fa[0][u] = Mma<T>::load_stream(w0 + (size_t)(ks + u) * 512);
-      if (ND == 2) fa[ND - 1][u] = Mma<T>::load_stream(w1 + (size_t)(ks + u) * 512);
+    for (int u = 0; u < U; ++u) {
+      const int ks = ks0 + c * U + u;
+      if (ks < ks1) {
+        b.fa[0][u] = Mma<T>::load_stream(w0 + (size_t)ks * 512);
+        if (ND == 2) b.fa[ND - 1][u] = Mma<T>::load_stream(w1 + (size_t)ks * 512);
+        b.fb[u] = make_b(ks);
+      } else {
+        b.fa[0][u] = Mma<T>::zero();
+        if (ND == 2) b.fa[ND - 1][u] = Mma<T>::zero();
+        b.fb[u] = Mma<T>::zero();
+      }
     }
-#pragma unroll
-    for (int u = 0; u < GEMM_UNROLL; ++u) fb[u] = make_b(ks + u);
-#pragma unroll
-    for (int u = 0; u < GEMM_UNROLL; ++u) {
-      acc[0] = Mma<T>::mma(fa[0][u], fb[u], acc[0]);
-      if (ND == 2) acc[ND - 1] = Mma<T>::mma(fa[ND - 1][u], fb[u], acc[ND - 1]);
-    }
-  }
-  for (; ks < ks1; ++ks) {
-    const Frag fb = make_b(ks);
-    acc[0] = Mma<T>::mma(Mma<T>::load_stream(w0 + (size_t)ks * 512), fb, acc[0]);
-    if (ND == 2) acc[ND - 1] = Mma<T>::mma(Mma<T>::load_stream(w1 + (size_t)ks * 512), fb, acc[ND - 1]);
-  }
+  };
 
-  // ---- combine the K-slices in wave order ----
-  // accumulator layout: lane holds features (lane/16)*4 + r, r = 0..3, of row lane%16
+  f32x4 acc[ND];
 #pragma unroll
-  for (int d = 0; d < ND; ++d)
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      part[(wave * ND + d) * 256 + j * 16 + kq * 4 + r] = acc[d][r];
-  __syncthreads();
+  for (int d = 0; d < ND; ++d) acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Epilogue threads: t = row * 16 + feature, t < 256 (the first four wavefronts,
-  // or a loop when the workgroup is smaller).
-  for (int t = tid; t < 256; t += blockDim.x) {
-    float y[ND];
+  // Adds the K-slices of a finished tile in wave order and applies the epilogue.
+  auto finish_tile = [&](int ti) {
+    const int tile = (int)blockIdx.x + ti * (int)gridDim.x;
+    float* pt = part + (ti & 1) * S * ND * 256;
+    // accumulator layout: lane holds features (lane/16)*4 + r, r = 0..3, of row lane%16
 #pragma unroll
     for (int d = 0; d < ND; ++d) {
-      float s = 0.0f;
-      for (int w = 0; w < S; ++w) s += part[(w * ND + d) * 256 + t];
-      y[d] = s;
-    }
-    const int row = t >> 4, f = t & 15, n = tile * 16 + f;
-    if (PRO == PRO_POST) {
-      float q = ssq;
-      if (blockDim.x < 256) {                       // small workgroup: this thread serves several t
-        q = 0.0f;
-        for (int p = f; p < a.n_part; p += 16) q += a.ss_in[p * 16 + row];
-      }
-      q += __shfl_xor(q, 1, WAVE); q += __shfl_xor(q, 2, WAVE);
-      q += __shfl_xor(q, 4, WAVE); q += __shfl_xor(q, 8, WAVE);
-      const float rs = 1.0f / sqrtf(q / (float)a.K + a.eps);
 #pragma unroll
-      for (int d = 0; d < ND; ++d) y[d] *= rs;
+      for (int r = 0; r < 4; ++r) pt[(wave * ND + d) * 256 + j * 16 + kq * 4 + r] = acc[d][r];
+      acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    if (a.bias != nullptr) y[0] += Store<T>::ld(static_cast<const T*>(a.bias) + n);
-    if (EPI == EPI_QKV) {
-      ybuf[t] = y[0];
-    } else if (EPI == EPI_RESID) {
-      float xn = 0.0f;
-      if (row < a.R) {
-        float* o = static_cast<float*>(a.out) + (size_t)row * a.ldo + n;
-        xn = *o + y[0];
-        *o = xn;
-        if (a.xg_out != nullptr)
-          Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n,
-                       xn * Store<T>::ld(static_cast<const T*>(a.gain_next) + n));
+    __syncthreads();
+    // Epilogue threads: t = row * 16 + feature, t < 256.
+    for (int t = tid; t < 256; t += blockDim.x) {
+      float y[ND];
+#pragma unroll
+      for (int d = 0; d < ND; ++d) {
+        float s = 0.0f;
+        for (int w = 0; w < S; ++w) s += pt[(w * ND + d) * 256 + t];
+        y[d] = s;
       }
-      if (a.ss_out != nullptr) {
-        float q = xn * xn;
+      const int row = t >> 4, f = t & 15, n = tile * 16 + f;
+      if (PRO == PRO_POST) {
+        float q = ssq;
+        if (blockDim.x < 256) {                     // small workgroup: this thread serves several t
+          q = 0.0f;
+          for (int p = f; p < a.n_part; p += 16) q += a.ss_in[p * 16 + row];
+        }
         q += __shfl_xor(q, 1, WAVE); q += __shfl_xor(q, 2, WAVE);
         q += __shfl_xor(q, 4, WAVE); q += __shfl_xor(q, 8, WAVE);
-        if (f == 0) a.ss_out[tile * 16 + row] = q;
+        const float rs = 1.0f / sqrtf(q / (float)a.K + a.eps);
+#pragma unroll
+        for (int d = 0; d < ND; ++d) y[d] *= rs;
       }
-    } else if (row < a.R) {
-      if (EPI == EPI_STORE) {
-        Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
-      } else if (EPI == EPI_ACT) {
-        Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, gelu_tanh(y[0]));
-      } else if (EPI == EPI_GATED) {
-        const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
-        Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[ND - 1]);
-      } else if (EPI == EPI_LOGITS) {
-        static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = a.scale * y[0];
+      if (a.bias != nullptr) y[0] += Store<T>::ld(static_cast<const T*>(a.bias) + n);
+      if (EPI == EPI_QKV) {
+        ybuf[t] = y[0];
+      } else if (EPI == EPI_RESID) {
+        float xn = 0.0f;
+        if (row < a.R) {
+          float* o = static_cast<float*>(a.out) + (size_t)row * a.ldo + n;
+          xn = *o + y[0];
+          *o = xn;
+          if (a.xg_out != nullptr)
+            Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n,
+                         xn * Store<T>::ld(static_cast<const T*>(a.gain_next) + n));
+        }
+        if (a.ss_out != nullptr) {
+          float q = xn * xn;
+          q += __shfl_xor(q, 1, WAVE); q += __shfl_xor(q, 2, WAVE);
+          q += __shfl_xor(q, 4, WAVE); q += __shfl_xor(q, 8, WAVE);
+          if (f == 0) a.ss_out[tile * 16 + row] = q;
+        }
+      } else if (row < a.R) {
+        if (EPI == EPI_STORE) {
+          if (a.hm_rows > 0)       // head-major: [head][hm_rows][d_head], this launch's rows start at hm_row0
+            Store<T>::st(static_cast<T*>(a.out) +
+                             ((size_t)(n / a.d_head) * a.hm_rows + a.hm_row0 + row) * a.d_head + n % a.d_head, y[0]);
+          else
+            Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
+        } else if (EPI == EPI_ACT) {
+          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, gelu_tanh(y[0]));
+        } else if (EPI == EPI_GATED) {
+          const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
+          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[ND - 1]);
+        } else if (EPI == EPI_LOGITS) {
+          static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = a.scale * y[0];
+        }
       }
     }
-  }
+    if (EPI == EPI_QKV) {
+      __syncthreads();
+      for (int t = tid; t < 256; t += blockDim.x) {
+        const int row = t >> 4, f = t & 15, n = tile * 16 + f;
+        if (row >= a.R) continue;
+        const int pos = a.row_pos[row];
+        float y = ybuf[t];
+        const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
+        const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
+        const int head = nn / a.d_head, d = nn % a.d_head;
+        if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
+          const float other = ybuf[t ^ 1];
+          const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
+          y = (d & 1) ? (other * cs[1] + y * cs[0]) : (y * cs[0] - other * cs[1]);
+        }
+        if (is_q) {
+          Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
+        } else if (pos >= 0) {
+          const int page = a.page_table[pos / a.page_size], slot = pos % a.page_size;
+          const size_t idx = ((((size_t)page * 2 + (is_k ? 0 : 1)) * a.n_kv_heads + head) * a.page_size + slot) *
+                                 a.d_head + d;
+          Store<T>::st(static_cast<T*>(a.kv_pool) + idx, y);
+        }
+      }
+    }
+  };
 
-  if (EPI == EPI_QKV) {
-    __syncthreads();
-    for (int t = tid; t < 256; t += blockDim.x) {
-      const int row = t >> 4, f = t & 15, n = tile * 16 + f;
-      if (row >= a.R) continue;
-      const int pos = a.row_pos[row];
-      float y = ybuf[t];
-      const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
-      const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
-      const int head = nn / a.d_head, d = nn % a.d_head;
-      if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
-        const float other = ybuf[t ^ 1];
-        const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
-        y = (d & 1) ? (other * cs[1] + y * cs[0]) : (y * cs[0] - other * cs[1]);
-      }
-      if (is_q) {
-        Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
-      } else if (pos >= 0) {
-        const int page = a.page_table[pos / a.page_size], slot = pos % a.page_size;
-        const size_t idx = ((((size_t)page * 2 + (is_k ? 0 : 1)) * a.n_kv_heads + head) * a.page_size + slot) *
-                               a.d_head + d;
-        Store<T>::st(static_cast<T*>(a.kv_pool) + idx, y);
-      }
+  auto compute_chunk = [&](const Buf& b, int g) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      acc[0] = Mma<T>::mma(b.fa[0][u], b.fb[u], acc[0]);
+      if (ND == 2) acc[ND - 1] = Mma<T>::mma(b.fa[ND - 1][u], b.fb[u], acc[ND - 1]);
     }
+    const int ti = g / nchunks;
+    if (g - ti * nchunks == nchunks - 1) finish_tile(ti);
+  };
+
+  // ---- software pipeline over the work list: the loads of chunk g+1 (possibly
+  // the first chunk of the next tile) are in flight while chunk g is multiplied
+  // and while a finished tile is reduced and written out ----
+  const int G = my_tiles * nchunks;
+  Buf b0, b1;
+  if (G > 0) load_chunk(b0, 0);
+  for (int g = 0; g < G; g += 2) {
+    if (g + 1 < G) load_chunk(b1, g + 1);
+    compute_chunk(b0, g);
+    if (g + 2 < G) load_chunk(b0, g + 2);
+    if (g + 1 < G) compute_chunk(b1, g + 1);
   }
 }
 

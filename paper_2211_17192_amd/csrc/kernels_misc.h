@@ -41,12 +41,34 @@ static __global__ __launch_bounds__(256) void embed_kernel(
   const T* e = tok_emb + (size_t)tok * d;
   const T* p = pos_emb ? pos_emb + (size_t)pos * d : nullptr;
   float q = 0.0f;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) {
-    float v = Store<T>::ld(e + i);
-    if (p) v += Store<T>::ld(p + i);
-    x[(size_t)r * d + i] = v;
-    if (xg) Store<T>::st(xg + (size_t)r * d + i, v * Store<T>::ld(gain_next + i));
-    q += v * v;
+  // 8 consecutive elements per thread and step, four steps in flight: the row
+  // comes from cold memory and the loop would otherwise pay its latency per step
+  const int ngroups = d >> 3;                       // d is a multiple of 32
+  for (int g0 = threadIdx.x; g0 < ngroups; g0 += blockDim.x * 4) {
+    float v[4][8], w[4][8], gn[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int g = g0 + u * blockDim.x;
+      if (g < ngroups) {
+        load8<T>(e + g * 8, v[u]);
+        if (p) load8<T>(p + g * 8, w[u]);
+        if (xg) load8<T>(gain_next + g * 8, gn[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int g = g0 + u * blockDim.x;
+      if (g < ngroups) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          float val = v[u][k];
+          if (p) val += w[u][k];
+          x[(size_t)r * d + g * 8 + k] = val;
+          if (xg) Store<T>::st(xg + (size_t)r * d + g * 8 + k, val * gn[u][k]);
+          q += val * val;
+        }
+      }
+    }
   }
   if (ss) {
     q = block_reduce(q, red, OpSumF(), 0.0f);

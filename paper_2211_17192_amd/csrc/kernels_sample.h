@@ -116,8 +116,7 @@ struct RowPair {
   bool vec;
 };
 
-__device__ __forceinline__ void weights4(const RowPair& rp, int k, double (&w)[4]) {
-  float zp[4], zq[4];
+__device__ __forceinline__ void load4(const RowPair& rp, int k, float (&zp)[4], float (&zq)[4]) {
   if (rp.vec && k + 3 < rp.V) {
     const float4 a = *reinterpret_cast<const float4*>(rp.zp + k);
     zp[0] = a.x; zp[1] = a.y; zp[2] = a.z; zp[3] = a.w;
@@ -132,6 +131,10 @@ __device__ __forceinline__ void weights4(const RowPair& rp, int k, double (&w)[4
       zq[e] = (rp.zq && k + e < rp.V) ? rp.zq[k + e] : -INFINITY;
     }
   }
+}
+
+__device__ __forceinline__ void calc4(const RowPair& rp, int k, const float (&zp)[4], const float (&zq)[4],
+                                      double (&w)[4]) {
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     double p = (k + e < rp.V) ? (double)exp_scaled(zp[e], rp.mp, rp.invT) * rp.invSp : 0.0;
@@ -142,6 +145,12 @@ __device__ __forceinline__ void weights4(const RowPair& rp, int k, double (&w)[4
     }
     w[e] = p;
   }
+}
+
+__device__ __forceinline__ void weights4(const RowPair& rp, int k, double (&w)[4]) {
+  float zp[4], zq[4];
+  load4(rp, k, zp, zq);
+  calc4(rp, k, zp, zq, w);
 }
 
 // Inverse-CDF draw: smallest k with cumulative weight > u * total weight, in
@@ -162,11 +171,24 @@ __device__ __forceinline__ int icdf_row(const float* zp, const RowStat& sp, cons
            (zq == nullptr || (reinterpret_cast<uintptr_t>(zq) & 15) == 0);
   const int nchunks = (V + SAMPLE_CHUNK - 1) / SAMPLE_CHUNK;
   __syncthreads();
-  for (int c = wave; c < nchunks; c += nw) {
-    double w[4];
-    weights4(rp, c * SAMPLE_CHUNK + lane * 4, w);
-    const double t = wave_sum((w[0] + w[1]) + (w[2] + w[3]));
-    if (lane == 0) sm.ctot[c] = t;
+  constexpr int CB = 4;                          // chunks whose loads a wavefront keeps in flight
+  for (int cb = wave; cb < nchunks; cb += nw * CB) {
+    float zpv[CB][4], zqv[CB][4];
+#pragma unroll
+    for (int u = 0; u < CB; ++u) {
+      const int c = cb + u * nw;
+      if (c < nchunks) load4(rp, c * SAMPLE_CHUNK + lane * 4, zpv[u], zqv[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < CB; ++u) {
+      const int c = cb + u * nw;
+      if (c < nchunks) {
+        double w[4];
+        calc4(rp, c * SAMPLE_CHUNK + lane * 4, zpv[u], zqv[u], w);
+        const double t = wave_sum((w[0] + w[1]) + (w[2] + w[3]));
+        if (lane == 0) sm.ctot[c] = t;
+      }
+    }
   }
   __syncthreads();
   if (wave == 0) {

@@ -23,6 +23,7 @@ namespace {
 using namespace sd;
 
 thread_local std::string g_load_error;
+int g_num_cus = 256;                 // compute units of the device, read at load
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
@@ -44,7 +45,7 @@ struct LayerW {
   void *lncg = nullptr, *cq = nullptr, *ck = nullptr, *cv = nullptr, *co = nullptr;
   void *ln2g = nullptr, *ln2b = nullptr, *w1 = nullptr, *wu = nullptr, *b1 = nullptr, *w2 = nullptr, *b2 = nullptr;
   void* kv = nullptr;                       // [page][2][Hkv][PS][dh]
-  void *cross_k = nullptr, *cross_v = nullptr;   // [enc_len][H*dh]
+  void *cross_k = nullptr, *cross_v = nullptr;   // [H][enc_len][dh]
 };
 
 struct Model {
@@ -81,6 +82,8 @@ bool cfg_ok(const sd_model_cfg& c, std::string& why) {
   if (c.arch == SD_ARCH_T5DEC && (c.enc_len < 1 || c.rel_buckets < 2 || c.rel_buckets % 2 ||
                                   c.rel_max_dist <= c.rel_buckets / 2))
     return bad("T5DEC needs enc_len, rel_buckets, rel_max_dist");
+  if (c.arch == SD_ARCH_T5DEC && c.rel_buckets > 64) return bad("at most 64 relative-position buckets");
+  if (c.arch == SD_ARCH_T5DEC && c.max_len > ATTN_LDS_DIST - 64) return bad("max_len too large for the relative-position table");
   if (c.arch != SD_ARCH_T5DEC && c.enc_len != 0) return bad("enc_len only for T5DEC");
   if (!(c.norm_eps > 0.0f)) return bad("norm_eps must be positive");
   return true;
@@ -209,8 +212,13 @@ void launch_gemm_t(hipStream_t s, GemmArgs a) {
   const int S = pick_waves(tiles, KS);
   a.ksteps_per_wave = (KS + S - 1) / S;
   const int ND = (EPI == EPI_GATED) ? 2 : 1;
-  const size_t lds = (size_t)(S * ND * 256 + S * 16 + ND * 256) * sizeof(float);
-  hipLaunchKernelGGL((gemm_kernel<T, PRO, EPI>), dim3(tiles), dim3(64 * S), lds, s, a);
+  const size_t lds = (size_t)(2 * S * ND * 256 + S * 16 + 256) * sizeof(float);
+  // one resident workgroup of 8 wavefronts per CU (more only when they are smaller), each
+  // taking the same number of tiles
+  const int capacity = g_num_cus * std::max(1, 8 / S);
+  const int per_wg = (tiles + capacity - 1) / capacity;
+  const int grid = (tiles + per_wg - 1) / per_wg;
+  hipLaunchKernelGGL((gemm_kernel<T, PRO, EPI>), dim3(grid), dim3(64 * S), lds, s, a);
 }
 
 template <typename T>
@@ -224,8 +232,8 @@ void launch_gemm(hipStream_t s, int pro, int epi, const GemmArgs& a) {
 }
 
 size_t attn_lds_bytes(int RG, int DH) {
-  const int NG = ATTN_THREADS / DH;
-  return (size_t)(RG * DH + RG * ATTN_BLOCK + NG * MAX_ROWS * DH + 3 * RG + RG * DH) * sizeof(float);
+  return (size_t)(RG * DH + RG * attn_block_keys(DH) + (ATTN_THREADS / 64) * attn_rows_per_pass(DH) * DH +
+                  3 * RG + RG * DH) * sizeof(float);
 }
 
 template <typename T>
@@ -292,7 +300,7 @@ void forward(sd_ctx* c, Model& m, int mode, int step, int R, int start, int row0
     g.rope = m.rope;
     launch_gemm<T>(s, pro, EPI_QKV, g);
     AttnArgs a{};
-    a.q = m.qbuf; a.out = m.attn; a.kv_pool = l.kv; a.page_table = m.page_table; a.page_size = m.page_size;
+    a.q = m.qbuf; a.out = m.attn; a.kv_pool = l.kv; a.page_table = m.page_table; a.page_size = m.page_size; a.n_pages = m.n_pages;
     a.row_pos = m.row_pos; a.R = R; a.H = f.n_heads; a.Hkv = f.n_kv_heads; a.cross = 0; a.kv_len = 0;
     a.scale = (f.arch == SD_ARCH_T5DEC) ? 1.0f : 1.0f / sqrtf((float)f.d_head);
     a.rel_bias = m.rel_bias; a.bucket_lut = m.bucket_lut; a.rel_buckets = f.rel_buckets;
@@ -351,8 +359,8 @@ void cross_kv(sd_ctx* c, Model& m, const void* enc) {
         g.W = which ? l.cv : l.ck;
         g.X = static_cast<const char*>(enc) + (size_t)r0 * f.d_model * m.esz;
         g.K = f.d_model; g.N = m.nq;
-        g.out = static_cast<char*>(which ? l.cross_v : l.cross_k) + (size_t)r0 * m.nq * m.esz;
-        g.ldo = m.nq;
+        g.out = which ? l.cross_v : l.cross_k;       // [head][enc_len][d_head]: one contiguous block per head
+        g.hm_rows = f.enc_len; g.hm_row0 = r0; g.d_head = f.d_head;
         launch_gemm<T>(c->stream, PRO_NONE, EPI_STORE, g);
       }
 }
@@ -527,6 +535,8 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
   if ((rt->max_gamma + 1) * (p_cfg->n_heads / p_cfg->n_kv_heads) > ATTN_MAX_RG ||
       2 * (q_cfg->n_heads / q_cfg->n_kv_heads) > ATTN_MAX_RG)
     return fail(nullptr, SD_EINVAL, "(max_gamma+1) x (query heads per kv head) exceeds the attention kernel's limit");
+  if ((std::max(p_cfg->max_len, q_cfg->max_len) + rt->page_size - 1) / rt->page_size > ATTN_LDS_PAGES)
+    return fail(nullptr, SD_EINVAL, "max_len / page_size exceeds the attention kernel's page-table cache");
   if (!rt->workspace || (reinterpret_cast<uintptr_t>(rt->workspace) & 255)) return fail(nullptr, SD_EINVAL, "workspace must be 256-byte aligned");
   const size_t need = sd_workspace_bytes(p_cfg, q_cfg, rt);
   if (rt->workspace_bytes < need) return fail(nullptr, SD_ENOMEM, "workspace too small: need " + std::to_string(need));
@@ -545,6 +555,12 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
       hipHostMalloc(reinterpret_cast<void**>(&c->h_params), sizeof(StepParams), hipHostMallocDefault) != hipSuccess)
     return bail(SD_EHIP, "pinned allocation failed");
   for (auto& e : c->ev) if (hipEventCreate(&e) != hipSuccess) return bail(SD_EHIP, "event creation failed");
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      g_num_cus = cus;
+  }
   if (allow_big_lds<bf16>() != hipSuccess || allow_big_lds<float>() != hipSuccess) return bail(SD_EHIP, "cannot raise the LDS limit");
   std::string err;
   sd_status st = (p_cfg->dtype == SD_BF16) ? load_model<bf16>(c->stream, c->p, p_w, n_p, err)
@@ -734,5 +750,11 @@ extern "C" sd_status sd_get_stats(sd_ctx* c, sd_stats* out) {
   *out = c->stats;
   return SD_OK;
 }
+
+#ifdef SD_KTIME
+extern "C" int sd_debug_ktime(unsigned long long* out64) {
+  return (int)hipMemcpyFromSymbol(out64, HIP_SYMBOL(sd::g_ktime), 64 * sizeof(unsigned long long));
+}
+#endif
 
 #include "spec_sample_api.hip"

