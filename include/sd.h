@@ -109,6 +109,8 @@ typedef struct {
   int64_t tokens;                           /* tokens they produced */
   int64_t accepted;                         /* sum of n */
   int64_t fallbacks;                        /* zero-residual fallbacks taken */
+  double  ffn_in_ms_sum;                    /* SD_FLAG_PROFILE, RMSNorm targets: time between HIP events around */
+  int64_t ffn_in_launches;                  /*   every gated FFN-in GEMM of the verify forwards, and their count */
 } sd_stats;
 
 /* Device bytes sd_load_models needs for this pair (weights, KV caches,
@@ -177,6 +179,8 @@ const char* sd_last_error(const sd_ctx* ctx);
  * sd_step_baseline: [1, vocab].  host_out: host, n floats (n <= rows*vocab). */
 sd_status sd_debug_logits(sd_ctx* ctx, int32_t which, float* host_out, size_t n);
 sd_status sd_get_stats(sd_ctx* ctx, sd_stats* out);
+/* Replace the flags given at load (SD_FLAG_GRAPH, SD_FLAG_PROFILE) for the following calls. */
+sd_status sd_set_flags(sd_ctx* ctx, int32_t flags);
 
 /*
  * The accept / resample part of Algorithm 1 on explicit logits, for `rows`

@@ -75,8 +75,12 @@ def bf16_round(a) -> np.ndarray:
 
 
 def bf16_bits_to_f64(u16) -> np.ndarray:
-    """Decode an array of bf16 bit patterns (uint16) to float64."""
+    """Decode an array of bf16 bit patterns (uint16) to float64 (exact).  Large
+    arrays go through torch's CPU conversion, which is multi-threaded."""
     u = np.ascontiguousarray(np.asarray(u16, dtype=np.uint16))
+    if u.size >= (1 << 20):
+        import torch
+        return torch.from_numpy(u.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
     return (u.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
@@ -94,11 +98,6 @@ def layer_norm(x, gain, bias, eps):
     mu = x.mean(axis=-1, keepdims=True)
     var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
     return (x - mu) / np.sqrt(var + eps) * gain + bias
-
-
-def rms_norm(x, gain, eps):
-    ms = (x ** 2).mean(axis=-1, keepdims=True)
-    return x / np.sqrt(ms + eps) * gain
 
 
 def gelu_tanh(x):
@@ -180,7 +179,16 @@ class Transformer:
         return to_f64(a)
 
     def linear(self, x, wname, bname=None):
-        y = x @ self.W(wname).T
+        """x @ W^T (+ bias).  A big weight is decoded and multiplied in blocks of
+        output features, so its float64 copy never exists as a whole; every
+        output element is still one full-length dot product."""
+        a = self.wt[wname]
+        if a.size <= (1 << 22):
+            y = x @ self.W(wname).T
+        else:
+            y = np.empty((x.shape[0], a.shape[0]))
+            for r0 in range(0, a.shape[0], 2048):
+                y[:, r0:r0 + 2048] = x @ to_f64(a[r0:r0 + 2048]).T
         if bname is not None:
             y = y + self.W(bname)
         return y
@@ -240,9 +248,9 @@ class Transformer:
         pos = np.arange(start_pos, start_pos + M)
         if start_pos + M > c.max_len:
             raise ValueError("sequence exceeds max_len")
-        x = self.W("tok_emb")[tokens]
+        x = to_f64(np.asarray(self.wt["tok_emb"])[tokens])          # decode only the rows that are used
         if c.arch == GPT:
-            x = x + self.W("pos_emb")[pos]
+            x = x + to_f64(np.asarray(self.wt["pos_emb"])[pos])
         scale = 1.0 if c.arch == T5DEC else 1.0 / np.sqrt(c.d_head)
         L = start_pos + M
         bias = None

@@ -99,7 +99,8 @@ class _RuntimeCfg(C.Structure):
 
 class _Stats(C.Structure):
     _fields_ = [("draft_ms", C.c_double), ("verify_ms", C.c_double), ("accept_ms", C.c_double),
-                ("steps", C.c_int64), ("tokens", C.c_int64), ("accepted", C.c_int64), ("fallbacks", C.c_int64)]
+                ("steps", C.c_int64), ("tokens", C.c_int64), ("accepted", C.c_int64), ("fallbacks", C.c_int64),
+                ("ffn_in_ms_sum", C.c_double), ("ffn_in_launches", C.c_int64)]
 
 
 lib.sd_workspace_bytes.restype = C.c_size_t
@@ -124,6 +125,8 @@ lib.sd_debug_logits.restype = C.c_int
 lib.sd_debug_logits.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float), C.c_size_t]
 lib.sd_get_stats.restype = C.c_int
 lib.sd_get_stats.argtypes = [C.c_void_p, C.POINTER(_Stats)]
+lib.sd_set_flags.restype = C.c_int
+lib.sd_set_flags.argtypes = [C.c_void_p, C.c_int32]
 
 
 def _cfg_struct(cfg: dict) -> _ModelCfg:
@@ -222,6 +225,9 @@ class SpecDecoder:
         s = _Stats()
         self._check(lib.sd_get_stats(self._ctx, C.byref(s)))
         return {k: getattr(s, k) for k, _ in _Stats._fields_}
+
+    def set_flags(self, flags: int):
+        self._check(lib.sd_set_flags(self._ctx, int(flags)))
 
     def reset(self):
         self._check(lib.sd_reset(self._ctx, -1))

@@ -16,6 +16,10 @@
 //    partial tiles are added through LDS in wave order 0..S-1.  S depends on
 //    (N, K) only, never on R, so a row's result is bit-identical whether it is
 //    computed alone or among gamma+1 rows.
+//  * Vector-memory loads complete in issue order as far as the wait counter can
+//    tell, so the kernel keeps them branch-free and issues whatever the epilogue
+//    reads (residual, bias, gain, rotary table) BEFORE the prefetch of the next
+//    chunk; otherwise every epilogue would drain the prefetch.
 //  * RMSNorm is folded around the GEMM: the producer of the residual stream
 //    (embedding or a residual-add epilogue) also writes xg = x * gain of the
 //    next norm in the storage type and, per 16-feature tile, the partial sums
@@ -73,12 +77,17 @@ template <> struct Mma<bf16> {
   static __device__ __forceinline__ Frag load_stream(const bf16* p) {
     return __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p));
   }
-  static __device__ __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f[e] = (bf16)0.0f; return f; }
   static __device__ __forceinline__ Frag from_floats(const float (&v)[8]) {
     Frag f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) f[e] = (bf16)v[e];
     return f;
+  }
+  static __device__ __forceinline__ Frag select(bool keep, const Frag& f) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 bits = __builtin_bit_cast(u32x4, f);
+    const unsigned m = keep ? 0xFFFFFFFFu : 0u;
+    return __builtin_bit_cast(Frag, bits & m);
   }
   static __device__ __forceinline__ f32x4 mma(const Frag& a, const Frag& b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -88,12 +97,17 @@ template <> struct Mma<float> {
   struct Frag { float v[8]; };
   static __device__ __forceinline__ Frag load(const float* p) { Frag f; load8<float>(p, f.v); return f; }
   static __device__ __forceinline__ Frag load_stream(const float* p) { return load(p); }
-  static __device__ __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f.v[e] = 0.0f; return f; }
   static __device__ __forceinline__ Frag from_floats(const float (&v)[8]) {
     Frag f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) f.v[e] = v[e];
     return f;
+  }
+  static __device__ __forceinline__ Frag select(bool keep, const Frag& f) {
+    Frag r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r.v[e] = keep ? f.v[e] : 0.0f;
+    return r;
   }
   // eight 16x16x4 steps; step e contracts the k indices {kq*8 + e}, the same
   // set on both operands
@@ -113,8 +127,9 @@ __device__ __forceinline__ float silu(float x) { return x / (1.0f + expf(-x)); }
 #define SD_EXP_UNROLL 8
 #endif
 constexpr int GEMM_UNROLL = SD_EXP_UNROLL;
-constexpr int GEMM_MAX_PART_LOADS = 64;     // n_part <= 16 * 64 (d_model <= 16384)
+constexpr int GEMM_PART_REGS = 16;          // partial sums of x^2 held in registers: n_part <= 256
 
+// Launched with 4 or 8 wavefronts; threads 0..255 (t = row * 16 + feature) run the epilogue.
 template <typename T, int PRO, int EPI>
 static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   extern __shared__ float lds[];
@@ -131,29 +146,22 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   float* stat = lds + 2 * S * ND * 256;              // [S][16]
   float* ybuf = stat + S * 16;                       // [256]
   const bool row_ok = (j < a.R);
-
-  // ---- PRO_POST: start fetching the partial sums of x^2; used in the epilogue.
-  // Epilogue thread t = (row t/16, feature t%16) adds the partials p = t%16 (mod 16).
-  float ssq = 0.0f;
-  if (PRO == PRO_POST && tid < 256) {
-    const int row = tid >> 4, f = tid & 15;
-    for (int p = f; p < a.n_part; p += 16) ssq += a.ss_in[p * 16 + row];
-  }
+  const bool epi_thread = tid < 256;
+  const int e_row = (tid >> 4) & 15, e_f = tid & 15;  // epilogue role of this thread
+  const int e_rowc = min(e_row, a.R - 1);             // clamped: loads stay in bounds
 
   // ---- PRO_LN: statistics of the fp32 rows, reduced across the workgroup ----
   float mu = 0.0f, rstd = 1.0f;
   if (PRO == PRO_LN) {
-    const float* x = static_cast<const float*>(a.X) + (size_t)j * a.K + kq * 8;
+    const float* x = static_cast<const float*>(a.X) + (size_t)min(j, a.R - 1) * a.K + kq * 8;
     float s = 0.0f;
-    if (row_ok) {
 #pragma unroll 4
-      for (int ks = ks0; ks < ks1; ++ks) {
-        float v[8]; load8<float>(x + ks * 32, v);
+    for (int ks = ks0; ks < ks1; ++ks) {
+      float v[8]; load8<float>(x + ks * 32, v);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) s += v[e];
-      }
+      for (int e = 0; e < 8; ++e) s += v[e];
     }
-    s += __shfl_xor(s, 16, WAVE); s += __shfl_xor(s, 32, WAVE);
+    s = lane_combine<16>(s, OpSumF()); s = lane_combine<32>(s, OpSumF());
     if (kq == 0) stat[wave * 16 + j] = s;
     __syncthreads();
     float t = 0.0f;
@@ -161,15 +169,13 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     mu = t / (float)a.K;
     __syncthreads();
     float s2 = 0.0f;
-    if (row_ok) {
 #pragma unroll 4
-      for (int ks = ks0; ks < ks1; ++ks) {
-        float v[8]; load8<float>(x + ks * 32, v);
+    for (int ks = ks0; ks < ks1; ++ks) {
+      float v[8]; load8<float>(x + ks * 32, v);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { const float d = v[e] - mu; s2 += d * d; }
-      }
+      for (int e = 0; e < 8; ++e) { const float d = v[e] - mu; s2 += d * d; }
     }
-    s2 += __shfl_xor(s2, 16, WAVE); s2 += __shfl_xor(s2, 32, WAVE);
+    s2 = lane_combine<16>(s2, OpSumF()); s2 = lane_combine<32>(s2, OpSumF());
     if (kq == 0) stat[wave * 16 + j] = s2;
     __syncthreads();
     float t2 = 0.0f;
@@ -180,24 +186,29 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   typedef typename Mma<T>::Frag Frag;
   struct Buf { Frag fa[ND][U]; Frag fb[U]; };
 
-  auto make_b = [&](int ks) -> Frag {
-    if (!row_ok) return Mma<T>::zero();
+  // All loads are unconditional: a branch around a load makes the compiler wait
+  // for every outstanding load before the next multiply, which would undo the
+  // pipelining.  Out-of-range rows / k-steps re-read a valid address and are
+  // replaced by zeros with a select when they are used.
+  const int jr = min(j, a.R - 1);
+  auto make_b = [&](int ks, bool valid) -> Frag {
     const int k = ks * 32 + kq * 8;
     if (PRO != PRO_LN) {
-      return Mma<T>::load(static_cast<const T*>(a.X) + (size_t)j * a.K + k);
+      return Mma<T>::load(static_cast<const T*>(a.X) + (size_t)jr * a.K + k);
     } else {
       float v[8], g[8], bb[8];
-      load8<float>(static_cast<const float*>(a.X) + (size_t)j * a.K + k, v);
+      load8<float>(static_cast<const float*>(a.X) + (size_t)jr * a.K + k, v);
       load8<T>(static_cast<const T*>(a.gain) + k, g);
       load8<T>(static_cast<const T*>(a.beta) + k, bb);
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = (v[e] - mu) * rstd * g[e] + bb[e];
-      return Mma<T>::from_floats(v);
+      return Mma<T>::select(valid && row_ok, Mma<T>::from_floats(v));
     }
   };
 
   // chunk g of this workgroup's work list: tile blockIdx.x + (g / nchunks) * gridDim.x,
   // k-steps ks0 + (g % nchunks) * U ... of this wave's K-slice
+  const int ks_last = max(ks1 - 1, 0);
   auto load_chunk = [&](Buf& b, int g) {
     const int ti = g / nchunks, c = g - ti * nchunks;
     const size_t tile = (size_t)blockIdx.x + (size_t)ti * gridDim.x;
@@ -206,15 +217,50 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int ks = ks0 + c * U + u;
-      if (ks < ks1) {
-        b.fa[0][u] = Mma<T>::load_stream(w0 + (size_t)ks * 512);
-        if (ND == 2) b.fa[ND - 1][u] = Mma<T>::load_stream(w1 + (size_t)ks * 512);
-        b.fb[u] = make_b(ks);
-      } else {
-        b.fa[0][u] = Mma<T>::zero();
-        if (ND == 2) b.fa[ND - 1][u] = Mma<T>::zero();
-        b.fb[u] = Mma<T>::zero();
-      }
+      const int ksc = min(ks, ks_last);
+      b.fa[0][u] = Mma<T>::load_stream(w0 + (size_t)ksc * 512);
+      if (ND == 2) b.fa[ND - 1][u] = Mma<T>::load_stream(w1 + (size_t)ksc * 512);
+      b.fb[u] = make_b(ksc, ks < ks1);
+    }
+  };
+
+  const int G = my_tiles * nchunks;
+  Buf b0, b1;
+  if (G > 0) load_chunk(b0, 0);
+
+  // ---- values the epilogue needs that do not depend on the tile ----
+  float sp[GEMM_PART_REGS];                      // PRO_POST: partial sums p = e_f, e_f + 16, ...
+  if (PRO == PRO_POST && epi_thread) {
+#pragma unroll
+    for (int u = 0; u < GEMM_PART_REGS; ++u) {
+      const int p = e_f + 16 * u;
+      const float v = a.ss_in[min(p, a.n_part - 1) * 16 + e_rowc];
+      sp[u] = (p < a.n_part) ? v : 0.0f;
+    }
+  }
+  int e_pos = -1;
+  size_t e_kvbase = 0;                            // EPI_QKV: cache offset of this row's page / slot
+  if (EPI == EPI_QKV && epi_thread) {
+    e_pos = (e_row < a.R) ? a.row_pos[e_rowc] : -1;
+    const int pc = max(e_pos, 0);
+    const int page = a.page_table[pc / a.page_size], slot = pc % a.page_size;
+    e_kvbase = (size_t)page * 2 * a.n_kv_heads * a.page_size * a.d_head + (size_t)slot * a.d_head;
+  }
+
+  // ---- per-tile epilogue inputs, issued before the prefetch of the next chunk ----
+  float pre_res = 0.0f, pre_bias = 0.0f, pre_gain = 0.0f, pre_cos = 1.0f, pre_sin = 0.0f;
+  auto prefetch_epilogue = [&](int ti) {
+    if (!epi_thread) return;
+    const int n = ((int)blockIdx.x + ti * (int)gridDim.x) * 16 + e_f;
+    if (a.bias != nullptr) pre_bias = Store<T>::ld(static_cast<const T*>(a.bias) + n);
+    if (EPI == EPI_RESID) {
+      pre_res = static_cast<const float*>(a.out)[(size_t)e_rowc * a.ldo + n];
+      if (a.xg_out != nullptr) pre_gain = Store<T>::ld(static_cast<const T*>(a.gain_next) + n);
+    }
+    if (EPI == EPI_QKV && a.rope != nullptr) {
+      const int nn = (n < a.nq) ? n : (n < a.nq + a.nkv ? n - a.nq : n - a.nq - a.nkv);
+      const float* cs = a.rope + ((size_t)max(e_pos, 0) * (a.d_head >> 1) + ((nn % a.d_head) >> 1)) * 2;
+      pre_cos = cs[0]; pre_sin = cs[1];
     }
   };
 
@@ -234,8 +280,8 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
       acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     __syncthreads();
-    // Epilogue threads: t = row * 16 + feature, t < 256.
-    for (int t = tid; t < 256; t += blockDim.x) {
+    if (epi_thread) {
+      const int t = tid, row = e_row, f = e_f, n = tile * 16 + f;
       float y[ND];
 #pragma unroll
       for (int d = 0; d < ND; ++d) {
@@ -243,36 +289,31 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         for (int w = 0; w < S; ++w) s += pt[(w * ND + d) * 256 + t];
         y[d] = s;
       }
-      const int row = t >> 4, f = t & 15, n = tile * 16 + f;
       if (PRO == PRO_POST) {
-        float q = ssq;
-        if (blockDim.x < 256) {                     // small workgroup: this thread serves several t
-          q = 0.0f;
-          for (int p = f; p < a.n_part; p += 16) q += a.ss_in[p * 16 + row];
-        }
-        q += __shfl_xor(q, 1, WAVE); q += __shfl_xor(q, 2, WAVE);
-        q += __shfl_xor(q, 4, WAVE); q += __shfl_xor(q, 8, WAVE);
+        float q = 0.0f;
+#pragma unroll
+        for (int u = 0; u < GEMM_PART_REGS; ++u) q += sp[u];
+        for (int p = f + 16 * GEMM_PART_REGS; p < a.n_part; p += 16) q += a.ss_in[p * 16 + e_rowc];
+        q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+        q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
         const float rs = 1.0f / sqrtf(q / (float)a.K + a.eps);
 #pragma unroll
         for (int d = 0; d < ND; ++d) y[d] *= rs;
       }
-      if (a.bias != nullptr) y[0] += Store<T>::ld(static_cast<const T*>(a.bias) + n);
+      y[0] += pre_bias;
       if (EPI == EPI_QKV) {
         ybuf[t] = y[0];
       } else if (EPI == EPI_RESID) {
         float xn = 0.0f;
         if (row < a.R) {
-          float* o = static_cast<float*>(a.out) + (size_t)row * a.ldo + n;
-          xn = *o + y[0];
-          *o = xn;
-          if (a.xg_out != nullptr)
-            Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n,
-                         xn * Store<T>::ld(static_cast<const T*>(a.gain_next) + n));
+          xn = pre_res + y[0];
+          static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = xn;
+          if (a.xg_out != nullptr) Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * pre_gain);
         }
         if (a.ss_out != nullptr) {
           float q = xn * xn;
-          q += __shfl_xor(q, 1, WAVE); q += __shfl_xor(q, 2, WAVE);
-          q += __shfl_xor(q, 4, WAVE); q += __shfl_xor(q, 8, WAVE);
+          q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+          q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
           if (f == 0) a.ss_out[tile * 16 + row] = q;
         }
       } else if (row < a.R) {
@@ -294,25 +335,20 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     }
     if (EPI == EPI_QKV) {
       __syncthreads();
-      for (int t = tid; t < 256; t += blockDim.x) {
-        const int row = t >> 4, f = t & 15, n = tile * 16 + f;
-        if (row >= a.R) continue;
-        const int pos = a.row_pos[row];
+      if (epi_thread && e_row < a.R) {
+        const int t = tid, n = tile * 16 + e_f;
         float y = ybuf[t];
         const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
         const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
         const int head = nn / a.d_head, d = nn % a.d_head;
-        if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
+        if (a.rope != nullptr && (is_q || is_k) && e_pos >= 0) {
           const float other = ybuf[t ^ 1];
-          const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
-          y = (d & 1) ? (other * cs[1] + y * cs[0]) : (y * cs[0] - other * cs[1]);
+          y = (d & 1) ? (other * pre_sin + y * pre_cos) : (y * pre_cos - other * pre_sin);
         }
         if (is_q) {
-          Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
-        } else if (pos >= 0) {
-          const int page = a.page_table[pos / a.page_size], slot = pos % a.page_size;
-          const size_t idx = ((((size_t)page * 2 + (is_k ? 0 : 1)) * a.n_kv_heads + head) * a.page_size + slot) *
-                                 a.d_head + d;
+          Store<T>::st(static_cast<T*>(a.q_out) + (size_t)e_row * a.nq + n, y);
+        } else if (e_pos >= 0) {
+          const size_t idx = e_kvbase + ((size_t)(is_k ? 0 : 1) * a.n_kv_heads + head) * a.page_size * a.d_head + d;
           Store<T>::st(static_cast<T*>(a.kv_pool) + idx, y);
         }
       }
@@ -320,26 +356,35 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   };
 
   auto compute_chunk = [&](const Buf& b, int g) {
+    const int ti = g / nchunks, c = g - ti * nchunks;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      acc[0] = Mma<T>::mma(b.fa[0][u], b.fb[u], acc[0]);
-      if (ND == 2) acc[ND - 1] = Mma<T>::mma(b.fa[ND - 1][u], b.fb[u], acc[ND - 1]);
+      const bool valid = (ks0 + c * U + u < ks1) && row_ok;
+      const Frag fb = (PRO == PRO_LN) ? b.fb[u] : Mma<T>::select(valid, b.fb[u]);
+      acc[0] = Mma<T>::mma(b.fa[0][u], fb, acc[0]);
+      if (ND == 2) acc[ND - 1] = Mma<T>::mma(b.fa[ND - 1][u], fb, acc[ND - 1]);
     }
+    if (c == nchunks - 1) finish_tile(ti);
+  };
+  // chunk g closes its tile: fetch what that tile's epilogue reads, before the
+  // loads of chunk g + 1 go out
+  auto before_prefetch = [&](int g) {
     const int ti = g / nchunks;
-    if (g - ti * nchunks == nchunks - 1) finish_tile(ti);
+    if (g - ti * nchunks == nchunks - 1) prefetch_epilogue(ti);
   };
 
   // ---- software pipeline over the work list: the loads of chunk g+1 (possibly
   // the first chunk of the next tile) are in flight while chunk g is multiplied
   // and while a finished tile is reduced and written out ----
-  const int G = my_tiles * nchunks;
-  Buf b0, b1;
-  if (G > 0) load_chunk(b0, 0);
   for (int g = 0; g < G; g += 2) {
+    before_prefetch(g);
     if (g + 1 < G) load_chunk(b1, g + 1);
     compute_chunk(b0, g);
-    if (g + 2 < G) load_chunk(b0, g + 2);
-    if (g + 1 < G) compute_chunk(b1, g + 1);
+    if (g + 1 < G) {
+      before_prefetch(g + 1);
+      if (g + 2 < G) load_chunk(b0, g + 2);
+      compute_chunk(b1, g + 1);
+    }
   }
 }
 

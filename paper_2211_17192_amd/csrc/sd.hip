@@ -163,6 +163,8 @@ struct sd_ctx {
   hipGraphExec_t graphs[SD_MAX_GAMMA + 1] = {};
   hipGraphExec_t graph_baseline = nullptr;
   hipEvent_t ev[4] = {};
+  std::vector<hipEvent_t> kev;       // 2 per Mp layer: around the gated FFN-in GEMM (SD_FLAG_PROFILE)
+  bool time_ffn = false;             // set while the verify forward of a profiled step is enqueued
   sd_stats stats{};
   std::string err;
 };
@@ -200,16 +202,14 @@ sd_status fail(sd_ctx* c, sd_status s, const std::string& msg) {
   } while (0)
 
 // ------------------------------------------------------------------ launches
-int pick_waves(int tiles, int ksteps) {
-  int S = 1;
-  while (S < 8 && tiles * S < 4096 && ksteps / (S * 2) >= 4) S *= 2;
-  return S;
-}
+// Wavefronts per workgroup (they split K): 8 when each still gets a full chunk of
+// k-steps, else 4.  Depends on K only, so a row's reduction order never changes.
+int pick_waves(int ksteps) { return (ksteps >= 8 * GEMM_UNROLL) ? 8 : 4; }
 
 template <typename T, int PRO, int EPI>
 void launch_gemm_t(hipStream_t s, GemmArgs a) {
   const int tiles = a.N / 16, KS = a.K / 32;
-  const int S = pick_waves(tiles, KS);
+  const int S = pick_waves(KS);
   a.ksteps_per_wave = (KS + S - 1) / S;
   const int ND = (EPI == EPI_GATED) ? 2 : 1;
   const size_t lds = (size_t)(2 * S * ND * 256 + S * 16 + 256) * sizeof(float);
@@ -327,7 +327,10 @@ void forward(sd_ctx* c, Model& m, int mode, int step, int R, int start, int row0
       launch_gemm<T>(s, PRO_LN, EPI_ACT, h);
     } else {
       h.W2 = l.wu; h.act = (f.arch == SD_ARCH_T5DEC) ? ACT_GELU : ACT_SILU;
+      const bool timed = c->time_ffn && &m == &c->p && 2 * li + 1 < (int)c->kev.size();
+      if (timed) hipEventRecord(c->kev[2 * li], s);
       launch_gemm<T>(s, PRO_POST, EPI_GATED, h);
+      if (timed) hipEventRecord(c->kev[2 * li + 1], s);
     }
     resid(l.w2, m.ffn, l.b2, f.d_ff, (li + 1 < n_layers) ? m.L[li + 1].ln1g : m.lnfg);
   }
@@ -380,7 +383,9 @@ void enqueue_step(sd_ctx* c, int gamma, bool profile) {
   }
   if (profile) hipEventRecord(c->ev[1], s);
   // p_1..p_{gamma+1} in one forward
+  c->time_ffn = profile;
   forward_any(c, c->p, ROWS_VERIFY, 0, gamma + 1, 0, 0, gamma + 1, c->p_logits);
+  c->time_ffn = false;
   if (profile) hipEventRecord(c->ev[2], s);
   hipLaunchKernelGGL(spec_verify_kernel, dim3(2 * gamma + 1, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
                      c->q_logits, (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V,
@@ -555,6 +560,10 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
       hipHostMalloc(reinterpret_cast<void**>(&c->h_params), sizeof(StepParams), hipHostMallocDefault) != hipSuccess)
     return bail(SD_EHIP, "pinned allocation failed");
   for (auto& e : c->ev) if (hipEventCreate(&e) != hipSuccess) return bail(SD_EHIP, "event creation failed");
+  if (p_cfg->arch != SD_ARCH_GPT) {
+    c->kev.assign(2 * (size_t)p_cfg->n_layers, nullptr);
+    for (auto& e : c->kev) if (hipEventCreate(&e) != hipSuccess) return bail(SD_EHIP, "event creation failed");
+  }
   {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
@@ -583,6 +592,7 @@ extern "C" void sd_free(sd_ctx* c) {
   for (auto& g : c->graphs) if (g) hipGraphExecDestroy(g);
   if (c->graph_baseline) hipGraphExecDestroy(c->graph_baseline);
   for (auto& e : c->ev) if (e) hipEventDestroy(e);
+  for (auto& e : c->kev) if (e) hipEventDestroy(e);
   if (c->h_state) hipHostFree(c->h_state);
   if (c->h_params) hipHostFree(c->h_params);
   if (c->own_stream && c->stream) hipStreamDestroy(c->stream);
@@ -690,6 +700,10 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
     hipEventElapsedTime(&a, c->ev[0], c->ev[1]); hipEventElapsedTime(&b, c->ev[1], c->ev[2]);
     hipEventElapsedTime(&d, c->ev[2], c->ev[3]);
     c->stats.draft_ms = a; c->stats.verify_ms = b; c->stats.accept_ms = d;
+    for (size_t i = 0; i + 1 < c->kev.size(); i += 2) {
+      float k = 0;
+      if (hipEventElapsedTime(&k, c->kev[i], c->kev[i + 1]) == hipSuccess) { c->stats.ffn_in_ms_sum += k; c->stats.ffn_in_launches += 1; }
+    }
   }
   return SD_OK;
 }
@@ -742,6 +756,13 @@ extern "C" sd_status sd_debug_logits(sd_ctx* c, int32_t which, float* host_out, 
   else return fail(c, SD_ESTATE, "no such logits from the last call");
   if (n > rows * V) return fail(c, SD_EINVAL, "more floats requested than the last call produced");
   HIP_TRY(c, hipMemcpy(host_out, src, n * sizeof(float), hipMemcpyDeviceToHost));
+  return SD_OK;
+}
+
+extern "C" sd_status sd_set_flags(sd_ctx* c, int32_t flags) {
+  if (!c) return SD_EINVAL;
+  if (flags & ~(SD_FLAG_GRAPH | SD_FLAG_PROFILE)) return fail(c, SD_EINVAL, "unknown flag");
+  c->rt.flags = flags;
   return SD_OK;
 }
 

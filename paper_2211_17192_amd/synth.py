@@ -235,8 +235,8 @@ def correlated_pair(cfg_p: dict, cfg_q: dict, seed: int, device="cpu", emb_rms: 
     return w_p, cfg_q, w_q
 
 
-def t5xxl_pair(device="cuda", seed: int = 4, gen_len: int = 128, emb_rms: float = 4.0,
-               head_std: float = 0.02, logit_scale: float = 1.0, q_logit_gain: float = 1.0):
+def t5xxl_pair(device="cuda", seed: int = 4, gen_len: int = 128, emb_rms: float = 32.0,
+               head_std: float = 0.1, logit_scale: float = 1.0, q_logit_gain: float = 1.0):
     """T5-XXL-shaped decoder (24 layers, d_model 4096, 64 heads x 64, d_ff 10240
     gated-GELU, vocab 32128, 512 encoder positions) with a T5-small-shaped draft
     (6 layers, d_model 512, 8 heads x 64, d_ff 2048), bf16, random init.  The
