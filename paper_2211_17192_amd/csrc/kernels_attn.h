@@ -5,7 +5,8 @@
 // QKV projection just before) or to a fixed block of encoder keys
 // (cross-attention).
 //
-// One workgroup of 1024 threads owns one kv head and walks its keys in blocks
+// One workgroup of 1024 threads owns one kv head (and a few of the query rows:
+// rows are independent, so splitting them needs no merge) and walks its keys in blocks
 // (512 keys, 256 for d_head 128) with an online softmax (running max m,
 // denominator l, unnormalised output O per row).  There is no split over
 // workgroups and therefore no cross-workgroup merge: device-scope atomics cost
@@ -64,6 +65,7 @@ struct AttnArgs {
   int page_size, n_pages;   // page_size a power of two, n_pages <= ATTN_LDS_PAGES
   const int* row_pos;       // [R]; self: causal limit of each row, < 0 = padding row
   int R, H, Hkv;
+  int rows_per_wg;          // grid.y = ceil(R / rows_per_wg): rows are independent, no merge needed
   int cross;                // 1: cross-attention over kv_len keys, no mask, no bias
   int kv_len;
   float scale;
@@ -87,14 +89,17 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   static_assert((ATTN_THREADS / OCT) * KPT == KB, "P*V mapping must cover the key block");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int hkv = blockIdx.x;
-  const int G = a.H / a.Hkv, RG = a.R * G;
+  // rows are independent: blockIdx.y takes rows [r0, r0 + R) of the launch
+  const int r0 = blockIdx.y * a.rows_per_wg;
+  const int R = min(a.rows_per_wg, a.R - r0);
+  const int G = a.H / a.Hkv, RG = R * G;
 #ifdef SD_KTIME
-  const int kt_base = (a.cross ? 8 : 0) + (a.R > 1 ? 16 : 0) + (a.Hkv > 8 ? 32 : 0);
+  const int kt_base = (a.cross ? 8 : 0) + (R > 1 ? 16 : 0) + (a.Hkv > 8 ? 32 : 0);
   unsigned long long kt_last = wall_clock64();
   if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&g_ktime[kt_base + 7], 1ull);
 #endif
 
-  if (tid < MAX_ROWS) s_pos[tid] = (tid < a.R) ? (a.cross ? 0 : a.row_pos[tid]) : -1;
+  if (tid < MAX_ROWS) s_pos[tid] = (tid < R) ? (a.cross ? 0 : a.row_pos[r0 + tid]) : -1;
   if (!a.cross) for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += ATTN_THREADS) s_pt[i] = a.page_table[i];
   // relative-position bias: table rows and distance -> bucket map into LDS, so
   // the score loop has no global loads
@@ -116,7 +121,7 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   const T* qg = static_cast<const T*>(a.q);
   for (int i = tid; i < RG * DH; i += ATTN_THREADS) {
     const int rg = i / DH, d = i % DH, r = rg / G, h = hkv * G + rg % G;
-    q_s[i] = Store<T>::ld(qg + (size_t)r * a.H * DH + h * DH + d);
+    q_s[i] = Store<T>::ld(qg + (size_t)(r0 + r) * a.H * DH + h * DH + d);
     acc_s[i] = 0.0f;
   }
   if (tid < RG) { m_s[tid] = -INFINITY; l_s[tid] = 0.0f; }
@@ -125,7 +130,7 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   int kv_len = a.kv_len;
   if (!a.cross) {
     int mx = -1;
-    for (int r = 0; r < a.R; ++r) mx = max(mx, s_pos[r]);
+    for (int r = 0; r < R; ++r) mx = max(mx, s_pos[r]);
     kv_len = mx + 1;
   }
   const int page_shift = __ffs(a.page_size) - 1, page_mask = a.page_size - 1;
@@ -267,7 +272,7 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   for (int i = tid; i < RG * DH; i += ATTN_THREADS) {
     const int rg = i / DH, d = i % DH, r = rg / G, h = hkv * G + rg % G;
     const float L = l_s[rg];
-    Store<T>::st(og + (size_t)r * a.H * DH + h * DH + d, (L > 0.0f) ? acc_s[i] / L : 0.0f);
+    Store<T>::st(og + (size_t)(r0 + r) * a.H * DH + h * DH + d, (L > 0.0f) ? acc_s[i] / L : 0.0f);
   }
   SD_STAMP(5);
 }

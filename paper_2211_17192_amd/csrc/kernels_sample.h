@@ -45,49 +45,65 @@ __device__ __forceinline__ float exp_scaled(float z, float m, float invT) {
   return __expf((z - m) * invT);
 }
 
+// A row of up to 32768 entries fits the registers of one 1024-thread workgroup:
+// thread tid holds float4 number it * 1024 + tid, it = 0..7.  In terms of the
+// 256-entry scan chunks, v[it] of wavefront w is lane-slice `lane` of chunk it * 16 + w.
+__device__ __forceinline__ bool row_fits_regs(const float* z, int V) {
+  return ((V & 3) == 0) && ((reinterpret_cast<uintptr_t>(z) & 15) == 0) &&
+         (V <= SAMPLE_REG_F4 * 4 * SAMPLE_THREADS) && (blockDim.x == SAMPLE_THREADS);
+}
+__device__ __forceinline__ void load_row_regs(const float* __restrict__ z, int V, float4 (&v)[SAMPLE_REG_F4]) {
+  const float4* z4 = reinterpret_cast<const float4*>(z);
+  const int n4 = V >> 2, tid = threadIdx.x;
+#pragma unroll
+  for (int it = 0; it < SAMPLE_REG_F4; ++it) {
+    const int i = it * SAMPLE_THREADS + tid;
+    const float4 t = z4[min(i, n4 - 1)];           // unconditional load, padding by select
+    v[it] = (i < n4) ? t : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+  }
+}
+__device__ __forceinline__ RowStat row_stats_regs(const float4 (&v)[SAMPLE_REG_F4], float invT, bool greedy,
+                                                  SampleSmem& sm) {
+  const int tid = threadIdx.x;
+  RowStat st; st.arg = 0; st.S = 0.0;
+  float m = -INFINITY;
+#pragma unroll
+  for (int it = 0; it < SAMPLE_REG_F4; ++it)
+    m = fmaxf(m, fmaxf(fmaxf(v[it].x, v[it].y), fmaxf(v[it].z, v[it].w)));
+  m = block_reduce(m, sm.redf, OpMaxF(), -INFINITY);
+  st.m = m;
+  if (greedy) {
+    int a = INT_MAX;
+#pragma unroll
+    for (int it = SAMPLE_REG_F4 - 1; it >= 0; --it) {
+      const int k = (it * SAMPLE_THREADS + tid) * 4;
+      if (v[it].w == m) a = k + 3;
+      if (v[it].z == m) a = k + 2;
+      if (v[it].y == m) a = k + 1;
+      if (v[it].x == m) a = k;
+    }
+    st.arg = block_reduce(a, sm.redi, OpMinI(), INT_MAX);
+    return st;
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int it = 0; it < SAMPLE_REG_F4; ++it)       // exp(-inf) = 0 for the padding
+    s += (exp_scaled(v[it].x, m, invT) + exp_scaled(v[it].y, m, invT)) +
+         (exp_scaled(v[it].z, m, invT) + exp_scaled(v[it].w, m, invT));
+  st.S = block_reduce((double)s, sm.redd, OpSumD(), 0.0);
+  return st;
+}
+
 // max / argmax / sum-of-exponentials of one logits row; every thread gets it.
 // Rows of up to 32768 entries are read from memory exactly once.
 __device__ __forceinline__ RowStat row_stats(const float* __restrict__ z, int V, float invT,
                                              bool greedy, SampleSmem& sm) {
   const int tid = threadIdx.x, nt = blockDim.x;
   RowStat st; st.arg = 0; st.S = 0.0;
-  const bool vec = ((V & 3) == 0) && ((reinterpret_cast<uintptr_t>(z) & 15) == 0) &&
-                   (V <= SAMPLE_REG_F4 * 4 * nt);
-  if (vec) {
-    const float4* z4 = reinterpret_cast<const float4*>(z);
-    const int n4 = V >> 2;
+  if (row_fits_regs(z, V)) {
     float4 v[SAMPLE_REG_F4];
-#pragma unroll
-    for (int it = 0; it < SAMPLE_REG_F4; ++it) {
-      const int i = it * nt + tid;
-      v[it] = (i < n4) ? z4[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-    }
-    float m = -INFINITY;
-#pragma unroll
-    for (int it = 0; it < SAMPLE_REG_F4; ++it)
-      m = fmaxf(m, fmaxf(fmaxf(v[it].x, v[it].y), fmaxf(v[it].z, v[it].w)));
-    m = block_reduce(m, sm.redf, OpMaxF(), -INFINITY);
-    st.m = m;
-    if (greedy) {
-      int a = INT_MAX;
-#pragma unroll
-      for (int it = SAMPLE_REG_F4 - 1; it >= 0; --it) {
-        const int k = (it * nt + tid) * 4;
-        if (v[it].w == m) a = k + 3;
-        if (v[it].z == m) a = k + 2;
-        if (v[it].y == m) a = k + 1;
-        if (v[it].x == m) a = k;
-      }
-      st.arg = block_reduce(a, sm.redi, OpMinI(), INT_MAX);
-      return st;
-    }
-    float s = 0.0f;
-#pragma unroll
-    for (int it = 0; it < SAMPLE_REG_F4; ++it)       // exp(-inf) = 0 for the padding
-      s += (exp_scaled(v[it].x, m, invT) + exp_scaled(v[it].y, m, invT)) +
-           (exp_scaled(v[it].z, m, invT) + exp_scaled(v[it].w, m, invT));
-    st.S = block_reduce((double)s, sm.redd, OpSumD(), 0.0);
-    return st;
+    load_row_regs(z, V, v);
+    return row_stats_regs(v, invT, greedy, sm);
   }
   float m = -INFINITY;
   for (int i = tid; i < V; i += nt) m = fmaxf(m, z[i]);
@@ -153,6 +169,75 @@ __device__ __forceinline__ void weights4(const RowPair& rp, int k, double (&w)[4
   calc4(rp, k, zp, zq, w);
 }
 
+// Wavefront 0: scan the chunk totals (lane l owns chunks [l*cpl, (l+1)*cpl)), find the
+// chunk in which the cumulative weight first exceeds u * total, and leave in sm:
+// total, chunk (or -1 - last chunk with positive weight when round-off keeps the
+// threshold out of reach) and the cumulative weight before that chunk.
+__device__ __forceinline__ void scan_chunk_totals(int nchunks, float u, SampleSmem& sm) {
+  const int lane = threadIdx.x & 63;
+  const int cpl = (nchunks + 63) / 64;
+  const int c0 = min(nchunks, lane * cpl), c1 = min(nchunks, c0 + cpl);
+  double local = 0.0;
+  for (int c = c0; c < c1; ++c) local += sm.ctot[c];
+  double inc = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const double t = __shfl_up(inc, o, WAVE);
+    if (lane >= o) inc += t;
+  }
+  const double total = __shfl(inc, 63, WAVE);
+  const double theta = (double)u * total;
+  double cum = inc - local;
+  int found = INT_MAX;
+  double before = 0.0;
+  for (int c = c0; c < c1; ++c) {
+    const double nx = cum + sm.ctot[c];
+    if (found == INT_MAX && nx > theta) { found = c; before = cum; }
+    cum = nx;
+  }
+  const int first = wave_min(found);
+  int lastpos = -1;
+  for (int c = c0; c < c1; ++c) if (sm.ctot[c] > 0.0) lastpos = c;
+  lastpos = wave_max(lastpos);
+  if (found == first && first != INT_MAX) { sm.chunk = first; sm.before = before; }
+  if (lane == 0) {
+    sm.total = total;
+    if (first == INT_MAX) { sm.chunk = -1 - lastpos; sm.before = 0.0; }
+  }
+}
+
+// One wavefront: entry by entry scan of a 256-entry chunk (lane holds entries k..k+3 with
+// weights w).  Returns in every lane the first entry whose cumulative weight exceeds theta,
+// or, in fallback mode / if none does, the last entry with positive weight.
+__device__ __forceinline__ int pick_in_chunk(const double (&w)[4], int k, int V, bool fallback, double theta,
+                                             double before) {
+  const int lane = threadIdx.x & 63;
+  const double local = (w[0] + w[1]) + (w[2] + w[3]);
+  double inc = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const double t = __shfl_up(inc, o, WAVE);
+    if (lane >= o) inc += t;
+  }
+  int cand = INT_MAX;
+  if (!fallback) {
+    double cum = before + (inc - local);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      cum += w[e];
+      if (cand == INT_MAX && cum > theta && k + e < V) cand = k + e;
+    }
+    cand = wave_min(cand);
+  }
+  if (cand == INT_MAX) {
+    int lp = -1;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) if (w[e] > 0.0 && k + e < V) lp = k + e;
+    cand = wave_max(lp);
+  }
+  return cand;
+}
+
 // Inverse-CDF draw: smallest k with cumulative weight > u * total weight, in
 // vocabulary order.  Chunks of 256 consecutive entries are summed by one
 // wavefront each (coalesced 1 KB reads), the chunk totals are scanned, and only
@@ -191,38 +276,7 @@ __device__ __forceinline__ int icdf_row(const float* zp, const RowStat& sp, cons
     }
   }
   __syncthreads();
-  if (wave == 0) {
-    // scan the chunk totals: lane l owns chunks [l*cpl, (l+1)*cpl)
-    const int cpl = (nchunks + 63) / 64;
-    const int c0 = min(nchunks, lane * cpl), c1 = min(nchunks, c0 + cpl);
-    double local = 0.0;
-    for (int c = c0; c < c1; ++c) local += sm.ctot[c];
-    double inc = local;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const double t = __shfl_up(inc, o, WAVE);
-      if (lane >= o) inc += t;
-    }
-    const double total = __shfl(inc, 63, WAVE);
-    const double theta = (double)u * total;
-    double cum = inc - local;
-    int found = INT_MAX;
-    double before = 0.0;
-    for (int c = c0; c < c1; ++c) {
-      const double nx = cum + sm.ctot[c];
-      if (found == INT_MAX && nx > theta) { found = c; before = cum; }
-      cum = nx;
-    }
-    const int first = wave_min(found);
-    int lastpos = -1;                         // fallback: last chunk with positive weight
-    for (int c = c0; c < c1; ++c) if (sm.ctot[c] > 0.0) lastpos = c;
-    lastpos = wave_max(lastpos);
-    if (found == first && first != INT_MAX) { sm.chunk = first; sm.before = before; }
-    if (lane == 0) {
-      sm.total = total;
-      if (first == INT_MAX) { sm.chunk = -1 - lastpos; sm.before = 0.0; }
-    }
-  }
+  if (wave == 0) scan_chunk_totals(nchunks, u, sm);
   __syncthreads();
   const double total = sm.total;
   if (!(total > 0.0)) return -1;
@@ -233,31 +287,60 @@ __device__ __forceinline__ int icdf_row(const float* zp, const RowStat& sp, cons
     const int k = c * SAMPLE_CHUNK + lane * 4;
     double w[4];
     weights4(rp, k, w);
-    const double local = (w[0] + w[1]) + (w[2] + w[3]);
-    double inc = local;
+    const int tok = pick_in_chunk(w, k, V, fallback, (double)u * total, sm.before);
+    if (lane == 0) sm.token = tok;
+  }
+  __syncthreads();
+  return sm.token;
+}
+
+// Inverse-CDF draw from rows held in registers (see row_fits_regs for the layout):
+// same arithmetic and summation order as icdf_row, without touching memory.
+__device__ __forceinline__ void weights_of(const float4& zp, const float4& zq, bool with_q, float mp, float mq,
+                                           double invSp, double invSq, float invT, double (&w)[4]) {
+  const float a[4] = {zp.x, zp.y, zp.z, zp.w}, b[4] = {zq.x, zq.y, zq.z, zq.w};
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const double t = __shfl_up(inc, o, WAVE);
-      if (lane >= o) inc += t;
+  for (int e = 0; e < 4; ++e) {
+    double p = (double)exp_scaled(a[e], mp, invT) * invSp;        // padding: exp(-inf) = 0
+    if (with_q) {
+      p -= (double)exp_scaled(b[e], mq, invT) * invSq;
+      p = p > 0.0 ? p : 0.0;
     }
-    int cand = INT_MAX;
-    if (!fallback) {
-      const double theta = (double)u * total;
-      double cum = sm.before + (inc - local);
+    w[e] = p;
+  }
+}
+
+__device__ __forceinline__ int icdf_regs(const float4 (&vp)[SAMPLE_REG_F4], const RowStat& sp,
+                                         const float4 (&vq)[SAMPLE_REG_F4], const RowStat& sq, bool with_q,
+                                         float invT, int V, float u, SampleSmem& sm) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int NW = SAMPLE_THREADS / 64;
+  const double invSp = 1.0 / sp.S, invSq = with_q ? 1.0 / sq.S : 0.0;
+  const int nchunks = (V + SAMPLE_CHUNK - 1) / SAMPLE_CHUNK;
+  __syncthreads();
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        cum += w[e];
-        if (cand == INT_MAX && cum > theta && k + e < V) cand = k + e;
-      }
-      cand = wave_min(cand);
-    }
-    if (cand == INT_MAX) {                    // last entry with positive weight
-      int lp = -1;
+  for (int it = 0; it < SAMPLE_REG_F4; ++it) {
+    const int c = it * NW + wave;
+    double w[4];
+    weights_of(vp[it], vq[it], with_q, sp.m, sq.m, invSp, invSq, invT, w);
+    const double t = wave_sum((w[0] + w[1]) + (w[2] + w[3]));
+    if (lane == 0 && c < nchunks) sm.ctot[c] = t;
+  }
+  __syncthreads();
+  if (wave == 0) scan_chunk_totals(nchunks, u, sm);
+  __syncthreads();
+  const double total = sm.total;
+  if (!(total > 0.0)) return -1;
+  const int chunk = sm.chunk;
+  const bool fallback = chunk < 0;            // threshold not reached by round-off
+  const int c = fallback ? (-1 - chunk) : chunk;
+  if (wave == c % NW) {
+    double w[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) if (w[e] > 0.0 && k + e < V) lp = k + e;
-      cand = wave_max(lp);
-    }
-    if (lane == 0) sm.token = cand;
+    for (int it = 0; it < SAMPLE_REG_F4; ++it)
+      if (it == c / NW) weights_of(vp[it], vq[it], with_q, sp.m, sq.m, invSp, invSq, invT, w);
+    const int tok = pick_in_chunk(w, c * SAMPLE_CHUNK + lane * 4, V, fallback, (double)u * total, sm.before);
+    if (lane == 0) sm.token = tok;
   }
   __syncthreads();
   return sm.token;
@@ -276,10 +359,16 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void sample_row_kernel(
   const float T = prm->temperature;
   const bool greedy = (T == 0.0f);
   const float invT = greedy ? 1.0f : 1.0f / T;
-  const RowStat rs = row_stats(logits, V, invT, greedy, sm);
   int tok;
-  if (greedy) tok = rs.arg;
-  else tok = icdf_row(logits, rs, nullptr, rs, invT, V, prm->uniforms[uniform_idx], sm);
+  if (row_fits_regs(logits, V)) {            // one read of the row: statistics and draw from registers
+    float4 v[SAMPLE_REG_F4];
+    load_row_regs(logits, V, v);
+    const RowStat rs = row_stats_regs(v, invT, greedy, sm);
+    tok = greedy ? rs.arg : icdf_regs(v, rs, v, rs, false, invT, V, prm->uniforms[uniform_idx], sm);
+  } else {
+    const RowStat rs = row_stats(logits, V, invT, greedy, sm);
+    tok = greedy ? rs.arg : icdf_row(logits, rs, nullptr, rs, invT, V, prm->uniforms[uniform_idx], sm);
+  }
   if (threadIdx.x == 0) {
     if (mode == 0) {
       st->x[slot] = tok;
@@ -307,6 +396,11 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void sample_row_kernel(
 // x, r, s: explicit arrays [rows, gamma] / [rows] or, when prm/st are given,
 // taken from the device-resident step parameters and state.
 // ---------------------------------------------------------------------------
+// MODE 0: everything in one launch (ticket).  MODE 1: row statistics only.  MODE 2: the
+// per-sequence tail only, grid (1, rows).  A device-scope atomic costs about 0.08 us of
+// chip-wide throughput, so with many sequences two launches (1 + 2) beat rows * (2*gamma+1)
+// tickets; with one sequence the single launch wins.
+template <int MODE>
 static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
     const float* __restrict__ p_logits, const float* __restrict__ q_logits,
     const int* __restrict__ x_in, const float* __restrict__ r_in, const float* __restrict__ s_in,
@@ -324,14 +418,14 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
   const float* Q = q_logits + (size_t)b * gamma * V;
   RowStat* my_stats = stats + (size_t)b * nrows;
 
-  if (!(greedy && j > gamma)) {          // argmax sampling never looks at q rows
+  if (MODE != 2 && !(greedy && j > gamma)) {          // argmax sampling never looks at q rows
     const float* z = (j <= gamma) ? P + (size_t)j * V : Q + (size_t)(j - gamma - 1) * V;
     const RowStat rs = row_stats(z, V, invT, greedy, sm);
     if (tid == 0) my_stats[j] = rs;
   }
-  // one counter per sequence, 256 bytes apart: device-scope atomics that queue on
-  // one cache line serialise at roughly 0.2 us each
-  if (!last_block_arrives(counters + (size_t)b * SAMPLE_COUNTER_STRIDE, (unsigned)nrows, &sm.flag)) return;
+  if (MODE == 1) return;
+  // one counter per sequence, 256 bytes apart
+  if (MODE == 0 && !last_block_arrives(counters + (size_t)b * SAMPLE_COUNTER_STRIDE, (unsigned)nrows, &sm.flag)) return;
 
   // ---- tail: one workgroup per sequence ----
   if (tid < nrows) srow[tid] = my_stats[tid];
@@ -365,8 +459,16 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
     t = srow[n].arg;
   } else {
     const float* zp = P + (size_t)n * V;
-    if (n < gamma) {
-      t = icdf_row(zp, srow[n], Q + (size_t)n * V, srow[gamma + 1 + n], invT, V, s, sm);
+    const float* zq = Q + (size_t)min(n, gamma - 1) * V;
+    const RowStat sq = srow[gamma + 1 + min(n, gamma - 1)];
+    if (row_fits_regs(zp, V) && row_fits_regs(zq, V)) {
+      float4 vp[SAMPLE_REG_F4], vq[SAMPLE_REG_F4];
+      load_row_regs(zp, V, vp);
+      load_row_regs(zq, V, vq);               // unconditional; unused when all guesses were kept
+      t = icdf_regs(vp, srow[n], vq, sq, n < gamma, invT, V, s, sm);
+      if (t < 0) { fell_back = 1; t = icdf_regs(vp, srow[n], vq, sq, false, invT, V, s, sm); }
+    } else if (n < gamma) {
+      t = icdf_row(zp, srow[n], zq, sq, invT, V, s, sm);
       if (t < 0) { fell_back = 1; t = icdf_row(zp, srow[n], nullptr, srow[n], invT, V, s, sm); }
     } else {
       t = icdf_row(zp, srow[n], nullptr, srow[n], invT, V, s, sm);

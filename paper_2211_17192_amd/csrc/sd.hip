@@ -237,10 +237,12 @@ size_t attn_lds_bytes(int RG, int DH) {
 }
 
 template <typename T>
-void launch_attn(hipStream_t s, const Model& m, const AttnArgs& a) {
-  const int G = a.H / a.Hkv, RG = a.R * G, DH = m.cfg.d_head;
-  const size_t lds = attn_lds_bytes(RG, DH);
-  const dim3 grid(a.Hkv), block(ATTN_THREADS);
+void launch_attn(hipStream_t s, const Model& m, AttnArgs a) {
+  const int G = a.H / a.Hkv, DH = m.cfg.d_head;
+  // few kv heads leave most CUs idle: split the (independent) rows over more workgroups
+  a.rows_per_wg = (a.Hkv * ((a.R + 1) / 2) <= g_num_cus) ? std::min(2, a.R) : a.R;
+  const size_t lds = attn_lds_bytes(a.rows_per_wg * G, DH);
+  const dim3 grid(a.Hkv, (a.R + a.rows_per_wg - 1) / a.rows_per_wg), block(ATTN_THREADS);
   if (DH == 32) hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, lds, s, a);
   else if (DH == 64) hipLaunchKernelGGL((attn_kernel<T, 64>), grid, block, lds, s, a);
   else hipLaunchKernelGGL((attn_kernel<T, 128>), grid, block, lds, s, a);
@@ -387,7 +389,7 @@ void enqueue_step(sd_ctx* c, int gamma, bool profile) {
   forward_any(c, c->p, ROWS_VERIFY, 0, gamma + 1, 0, 0, gamma + 1, c->p_logits);
   c->time_ffn = false;
   if (profile) hipEventRecord(c->ev[2], s);
-  hipLaunchKernelGGL(spec_verify_kernel, dim3(2 * gamma + 1, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
+  hipLaunchKernelGGL(spec_verify_kernel<0>, dim3(2 * gamma + 1, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
                      c->q_logits, (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V,
                      0.0f, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr, c->d_state);
   if (profile) hipEventRecord(c->ev[3], s);

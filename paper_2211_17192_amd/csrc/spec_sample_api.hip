@@ -26,10 +26,19 @@ extern "C" sd_status sd_spec_sample(const float* p_logits, const float* q_logits
   unsigned int* counters = static_cast<unsigned int*>(scratch);
   sd::RowStat* stats = reinterpret_cast<sd::RowStat*>(
       static_cast<char*>(scratch) + scratch_align((size_t)rows * sd::SAMPLE_COUNTER_STRIDE * sizeof(unsigned int), 256));
-  dim3 grid(2 * gamma + 1, rows);
-  hipLaunchKernelGGL(sd::spec_verify_kernel, grid, dim3(sd::SAMPLE_THREADS), 0,
-                     static_cast<hipStream_t>(stream), p_logits, q_logits, x, r, s, gamma, vocab,
-                     temperature, (const sd::StepParams*)nullptr, stats, counters, out_n, out_t,
-                     (sd::SeqState*)nullptr);
+  const dim3 grid(2 * gamma + 1, rows), block(sd::SAMPLE_THREADS);
+  hipStream_t s_ = static_cast<hipStream_t>(stream);
+  if (rows * (2 * gamma + 1) <= 64) {           // few tickets: one launch
+    hipLaunchKernelGGL(sd::spec_verify_kernel<0>, grid, block, 0, s_, p_logits, q_logits, x, r, s, gamma, vocab,
+                       temperature, (const sd::StepParams*)nullptr, stats, counters, out_n, out_t,
+                       (sd::SeqState*)nullptr);
+  } else {                                       // many sequences: statistics, then one tail workgroup each
+    hipLaunchKernelGGL(sd::spec_verify_kernel<1>, grid, block, 0, s_, p_logits, q_logits, x, r, s, gamma, vocab,
+                       temperature, (const sd::StepParams*)nullptr, stats, counters, out_n, out_t,
+                       (sd::SeqState*)nullptr);
+    hipLaunchKernelGGL(sd::spec_verify_kernel<2>, dim3(1, rows), block, 0, s_, p_logits, q_logits, x, r, s, gamma,
+                       vocab, temperature, (const sd::StepParams*)nullptr, stats, counters, out_n, out_t,
+                       (sd::SeqState*)nullptr);
+  }
   return hipGetLastError() == hipSuccess ? SD_OK : SD_EHIP;
 }
