@@ -24,6 +24,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 GEN_LEN = 128                   # tokens generated per sequence (T5-XXL-shaped workload)
 TEMPERATURE = 1.0
+# HBM bytes of one FFN-in launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled by what
+# the same counters read for a 256 MiB copy (profiles/ffn_in_hbm_traffic.txt has the run); None = not measured
+TRAFFIC_FFN_IN = 168567808   # bytes: (82248.5 KiB fetched x 2.0 + 120 KiB written)
 
 
 def expected_tokens(alpha, gamma):
@@ -58,6 +61,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--gammas", type=str, default="3,5,7")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a 256 MiB device-to-device copy (reference for the profiler's byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (nothing here uses a second GPU)")
@@ -134,13 +139,24 @@ def main():
                    "c": pr["c"], "verify_GBps": pr["verify_GBps"],
                    "verify_frac_of_hbm_peak": pr["verify_GBps"] / HBM_PEAK_GBPS})
 
-    # roofline of the dominant kernel: the gated FFN-in GEMM streams both d_ff x d_model matrices once
+    # Roofline of the dominant kernel: the gated FFN-in GEMM streams both d_ff x d_model matrices
+    # of a layer exactly once (algorithmic bytes per launch = 2 * d_ff * d_model * 2).  Its mean
+    # launch duration: all 24 layers' launches, back to back from one graph, between two HIP events
+    # on the library's stream (every launch reads another layer's weights, so nothing is cached).
     ffn_bytes = 2 * cfg_p["d_ff"] * cfg_p["d_model"] * 2
-    ffn_us = prof[best]["ffn_in_us"]
+    ffn_us = dec.time_ffn_in(best + 1, reps=20)
     roofline = {"bound": "hbm", "kernel": "gemm_kernel<bf16, PRO_POST, EPI_GATED> (Mp FFN-in, gated GELU)",
                 "achieved": ffn_bytes / ffn_us / 1e3, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": ffn_bytes / ffn_us / 1e3 / HBM_PEAK_GBPS, "bytes_per_launch": ffn_bytes,
-                "us_per_launch": ffn_us, "traffic": None}
+                "us_per_launch": ffn_us, "us_per_launch_between_events_in_step": prof[best]["ffn_in_us"],
+                "rows": best + 1, "traffic": TRAFFIC_FFN_IN}
+    if args.calibrate:          # a plain copy of known size, for scaling the rocprofv3 byte counters
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = None
     if want_cpu:

@@ -181,6 +181,16 @@ sd_status sd_debug_logits(sd_ctx* ctx, int32_t which, float* host_out, size_t n)
 sd_status sd_get_stats(sd_ctx* ctx, sd_stats* out);
 /* Replace the flags given at load (SD_FLAG_GRAPH, SD_FLAG_PROFILE) for the following calls. */
 sd_status sd_set_flags(sd_ctx* ctx, int32_t flags);
+/* Measurement: the FFN-in GEMM of every Mp layer (the kernel that streams the
+ * most weight bytes of the verify forward, section 3.4), `rows` activation rows
+ * (1..16), launched reps times over all layers from one hipGraph between two HIP
+ * events on the library's stream.  Every launch streams another layer's weights
+ * (2 * d_ff * d_model elements for gated blocks, half for GPT blocks), so none is
+ * served from cache.  *us_per_launch (host) = mean time of one launch in
+ * microseconds.  Needs a prefilled sequence only in so far as the activations it
+ * multiplies are whatever the last forward left; it overwrites Mp's FFN scratch
+ * rows, nothing else.  Synchronous. */
+sd_status sd_time_ffn_in(sd_ctx* ctx, int32_t rows, int32_t reps, double* us_per_launch);
 
 /*
  * The accept / resample part of Algorithm 1 on explicit logits, for `rows`

@@ -127,6 +127,8 @@ lib.sd_get_stats.restype = C.c_int
 lib.sd_get_stats.argtypes = [C.c_void_p, C.POINTER(_Stats)]
 lib.sd_set_flags.restype = C.c_int
 lib.sd_set_flags.argtypes = [C.c_void_p, C.c_int32]
+lib.sd_time_ffn_in.restype = C.c_int
+lib.sd_time_ffn_in.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
 
 
 def _cfg_struct(cfg: dict) -> _ModelCfg:
@@ -225,6 +227,12 @@ class SpecDecoder:
         s = _Stats()
         self._check(lib.sd_get_stats(self._ctx, C.byref(s)))
         return {k: getattr(s, k) for k, _ in _Stats._fields_}
+
+    def time_ffn_in(self, rows: int, reps: int = 20) -> float:
+        """Mean duration (microseconds) of one launch of Mp's FFN-in GEMM over `rows` rows."""
+        us = C.c_double(0.0)
+        self._check(lib.sd_time_ffn_in(self._ctx, int(rows), int(reps), C.byref(us)))
+        return us.value
 
     def set_flags(self, flags: int):
         self._check(lib.sd_set_flags(self._ctx, int(flags)))

@@ -768,6 +768,46 @@ extern "C" sd_status sd_set_flags(sd_ctx* c, int32_t flags) {
   return SD_OK;
 }
 
+extern "C" sd_status sd_time_ffn_in(sd_ctx* c, int32_t rows, int32_t reps, double* us_per_launch) {
+  if (!c || !us_per_launch) return SD_EINVAL;
+  if (rows < 1 || rows > MAX_ROWS || reps < 1 || reps > 1000) return fail(c, SD_EINVAL, "rows must be 1..16, reps 1..1000");
+  Model& m = c->p;
+  const sd_model_cfg& f = m.cfg;
+  const bool rms = f.arch != SD_ARCH_GPT;
+  hipGraph_t g = nullptr;
+  hipGraphExec_t ge = nullptr;
+  HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+  for (const LayerW& l : m.L) {
+    GemmArgs h{};
+    h.R = rows; h.eps = f.norm_eps; h.K = f.d_model; h.N = f.d_ff; h.out = m.ffn; h.ldo = f.d_ff; h.W = l.w1;
+    if (rms) {
+      h.X = m.xg; h.ss_in = m.ss; h.n_part = f.d_model / 16;
+      h.W2 = l.wu; h.act = (f.arch == SD_ARCH_T5DEC) ? ACT_GELU : ACT_SILU;
+      if (f.dtype == SD_BF16) launch_gemm<bf16>(c->stream, PRO_POST, EPI_GATED, h);
+      else launch_gemm<float>(c->stream, PRO_POST, EPI_GATED, h);
+    } else {
+      h.X = m.x; h.gain = l.ln2g; h.beta = l.ln2b; h.bias = l.b1;
+      if (f.dtype == SD_BF16) launch_gemm<bf16>(c->stream, PRO_LN, EPI_ACT, h);
+      else launch_gemm<float>(c->stream, PRO_LN, EPI_ACT, h);
+    }
+  }
+  HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
+  hipError_t e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+  hipGraphDestroy(g);
+  if (e != hipSuccess) return fail(c, SD_EHIP, std::string("graph instantiate: ") + hipGetErrorString(e));
+  hipGraphLaunch(ge, c->stream);                       // warm-up
+  hipEventRecord(c->ev[0], c->stream);
+  for (int i = 0; i < reps; ++i) hipGraphLaunch(ge, c->stream);
+  hipEventRecord(c->ev[1], c->stream);
+  e = hipStreamSynchronize(c->stream);
+  float ms = 0.0f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, c->ev[0], c->ev[1]);
+  hipGraphExecDestroy(ge);
+  if (e != hipSuccess) return fail(c, SD_EHIP, std::string("sd_time_ffn_in: ") + hipGetErrorString(e));
+  *us_per_launch = 1e3 * (double)ms / ((double)reps * (double)m.L.size());
+  return SD_OK;
+}
+
 extern "C" sd_status sd_get_stats(sd_ctx* c, sd_stats* out) {
   if (!c || !out) return SD_EINVAL;
   *out = c->stats;
