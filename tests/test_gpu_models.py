@@ -231,3 +231,47 @@ def test_error_paths():
     wq2 = dict(w_q); wq2.pop("head")
     with pytest.raises(binding.SdError):
         make_decoder(cfg_p, w_p, cfg_q, wq2)
+
+
+def test_gpt_pair_bf16_all_gammas():
+    """The GPT-like bf16 pair (12 layers, d_model 768, vocab 8192; draft 2 layers,
+    d_model 256): 128-token prompt, gamma = 3 / 5 / 7 at temperature 1 with graph
+    replay, every iteration checked against the oracle at both levels.  (The run
+    is cut to 40 new tokens per gamma to keep the float64 oracle within a minute.)"""
+    cfg_p, w_p, cfg_q, w_q = synth.gpt_pair("cpu", emb_rms=4.0, head_std=0.1)
+    sp, sq = oracle_models(cfg_p, w_p, cfg_q, w_q)
+    prompt = synth.random_tokens(5, 128, cfg_p["vocab"])
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=7, flags=1)
+    accepted = []
+    for gamma, useed in ((3, 11), (5, 12), (7, 13)):
+        dec.reset()
+        dec.prefill(prompt)
+        toks, tol, worst, mean_n = run_pair(dec, sp, sq, prompt, 40, gamma, 1.0, useed, "bf16", False)
+        print(f"gpt pair gamma={gamma}: worst logit error {worst}, tolerated {tol}, mean n {mean_n:.2f}")
+        assert tol["accept"] + tol["draw"] <= 1, tol
+        accepted.append(mean_n)
+    assert max(accepted) > 0.5                      # the correlated draft gets guesses accepted
+    dec.close()
+
+
+def test_t5xxl_full_size_iteration_matches_oracle():
+    """The headline workload at full size (Mp 24 layers, d_model 4096, d_ff 10240,
+    vocab 32128, 512 encoder positions; Mq 6 layers, d_model 512), in the launch
+    configuration bench.py times (graph replay, gamma = 5, temperature 1): the first
+    eight tokens from the start token, all gamma+1 target rows and gamma draft rows
+    of logits against the float64 oracle (level M), and the oracle's Algorithm-1
+    arithmetic on the GPU's logits against the GPU's tokens (level S)."""
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q, enc_p, enc_q = synth.t5xxl_pair("cuda")
+    host = (synth.to_numpy_weights(w_p), synth.to_numpy_weights(w_q), synth.to_numpy_weights({"p": enc_p, "q": enc_q}))
+    dec = binding.SpecDecoder(cfg_p, w_p, cfg_q, w_q, max_gamma=7, flags=binding.SD_FLAG_GRAPH)
+    del w_p, w_q
+    torch.cuda.empty_cache()
+    mp = T.Transformer(T.ModelConfig(**cfg_p), host[0])
+    mq = T.Transformer(T.ModelConfig(**cfg_q), host[1])
+    mp.set_encoder_output(host[2]["p"]); mq.set_encoder_output(host[2]["q"])
+    dec.prefill([0], enc_p, enc_q)
+    toks, tol, worst, mean_n = run_pair(dec, T.CachedScorer(mp), T.CachedScorer(mq), [0], 8, 5, 1.0, 21, "bf16", False)
+    print(f"T5-XXL-shaped pair, gamma=5: worst logit error {worst}, tolerated {tol}, mean n {mean_n:.2f}")
+    assert tol["accept"] + tol["draw"] <= 1, tol
+    dec.close()
