@@ -47,8 +47,26 @@ enum { SD_MAX_GAMMA = 15 };       /* a forward handles at most SD_MAX_GAMMA+1 ro
 /* Flags of sd_runtime_cfg.flags */
 enum {
   SD_FLAG_GRAPH   = 1,  /* replay each iteration as one hipGraph (draft loop, verify, accept) */
-  SD_FLAG_PROFILE = 2   /* record HIP events around the draft / verify / accept phases */
+  SD_FLAG_PROFILE = 2,  /* record HIP events around the draft / verify / accept phases */
+  SD_FLAG_BETA    = 4   /* also compute beta_i = sum_x min(p_i(x), q_i(x)) of every guess (section 3.1)
+                           in each sd_step: one more small launch; feeds sd_stats.beta_sum */
 };
+
+/*
+ * Sampling options beyond the temperature.
+ *   lenience : appendix A.5.  q is multiplied by l in (0, 1] before the
+ *       comparison with p: guess x_i is kept iff r_i <= p_i(x_i) / (l q_i(x_i)),
+ *       so no token is produced with more than 1/l times its probability under
+ *       Mp.  After a rejection the extra token is drawn from
+ *       norm(max(0, p - l q)) (the appendix leaves this distribution open; this
+ *       one keeps the 1/l bound).  With temperature 0 the variant the appendix
+ *       sketches for argmax sampling is used: x_i is kept iff
+ *       p_i(x_i) >= l max p_i with p_i = softmax of the unscaled logits, decided
+ *       as z[x_i] - max z >= ln l in double precision.  l = 1 is Algorithm 1.
+ */
+typedef struct {
+  float lenience;
+} sd_sampling;
 
 /*
  * Model description.  The paper treats Mp and Mq as black boxes (section 2.1)
@@ -111,6 +129,9 @@ typedef struct {
   int64_t fallbacks;                        /* zero-residual fallbacks taken */
   double  ffn_in_ms_sum;                    /* SD_FLAG_PROFILE, RMSNorm targets: time between HIP events around */
   int64_t ffn_in_launches;                  /*   every gated FFN-in GEMM of the verify forwards, and their count */
+  int64_t tested;                           /* acceptance tests that counted: sum of min(n+1, gamma) */
+  double  beta_sum;                         /* SD_FLAG_BETA: sum of beta_i over those same guesses */
+  int64_t beta_count;                       /*   and their number; beta_sum / beta_count estimates alpha = E(beta) */
 } sd_stats;
 
 /* Device bytes sd_load_models needs for this pair (weights, KV caches,
@@ -179,8 +200,47 @@ const char* sd_last_error(const sd_ctx* ctx);
  * sd_step_baseline: [1, vocab].  host_out: host, n floats (n <= rows*vocab). */
 sd_status sd_debug_logits(sd_ctx* ctx, int32_t which, float* host_out, size_t n);
 sd_status sd_get_stats(sd_ctx* ctx, sd_stats* out);
-/* Replace the flags given at load (SD_FLAG_GRAPH, SD_FLAG_PROFILE) for the following calls. */
+/* Replace the flags given at load for the following calls (captured graphs are rebuilt). */
 sd_status sd_set_flags(sd_ctx* ctx, int32_t flags);
+/* Sampling options for the following sd_step calls (host struct, copied).
+ * SD_EINVAL unless 0 < lenience <= 1. */
+sd_status sd_set_sampling(sd_ctx* ctx, const sd_sampling* opt);
+
+/*
+ * Section 3.5 (choosing gamma): the integer gamma in 1..gamma_max that maximises
+ * the expected walltime improvement of Theorem 3.8,
+ *     (1 - alpha^(gamma+1)) / ((1 - alpha) (gamma c + 1)),
+ * for an acceptance rate alpha in [0, 1) and a cost coefficient c >= 0
+ * (Definition 3.7: time of one Mq run over time of one Mp run); ties go to the
+ * smaller gamma.  gamma, improvement: host outputs (improvement may be NULL).
+ * Pure host arithmetic: needs no GPU and no context.
+ */
+sd_status sd_choose_gamma(double alpha, double c, int32_t gamma_max, int32_t* gamma, double* improvement);
+
+/*
+ * Measure the two run times behind the cost coefficient c on a prefilled
+ * sequence: one draft step of Mq (1-row forward + draw) and one standard
+ * decoding step of Mp (1-row forward + draw), each replayed reps (1..1000)
+ * times from a hipGraph between two HIP events.  mq_us, mp_us: host outputs,
+ * microseconds per run.  The runs write only cache rows beyond the committed
+ * sequence (or rewrite a committed row with the same values) and commit
+ * nothing.  SD_ESTATE unless the context is prefilled and no sd_step_baseline
+ * has made Mq's cache stale.
+ */
+sd_status sd_measure_cost(sd_ctx* ctx, int32_t reps, double* mq_us, double* mp_us);
+
+/*
+ * gamma for this pair from what the context has measured so far: alpha from
+ * all sd_step calls since load (sd_reset does not clear it: alpha describes the
+ * pair and the task, not one sequence), as the mean of beta_i over the guesses
+ * whose test counted when SD_FLAG_BETA was on, else as accepted / tested (both
+ * estimate E(beta), Definition 3.1 and Corollary 3.6); c from
+ * sd_measure_cost(reps) (needs the prefilled sequence); then sd_choose_gamma with
+ * gamma_max = max_gamma of the context.  All outputs host; alpha, c, improvement
+ * may be NULL.  SD_ESTATE if no acceptance test has been recorded yet.
+ */
+sd_status sd_autotune_gamma(sd_ctx* ctx, int32_t reps, int32_t* gamma, double* alpha, double* c,
+                            double* improvement);
 /* Measurement: the FFN-in GEMM of every Mp layer (the kernel that streams the
  * most weight bytes of the verify forward, section 3.4), `rows` activation rows
  * (1..16), launched reps times over all layers from one hipGraph between two HIP
@@ -205,6 +265,15 @@ sd_status sd_time_ffn_in(sd_ctx* ctx, int32_t rows, int32_t reps, double* us_per
  * Asynchronous on `stream`; no host output.
  */
 size_t    sd_spec_sample_scratch_bytes(int32_t rows, int32_t gamma);
+/* The same with sampling options (opt: host, NULL = defaults) and, when beta is
+ * not NULL, the acceptance probabilities as a side output: beta: dev,
+ * [rows, gamma] fp32, beta[b][i] = sum_x min(p_{i+1}(x) / l, q_{i+1}(x))
+ * (section 3.1, appendix A.5).  sd_spec_sample is this with opt = beta = NULL. */
+sd_status sd_spec_sample_ex(const float* p_logits, const float* q_logits, const int32_t* x,
+                            const float* r, const float* s, int32_t rows, int32_t gamma,
+                            int32_t vocab, float temperature, const sd_sampling* opt,
+                            int32_t* out_n, int32_t* out_t, float* beta,
+                            void* scratch, void* stream);
 sd_status sd_spec_sample(const float* p_logits, const float* q_logits, const int32_t* x,
                          const float* r, const float* s, int32_t rows, int32_t gamma,
                          int32_t vocab, float temperature,

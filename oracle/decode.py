@@ -11,10 +11,10 @@ from __future__ import annotations
 
 import numpy as np
 
-from .sampling import accept_and_resample, icdf, standardise
+from .sampling import accept_and_resample, accept_and_resample_argmax_lenient, icdf, standardise
 
 
-def speculative_decoding_step(mp, mq, prefix, gamma: int, temperature: float, uniforms):
+def speculative_decoding_step(mp, mq, prefix, gamma: int, temperature: float, uniforms, lenience: float = 1.0):
     """One run of Algorithm 1.  Returns (new_prefix, n, info).
 
     1. for i = 1..gamma: q_i = Mq(prefix + x_<i), x_i ~ q_i        (serial)
@@ -22,6 +22,9 @@ def speculative_decoding_step(mp, mq, prefix, gamma: int, temperature: float, un
     3. n = number of guesses before the first r_i > p_i(x_i)/q_i(x_i)
     4. t ~ p_{n+1}, replaced by norm(max(0, p_{n+1}-q_{n+1})) when n < gamma
     5. return prefix + [x_1..x_n, t]
+
+    lenience < 1 relaxes step 3 as appendix A.5 describes (q multiplied by l; at
+    temperature 0 the argmax variant).
     """
     u = np.asarray(uniforms, dtype=np.float64)
     if u.shape != (2 * gamma + 1,):
@@ -39,13 +42,19 @@ def speculative_decoding_step(mp, mq, prefix, gamma: int, temperature: float, un
         q_logits.append(zq)
     zp = mp.score(prefix + x, gamma + 1)
     p_rows = np.stack([standardise(z, temperature) for z in zp])
-    n, t, info = accept_and_resample(p_rows, np.stack(q_rows), x, r, s)
+    if temperature == 0 and lenience < 1.0:
+        n, t = accept_and_resample_argmax_lenient(zp, x, lenience)
+        info = {"fallback": False, "ratios": None, "margins": None}
+    else:
+        n, t, info = accept_and_resample(p_rows, np.stack(q_rows), x, r, s,
+                                         lenience=float(np.float32(lenience)))
     info.update({"x": list(x), "p_logits": zp, "q_logits": np.stack(q_logits),
                  "p_rows": p_rows, "q_rows": np.stack(q_rows)})
     return prefix + x[:n] + [t], n, info
 
 
-def speculative_decode(mp, mq, prompt, n_new: int, gamma: int, temperature: float, uniform_rows):
+def speculative_decode(mp, mq, prompt, n_new: int, gamma: int, temperature: float, uniform_rows,
+                       lenience: float = 1.0):
     """Repeat Algorithm 1 until n_new tokens exist; the surplus of the last
     run is dropped.  uniform_rows yields one [2*gamma+1] row per run.
     Returns (tokens, records) with one record (n, emitted tokens, info) per run."""
@@ -54,7 +63,7 @@ def speculative_decode(mp, mq, prompt, n_new: int, gamma: int, temperature: floa
     records = []
     it = iter(uniform_rows)
     while len(prefix) < target:
-        new_prefix, n, info = speculative_decoding_step(mp, mq, prefix, gamma, temperature, next(it))
+        new_prefix, n, info = speculative_decoding_step(mp, mq, prefix, gamma, temperature, next(it), lenience)
         records.append((n, new_prefix[len(prefix):], info))
         prefix = new_prefix
     return prefix[:target], records

@@ -128,11 +128,38 @@ def accept_and_resample(p_rows, q_rows, x, r, s, lenience: float = 1.0):
     return n, t, info
 
 
-def accept_and_resample_from_logits(p_logits, q_logits, x, r, s, temperature: float):
-    """Same as accept_and_resample, starting from logits rows (section 2.2 first)."""
+def accept_and_resample_argmax_lenient(p_logits, x, lenience: float):
+    """Appendix A.5, last paragraph: lenience under argmax sampling (temperature 0).
+
+    The one-hot distributions leave the ordinary test nothing to relax, so the
+    lenience is applied before standardising: guess x_i is kept when
+    p_i(x_i) >= l * max p_i, where p_i is the softmax of the unscaled logits (the
+    paper prints "<=", which would keep exactly the unlikely tokens; read as a
+    misprint).  In logits: z[x_i] - max z >= ln l.  The extra token is the argmax
+    of the row after the kept guesses.  Returns (n, t).
+    """
+    z = np.asarray(p_logits, np.float64)
+    gamma = len(x)
+    if z.shape[0] != gamma + 1:
+        raise ValueError("shape mismatch")
+    log_l = np.log(np.float64(np.float32(lenience)))
+    n = gamma
+    for i in range(gamma):
+        if z[i, x[i]] - np.max(z[i]) < log_l:
+            n = i
+            break
+    return n, int(np.argmax(z[n]))
+
+
+def accept_and_resample_from_logits(p_logits, q_logits, x, r, s, temperature: float, lenience: float = 1.0):
+    """Same as accept_and_resample, starting from logits rows (section 2.2 first).
+    With temperature 0 and lenience < 1 the argmax variant of the lenient test applies."""
+    if temperature == 0 and lenience < 1.0:
+        n, t = accept_and_resample_argmax_lenient(p_logits, x, lenience)
+        return n, t, {"fallback": False, "ratios": None, "margins": None}
     p_rows = np.stack([standardise(z, temperature) for z in p_logits])
     q_rows = np.stack([standardise(z, temperature) for z in q_logits])
-    return accept_and_resample(p_rows, q_rows, x, r, s)
+    return accept_and_resample(p_rows, q_rows, x, r, s, lenience=np.float64(np.float32(lenience)))
 
 
 def icdf_edge_distance(weights, u: float, k: int) -> float:

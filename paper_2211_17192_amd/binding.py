@@ -22,7 +22,7 @@ lib = C.CDLL(LIB_PATH)
 SD_OK, SD_EINVAL, SD_ESTATE, SD_ERANGE, SD_ENOMEM, SD_EHIP = range(6)
 SD_F32, SD_BF16 = 0, 1
 SD_MAX_GAMMA = 15
-SD_FLAG_GRAPH, SD_FLAG_PROFILE = 1, 2
+SD_FLAG_GRAPH, SD_FLAG_PROFILE, SD_FLAG_BETA = 1, 2, 4
 STATUS_NAMES = ["SD_OK", "SD_EINVAL", "SD_ESTATE", "SD_ERANGE", "SD_ENOMEM", "SD_EHIP"]
 
 
@@ -49,6 +49,27 @@ lib.sd_spec_sample.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_int3
                                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 
 
+class _Sampling(C.Structure):
+    _fields_ = [("lenience", C.c_float)]
+
+
+lib.sd_spec_sample_ex.restype = C.c_int
+lib.sd_spec_sample_ex.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                                     C.POINTER(_Sampling), C.c_void_p, C.c_void_p, C.c_void_p,
+                                                     C.c_void_p, C.c_void_p]
+lib.sd_choose_gamma.restype = C.c_int
+lib.sd_choose_gamma.argtypes = [C.c_double, C.c_double, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
+
+
+def choose_gamma(alpha: float, c: float, gamma_max: int):
+    """sd_choose_gamma: (gamma, predicted improvement factor).  Host arithmetic only."""
+    g, v = C.c_int32(0), C.c_double(0.0)
+    st = lib.sd_choose_gamma(float(alpha), float(c), int(gamma_max), C.byref(g), C.byref(v))
+    if st != SD_OK:
+        raise SdError(st, "sd_choose_gamma")
+    return g.value, v.value
+
+
 def spec_sample_scratch(rows: int, gamma: int) -> torch.Tensor:
     n = lib.sd_spec_sample_scratch_bytes(rows, gamma)
     if n == 0:
@@ -56,10 +77,13 @@ def spec_sample_scratch(rows: int, gamma: int) -> torch.Tensor:
     return torch.zeros(n, dtype=torch.uint8, device="cuda")
 
 
-def spec_sample(p_logits, q_logits, x, r, s, temperature: float, scratch=None, out_n=None, out_t=None):
+def spec_sample(p_logits, q_logits, x, r, s, temperature: float, scratch=None, out_n=None, out_t=None,
+                lenience=None, beta=None):
     """sd_spec_sample on cuda tensors: p_logits [rows, gamma+1, V] fp32, q_logits
     [rows, gamma, V] fp32, x [rows, gamma] int32, r [rows, gamma] fp32, s [rows] fp32.
-    Returns device tensors (n [rows], t [rows]); asynchronous on the current stream."""
+    Returns device tensors (n [rows], t [rows]); asynchronous on the current stream.
+    With lenience or beta (a [rows, gamma] fp32 cuda tensor that receives the
+    acceptance probabilities) the call goes to sd_spec_sample_ex."""
     rows, g1, V = p_logits.shape
     gamma = g1 - 1
     for t_, dt in ((p_logits, torch.float32), (q_logits, torch.float32), (x, torch.int32)):
@@ -70,8 +94,16 @@ def spec_sample(p_logits, q_logits, x, r, s, temperature: float, scratch=None, o
     if out_n is None:
         out_n = torch.empty(rows, dtype=torch.int32, device="cuda")
         out_t = torch.empty(rows, dtype=torch.int32, device="cuda")
-    st = lib.sd_spec_sample(_ptr(p_logits), _ptr(q_logits), _ptr(x), _ptr(r), _ptr(s), rows, gamma, V,
-                            float(temperature), _ptr(out_n), _ptr(out_t), _ptr(scratch), _stream())
+    if lenience is None and beta is None:
+        st = lib.sd_spec_sample(_ptr(p_logits), _ptr(q_logits), _ptr(x), _ptr(r), _ptr(s), rows, gamma, V,
+                                float(temperature), _ptr(out_n), _ptr(out_t), _ptr(scratch), _stream())
+    else:
+        if beta is not None:
+            assert beta.is_cuda and beta.is_contiguous() and beta.dtype == torch.float32 and beta.shape == (rows, gamma)
+        opt = _Sampling(1.0 if lenience is None else float(lenience))
+        st = lib.sd_spec_sample_ex(_ptr(p_logits), _ptr(q_logits), _ptr(x), _ptr(r), _ptr(s), rows, gamma, V,
+                                   float(temperature), C.byref(opt), _ptr(out_n), _ptr(out_t),
+                                   _ptr(beta) if beta is not None else None, _ptr(scratch), _stream())
     if st != SD_OK:
         raise SdError(st, "sd_spec_sample")
     return out_n, out_t
@@ -100,7 +132,8 @@ class _RuntimeCfg(C.Structure):
 class _Stats(C.Structure):
     _fields_ = [("draft_ms", C.c_double), ("verify_ms", C.c_double), ("accept_ms", C.c_double),
                 ("steps", C.c_int64), ("tokens", C.c_int64), ("accepted", C.c_int64), ("fallbacks", C.c_int64),
-                ("ffn_in_ms_sum", C.c_double), ("ffn_in_launches", C.c_int64)]
+                ("ffn_in_ms_sum", C.c_double), ("ffn_in_launches", C.c_int64),
+                ("tested", C.c_int64), ("beta_sum", C.c_double), ("beta_count", C.c_int64)]
 
 
 lib.sd_workspace_bytes.restype = C.c_size_t
@@ -129,6 +162,13 @@ lib.sd_set_flags.restype = C.c_int
 lib.sd_set_flags.argtypes = [C.c_void_p, C.c_int32]
 lib.sd_time_ffn_in.restype = C.c_int
 lib.sd_time_ffn_in.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
+lib.sd_set_sampling.restype = C.c_int
+lib.sd_set_sampling.argtypes = [C.c_void_p, C.POINTER(_Sampling)]
+lib.sd_measure_cost.restype = C.c_int
+lib.sd_measure_cost.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+lib.sd_autotune_gamma.restype = C.c_int
+lib.sd_autotune_gamma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
+                                  C.POINTER(C.c_double), C.POINTER(C.c_double)]
 
 
 def _cfg_struct(cfg: dict) -> _ModelCfg:
@@ -236,6 +276,22 @@ class SpecDecoder:
 
     def set_flags(self, flags: int):
         self._check(lib.sd_set_flags(self._ctx, int(flags)))
+
+    def set_sampling(self, lenience: float = 1.0):
+        opt = _Sampling(float(lenience))
+        self._check(lib.sd_set_sampling(self._ctx, C.byref(opt)))
+
+    def measure_cost(self, reps: int = 20):
+        """(microseconds of one Mq draft step, microseconds of one standard Mp decoding step)."""
+        a, b = C.c_double(0.0), C.c_double(0.0)
+        self._check(lib.sd_measure_cost(self._ctx, int(reps), C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def autotune_gamma(self, reps: int = 20) -> dict:
+        g = C.c_int32(0)
+        a, c, v = C.c_double(0.0), C.c_double(0.0), C.c_double(0.0)
+        self._check(lib.sd_autotune_gamma(self._ctx, int(reps), C.byref(g), C.byref(a), C.byref(c), C.byref(v)))
+        return {"gamma": g.value, "alpha": a.value, "c": c.value, "improvement": v.value}
 
     def reset(self):
         self._check(lib.sd_reset(self._ctx, -1))

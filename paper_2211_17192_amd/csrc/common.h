@@ -26,13 +26,17 @@ struct SeqState {
   int32_t out[16];             // tokens emitted by the last iteration, -1 padded
   int32_t fallbacks;           // zero-residual fallbacks taken so far
   int32_t pad[3];
+  float   beta[16];            // acceptance probabilities beta_1..beta_gamma of the last iteration (when asked for)
 };
 
 // Per-call parameters that change between iterations; they live in device
 // memory so that a captured graph can be replayed unchanged.
 struct StepParams {
+  double log_lenience;         // ln(lenience), for the argmax-sampling variant of the lenient test
   float temperature;
+  float lenience;              // factor l of the lenient acceptance test, 1 = the exact algorithm
   float uniforms[2 * 15 + 1];  // [0,g) draft draws, [g,2g) accept tests, [2g] final draw
+  float pad;
 };
 
 template <typename T> struct Store;

@@ -246,11 +246,11 @@ __device__ __forceinline__ int pick_in_chunk(const double (&w)[4], int k, int V,
 // to the unadjusted row).
 __device__ __forceinline__ int icdf_row(const float* zp, const RowStat& sp, const float* zq,
                                         const RowStat& sq, float invT, int V, float u,
-                                        SampleSmem& sm) {
+                                        SampleSmem& sm, double qscale = 1.0) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
   RowPair rp;
   rp.zp = zp; rp.zq = zq; rp.mp = sp.m; rp.mq = sq.m;
-  rp.invSp = 1.0 / sp.S; rp.invSq = zq ? 1.0 / sq.S : 0.0;
+  rp.invSp = 1.0 / sp.S; rp.invSq = zq ? qscale / sq.S : 0.0;     // q enters the residual as qscale * q
   rp.invT = invT; rp.V = V;
   rp.vec = ((V & 3) == 0) && ((reinterpret_cast<uintptr_t>(zp) & 15) == 0) &&
            (zq == nullptr || (reinterpret_cast<uintptr_t>(zq) & 15) == 0);
@@ -312,10 +312,10 @@ __device__ __forceinline__ void weights_of(const float4& zp, const float4& zq, b
 
 __device__ __forceinline__ int icdf_regs(const float4 (&vp)[SAMPLE_REG_F4], const RowStat& sp,
                                          const float4 (&vq)[SAMPLE_REG_F4], const RowStat& sq, bool with_q,
-                                         float invT, int V, float u, SampleSmem& sm) {
+                                         float invT, int V, float u, SampleSmem& sm, double qscale = 1.0) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int NW = SAMPLE_THREADS / 64;
-  const double invSp = 1.0 / sp.S, invSq = with_q ? 1.0 / sq.S : 0.0;
+  const double invSp = 1.0 / sp.S, invSq = with_q ? qscale / sq.S : 0.0;
   const int nchunks = (V + SAMPLE_CHUNK - 1) / SAMPLE_CHUNK;
   __syncthreads();
 #pragma unroll
@@ -397,16 +397,19 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void sample_row_kernel(
 // taken from the device-resident step parameters and state.
 // ---------------------------------------------------------------------------
 // MODE 0: everything in one launch (ticket).  MODE 1: row statistics only.  MODE 2: the
-// per-sequence tail only, grid (1, rows).  A device-scope atomic costs about 0.08 us of
+// per-sequence tail only, grid (1, rows).  MODE 3: the acceptance probabilities beta_i as a
+// side output, grid (gamma, rows), after the statistics exist.  A device-scope atomic costs about 0.08 us of
 // chip-wide throughput, so with many sequences two launches (1 + 2) beat rows * (2*gamma+1)
 // tickets; with one sequence the single launch wins.
 template <int MODE>
 static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
     const float* __restrict__ p_logits, const float* __restrict__ q_logits,
     const int* __restrict__ x_in, const float* __restrict__ r_in, const float* __restrict__ s_in,
-    int gamma, int V, float temperature, const StepParams* __restrict__ prm,
+    int gamma, int V, float temperature, float lenience_in, double log_lenience_in,
+    const StepParams* __restrict__ prm,
     RowStat* __restrict__ stats, unsigned int* __restrict__ counters,
-    int* __restrict__ out_n, int* __restrict__ out_t, SeqState* __restrict__ st) {
+    int* __restrict__ out_n, int* __restrict__ out_t, float* __restrict__ beta_out,
+    SeqState* __restrict__ st) {
   __shared__ SampleSmem sm;
   __shared__ RowStat srow[2 * 15 + 1];
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
@@ -414,9 +417,40 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
   const float T = prm ? prm->temperature : temperature;
   const bool greedy = (T == 0.0f);
   const float invT = greedy ? 1.0f : 1.0f / T;
+  const double len = (double)(prm ? prm->lenience : lenience_in);            // appendix A.5, 1 = exact
+  const double log_len = prm ? prm->log_lenience : log_lenience_in;
   const float* P = p_logits + (size_t)b * (gamma + 1) * V;
   const float* Q = q_logits + (size_t)b * gamma * V;
   RowStat* my_stats = stats + (size_t)b * nrows;
+
+  if (MODE == 3) {
+    // beta_{j+1} = sum_x min(p(x) / l, q(x)): the probability that guess j+1 is accepted
+    // (section 3.1; with lenience, appendix A.5).  Needs the statistics of a MODE 0 / 1 launch.
+    if (j >= gamma) return;
+    const RowStat sp = my_stats[j];
+    const float* zp = P + (size_t)j * V;
+    float* dst = st ? st->beta : beta_out + (size_t)b * gamma;
+    if (greedy) {                                // one-hot q at its argmax: accepted or not
+      const int aq = row_stats(Q + (size_t)j * V, V, 1.0f, true, sm).arg;   // argmax sampling keeps no q statistics
+      if (tid == 0) {
+        const bool acc = (len < 1.0) ? ((double)zp[aq] - (double)sp.m >= log_len) : (aq == sp.arg);
+        dst[j] = acc ? 1.0f : 0.0f;
+      }
+      return;
+    }
+    const RowStat sq = my_stats[gamma + 1 + j];
+    const float* zq = Q + (size_t)j * V;
+    const double ip = (1.0 / sp.S) / len, iq = 1.0 / sq.S;
+    double acc = 0.0;
+    for (int k = tid; k < V; k += SAMPLE_THREADS) {
+      const double pv = (double)exp_scaled(zp[k], sp.m, invT) * ip;
+      const double qv = (double)exp_scaled(zq[k], sq.m, invT) * iq;
+      acc += pv < qv ? pv : qv;
+    }
+    acc = block_reduce(acc, sm.redd, OpSumD(), 0.0);
+    if (tid == 0) dst[j] = (float)acc;
+    return;
+  }
 
   if (MODE != 2 && !(greedy && j > gamma)) {          // argmax sampling never looks at q rows
     const float* z = (j <= gamma) ? P + (size_t)j * V : Q + (size_t)(j - gamma - 1) * V;
@@ -439,12 +473,15 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
     if (tid < gamma) {
       const int xi = min(max(x[tid], 0), V - 1);
       if (greedy) {
-        reject = (srow[tid].arg != xi);
+        // lenient argmax sampling: keep x when p(x) >= l * max p, p = softmax of the raw logits
+        reject = (len < 1.0) ? ((double)P[(size_t)tid * V + xi] - (double)srow[tid].m < log_len)
+                             : (srow[tid].arg != xi);
       } else {
         const RowStat sp = srow[tid], sq = srow[gamma + 1 + tid];
         const double p = (double)exp_scaled(P[(size_t)tid * V + xi], sp.m, invT) * (1.0 / sp.S);
         const double q = (double)exp_scaled(Q[(size_t)tid * V + xi], sq.m, invT) * (1.0 / sq.S);
-        const double ratio = (q > 0.0) ? p / q : INFINITY;
+        const double lq = q * len;
+        const double ratio = (lq > 0.0) ? p / lq : INFINITY;
         reject = ((double)r[tid] > ratio);
       }
     }
@@ -465,10 +502,10 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
       float4 vp[SAMPLE_REG_F4], vq[SAMPLE_REG_F4];
       load_row_regs(zp, V, vp);
       load_row_regs(zq, V, vq);               // unconditional; unused when all guesses were kept
-      t = icdf_regs(vp, srow[n], vq, sq, n < gamma, invT, V, s, sm);
+      t = icdf_regs(vp, srow[n], vq, sq, n < gamma, invT, V, s, sm, len);
       if (t < 0) { fell_back = 1; t = icdf_regs(vp, srow[n], vq, sq, false, invT, V, s, sm); }
     } else if (n < gamma) {
-      t = icdf_row(zp, srow[n], zq, sq, invT, V, s, sm);
+      t = icdf_row(zp, srow[n], zq, sq, invT, V, s, sm, len);
       if (t < 0) { fell_back = 1; t = icdf_row(zp, srow[n], nullptr, srow[n], invT, V, s, sm); }
     } else {
       t = icdf_row(zp, srow[n], nullptr, srow[n], invT, V, s, sm);

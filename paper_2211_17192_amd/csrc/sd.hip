@@ -166,6 +166,11 @@ struct sd_ctx {
   std::vector<hipEvent_t> kev;       // 2 per Mp layer: around the gated FFN-in GEMM (SD_FLAG_PROFILE)
   bool time_ffn = false;             // set while the verify forward of a profiled step is enqueued
   sd_stats stats{};
+  sd_sampling sampling{1.0f};
+  // acceptance statistics for the choice of gamma: they describe the pair and the task, not one
+  // sequence, so sd_reset leaves them alone
+  int64_t tune_accepted = 0, tune_tested = 0, tune_beta_count = 0;
+  double tune_beta_sum = 0.0;
   std::string err;
 };
 
@@ -391,7 +396,13 @@ void enqueue_step(sd_ctx* c, int gamma, bool profile) {
   if (profile) hipEventRecord(c->ev[2], s);
   hipLaunchKernelGGL(spec_verify_kernel<0>, dim3(2 * gamma + 1, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
                      c->q_logits, (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V,
-                     0.0f, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr, c->d_state);
+                     0.0f, 1.0f, 0.0, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr,
+                     (float*)nullptr, c->d_state);
+  if (c->rt.flags & SD_FLAG_BETA)               // side output: beta_i of every guess, into the state
+    hipLaunchKernelGGL(spec_verify_kernel<3>, dim3(gamma, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
+                       c->q_logits, (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V,
+                       0.0f, 1.0f, 0.0, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr,
+                       (float*)nullptr, c->d_state);
   if (profile) hipEventRecord(c->ev[3], s);
 }
 
@@ -667,6 +678,8 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
   if (c->len + gamma + 1 > std::min(c->p.cfg.max_len, c->q.cfg.max_len)) return fail(c, SD_ERANGE, "sequence would exceed max_len");
 
   c->h_params->temperature = temperature;
+  c->h_params->lenience = c->sampling.lenience;
+  c->h_params->log_lenience = std::log((double)c->sampling.lenience);
   for (int i = 0; i < 2 * gamma + 1; ++i) c->h_params->uniforms[i] = uniforms ? uniforms[i] : 0.5f;
   const bool profile = (c->rt.flags & SD_FLAG_PROFILE) != 0;
   const bool graph = (c->rt.flags & SD_FLAG_GRAPH) != 0 && !profile;
@@ -697,6 +710,15 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
   c->len = hs.len; c->last_tok = hs.last_tok;
   c->last_gamma = gamma; c->last_kind = 0;
   c->stats.steps += 1; c->stats.tokens += hs.n + 1; c->stats.accepted += hs.n; c->stats.fallbacks = hs.fallbacks;
+  const int tested = std::min(hs.n + 1, gamma);          // guesses whose test decided something
+  c->stats.tested += tested;
+  c->tune_tested += tested; c->tune_accepted += hs.n;
+  if (c->rt.flags & SD_FLAG_BETA) {
+    double b = 0.0;
+    for (int i = 0; i < tested; ++i) b += (double)hs.beta[i];
+    c->stats.beta_sum += b; c->stats.beta_count += tested;
+    c->tune_beta_sum += b; c->tune_beta_count += tested;
+  }
   if (profile) {
     float a = 0, b = 0, d = 0;
     hipEventElapsedTime(&a, c->ev[0], c->ev[1]); hipEventElapsedTime(&b, c->ev[1], c->ev[2]);
@@ -718,6 +740,7 @@ extern "C" sd_status sd_step_baseline(sd_ctx* c, float temperature, const float*
   if (st != SD_OK) return st;
   if (c->len + 1 > c->p.cfg.max_len) return fail(c, SD_ERANGE, "sequence would exceed max_len");
   c->h_params->temperature = temperature;
+  c->h_params->lenience = 1.0f; c->h_params->log_lenience = 0.0;
   c->h_params->uniforms[0] = uniforms ? uniforms[0] : 0.5f;
   if ((c->rt.flags & SD_FLAG_GRAPH) != 0) {
     if (!c->graph_baseline) {
@@ -763,8 +786,104 @@ extern "C" sd_status sd_debug_logits(sd_ctx* c, int32_t which, float* host_out, 
 
 extern "C" sd_status sd_set_flags(sd_ctx* c, int32_t flags) {
   if (!c) return SD_EINVAL;
-  if (flags & ~(SD_FLAG_GRAPH | SD_FLAG_PROFILE)) return fail(c, SD_EINVAL, "unknown flag");
+  if (flags & ~(SD_FLAG_GRAPH | SD_FLAG_PROFILE | SD_FLAG_BETA)) return fail(c, SD_EINVAL, "unknown flag");
+  if ((flags ^ c->rt.flags) & SD_FLAG_BETA) {            // the captured iteration changes
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (auto& g : c->graphs) if (g) { hipGraphExecDestroy(g); g = nullptr; }
+  }
   c->rt.flags = flags;
+  return SD_OK;
+}
+
+extern "C" sd_status sd_set_sampling(sd_ctx* c, const sd_sampling* opt) {
+  if (!c || !opt) return SD_EINVAL;
+  if (!(opt->lenience > 0.0f && opt->lenience <= 1.0f)) return fail(c, SD_EINVAL, "lenience must lie in (0, 1]");
+  c->sampling = *opt;
+  return SD_OK;
+}
+
+// Theorem 3.8 for one gamma; alpha -> 1 has the limit (gamma + 1) / (gamma c + 1).
+static double improvement_factor(double alpha, double c, int gamma) {
+  double tokens = 0.0, a = 1.0;                          // 1 + alpha + ... + alpha^gamma (Eq. 1)
+  for (int i = 0; i <= gamma; ++i) { tokens += a; a *= alpha; }
+  return tokens / ((double)gamma * c + 1.0);
+}
+
+extern "C" sd_status sd_choose_gamma(double alpha, double cost, int32_t gamma_max, int32_t* gamma, double* improvement) {
+  if (!gamma || gamma_max < 1 || !(alpha >= 0.0 && alpha < 1.0) || !(cost >= 0.0) || !std::isfinite(cost)) return SD_EINVAL;
+  int best = 1;
+  double best_v = improvement_factor(alpha, cost, 1);
+  for (int g = 2; g <= gamma_max; ++g) {
+    const double v = improvement_factor(alpha, cost, g);
+    if (v > best_v) { best_v = v; best = g; }
+  }
+  *gamma = best;
+  if (improvement) *improvement = best_v;
+  return SD_OK;
+}
+
+extern "C" sd_status sd_measure_cost(sd_ctx* c, int32_t reps, double* mq_us, double* mp_us) {
+  if (!c || !mq_us || !mp_us) return SD_EINVAL;
+  if (reps < 1 || reps > 1000) return fail(c, SD_EINVAL, "reps must be 1..1000");
+  if (c->state != 1) return fail(c, SD_ESTATE, "sd_measure_cost needs a prefilled sequence with a valid Mq cache");
+  if (c->len + 2 > std::min(c->p.cfg.max_len, c->q.cfg.max_len)) return fail(c, SD_ERANGE, "no room behind the committed sequence");
+  const int V = c->p.cfg.vocab;
+  // step parameters for the draws: whatever temperature was used last is fine, the uniform must be valid
+  c->h_params->uniforms[0] = 0.5f; c->h_params->uniforms[1] = 0.5f;
+  if (!(c->h_params->temperature >= 0.0f)) c->h_params->temperature = 1.0f;
+  c->h_params->lenience = c->sampling.lenience;
+  c->h_params->log_lenience = std::log((double)c->sampling.lenience);
+  HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  double us[2] = {0.0, 0.0};
+  for (int which = 0; which < 2; ++which) {
+    hipGraph_t g = nullptr;
+    hipGraphExec_t ge = nullptr;
+    HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+    if (which == 0) {      // a draft step that is not the first of an iteration: guess x_1 in, q_2 and x_2 out
+      forward_any(c, c->q, ROWS_DRAFT_NEXT, 1, 1, 0, 0, 1, c->q_logits + (size_t)V);
+      hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, c->stream, c->q_logits + (size_t)V, V,
+                         c->d_params, 1, c->d_state, 0, 1);
+    } else {               // standard decoding's forward and draw; the draw lands in a guess slot, nothing is committed
+      forward_any(c, c->p, ROWS_BASELINE, 0, 1, 0, 0, 1, c->p_logits);
+      hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
+                         c->d_params, 0, c->d_state, 0, 1);
+    }
+    HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
+    hipError_t e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+    hipGraphDestroy(g);
+    if (e != hipSuccess) return fail(c, SD_EHIP, std::string("graph instantiate: ") + hipGetErrorString(e));
+    hipGraphLaunch(ge, c->stream);                       // warm-up
+    hipEventRecord(c->ev[0], c->stream);
+    for (int i = 0; i < reps; ++i) hipGraphLaunch(ge, c->stream);
+    hipEventRecord(c->ev[1], c->stream);
+    e = hipStreamSynchronize(c->stream);
+    float ms = 0.0f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, c->ev[0], c->ev[1]);
+    hipGraphExecDestroy(ge);
+    if (e != hipSuccess) return fail(c, SD_EHIP, std::string("sd_measure_cost: ") + hipGetErrorString(e));
+    us[which] = 1e3 * (double)ms / (double)reps;
+  }
+  c->last_kind = -1;                                     // the logits buffers no longer hold a step's rows
+  *mq_us = us[0]; *mp_us = us[1];
+  return SD_OK;
+}
+
+extern "C" sd_status sd_autotune_gamma(sd_ctx* c, int32_t reps, int32_t* gamma, double* alpha, double* cost,
+                                       double* improvement) {
+  if (!c || !gamma) return SD_EINVAL;
+  if (c->tune_tested < 1) return fail(c, SD_ESTATE, "no acceptance test recorded yet: run sd_step first");
+  double a = (c->tune_beta_count > 0) ? c->tune_beta_sum / (double)c->tune_beta_count
+                                      : (double)c->tune_accepted / (double)c->tune_tested;
+  a = std::min(std::max(a, 0.0), 1.0 - 1e-9);
+  double mq = 0.0, mp = 0.0;
+  sd_status st = sd_measure_cost(c, reps, &mq, &mp);
+  if (st != SD_OK) return st;
+  const double cc = mq / mp;
+  st = sd_choose_gamma(a, cc, c->rt.max_gamma, gamma, improvement);
+  if (st != SD_OK) return fail(c, st, "sd_choose_gamma rejected the measured alpha / c");
+  if (alpha) *alpha = a;
+  if (cost) *cost = cc;
   return SD_OK;
 }
 

@@ -32,3 +32,30 @@ def test_workspace_sizing_needs_no_gpu():
     assert binding.lib.sd_workspace_bytes(ctypes.byref(cp), ctypes.byref(cq), ctypes.byref(rt)) == 0
     rt.batch, rt.max_gamma = 1, 16
     assert binding.lib.sd_workspace_bytes(ctypes.byref(cp), ctypes.byref(cq), ctypes.byref(rt)) == 0
+
+
+def test_choose_gamma_matches_brute_force_and_the_papers_rule():
+    """Section 3.5 host logic through the C ABI: the chosen gamma maximises Theorem 3.8
+    (checked against the oracle's search and a direct evaluation), gamma never shrinks as
+    alpha grows or c falls, and Corollary 3.9's condition alpha > c decides whether any
+    gamma gives an improvement."""
+    import numpy as np
+    from oracle import analysis
+    from paper_2211_17192_amd import binding
+    for c in (0.0, 0.01, 0.02, 0.05, 0.1, 0.2, 0.4):
+        prev = 0
+        for alpha in np.linspace(0.05, 0.95, 19):
+            g, v = binding.choose_gamma(alpha, c, 15)
+            assert g == analysis.optimal_gamma(alpha, c, 15)
+            direct = (1 - alpha ** (g + 1)) / ((1 - alpha) * (g * c + 1))
+            assert abs(v - direct) < 1e-12 * direct
+            for other in range(1, 16):
+                assert v >= analysis.walltime_improvement(alpha, other, c) - 1e-12
+            assert (v > 1.0) == (alpha > c) or abs(alpha - c) < 1e-9
+            assert g >= prev
+            prev = g
+    # c = 0: more guesses always help, the search stops at the cap
+    assert binding.choose_gamma(0.5, 0.0, 7)[0] == 7
+    g = ctypes.c_int32(0)
+    for bad in ((1.0, 0.1, 5), (-0.1, 0.1, 5), (0.5, -1.0, 5), (0.5, 0.1, 0), (float("nan"), 0.1, 5)):
+        assert binding.lib.sd_choose_gamma(bad[0], bad[1], bad[2], ctypes.byref(g), None) == binding.SD_EINVAL

@@ -275,3 +275,85 @@ def test_t5xxl_full_size_iteration_matches_oracle():
     print(f"T5-XXL-shaped pair, gamma=5: worst logit error {worst}, tolerated {tol}, mean n {mean_n:.2f}")
     assert tol["accept"] + tol["draw"] <= 1, tol
     dec.close()
+
+
+# ----------------------------------------------------------------------------
+# beyond Algorithm 1: lenience (appendix A.5), beta side output (section 3.1),
+# choice of gamma (section 3.5)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("temperature,lenience", [(1.0, 0.5), (0.0, 0.2)])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_lenient_decoding_and_beta_statistics_match_oracle(temperature, lenience, flags):
+    """The tiny fp32 pair decoded with lenience on the GPU and by the independent oracle run:
+    same tokens; the beta sums the context collects equal the oracle's sum of
+    sum_x min(p_i/l, q_i) over the guesses whose test counted."""
+    from oracle import analysis
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    sp, sq = oracle_models(cfg_p, w_p, cfg_q, w_q)
+    prompt = synth.random_tokens(1, 16, cfg_p["vocab"])
+    gamma = 4
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=flags | binding.SD_FLAG_BETA)
+    dec.set_sampling(lenience=lenience)
+    dec.prefill(prompt)
+    urows = synth.uniform_stream(2, 400 * 9).reshape(400, -1)
+    prefix = [int(t) for t in prompt]
+    beta_sum, beta_cnt, kept, kept_strict, mismatches = 0.0, 0, 0, 0, 0
+    l64 = float(np.float32(lenience))
+    for it in range(24):
+        u = urows[it]
+        n_g, toks_g = dec.step(gamma, temperature, u, prefix=prefix)
+        new_o, n_o, info = decode.speculative_decoding_step(sp, sq, prefix, gamma, temperature, u, lenience)
+        if new_o[len(prefix):] != toks_g:
+            assert temperature > 0 and info["margins"] is not None and np.min(info["margins"]) < 1e-3
+            mismatches += 1
+            break                                   # the sequences part ways at a tolerated decision
+        tested = min(n_o + 1, gamma)
+        for i in range(tested):
+            if temperature == 0:
+                ok = sampling.accept_and_resample_argmax_lenient(
+                    info["p_logits"][i:i + 2], [int(np.argmax(info["q_logits"][i]))], lenience)[0] == 1
+                beta_sum += 1.0 if ok else 0.0
+            else:
+                beta_sum += analysis.lenient_alpha(info["p_rows"][i], info["q_rows"][i], l64)
+        beta_cnt += tested
+        kept += n_o
+        kept_strict += decode.speculative_decoding_step(sp, sq, prefix, gamma, temperature, u)[1]
+        prefix = new_o
+    st = dec.stats()
+    assert mismatches <= 1
+    if mismatches == 0:
+        assert st["tested"] == beta_cnt and st["beta_count"] == beta_cnt and st["accepted"] == kept
+        assert abs(st["beta_sum"] - beta_sum) <= 1e-4 * max(beta_sum, 1.0)
+        assert kept >= kept_strict
+    dec.close()
+
+
+def test_gamma_autotuner_and_cost_measurement_leave_decoding_untouched():
+    """sd_measure_cost / sd_autotune_gamma between iterations: positive times, gamma equal to
+    sd_choose_gamma on the reported alpha and c, alpha equal to accepted / tested, and the
+    tokens decoded afterwards are the ones a context that never measured produces."""
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q, enc_p, enc_q = small_pair(T.T5DEC, "bf16")
+    prompt = synth.random_tokens(4, 9, cfg_p["vocab"])
+    urows = synth.uniform_stream(8, 40 * 11).reshape(40, -1)
+    outs = []
+    for measure in (False, True):
+        dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=5, flags=1)
+        dec.prefill(prompt, enc_p.cuda(), enc_q.cuda())
+        toks = []
+        for it in range(12):
+            if measure and it == 6:
+                mq_us, mp_us = dec.measure_cost(reps=5)
+                assert 0.0 < mq_us < 1e5 and 0.0 < mp_us < 1e5
+                tuned = dec.autotune_gamma(reps=5)
+                st = dec.stats()
+                assert abs(tuned["alpha"] - min(st["accepted"] / st["tested"], 1 - 1e-9)) < 1e-12
+                assert tuned["c"] > 0.0
+                g, v = binding.choose_gamma(tuned["alpha"], tuned["c"], 5)
+                assert (g, v) == (tuned["gamma"], tuned["improvement"])
+            n, t = dec.step(5, 1.0, urows[it])
+            toks += t
+        outs.append(toks)
+        dec.close()
+    assert outs[0] == outs[1]

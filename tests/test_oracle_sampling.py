@@ -228,6 +228,54 @@ def test_lenient_alpha_formula_against_enumeration():
     assert abs(acc / (len(gd) * len(gr)) - analysis.lenient_alpha(P1, Q1, l)) < 1e-12
 
 
+def test_lenient_output_distribution_closed_form_and_bound():
+    """Appendix A.5: with lenience l no token comes out with more than p(x)/l.  By exact
+    enumeration over (draft draw, test uniform, final draw) the one-guess output
+    distribution is min(q, p/l) + (1 - alpha_l) * max(0, p - l q) / (1 - l alpha_l)."""
+    for l in (0.5, 0.25):
+        p, q = np.array(P1), np.array(Q1)
+        gd, gr, gs = grid(8), grid(64), grid(512)
+        counts = np.zeros(4)
+        p_rows = np.array([P1, P1])
+        for d, r in itertools.product(gd, gr):
+            x = sampling.icdf(Q1, d)
+            n, _, _ = sampling.accept_and_resample(p_rows, np.array([Q1]), [x], [r], 0.5, lenience=l)
+            if n == 1:
+                counts[x] += len(gs)
+            else:
+                for sv in gs:
+                    _, t, _ = sampling.accept_and_resample(p_rows, np.array([Q1]), [x], [r], sv, lenience=l)
+                    counts[t] += 1
+        out = counts / (len(gd) * len(gr) * len(gs))
+        alpha = analysis.lenient_alpha(P1, Q1, l)
+        closed = np.minimum(q, p / l) + (1 - alpha) * np.maximum(0, p - l * q) / (1 - l * alpha)
+        # the final-draw grid resolves the residual only to 1/512 per reject case
+        np.testing.assert_allclose(out, closed, atol=2e-3)
+        assert abs(out.sum() - 1) < 1e-12
+        assert np.all(out <= p / l + 2e-3) and np.all(closed <= p / l + 1e-15)
+
+
+def test_argmax_lenience_special_cases():
+    """Appendix A.5, temperature 0: l = 1 is the exact argmax test (no ties), a tiny l
+    keeps every guess, kept guesses grow as l shrinks, and a hand-worked row."""
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        zp = rng.normal(0, 2, size=(4, 9))
+        zq = rng.normal(0, 2, size=(3, 9))
+        x = [int(np.argmax(zq[i])) if rng.random() < 0.5 else int(np.argmax(zp[i])) for i in range(3)]
+        n1, t1, _ = sampling.accept_and_resample_from_logits(zp, zq, x, [0.5] * 3, 0.5, 0.0)
+        n2, t2 = sampling.accept_and_resample_argmax_lenient(zp, x, 1.0)
+        assert (n1, t1) == (n2, t2)
+        ns = [sampling.accept_and_resample_argmax_lenient(zp, x, l)[0] for l in (1.0, 0.5, 0.1, 1e-3, 1e-30)]
+        assert ns == sorted(ns) and ns[-1] == 3
+    # softmax([0, ln 2, ln 4]) = [1/7, 2/7, 4/7]: token 1 has half the top probability
+    z = np.log(np.array([[1.0, 2.0, 4.0], [1.0, 1.0, 8.0]]))
+    assert sampling.accept_and_resample_argmax_lenient(z, [1], 0.51) == (0, 2)
+    assert sampling.accept_and_resample_argmax_lenient(z, [1], 0.49) == (1, 2)
+    assert sampling.accept_and_resample_argmax_lenient(z, [0], 0.26) == (0, 2)
+    assert sampling.accept_and_resample_argmax_lenient(z, [0], 0.24) == (1, 2)
+
+
 def test_uniform_validation():
     mp, mq = table_models()
     with pytest.raises(ValueError):
