@@ -25,12 +25,21 @@ from __future__ import annotations
 import numpy as np
 
 
-def standardise(logits, temperature: float) -> np.ndarray:
+def standardise(logits, temperature: float, top_k: int = 0, top_p: float = 0.0) -> np.ndarray:
     """Section 2.2: turn one logits row into the distribution that is sampled.
 
     temperature > 0: softmax(logits / temperature).
     temperature == 0: argmax sampling, i.e. all mass on the (lowest-index)
     maximum -- "zeroing out non-max elements and normalizing".
+    top_k > 0: only the k most probable tokens keep their mass (top-k sampling);
+    0 < top_p < 1: then only the smallest set of most probable tokens whose mass
+    reaches top_p keeps its mass (nucleus sampling); the rest is renormalised.
+    The section names both as samplers that become plain sampling from an
+    adjusted distribution but does not define them; the definitions used here:
+    a token is kept by top-k when its logit is >= the k-th largest logit, and by
+    the nucleus when its logit is >= the logit of the token at which the
+    descending cumulative mass first reaches top_p -- so tokens tied with the
+    last kept one are kept with it.  Argmax sampling ignores both.
     """
     z = np.asarray(logits, dtype=np.float64)
     if z.ndim != 1:
@@ -43,7 +52,31 @@ def standardise(logits, temperature: float) -> np.ndarray:
         return out
     y = z / float(temperature)
     e = np.exp(y - np.max(y))
+    if top_k > 0:
+        kth = np.sort(z)[::-1][min(int(top_k), z.size) - 1]
+        e = np.where(z >= kth, e, 0.0)
+    if 0.0 < top_p < 1.0:
+        order = np.argsort(-z, kind="stable")
+        cum = np.cumsum(e[order])
+        first = int(np.nonzero(cum >= top_p * cum[-1])[0][0])
+        e = np.where(z >= z[order[first]], e, 0.0)
     return e / np.sum(e)
+
+
+def nucleus_margin(logits, temperature: float, top_k: int, top_p: float) -> float:
+    """How close the nucleus decision of standardise() is to flipping: the smallest
+    distance, in units of total mass, between top_p and the descending cumulative
+    mass at a boundary between distinct logit values.  Tests use it to recognise
+    rows where fp32 and fp64 arithmetic may legitimately choose different sets."""
+    z = np.asarray(logits, dtype=np.float64)
+    y = z / float(temperature)
+    e = np.exp(y - np.max(y))
+    if top_k > 0:
+        kth = np.sort(z)[::-1][min(int(top_k), z.size) - 1]
+        e = np.where(z >= kth, e, 0.0)
+    order = np.argsort(-z, kind="stable")
+    cum = np.cumsum(e[order]) / np.sum(e)
+    return float(np.min(np.abs(cum - top_p)))
 
 
 def icdf(weights, u: float) -> int:
@@ -151,14 +184,16 @@ def accept_and_resample_argmax_lenient(p_logits, x, lenience: float):
     return n, int(np.argmax(z[n]))
 
 
-def accept_and_resample_from_logits(p_logits, q_logits, x, r, s, temperature: float, lenience: float = 1.0):
-    """Same as accept_and_resample, starting from logits rows (section 2.2 first).
-    With temperature 0 and lenience < 1 the argmax variant of the lenient test applies."""
+def accept_and_resample_from_logits(p_logits, q_logits, x, r, s, temperature: float, lenience: float = 1.0,
+                                    top_k: int = 0, top_p: float = 0.0):
+    """Same as accept_and_resample, starting from logits rows (section 2.2 first; the same
+    standardisation for both models).  With temperature 0 and lenience < 1 the argmax
+    variant of the lenient test applies."""
     if temperature == 0 and lenience < 1.0:
         n, t = accept_and_resample_argmax_lenient(p_logits, x, lenience)
         return n, t, {"fallback": False, "ratios": None, "margins": None}
-    p_rows = np.stack([standardise(z, temperature) for z in p_logits])
-    q_rows = np.stack([standardise(z, temperature) for z in q_logits])
+    p_rows = np.stack([standardise(z, temperature, top_k, top_p) for z in p_logits])
+    q_rows = np.stack([standardise(z, temperature, top_k, top_p) for z in q_logits])
     return accept_and_resample(p_rows, q_rows, x, r, s, lenience=np.float64(np.float32(lenience)))
 
 

@@ -276,6 +276,63 @@ def test_argmax_lenience_special_cases():
     assert sampling.accept_and_resample_argmax_lenient(z, [0], 0.24) == (1, 2)
 
 
+def test_top_k_and_nucleus_standardisation():
+    """Section 2.2: top-k and nucleus sampling as plain sampling from an adjusted distribution.
+    Hand-worked dyadic rows, reductions to argmax / plain sampling, and a brute-force
+    restatement (smallest prefix of the descending order whose mass reaches top_p)."""
+    z = np.log(np.array([1 / 2, 1 / 4, 1 / 8, 1 / 8]))
+    np.testing.assert_allclose(sampling.standardise(z, 1.0, top_k=2), [2 / 3, 1 / 3, 0, 0], atol=1e-15)
+    np.testing.assert_allclose(sampling.standardise(z, 1.0, top_k=3), [1 / 2, 1 / 4, 1 / 8, 1 / 8], atol=1e-15)  # tie kept
+    np.testing.assert_allclose(sampling.standardise(z, 1.0, top_p=0.4), [1, 0, 0, 0], atol=1e-15)
+    np.testing.assert_allclose(sampling.standardise(z, 1.0, top_p=0.7), [2 / 3, 1 / 3, 0, 0], atol=1e-15)
+    np.testing.assert_allclose(sampling.standardise(z, 1.0, top_p=0.8), [1 / 2, 1 / 4, 1 / 8, 1 / 8], atol=1e-15)
+    # top-k first, nucleus on what is left: {1/2, 1/4} -> {2/3, 1/3}; 0.6 needs only the first
+    np.testing.assert_allclose(sampling.standardise(z, 1.0, top_k=2, top_p=0.6), [1, 0, 0, 0], atol=1e-15)
+    np.testing.assert_allclose(sampling.standardise(z, 1.0, top_k=2, top_p=0.7), [2 / 3, 1 / 3, 0, 0], atol=1e-15)
+    rng = np.random.default_rng(11)
+    for _ in range(40):
+        v = int(rng.integers(5, 60))
+        z = rng.normal(0, 2.5, size=v)
+        T = float(rng.choice([0.5, 1.0, 1.7]))
+        plain = sampling.standardise(z, T)
+        np.testing.assert_array_equal(sampling.standardise(z, T, top_k=v + 3), plain)
+        np.testing.assert_array_equal(sampling.standardise(z, T, top_p=1.0), plain)
+        np.testing.assert_array_equal(sampling.standardise(z, T, top_k=1), sampling.standardise(z, 0.0))
+        np.testing.assert_array_equal(sampling.standardise(z, T, top_p=1e-9), sampling.standardise(z, 0.0))
+        k = int(rng.integers(1, v + 1))
+        top_p = float(rng.uniform(0.05, 0.95))
+        # brute force, top-k: exactly the k largest survive, with their softmax ratios
+        got = sampling.standardise(z, T, top_k=k)
+        keep = sorted(range(v), key=lambda i: -z[i])[:k]
+        want = np.zeros(v); want[keep] = plain[keep] / plain[keep].sum()
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=0)
+        # brute force, nucleus: grow the set one token at a time in descending probability
+        got = sampling.standardise(z, T, top_p=top_p)
+        order = sorted(range(v), key=lambda i: -plain[i])
+        mass, m = 0.0, 0
+        while mass < top_p:
+            mass += plain[order[m]]; m += 1
+        if sampling.nucleus_margin(z, T, 0, top_p) > 1e-9:
+            want = np.zeros(v); want[order[:m]] = plain[order[:m]] / plain[order[:m]].sum()
+            np.testing.assert_allclose(got, want, rtol=1e-12, atol=0)
+
+
+def test_speculative_sampling_with_top_k_is_distributed_as_the_adjusted_p():
+    """Section 2.2 + appendix A.1: with the same standardisation applied to both models the
+    one-guess output is distributed as the standardised p (exact enumeration)."""
+    mp, mq = table_models()
+    want = sampling.standardise(np.log(np.array(P1)), 1.0, top_k=2)      # {5/16, 7/16} renormalised
+    np.testing.assert_allclose(want, [0, 5 / 12, 0, 7 / 12], atol=1e-15)
+    counts = np.zeros(4)
+    gd, gr, gs = grid(12), grid(8), grid(8)
+    for d, r, sv in itertools.product(gd, gr, gs):
+        out, n, _ = decode.speculative_decoding_step(mp, mq, [0], 1, 1.0, [d, r, sv], top_k=2)
+        counts[out[1]] += 1
+    # q keeps {1/2, 1/4} -> {2/3, 1/3} (draw threshold 8/12); token 0 is always dropped, token 1 always
+    # kept; the residual {0, 1/12, 0, 7/12} normalises to {0, 1/8, 0, 7/8} (threshold 1/8)
+    np.testing.assert_allclose(counts / counts.sum(), want, atol=1e-12)
+
+
 def test_uniform_validation():
     mp, mq = table_models()
     with pytest.raises(ValueError):
