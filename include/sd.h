@@ -63,9 +63,20 @@ enum {
  *       sketches for argmax sampling is used: x_i is kept iff
  *       p_i(x_i) >= l max p_i with p_i = softmax of the unscaled logits, decided
  *       as z[x_i] - max z >= ln l in double precision.  l = 1 is Algorithm 1.
+ *   top_k, top_p : section 2.2 names top-k and nucleus sampling among the
+ *       samplers that amount to plain sampling from an adjusted distribution.
+ *       top_k > 0 keeps the tokens whose logit is >= the k-th largest logit;
+ *       0 < top_p < 1 then keeps the tokens whose logit is >= that of the token
+ *       at which the descending cumulative probability first reaches top_p
+ *       (tokens tied with the last kept one are kept); the rest is renormalised.
+ *       The same rule is applied to Mp and Mq rows.  0 switches either off;
+ *       temperature 0 ignores both.  Needs vocab <= 32768 and vocab % 4 == 0
+ *       (the row is filtered in registers); SD_EINVAL otherwise.
  */
 typedef struct {
-  float lenience;
+  float   lenience;
+  int32_t top_k;
+  float   top_p;
 } sd_sampling;
 
 /*
@@ -202,8 +213,9 @@ sd_status sd_debug_logits(sd_ctx* ctx, int32_t which, float* host_out, size_t n)
 sd_status sd_get_stats(sd_ctx* ctx, sd_stats* out);
 /* Replace the flags given at load for the following calls (captured graphs are rebuilt). */
 sd_status sd_set_flags(sd_ctx* ctx, int32_t flags);
-/* Sampling options for the following sd_step calls (host struct, copied).
- * SD_EINVAL unless 0 < lenience <= 1. */
+/* Sampling options for the following sd_step / sd_step_baseline calls (host
+ * struct, copied).  SD_EINVAL unless 0 < lenience <= 1, top_k >= 0,
+ * 0 <= top_p <= 1, and the vocabulary fits the filter when one is on. */
 sd_status sd_set_sampling(sd_ctx* ctx, const sd_sampling* opt);
 
 /*

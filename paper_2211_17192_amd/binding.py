@@ -50,7 +50,7 @@ lib.sd_spec_sample.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_int3
 
 
 class _Sampling(C.Structure):
-    _fields_ = [("lenience", C.c_float)]
+    _fields_ = [("lenience", C.c_float), ("top_k", C.c_int32), ("top_p", C.c_float)]
 
 
 lib.sd_spec_sample_ex.restype = C.c_int
@@ -78,7 +78,7 @@ def spec_sample_scratch(rows: int, gamma: int) -> torch.Tensor:
 
 
 def spec_sample(p_logits, q_logits, x, r, s, temperature: float, scratch=None, out_n=None, out_t=None,
-                lenience=None, beta=None):
+                lenience=None, beta=None, top_k=0, top_p=0.0):
     """sd_spec_sample on cuda tensors: p_logits [rows, gamma+1, V] fp32, q_logits
     [rows, gamma, V] fp32, x [rows, gamma] int32, r [rows, gamma] fp32, s [rows] fp32.
     Returns device tensors (n [rows], t [rows]); asynchronous on the current stream.
@@ -94,13 +94,13 @@ def spec_sample(p_logits, q_logits, x, r, s, temperature: float, scratch=None, o
     if out_n is None:
         out_n = torch.empty(rows, dtype=torch.int32, device="cuda")
         out_t = torch.empty(rows, dtype=torch.int32, device="cuda")
-    if lenience is None and beta is None:
+    if lenience is None and beta is None and not top_k and not top_p:
         st = lib.sd_spec_sample(_ptr(p_logits), _ptr(q_logits), _ptr(x), _ptr(r), _ptr(s), rows, gamma, V,
                                 float(temperature), _ptr(out_n), _ptr(out_t), _ptr(scratch), _stream())
     else:
         if beta is not None:
             assert beta.is_cuda and beta.is_contiguous() and beta.dtype == torch.float32 and beta.shape == (rows, gamma)
-        opt = _Sampling(1.0 if lenience is None else float(lenience))
+        opt = _Sampling(1.0 if lenience is None else float(lenience), int(top_k), float(top_p))
         st = lib.sd_spec_sample_ex(_ptr(p_logits), _ptr(q_logits), _ptr(x), _ptr(r), _ptr(s), rows, gamma, V,
                                    float(temperature), C.byref(opt), _ptr(out_n), _ptr(out_t),
                                    _ptr(beta) if beta is not None else None, _ptr(scratch), _stream())
@@ -277,8 +277,8 @@ class SpecDecoder:
     def set_flags(self, flags: int):
         self._check(lib.sd_set_flags(self._ctx, int(flags)))
 
-    def set_sampling(self, lenience: float = 1.0):
-        opt = _Sampling(float(lenience))
+    def set_sampling(self, lenience: float = 1.0, top_k: int = 0, top_p: float = 0.0):
+        opt = _Sampling(float(lenience), int(top_k), float(top_p))
         self._check(lib.sd_set_sampling(self._ctx, C.byref(opt)))
 
     def measure_cost(self, reps: int = 20):

@@ -36,7 +36,9 @@ struct StepParams {
   float temperature;
   float lenience;              // factor l of the lenient acceptance test, 1 = the exact algorithm
   float uniforms[2 * 15 + 1];  // [0,g) draft draws, [g,2g) accept tests, [2g] final draw
-  float pad;
+  float top_p;                 // nucleus mass, outside (0,1) = off
+  int32_t top_k;               // top-k sampling, 0 = off
+  int32_t pad;
 };
 
 template <typename T> struct Store;
@@ -138,6 +140,7 @@ struct OpSumF { __device__ float operator()(float a, float b) const { return a +
 struct OpSumD { __device__ double operator()(double a, double b) const { return a + b; } };
 struct OpMaxF { __device__ float operator()(float a, float b) const { return fmaxf(a, b); } };
 struct OpMinI { __device__ int operator()(int a, int b) const { return min(a, b); } };
+struct OpSumI { __device__ int operator()(int a, int b) const { return a + b; } };
 struct OpMaxI { __device__ int operator()(int a, int b) const { return max(a, b); } };
 
 __device__ __forceinline__ float wave_sum(float v) { return wave_allreduce(v, OpSumF()); }

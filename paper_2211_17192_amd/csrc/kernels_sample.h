@@ -25,7 +25,9 @@ constexpr int SAMPLE_REG_F4 = 8;            // a row up to 32768 entries is held
 struct RowStat {
   float  m;      // max logit
   int    arg;    // lowest index attaining it
-  double S;      // sum of e_k
+  double S;      // sum of e_k over the kept entries
+  float  thr;    // entries with a logit below it are dropped (top-k / nucleus); -inf: none
+  float  pad;
 };
 
 struct SampleSmem {
@@ -41,8 +43,17 @@ struct SampleSmem {
   double ctot[SAMPLE_MAX_CHUNKS];
 };
 
-__device__ __forceinline__ float exp_scaled(float z, float m, float invT) {
-  return __expf((z - m) * invT);
+__device__ __forceinline__ float exp_scaled(float z, float m, float invT, float thr) {
+  return (z >= thr) ? __expf((z - m) * invT) : 0.0f;      // padding (-inf) passes the test and gives 0
+}
+
+// Order-preserving map of a float onto unsigned integers, and back.
+__device__ __forceinline__ unsigned float_key(float z) {
+  const unsigned u = __float_as_uint(z);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_float(unsigned k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
 // A row of up to 32768 entries fits the registers of one 1024-thread workgroup:
@@ -62,10 +73,16 @@ __device__ __forceinline__ void load_row_regs(const float* __restrict__ z, int V
     v[it] = (i < n4) ? t : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
   }
 }
+// top_k > 0 / 0 < top_p < 1 (section 2.2: top-k and nucleus sampling as an adjusted
+// distribution): the kept set is {z >= thr}.  Top-k: thr = k-th largest logit, found bit by
+// bit on the order-preserving integer key (32 counting passes over the registers).  Nucleus,
+// applied to what top-k left: thr = the largest value whose upper set still carries top_p of
+// the mass, found the same way with sums in place of counts.  Ties with the last kept entry
+// are kept.  Argmax sampling ignores both.
 __device__ __forceinline__ RowStat row_stats_regs(const float4 (&v)[SAMPLE_REG_F4], float invT, bool greedy,
-                                                  SampleSmem& sm) {
+                                                  SampleSmem& sm, int top_k = 0, float top_p = 0.0f, int V = 0) {
   const int tid = threadIdx.x;
-  RowStat st; st.arg = 0; st.S = 0.0;
+  RowStat st; st.arg = 0; st.S = 0.0; st.thr = -INFINITY; st.pad = 0.0f;
   float m = -INFINITY;
 #pragma unroll
   for (int it = 0; it < SAMPLE_REG_F4; ++it)
@@ -85,26 +102,61 @@ __device__ __forceinline__ RowStat row_stats_regs(const float4 (&v)[SAMPLE_REG_F
     st.arg = block_reduce(a, sm.redi, OpMinI(), INT_MAX);
     return st;
   }
+  float thr = -INFINITY;
+  if (top_k > 0 && top_k < V) {
+    unsigned tau = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+      const unsigned cand = tau | (1u << bit);
+      int cnt = 0;
+#pragma unroll
+      for (int it = 0; it < SAMPLE_REG_F4; ++it)
+        cnt += (int)(float_key(v[it].x) >= cand) + (int)(float_key(v[it].y) >= cand) +
+               (int)(float_key(v[it].z) >= cand) + (int)(float_key(v[it].w) >= cand);
+      cnt = block_reduce(cnt, sm.redi, OpSumI(), 0);
+      if (cnt >= top_k) tau = cand;
+    }
+    thr = key_float(tau);
+  }
   float s = 0.0f;
 #pragma unroll
   for (int it = 0; it < SAMPLE_REG_F4; ++it)       // exp(-inf) = 0 for the padding
-    s += (exp_scaled(v[it].x, m, invT) + exp_scaled(v[it].y, m, invT)) +
-         (exp_scaled(v[it].z, m, invT) + exp_scaled(v[it].w, m, invT));
-  st.S = block_reduce((double)s, sm.redd, OpSumD(), 0.0);
+    s += (exp_scaled(v[it].x, m, invT, thr) + exp_scaled(v[it].y, m, invT, thr)) +
+         (exp_scaled(v[it].z, m, invT, thr) + exp_scaled(v[it].w, m, invT, thr));
+  double S = block_reduce((double)s, sm.redd, OpSumD(), 0.0);
+  if (top_p > 0.0f && top_p < 1.0f) {
+    const double target = (double)top_p * S;
+    const float floor_thr = thr;                   // what top-k dropped stays dropped
+    unsigned tau = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+      const unsigned cand = tau | (1u << bit);
+      const float ct = fmaxf(key_float(cand), floor_thr);
+      float part = 0.0f;
+#pragma unroll
+      for (int it = 0; it < SAMPLE_REG_F4; ++it)
+        part += (exp_scaled(v[it].x, m, invT, ct) + exp_scaled(v[it].y, m, invT, ct)) +
+                (exp_scaled(v[it].z, m, invT, ct) + exp_scaled(v[it].w, m, invT, ct));
+      const double mass = block_reduce((double)part, sm.redd, OpSumD(), 0.0);
+      if (mass >= target) { tau = cand; S = mass; }
+    }
+    thr = fmaxf(key_float(tau), floor_thr);
+  }
+  st.S = S;
+  st.thr = thr;
   return st;
 }
 
 // max / argmax / sum-of-exponentials of one logits row; every thread gets it.
 // Rows of up to 32768 entries are read from memory exactly once.
 __device__ __forceinline__ RowStat row_stats(const float* __restrict__ z, int V, float invT,
-                                             bool greedy, SampleSmem& sm) {
+                                             bool greedy, SampleSmem& sm, int top_k = 0, float top_p = 0.0f) {
   const int tid = threadIdx.x, nt = blockDim.x;
-  RowStat st; st.arg = 0; st.S = 0.0;
+  RowStat st; st.arg = 0; st.S = 0.0; st.thr = -INFINITY; st.pad = 0.0f;
   if (row_fits_regs(z, V)) {
     float4 v[SAMPLE_REG_F4];
     load_row_regs(z, V, v);
-    return row_stats_regs(v, invT, greedy, sm);
+    return row_stats_regs(v, invT, greedy, sm, top_k, top_p, V);
   }
+  // longer rows: no top-k / nucleus (the host side refuses the combination)
   float m = -INFINITY;
   for (int i = tid; i < V; i += nt) m = fmaxf(m, z[i]);
   m = block_reduce(m, sm.redf, OpMaxF(), -INFINITY);
@@ -116,7 +168,7 @@ __device__ __forceinline__ RowStat row_stats(const float* __restrict__ z, int V,
     return st;
   }
   double s = 0.0;
-  for (int i = tid; i < V; i += nt) s += (double)exp_scaled(z[i], m, invT);
+  for (int i = tid; i < V; i += nt) s += (double)exp_scaled(z[i], m, invT, -INFINITY);
   st.S = block_reduce(s, sm.redd, OpSumD(), 0.0);
   return st;
 }
@@ -126,6 +178,7 @@ __device__ __forceinline__ RowStat row_stats(const float* __restrict__ z, int V,
 struct RowPair {
   const float* zp; const float* zq;     // zq == nullptr: plain row
   float mp, mq;
+  float tp, tq;                         // drop thresholds of the two rows
   double invSp, invSq;
   float invT;
   int V;
@@ -153,9 +206,9 @@ __device__ __forceinline__ void calc4(const RowPair& rp, int k, const float (&zp
                                       double (&w)[4]) {
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    double p = (k + e < rp.V) ? (double)exp_scaled(zp[e], rp.mp, rp.invT) * rp.invSp : 0.0;
+    double p = (k + e < rp.V) ? (double)exp_scaled(zp[e], rp.mp, rp.invT, rp.tp) * rp.invSp : 0.0;
     if (rp.zq) {
-      const double q = (k + e < rp.V) ? (double)exp_scaled(zq[e], rp.mq, rp.invT) * rp.invSq : 0.0;
+      const double q = (k + e < rp.V) ? (double)exp_scaled(zq[e], rp.mq, rp.invT, rp.tq) * rp.invSq : 0.0;
       p -= q;
       p = p > 0.0 ? p : 0.0;
     }
@@ -249,7 +302,7 @@ __device__ __forceinline__ int icdf_row(const float* zp, const RowStat& sp, cons
                                         SampleSmem& sm, double qscale = 1.0) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
   RowPair rp;
-  rp.zp = zp; rp.zq = zq; rp.mp = sp.m; rp.mq = sq.m;
+  rp.zp = zp; rp.zq = zq; rp.mp = sp.m; rp.mq = sq.m; rp.tp = sp.thr; rp.tq = sq.thr;
   rp.invSp = 1.0 / sp.S; rp.invSq = zq ? qscale / sq.S : 0.0;     // q enters the residual as qscale * q
   rp.invT = invT; rp.V = V;
   rp.vec = ((V & 3) == 0) && ((reinterpret_cast<uintptr_t>(zp) & 15) == 0) &&
@@ -297,13 +350,14 @@ __device__ __forceinline__ int icdf_row(const float* zp, const RowStat& sp, cons
 // Inverse-CDF draw from rows held in registers (see row_fits_regs for the layout):
 // same arithmetic and summation order as icdf_row, without touching memory.
 __device__ __forceinline__ void weights_of(const float4& zp, const float4& zq, bool with_q, float mp, float mq,
-                                           double invSp, double invSq, float invT, double (&w)[4]) {
+                                           float tp, float tq, double invSp, double invSq, float invT,
+                                           double (&w)[4]) {
   const float a[4] = {zp.x, zp.y, zp.z, zp.w}, b[4] = {zq.x, zq.y, zq.z, zq.w};
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    double p = (double)exp_scaled(a[e], mp, invT) * invSp;        // padding: exp(-inf) = 0
+    double p = (double)exp_scaled(a[e], mp, invT, tp) * invSp;    // padding: exp(-inf) = 0
     if (with_q) {
-      p -= (double)exp_scaled(b[e], mq, invT) * invSq;
+      p -= (double)exp_scaled(b[e], mq, invT, tq) * invSq;
       p = p > 0.0 ? p : 0.0;
     }
     w[e] = p;
@@ -322,7 +376,7 @@ __device__ __forceinline__ int icdf_regs(const float4 (&vp)[SAMPLE_REG_F4], cons
   for (int it = 0; it < SAMPLE_REG_F4; ++it) {
     const int c = it * NW + wave;
     double w[4];
-    weights_of(vp[it], vq[it], with_q, sp.m, sq.m, invSp, invSq, invT, w);
+    weights_of(vp[it], vq[it], with_q, sp.m, sq.m, sp.thr, sq.thr, invSp, invSq, invT, w);
     const double t = wave_sum((w[0] + w[1]) + (w[2] + w[3]));
     if (lane == 0 && c < nchunks) sm.ctot[c] = t;
   }
@@ -338,7 +392,7 @@ __device__ __forceinline__ int icdf_regs(const float4 (&vp)[SAMPLE_REG_F4], cons
     double w[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int it = 0; it < SAMPLE_REG_F4; ++it)
-      if (it == c / NW) weights_of(vp[it], vq[it], with_q, sp.m, sq.m, invSp, invSq, invT, w);
+      if (it == c / NW) weights_of(vp[it], vq[it], with_q, sp.m, sq.m, sp.thr, sq.thr, invSp, invSq, invT, w);
     const int tok = pick_in_chunk(w, c * SAMPLE_CHUNK + lane * 4, V, fallback, (double)u * total, sm.before);
     if (lane == 0) sm.token = tok;
   }
@@ -363,7 +417,7 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void sample_row_kernel(
   if (row_fits_regs(logits, V)) {            // one read of the row: statistics and draw from registers
     float4 v[SAMPLE_REG_F4];
     load_row_regs(logits, V, v);
-    const RowStat rs = row_stats_regs(v, invT, greedy, sm);
+    const RowStat rs = row_stats_regs(v, invT, greedy, sm, prm->top_k, prm->top_p, V);
     tok = greedy ? rs.arg : icdf_regs(v, rs, v, rs, false, invT, V, prm->uniforms[uniform_idx], sm);
   } else {
     const RowStat rs = row_stats(logits, V, invT, greedy, sm);
@@ -405,7 +459,7 @@ template <int MODE>
 static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
     const float* __restrict__ p_logits, const float* __restrict__ q_logits,
     const int* __restrict__ x_in, const float* __restrict__ r_in, const float* __restrict__ s_in,
-    int gamma, int V, float temperature, float lenience_in, double log_lenience_in,
+    int gamma, int V, float temperature, float lenience_in, double log_lenience_in, int top_k_in, float top_p_in,
     const StepParams* __restrict__ prm,
     RowStat* __restrict__ stats, unsigned int* __restrict__ counters,
     int* __restrict__ out_n, int* __restrict__ out_t, float* __restrict__ beta_out,
@@ -419,6 +473,8 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
   const float invT = greedy ? 1.0f : 1.0f / T;
   const double len = (double)(prm ? prm->lenience : lenience_in);            // appendix A.5, 1 = exact
   const double log_len = prm ? prm->log_lenience : log_lenience_in;
+  const int top_k = prm ? prm->top_k : top_k_in;                             // section 2.2, same for p and q
+  const float top_p = prm ? prm->top_p : top_p_in;
   const float* P = p_logits + (size_t)b * (gamma + 1) * V;
   const float* Q = q_logits + (size_t)b * gamma * V;
   RowStat* my_stats = stats + (size_t)b * nrows;
@@ -443,8 +499,8 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
     const double ip = (1.0 / sp.S) / len, iq = 1.0 / sq.S;
     double acc = 0.0;
     for (int k = tid; k < V; k += SAMPLE_THREADS) {
-      const double pv = (double)exp_scaled(zp[k], sp.m, invT) * ip;
-      const double qv = (double)exp_scaled(zq[k], sq.m, invT) * iq;
+      const double pv = (double)exp_scaled(zp[k], sp.m, invT, sp.thr) * ip;
+      const double qv = (double)exp_scaled(zq[k], sq.m, invT, sq.thr) * iq;
       acc += pv < qv ? pv : qv;
     }
     acc = block_reduce(acc, sm.redd, OpSumD(), 0.0);
@@ -454,7 +510,7 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
 
   if (MODE != 2 && !(greedy && j > gamma)) {          // argmax sampling never looks at q rows
     const float* z = (j <= gamma) ? P + (size_t)j * V : Q + (size_t)(j - gamma - 1) * V;
-    const RowStat rs = row_stats(z, V, invT, greedy, sm);
+    const RowStat rs = row_stats(z, V, invT, greedy, sm, top_k, top_p);
     if (tid == 0) my_stats[j] = rs;
   }
   if (MODE == 1) return;
@@ -478,8 +534,8 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
                              : (srow[tid].arg != xi);
       } else {
         const RowStat sp = srow[tid], sq = srow[gamma + 1 + tid];
-        const double p = (double)exp_scaled(P[(size_t)tid * V + xi], sp.m, invT) * (1.0 / sp.S);
-        const double q = (double)exp_scaled(Q[(size_t)tid * V + xi], sq.m, invT) * (1.0 / sq.S);
+        const double p = (double)exp_scaled(P[(size_t)tid * V + xi], sp.m, invT, sp.thr) * (1.0 / sp.S);
+        const double q = (double)exp_scaled(Q[(size_t)tid * V + xi], sq.m, invT, sq.thr) * (1.0 / sq.S);
         const double lq = q * len;
         const double ratio = (lq > 0.0) ? p / lq : INFINITY;
         reject = ((double)r[tid] > ratio);

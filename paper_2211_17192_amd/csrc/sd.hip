@@ -166,7 +166,7 @@ struct sd_ctx {
   std::vector<hipEvent_t> kev;       // 2 per Mp layer: around the gated FFN-in GEMM (SD_FLAG_PROFILE)
   bool time_ffn = false;             // set while the verify forward of a profiled step is enqueued
   sd_stats stats{};
-  sd_sampling sampling{1.0f};
+  sd_sampling sampling{1.0f, 0, 0.0f};
   // acceptance statistics for the choice of gamma: they describe the pair and the task, not one
   // sequence, so sd_reset leaves them alone
   int64_t tune_accepted = 0, tune_tested = 0, tune_beta_count = 0;
@@ -396,12 +396,12 @@ void enqueue_step(sd_ctx* c, int gamma, bool profile) {
   if (profile) hipEventRecord(c->ev[2], s);
   hipLaunchKernelGGL(spec_verify_kernel<0>, dim3(2 * gamma + 1, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
                      c->q_logits, (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V,
-                     0.0f, 1.0f, 0.0, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr,
+                     0.0f, 1.0f, 0.0, 0, 0.0f, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr,
                      (float*)nullptr, c->d_state);
   if (c->rt.flags & SD_FLAG_BETA)               // side output: beta_i of every guess, into the state
     hipLaunchKernelGGL(spec_verify_kernel<3>, dim3(gamma, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
                        c->q_logits, (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V,
-                       0.0f, 1.0f, 0.0, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr,
+                       0.0f, 1.0f, 0.0, 0, 0.0f, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr,
                        (float*)nullptr, c->d_state);
   if (profile) hipEventRecord(c->ev[3], s);
 }
@@ -680,6 +680,7 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
   c->h_params->temperature = temperature;
   c->h_params->lenience = c->sampling.lenience;
   c->h_params->log_lenience = std::log((double)c->sampling.lenience);
+  c->h_params->top_k = c->sampling.top_k; c->h_params->top_p = c->sampling.top_p;
   for (int i = 0; i < 2 * gamma + 1; ++i) c->h_params->uniforms[i] = uniforms ? uniforms[i] : 0.5f;
   const bool profile = (c->rt.flags & SD_FLAG_PROFILE) != 0;
   const bool graph = (c->rt.flags & SD_FLAG_GRAPH) != 0 && !profile;
@@ -741,6 +742,7 @@ extern "C" sd_status sd_step_baseline(sd_ctx* c, float temperature, const float*
   if (c->len + 1 > c->p.cfg.max_len) return fail(c, SD_ERANGE, "sequence would exceed max_len");
   c->h_params->temperature = temperature;
   c->h_params->lenience = 1.0f; c->h_params->log_lenience = 0.0;
+  c->h_params->top_k = c->sampling.top_k; c->h_params->top_p = c->sampling.top_p;
   c->h_params->uniforms[0] = uniforms ? uniforms[0] : 0.5f;
   if ((c->rt.flags & SD_FLAG_GRAPH) != 0) {
     if (!c->graph_baseline) {
@@ -798,6 +800,10 @@ extern "C" sd_status sd_set_flags(sd_ctx* c, int32_t flags) {
 extern "C" sd_status sd_set_sampling(sd_ctx* c, const sd_sampling* opt) {
   if (!c || !opt) return SD_EINVAL;
   if (!(opt->lenience > 0.0f && opt->lenience <= 1.0f)) return fail(c, SD_EINVAL, "lenience must lie in (0, 1]");
+  if (opt->top_k < 0 || !(opt->top_p >= 0.0f && opt->top_p <= 1.0f)) return fail(c, SD_EINVAL, "top_k must be >= 0 and top_p in [0, 1]");
+  const bool filter = opt->top_k > 0 || (opt->top_p > 0.0f && opt->top_p < 1.0f);
+  if (filter && (c->p.cfg.vocab > SAMPLE_REG_F4 * 4 * SAMPLE_THREADS || (c->p.cfg.vocab & 3)))
+    return fail(c, SD_EINVAL, "top-k / nucleus need vocab <= 32768 and vocab % 4 == 0");
   c->sampling = *opt;
   return SD_OK;
 }
@@ -833,6 +839,7 @@ extern "C" sd_status sd_measure_cost(sd_ctx* c, int32_t reps, double* mq_us, dou
   if (!(c->h_params->temperature >= 0.0f)) c->h_params->temperature = 1.0f;
   c->h_params->lenience = c->sampling.lenience;
   c->h_params->log_lenience = std::log((double)c->sampling.lenience);
+  c->h_params->top_k = c->sampling.top_k; c->h_params->top_p = c->sampling.top_p;
   HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   double us[2] = {0.0, 0.0};

@@ -2,6 +2,7 @@
 // half of Algorithm 1 on explicit logits).  See include/sd.h.
 #include <hip/hip_runtime.h>
 #include <cmath>
+#include <cstdint>
 #include "../../include/sd.h"
 #include "kernels_sample.h"
 
@@ -27,6 +28,13 @@ extern "C" sd_status sd_spec_sample_ex(const float* p_logits, const float* q_log
   const float len = opt ? opt->lenience : 1.0f;
   if (!(len > 0.0f && len <= 1.0f)) return SD_EINVAL;
   const double log_len = std::log((double)len);
+  const int top_k = opt ? opt->top_k : 0;
+  const float top_p = opt ? opt->top_p : 0.0f;
+  if (top_k < 0 || !(top_p >= 0.0f && top_p <= 1.0f)) return SD_EINVAL;
+  if ((top_k > 0 || (top_p > 0.0f && top_p < 1.0f)) &&
+      (vocab > sd::SAMPLE_REG_F4 * 4 * sd::SAMPLE_THREADS || (vocab & 3) ||
+       (reinterpret_cast<uintptr_t>(p_logits) & 15) || (reinterpret_cast<uintptr_t>(q_logits) & 15)))
+    return SD_EINVAL;                            // the filters run on rows held in registers
   unsigned int* counters = static_cast<unsigned int*>(scratch);
   sd::RowStat* stats = reinterpret_cast<sd::RowStat*>(
       static_cast<char*>(scratch) + scratch_align((size_t)rows * sd::SAMPLE_COUNTER_STRIDE * sizeof(unsigned int), 256));
@@ -34,7 +42,7 @@ extern "C" sd_status sd_spec_sample_ex(const float* p_logits, const float* q_log
   hipStream_t s_ = static_cast<hipStream_t>(stream);
 #define SD_VERIFY(MODE, GRID)                                                                                   \
   hipLaunchKernelGGL(sd::spec_verify_kernel<MODE>, GRID, block, 0, s_, p_logits, q_logits, x, r, s, gamma, vocab, \
-                     temperature, len, log_len, (const sd::StepParams*)nullptr, stats, counters, out_n, out_t,  \
+                     temperature, len, log_len, top_k, top_p, (const sd::StepParams*)nullptr, stats, counters, out_n, out_t,  \
                      beta, (sd::SeqState*)nullptr)
   if (rows * (2 * gamma + 1) <= 64) {           // few tickets: one launch
     SD_VERIFY(0, grid);

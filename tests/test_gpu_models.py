@@ -357,3 +357,47 @@ def test_gamma_autotuner_and_cost_measurement_leave_decoding_untouched():
         outs.append(toks)
         dec.close()
     assert outs[0] == outs[1]
+
+
+@pytest.mark.parametrize("top_k,top_p", [(5, 0.0), (0, 0.85), (12, 0.9)])
+def test_top_k_and_nucleus_decoding_matches_oracle(top_k, top_p):
+    """The tiny fp32 pair decoded with top-k / nucleus standardisation (section 2.2): draft
+    draws, acceptance tests and the extra token against the independent oracle run, and
+    plain decoding with the same filter against the oracle's plain decoding."""
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    sp, sq = oracle_models(cfg_p, w_p, cfg_q, w_q)
+    prompt = synth.random_tokens(1, 16, cfg_p["vocab"])
+    gamma = 4
+    tp = float(np.float32(top_p))
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=1)
+    dec.set_sampling(top_k=top_k, top_p=top_p)
+    dec.prefill(prompt)
+    urows = synth.uniform_stream(3, 400 * 9).reshape(400, -1)
+    prefix = [int(t) for t in prompt]
+    kept, broke = 0, 0
+    for it in range(30):
+        u = urows[it]
+        n_g, toks_g = dec.step(gamma, 1.0, u, prefix=prefix)
+        new_o, n_o, info = decode.speculative_decoding_step(sp, sq, prefix, gamma, 1.0, u, 1.0, top_k, tp)
+        if new_o[len(prefix):] != toks_g:
+            # explained by a near-threshold acceptance test or a nucleus boundary next to top_p
+            rows = list(info["p_logits"]) + list(info["q_logits"])
+            near = min(sampling.nucleus_margin(z, 1.0, top_k, tp) for z in rows) if 0 < tp < 1 else 1.0
+            assert np.min(info["margins"]) < 1e-3 or near < 1e-4, (it, toks_g, new_o[len(prefix):])
+            broke += 1
+            break
+        for i in range(gamma):                       # every guess lies in q's kept set
+            assert info["q_rows"][i][info["x"][i]] > 0
+        kept += n_o
+        prefix = new_o
+    assert broke <= 1 and kept > 0
+    # plain decoding with the same standardisation
+    dec.reset(); dec.prefill(prompt)
+    ub = synth.uniform_stream(4, 20)
+    got = [dec.step_baseline(1.0, ub[i]) for i in range(20)]
+    want = decode.plain_decode(sp, prompt, 20, 1.0, ub, top_k, tp)[len(prompt):]
+    if got != want:
+        j = next(i for i in range(20) if got[i] != want[i])
+        z = sp.score([int(t) for t in prompt] + want[:j], 1)[0]
+        assert 0 < tp < 1 and sampling.nucleus_margin(z, 1.0, top_k, tp) < 1e-4
+    dec.close()

@@ -170,3 +170,66 @@ def test_lenient_argmax_sampling_matches_oracle(lenience):
             ok = sampling.accept_and_resample_argmax_lenient(zp[b, i:i + 2], [int(xg[b, i])], lenience)[0] == 1
             assert float(beta[b, i]) == (1.0 if ok else 0.0)
     assert 0 < kept < rows * gamma
+
+
+@pytest.mark.parametrize("rows,gamma,vocab,temperature,top_k,top_p", [
+    (16, 5, 32128, 1.0, 40, 0.0), (16, 5, 32128, 1.0, 0, 0.9), (70, 3, 32128, 0.7, 50, 0.8),
+    (8, 4, 4096, 1.0, 1, 0.0), (8, 4, 1000, 1.3, 0, 0.5), (4, 2, 256, 1.0, 300, 0.999),
+])
+def test_top_k_and_nucleus_match_oracle(rows, gamma, vocab, temperature, top_k, top_p):
+    """Section 2.2 standardisation with top-k / nucleus inside the kernel, the same for p and q
+    rows: n, t and beta against the oracle.  The guesses are drawn from the filtered q, as
+    Algorithm 1 does.  Rows whose nucleus boundary lies within 1e-5 of top_p (fp32 vs fp64
+    exponentials may then choose different sets) are skipped and counted."""
+    from paper_2211_17192_amd import binding
+    zp, zq, _, r, s = synth.sampler_case(rows, gamma, vocab, 1.0, 44)
+    # peaked rows (logit std 7.5): with flatter ones the tokens at a nucleus boundary carry ~1e-5
+    # of the mass each over 32128 entries, and most boundaries would sit inside the skip margin
+    zp, zq = (zp * np.float32(2.5)).astype(np.float32), (zq * np.float32(2.5)).astype(np.float32)
+    tp = float(np.float32(top_p))
+    d = synth.uniform_stream(45, rows * gamma).reshape(rows, gamma)
+    q_rows = [[sampling.standardise(zq[b, i], temperature, top_k, tp) for i in range(gamma)] for b in range(rows)]
+    x = np.array([[sampling.icdf(q_rows[b][i], d[b, i]) for i in range(gamma)] for b in range(rows)], dtype=np.int32)
+    beta = torch.full((rows, gamma), -1.0, device="cuda")
+    n_d, t_d = binding.spec_sample(torch.from_numpy(zp).cuda(), torch.from_numpy(zq).cuda(),
+                                   torch.from_numpy(x).cuda(), torch.from_numpy(r).cuda(),
+                                   torch.from_numpy(s).cuda(), temperature, beta=beta, top_k=top_k, top_p=top_p)
+    torch.cuda.synchronize()
+    n_g, t_g, beta_g = n_d.cpu().numpy(), t_d.cpu().numpy(), beta.cpu().numpy()
+    skipped, tolerated, rejected = 0, 0, 0
+    for b in range(rows):
+        if 0.0 < tp < 1.0:
+            margin = min(sampling.nucleus_margin(z, temperature, top_k, tp) for z in list(zp[b]) + list(zq[b]))
+            if margin < 1e-5:
+                skipped += 1
+                continue
+        p_rows = np.stack([sampling.standardise(z, temperature, top_k, tp) for z in zp[b]])
+        qr = np.stack(q_rows[b])
+        n_o, t_o, info = sampling.accept_and_resample(p_rows, qr, list(x[b]), r[b], s[b])
+        rejected += int(n_o < gamma)
+        for i in range(gamma):
+            want = sampling.beta(p_rows[i], qr[i])
+            assert abs(beta_g[b, i] - want) <= 2e-6 * max(want, 1e-3), (b, i, beta_g[b, i], want)
+        if (n_g[b], t_g[b]) == (n_o, t_o):
+            continue
+        if n_g[b] != n_o:
+            assert info["margins"][min(n_g[b], n_o)] < 1e-3
+        else:
+            w = p_rows[n_o] if n_o == gamma else sampling.adjusted_distribution(p_rows[n_o], qr[n_o])
+            assert sampling.icdf_edge_distance(w, s[b], int(t_g[b])) < 1e-5
+        tolerated += 1
+    assert tolerated <= 1 and skipped <= rows // 4
+    if top_k != 1:
+        assert rejected > 0
+
+
+def test_filters_refuse_vocabularies_they_cannot_hold():
+    from paper_2211_17192_amd import binding
+    z = torch.zeros(1, 2, 40000, device="cuda")
+    with pytest.raises(binding.SdError):
+        binding.spec_sample(z, z[:, :1].contiguous(), torch.zeros(1, 1, dtype=torch.int32, device="cuda"),
+                            torch.full((1, 1), 0.5, device="cuda"), torch.full((1,), 0.5, device="cuda"), 1.0, top_k=5)
+    z = torch.zeros(1, 2, 1001, device="cuda")
+    with pytest.raises(binding.SdError):
+        binding.spec_sample(z, z[:, :1].contiguous(), torch.zeros(1, 1, dtype=torch.int32, device="cuda"),
+                            torch.full((1, 1), 0.5, device="cuda"), torch.full((1,), 0.5, device="cuda"), 1.0, top_p=0.5)
