@@ -42,7 +42,8 @@ typedef enum {
 typedef enum { SD_F32 = 0, SD_BF16 = 1 } sd_dtype;
 
 enum { SD_ARCH_GPT = 0, SD_ARCH_T5DEC = 1, SD_ARCH_GQA = 2 };
-enum { SD_MAX_GAMMA = 15 };       /* a forward handles at most SD_MAX_GAMMA+1 rows */
+enum { SD_MAX_GAMMA = 15 };       /* a sequence contributes at most SD_MAX_GAMMA+1 rows to a forward */
+enum { SD_MAX_BATCH = 64 };       /* sequences decoded together */
 
 /* Flags of sd_runtime_cfg.flags */
 enum {
@@ -123,7 +124,9 @@ typedef struct {
 } sd_tensor;
 
 typedef struct {
-  int32_t batch;            /* sequences decoded together; only 1 is supported */
+  int32_t batch;            /* sequences decoded together, 1..SD_MAX_BATCH (1 for T5DEC models).  Rows are
+                               independent: own prompt, own uniforms, own n, own KV pages.  The paper's
+                               runs are single-sequence; this is the same algorithm per row. */
   int32_t max_gamma;        /* largest gamma sd_step will be called with, 1..SD_MAX_GAMMA */
   int32_t page_size;        /* KV-cache page, positions; power of two, >= 16 */
   void*   workspace;        /* dev, 256-byte aligned, caller-owned, outlives the context */
@@ -164,7 +167,8 @@ sd_status sd_load_models(sd_ctx** out,
  * token.  prompt: host, prompt_len >= 1 ids.  enc_out_p / enc_out_q: dev,
  * [enc_len, d_model] of the respective model in its dtype (T5DEC), else NULL;
  * their cross-attention keys / values are computed here, once.
- * row must be 0.  Requires prompt_len + max_gamma + 1 <= max_len of both models. */
+ * row: the sequence, 0..batch-1; sd_step needs every sequence prefilled.
+ * Requires prompt_len + max_gamma + 1 <= max_len of both models. */
 sd_status sd_prefill(sd_ctx* ctx, int32_t row, const int32_t* prompt, int32_t prompt_len,
                      const void* enc_out_p, const void* enc_out_q);
 
@@ -184,6 +188,9 @@ sd_status sd_prefill(sd_ctx* ctx, int32_t row, const int32_t* prompt, int32_t pr
  *   out_n       : host, receives n, the number of accepted guesses.
  * On return the committed sequence is n+1 tokens longer and both KV caches
  * are rolled back to it.
+ * With batch > 1 every sequence takes one run, all in the same launches:
+ * uniforms is [batch][2*gamma+1], out_tokens [batch][gamma+1], out_n [batch];
+ * each sequence has its own n and its own roll-back; prefix must be NULL.
  */
 sd_status sd_step(sd_ctx* ctx, const int32_t* prefix, int32_t prefix_len,
                   int32_t gamma, float temperature, const float* uniforms,
@@ -191,13 +198,15 @@ sd_status sd_step(sd_ctx* ctx, const int32_t* prefix, int32_t prefix_len,
 
 /* Standard decoding (section 1 / the denominator of Theorem 3.8): one Mp
  * forward on the last token, one draw from p with uniforms[0] (host; may be
- * NULL iff temperature == 0).  out_token: host.  Leaves Mq's cache behind:
+ * NULL iff temperature == 0).  out_token: host.  With batch > 1: uniforms
+ * [batch], out_token [batch], one token per sequence.  Leaves Mq's cache behind:
  * sd_step after sd_step_baseline needs sd_reset + sd_prefill first
  * (SD_ESTATE otherwise). */
 sd_status sd_step_baseline(sd_ctx* ctx, float temperature, const float* uniforms,
                            int32_t* out_token);
 
-/* Forget the sequence (row must be 0 or -1): KV lengths to zero, state EMPTY. */
+/* Forget sequence `row` (-1: all of them, and the statistics): it must be prefilled again
+ * before the next sd_step. */
 sd_status sd_reset(sd_ctx* ctx, int32_t row);
 
 void sd_free(sd_ctx* ctx);
@@ -207,8 +216,8 @@ void sd_free(sd_ctx* ctx);
 const char* sd_last_error(const sd_ctx* ctx);
 
 /* Measurement / test access.  which = 0: Mp logits of the last step,
- * [gamma+1, vocab]; which = 1: Mq logits, [gamma, vocab]; which = 2 after
- * sd_step_baseline: [1, vocab].  host_out: host, n floats (n <= rows*vocab). */
+ * [batch, gamma+1, vocab]; which = 1: Mq logits, [batch, gamma, vocab]; which = 2
+ * after sd_step_baseline: [batch, vocab].  host_out: host, n floats (n <= rows*vocab). */
 sd_status sd_debug_logits(sd_ctx* ctx, int32_t which, float* host_out, size_t n);
 sd_status sd_get_stats(sd_ctx* ctx, sd_stats* out);
 /* Replace the flags given at load for the following calls (captured graphs are rebuilt). */

@@ -202,11 +202,12 @@ class SpecDecoder:
     """One (Mp, Mq) pair bound with sd_load_models.  Weights are dicts name -> cuda tensor."""
 
     def __init__(self, cfg_p: dict, w_p: dict, cfg_q: dict, w_q: dict, max_gamma: int = 7,
-                 page_size: int = 16, flags: int = 0):
+                 page_size: int = 16, flags: int = 0, batch: int = 1):
         self._ctx = C.c_void_p()
         self.cfg_p, self.cfg_q = cfg_p, cfg_q
+        self.batch = int(batch)
         cp, cq = _cfg_struct(cfg_p), _cfg_struct(cfg_q)
-        rt = _RuntimeCfg(batch=1, max_gamma=max_gamma, page_size=page_size, workspace=None,
+        rt = _RuntimeCfg(batch=self.batch, max_gamma=max_gamma, page_size=page_size, workspace=None,
                          workspace_bytes=0, stream=None, flags=flags)
         need = lib.sd_workspace_bytes(C.byref(cp), C.byref(cq), C.byref(rt))
         if need == 0:
@@ -228,35 +229,41 @@ class SpecDecoder:
         if st != SD_OK:
             raise SdError(st, (lib.sd_last_error(self._ctx) or b"").decode())
 
-    def prefill(self, prompt, enc_p=None, enc_q=None):
+    def prefill(self, prompt, enc_p=None, enc_q=None, row: int = 0):
         p = np.ascontiguousarray(np.asarray(prompt, dtype=np.int32))
         torch.cuda.synchronize()
-        self._check(lib.sd_prefill(self._ctx, 0, p.ctypes.data_as(C.POINTER(C.c_int32)), len(p),
+        self._check(lib.sd_prefill(self._ctx, int(row), p.ctypes.data_as(C.POINTER(C.c_int32)), len(p),
                                    _ptr(enc_p), _ptr(enc_q)))
 
     def step(self, gamma: int, temperature: float, uniforms=None, prefix=None):
-        out = (C.c_int32 * (gamma + 1))()
-        n = C.c_int32()
+        """One run of Algorithm 1.  batch 1: uniforms [2*gamma+1] -> (n, tokens).
+        batch B > 1: uniforms [B, 2*gamma+1] -> list of (n, tokens), one per sequence."""
+        B = self.batch
+        out = (C.c_int32 * (B * (gamma + 1)))()
+        n = (C.c_int32 * B)()
         u = None
         if uniforms is not None:
             ua = np.ascontiguousarray(np.asarray(uniforms, dtype=np.float32))
-            assert ua.shape == (2 * gamma + 1,)
+            assert ua.shape == ((2 * gamma + 1,) if B == 1 else (B, 2 * gamma + 1))
             u = ua.ctypes.data_as(C.POINTER(C.c_float))
         pp, pl = None, 0
         if prefix is not None:
             pa = np.ascontiguousarray(np.asarray(prefix, dtype=np.int32))
             pp, pl = pa.ctypes.data_as(C.POINTER(C.c_int32)), len(pa)
-        self._check(lib.sd_step(self._ctx, pp, pl, gamma, float(temperature), u, out, C.byref(n)))
-        return n.value, [out[i] for i in range(n.value + 1)]
+        self._check(lib.sd_step(self._ctx, pp, pl, gamma, float(temperature), u, out, n))
+        res = [(n[b], [out[b * (gamma + 1) + i] for i in range(n[b] + 1)]) for b in range(B)]
+        return res[0] if B == 1 else res
 
-    def step_baseline(self, temperature: float, uniform=None) -> int:
-        tok = C.c_int32()
+    def step_baseline(self, temperature: float, uniform=None):
+        """One standard decoding step: a token (batch 1) or a list of tokens, one per sequence."""
+        B = self.batch
+        tok = (C.c_int32 * B)()
         u = None
         if uniform is not None:
-            ua = np.asarray([uniform], dtype=np.float32)
+            ua = np.ascontiguousarray(np.asarray(uniform, dtype=np.float32).reshape(B))
             u = ua.ctypes.data_as(C.POINTER(C.c_float))
-        self._check(lib.sd_step_baseline(self._ctx, float(temperature), u, C.byref(tok)))
-        return tok.value
+        self._check(lib.sd_step_baseline(self._ctx, float(temperature), u, tok))
+        return tok[0] if B == 1 else [tok[b] for b in range(B)]
 
     def logits(self, which: int, rows: int) -> np.ndarray:
         out = np.empty((rows, self.vocab), dtype=np.float32)
@@ -293,8 +300,8 @@ class SpecDecoder:
         self._check(lib.sd_autotune_gamma(self._ctx, int(reps), C.byref(g), C.byref(a), C.byref(c), C.byref(v)))
         return {"gamma": g.value, "alpha": a.value, "c": c.value, "improvement": v.value}
 
-    def reset(self):
-        self._check(lib.sd_reset(self._ctx, -1))
+    def reset(self, row: int = -1):
+        self._check(lib.sd_reset(self._ctx, int(row)))
 
     def close(self):
         if self._ctx:

@@ -66,6 +66,9 @@ struct AttnArgs {
   const int* row_pos;       // [R]; self: causal limit of each row, < 0 = padding row
   int R, H, Hkv;
   int rows_per_wg;          // grid.y = ceil(R / rows_per_wg): rows are independent, no merge needed
+  // several sequences in one launch: grid.z = sequences, R rows each, one after the other in
+  // q / out / row_pos; sequence z uses the page table at page_table + (seq0 + z) * pt_stride
+  int seq0, pt_stride;
   int cross;                // 1: cross-attention over kv_len keys, no mask, no bias
   int kv_len;
   float scale;
@@ -90,8 +93,10 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int hkv = blockIdx.x;
   // rows are independent: blockIdx.y takes rows [r0, r0 + R) of the launch
-  const int r0 = blockIdx.y * a.rows_per_wg;
-  const int R = min(a.rows_per_wg, a.R - r0);
+  const int rs = blockIdx.y * a.rows_per_wg;                   // first row within the sequence
+  const int R = min(a.rows_per_wg, a.R - rs);
+  const int r0 = blockIdx.z * a.R + rs;                        // first row within the launch
+  const int* page_table = a.page_table + (size_t)(a.seq0 + blockIdx.z) * a.pt_stride;
   const int G = a.H / a.Hkv, RG = R * G;
 #ifdef SD_KTIME
   const int kt_base = (a.cross ? 8 : 0) + (R > 1 ? 16 : 0) + (a.Hkv > 8 ? 32 : 0);
@@ -100,7 +105,7 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
 #endif
 
   if (tid < MAX_ROWS) s_pos[tid] = (tid < R) ? (a.cross ? 0 : a.row_pos[r0 + tid]) : -1;
-  if (!a.cross) for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += ATTN_THREADS) s_pt[i] = a.page_table[i];
+  if (!a.cross) for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += ATTN_THREADS) s_pt[i] = page_table[i];
   // relative-position bias: table rows and distance -> bucket map into LDS, so
   // the score loop has no global loads
   const bool use_bias = !a.cross && a.rel_bias != nullptr;

@@ -67,6 +67,10 @@ struct GemmArgs {
   const int* page_table;
   int page_size, n_kv_heads, d_head;
   const int* row_pos;     // [R] position of each row; < 0: row is padding
+  // several sequences in one launch (all optional)
+  const int* row_seq;     // EPI_QKV: [R] sequence of each row; its page table starts at page_table + seq * pt_stride
+  int pt_stride;
+  const int* out_row;     // EPI_LOGITS: [R] row of `out` each input row goes to, < 0: dropped
   const float* rope;      // [max_len][d_head/2][2] (cos, sin) or nullptr
 };
 
@@ -243,7 +247,8 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   if (EPI == EPI_QKV && epi_thread) {
     e_pos = (e_row < a.R) ? a.row_pos[e_rowc] : -1;
     const int pc = max(e_pos, 0);
-    const int page = a.page_table[pc / a.page_size], slot = pc % a.page_size;
+    const int pt0 = (a.row_seq != nullptr) ? a.row_seq[e_rowc] * a.pt_stride : 0;
+    const int page = a.page_table[pt0 + pc / a.page_size], slot = pc % a.page_size;
     e_kvbase = (size_t)page * 2 * a.n_kv_heads * a.page_size * a.d_head + (size_t)slot * a.d_head;
   }
 
@@ -329,7 +334,8 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
           const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
           Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[ND - 1]);
         } else if (EPI == EPI_LOGITS) {
-          static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = a.scale * y[0];
+          const int orow = (a.out_row != nullptr) ? a.out_row[row] : row;
+          if (orow >= 0) static_cast<float*>(a.out)[(size_t)orow * a.ldo + n] = a.scale * y[0];
         }
       }
     }

@@ -19,22 +19,31 @@ enum {
 // a one-token sequence): it is embedded as token 0 at position 0 and ignored.
 // For RMSNorm models the kernel also writes xg = x * gain of the first norm in
 // the storage type and the row's sum of squares (one partial: ss[0][r]).
+// Several sequences: the launch covers sequences seq0, seq0+1, ... with rps rows
+// each (row r belongs to sequence seq0 + r / rps); `st` is the array of sequence
+// states.  row_seq[r] (when given) receives the row's sequence, logit_row[r] the
+// row of the logits buffer its LM-head output belongs in (< 0: not needed):
+// p rows [seq][gamma+1], q rows [seq][gamma], one row per sequence for plain decoding.
 template <typename T>
 static __global__ __launch_bounds__(256) void embed_kernel(
     int mode, int step, const SeqState* __restrict__ st, const int* __restrict__ prompt, int start,
     const T* __restrict__ tok_emb, const T* __restrict__ pos_emb, int d, int vocab,
     float* __restrict__ x, int* __restrict__ row_pos, const T* __restrict__ gain_next,
-    T* __restrict__ xg, float* __restrict__ ss) {
+    T* __restrict__ xg, float* __restrict__ ss,
+    int rps, int seq0, int gamma, int* __restrict__ row_seq, int* __restrict__ logit_row) {
   __shared__ float red[16];
   const int r = blockIdx.x;
-  int tok, pos;
+  const int j = r % rps, seq = seq0 + r / rps;
+  st += seq;
+  int tok, pos, lrow = -1;
   switch (mode) {
-    case ROWS_VERIFY:      tok = (r == 0) ? st->last_tok : st->x[r - 1]; pos = st->len - 1 + r; break;
-    case ROWS_DRAFT_FIRST: tok = (r == 0) ? st->prev_tok : st->last_tok; pos = st->len - 2 + r; break;
-    case ROWS_DRAFT_NEXT:  tok = st->x[step - 1]; pos = st->len - 1 + step; break;
-    case ROWS_BASELINE:    tok = st->last_tok; pos = st->len - 1; break;
+    case ROWS_VERIFY:      tok = (j == 0) ? st->last_tok : st->x[j - 1]; pos = st->len - 1 + j; lrow = seq * (gamma + 1) + j; break;
+    case ROWS_DRAFT_FIRST: tok = (j == 0) ? st->prev_tok : st->last_tok; pos = st->len - 2 + j; lrow = (j == 1) ? seq * gamma : -1; break;
+    case ROWS_DRAFT_NEXT:  tok = st->x[step - 1]; pos = st->len - 1 + step; lrow = seq * gamma + step; break;
+    case ROWS_BASELINE:    tok = st->last_tok; pos = st->len - 1; lrow = seq; break;
     default:               tok = prompt[start + r]; pos = start + r; break;
   }
+  if (threadIdx.x == 0 && row_seq) { row_seq[r] = seq; logit_row[r] = lrow; }
   if (threadIdx.x == 0) row_pos[r] = pos;
   if (pos < 0) { tok = 0; pos = 0; }
   tok = min(max(tok, 0), vocab - 1);

@@ -406,10 +406,15 @@ __device__ __forceinline__ int icdf_regs(const float4 (&vp)[SAMPLE_REG_F4], cons
 //   mode 0: store the token as guess number `slot` (st->x[slot])
 //   mode 1: commit it (standard decoding): len += 1
 // ---------------------------------------------------------------------------
+// Several sequences: grid = sequences; sequence b reads the row at logits + b * seq_stride
+// (floats) and uses prm[b], st[b].
 static __global__ __launch_bounds__(SAMPLE_THREADS) void sample_row_kernel(
     const float* __restrict__ logits, int V, const StepParams* __restrict__ prm, int uniform_idx,
-    SeqState* __restrict__ st, int mode, int slot) {
+    SeqState* __restrict__ st, int mode, int slot, size_t seq_stride) {
   __shared__ SampleSmem sm;
+  logits += (size_t)blockIdx.x * seq_stride;
+  prm += blockIdx.x;
+  st += blockIdx.x;
   const float T = prm->temperature;
   const bool greedy = (T == 0.0f);
   const float invT = greedy ? 1.0f : 1.0f / T;
@@ -468,6 +473,8 @@ static __global__ __launch_bounds__(SAMPLE_THREADS) void spec_verify_kernel(
   __shared__ RowStat srow[2 * 15 + 1];
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int nrows = 2 * gamma + 1;
+  if (prm) prm += b;                     // in-model use: per-sequence parameters and state
+  if (st) st += b;
   const float T = prm ? prm->temperature : temperature;
   const bool greedy = (T == 0.0f);
   const float invT = greedy ? 1.0f : 1.0f / T;

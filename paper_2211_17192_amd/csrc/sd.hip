@@ -56,7 +56,10 @@ struct Model {
   int* bucket_lut = nullptr;
   float* rope = nullptr;
   std::vector<LayerW> L;
-  int* page_table = nullptr;
+  int batch = 1;               // sequences; each owns n_pages pages of every layer's pool
+  int rows_cap = MAX_ROWS;     // activation rows: one group of MAX_ROWS rows per sequence at most
+  int* page_table = nullptr;   // [batch][n_pages]
+  int *row_seq = nullptr, *logit_row = nullptr;   // [rows_cap], written by the embedding kernel
   float* x = nullptr;
   void* xg = nullptr;          // x * gain of the next RMSNorm, storage type
   float* ss = nullptr;         // [d_model/16][16] partial sums of x^2
@@ -90,8 +93,10 @@ bool cfg_ok(const sd_model_cfg& c, std::string& why) {
 }
 
 // Lays a model out in the arena (or sizes it).
-void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size) {
+void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size, int batch) {
   m.cfg = c;
+  m.batch = batch;
+  m.rows_cap = MAX_ROWS * batch;
   m.esz = (c.dtype == SD_BF16) ? 2 : 4;
   const size_t e = m.esz, d = c.d_model, ff = c.d_ff, V = c.vocab;
   m.nq = c.n_heads * c.d_head;
@@ -129,16 +134,19 @@ void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size) {
       l.cross_k = A.take((size_t)c.enc_len * m.nq * e);
       l.cross_v = A.take((size_t)c.enc_len * m.nq * e);
     }
-    l.kv = A.take((size_t)m.n_pages * 2 * c.n_kv_heads * page_size * c.d_head * e);
+    l.kv = A.take((size_t)batch * m.n_pages * 2 * c.n_kv_heads * page_size * c.d_head * e);
   }
-  m.page_table = static_cast<int*>(A.take((size_t)m.n_pages * sizeof(int)));
-  m.x = static_cast<float*>(A.take((size_t)MAX_ROWS * d * sizeof(float)));
-  m.xg = A.take((size_t)MAX_ROWS * d * e);
-  m.ss = static_cast<float*>(A.take((size_t)(d / 16) * 16 * sizeof(float)));
-  m.qbuf = A.take((size_t)MAX_ROWS * m.nq * e);
-  m.attn = A.take((size_t)MAX_ROWS * m.nq * e);
-  m.ffn = A.take((size_t)MAX_ROWS * ff * e);
-  m.row_pos = static_cast<int*>(A.take(MAX_ROWS * sizeof(int)));
+  const size_t rows = (size_t)m.rows_cap;
+  m.page_table = static_cast<int*>(A.take((size_t)batch * m.n_pages * sizeof(int)));
+  m.x = static_cast<float*>(A.take(rows * d * sizeof(float)));
+  m.xg = A.take(rows * d * e);
+  m.ss = static_cast<float*>(A.take((size_t)batch * (d / 16) * 16 * sizeof(float)));   // [group][d/16][16]
+  m.qbuf = A.take(rows * m.nq * e);
+  m.attn = A.take(rows * m.nq * e);
+  m.ffn = A.take(rows * ff * e);
+  m.row_pos = static_cast<int*>(A.take(rows * sizeof(int)));
+  m.row_seq = static_cast<int*>(A.take(rows * sizeof(int)));
+  m.logit_row = static_cast<int*>(A.take(rows * sizeof(int)));
   m.prompt = static_cast<int*>(A.take((size_t)c.max_len * sizeof(int)));
 }
 
@@ -156,9 +164,10 @@ struct sd_ctx {
   unsigned int* d_counter = nullptr;
   SeqState* h_state = nullptr;       // pinned
   StepParams* h_params = nullptr;    // pinned
-  // host mirror of the sequence
-  int state = 0;                     // 0 EMPTY, 1 READY, 2 Mq cache stale (after baseline steps)
-  int len = 0, last_tok = -1;
+  int batch = 1;
+  // host mirror of the sequences
+  int state = 0;                     // 0 not all rows prefilled, 1 READY, 2 Mq cache stale (after baseline steps)
+  std::vector<int> len, last_tok, ready;
   int last_gamma = 0, last_kind = -1;   // for sd_debug_logits
   hipGraphExec_t graphs[SD_MAX_GAMMA + 1] = {};
   hipGraphExec_t graph_baseline = nullptr;
@@ -177,18 +186,20 @@ struct sd_ctx {
 namespace {
 
 void plan_ctx(Arena& A, sd_ctx& c, const sd_model_cfg& pc, const sd_model_cfg& qc, const sd_runtime_cfg& rt) {
-  plan_model(A, c.p, pc, rt.page_size);
-  plan_model(A, c.q, qc, rt.page_size);
-  c.d_state = static_cast<SeqState*>(A.take(sizeof(SeqState)));
-  c.d_params = static_cast<StepParams*>(A.take(sizeof(StepParams)));
-  c.p_logits = static_cast<float*>(A.take((size_t)MAX_ROWS * pc.vocab * sizeof(float)));
-  c.q_logits = static_cast<float*>(A.take((size_t)SD_MAX_GAMMA * pc.vocab * sizeof(float)));
-  c.d_stats = static_cast<RowStat*>(A.take((2 * SD_MAX_GAMMA + 1) * sizeof(RowStat)));
-  c.d_counter = static_cast<unsigned int*>(A.take(256));
+  const size_t B = (size_t)rt.batch;
+  c.batch = rt.batch;
+  plan_model(A, c.p, pc, rt.page_size, rt.batch);
+  plan_model(A, c.q, qc, rt.page_size, rt.batch);
+  c.d_state = static_cast<SeqState*>(A.take(B * sizeof(SeqState)));
+  c.d_params = static_cast<StepParams*>(A.take(B * sizeof(StepParams)));
+  c.p_logits = static_cast<float*>(A.take(B * (rt.max_gamma + 1) * pc.vocab * sizeof(float)));   // [seq][gamma+1][V]
+  c.q_logits = static_cast<float*>(A.take(B * rt.max_gamma * pc.vocab * sizeof(float)));         // [seq][gamma][V]
+  c.d_stats = static_cast<RowStat*>(A.take(B * (2 * SD_MAX_GAMMA + 1) * sizeof(RowStat)));
+  c.d_counter = static_cast<unsigned int*>(A.take(B * SAMPLE_COUNTER_STRIDE * sizeof(unsigned int)));
 }
 
 bool rt_ok(const sd_runtime_cfg& rt, std::string& why) {
-  if (rt.batch != 1) { why = "only batch 1 is supported"; return false; }
+  if (rt.batch < 1 || rt.batch > SD_MAX_BATCH) { why = "batch out of range"; return false; }
   if (rt.max_gamma < 1 || rt.max_gamma > SD_MAX_GAMMA) { why = "max_gamma out of range"; return false; }
   if (rt.page_size < 16 || (rt.page_size & (rt.page_size - 1))) { why = "page_size must be a power of two >= 16"; return false; }
   return true;
@@ -242,12 +253,12 @@ size_t attn_lds_bytes(int RG, int DH) {
 }
 
 template <typename T>
-void launch_attn(hipStream_t s, const Model& m, AttnArgs a) {
+void launch_attn(hipStream_t s, const Model& m, AttnArgs a, int nseq) {
   const int G = a.H / a.Hkv, DH = m.cfg.d_head;
   // few kv heads leave most CUs idle: split the (independent) rows over more workgroups
-  a.rows_per_wg = (a.Hkv * ((a.R + 1) / 2) <= g_num_cus) ? std::min(2, a.R) : a.R;
+  a.rows_per_wg = (nseq * a.Hkv * ((a.R + 1) / 2) <= g_num_cus) ? std::min(2, a.R) : a.R;
   const size_t lds = attn_lds_bytes(a.rows_per_wg * G, DH);
-  const dim3 grid(a.Hkv, (a.R + a.rows_per_wg - 1) / a.rows_per_wg), block(ATTN_THREADS);
+  const dim3 grid(a.Hkv, (a.R + a.rows_per_wg - 1) / a.rows_per_wg, nseq), block(ATTN_THREADS);
   if (DH == 32) hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, lds, s, a);
   else if (DH == 64) hipLaunchKernelGGL((attn_kernel<T, 64>), grid, block, lds, s, a);
   else hipLaunchKernelGGL((attn_kernel<T, 128>), grid, block, lds, s, a);
@@ -266,95 +277,144 @@ hipError_t allow_big_lds() {
 // Rows one prefill pass may carry so that rows x (query heads per kv head) fits the attention kernel.
 int prefill_rows(const sd_model_cfg& c) { return std::min(MAX_ROWS, ATTN_MAX_RG / (c.n_heads / c.n_kv_heads)); }
 
-// One forward of model m over R rows chosen by (mode, step); optionally the
-// LM head on rows [row0, row0+nrows) into `logits` (fp32 [nrows][vocab]).
+// Which rows a forward processes: sequences seq0 .. seq0+nseq-1 with rps rows each, chosen
+// by (mode, step) from the device-resident sequence states (ROWS_PREFILL: rps prompt tokens
+// of sequence seq0 from position start).  gamma fixes where the LM-head rows land in the
+// logits buffers ([seq][gamma+1][V] for Mp, [seq][gamma][V] for Mq).
+struct Rows { int mode, step, rps, start, seq0, nseq, gamma; };
+
+// One forward of model m; with `logits` the LM head runs on every row and each row's
+// output goes where the embedding kernel's row map says (or nowhere).
+// The kernels take at most MAX_ROWS rows, so the sequences are cut into groups of
+// MAX_ROWS / rps whole sequences; every operation is launched once per group (each launch
+// streams the operation's weights again: more than one group costs bandwidth, not correctness).
 template <typename T>
-void forward(sd_ctx* c, Model& m, int mode, int step, int R, int start, int row0, int nrows, float* logits) {
+void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
   hipStream_t s = c->stream;
   const sd_model_cfg& f = m.cfg;
   const int d = f.d_model;
+  const size_t e = m.esz;
   const bool rms = (f.arch != SD_ARCH_GPT);
   const int pro = rms ? PRO_POST : PRO_LN;
   const int n_layers = (int)m.L.size();
-  hipLaunchKernelGGL((embed_kernel<T>), dim3(R), dim3(256), 0, s, mode, step, c->d_state, m.prompt, start,
-                     static_cast<const T*>(m.tok_emb), static_cast<const T*>(m.pos_emb), d, f.vocab, m.x,
-                     m.row_pos, static_cast<const T*>(rms ? m.L[0].ln1g : nullptr),
-                     static_cast<T*>(rms ? m.xg : nullptr), rms ? m.ss : nullptr);
+  const int spg = std::max(1, MAX_ROWS / rw.rps);                  // sequences per group
+  const int n_groups = (rw.nseq + spg - 1) / spg;
+  struct Grp { int seq0, ns, R; float* x; char* xg; float* ss; char *qbuf, *attn, *ffn; int *row_pos, *row_seq, *logit_row; };
+  auto group = [&](int g) {
+    Grp q;
+    q.seq0 = rw.seq0 + g * spg;
+    q.ns = std::min(spg, rw.seq0 + rw.nseq - q.seq0);
+    q.R = q.ns * rw.rps;
+    const size_t off = (size_t)g * MAX_ROWS;
+    q.x = m.x + off * d;
+    q.xg = static_cast<char*>(m.xg) + off * d * e;
+    q.ss = m.ss + (size_t)g * (d / 16) * 16;
+    q.qbuf = static_cast<char*>(m.qbuf) + off * m.nq * e;
+    q.attn = static_cast<char*>(m.attn) + off * m.nq * e;
+    q.ffn = static_cast<char*>(m.ffn) + off * f.d_ff * e;
+    q.row_pos = m.row_pos + off; q.row_seq = m.row_seq + off; q.logit_row = m.logit_row + off;
+    return q;
+  };
+  for (int g = 0; g < n_groups; ++g) {
+    const Grp q = group(g);
+    hipLaunchKernelGGL((embed_kernel<T>), dim3(q.R), dim3(256), 0, s, rw.mode, rw.step, c->d_state, m.prompt, rw.start,
+                       static_cast<const T*>(m.tok_emb), static_cast<const T*>(m.pos_emb), d, f.vocab, q.x,
+                       q.row_pos, static_cast<const T*>(rms ? m.L[0].ln1g : nullptr),
+                       reinterpret_cast<T*>(rms ? q.xg : nullptr), rms ? q.ss : nullptr,
+                       rw.rps, q.seq0, rw.gamma, q.row_seq, q.logit_row);
+  }
   int n_part = 1;                                   // partial sums of x^2 the next norm has to add
   // input of a normed GEMM: LayerNorm reads the fp32 rows, RMSNorm the pre-scaled rows + partials
-  auto normed = [&](GemmArgs& g, const void* gain, const void* beta) {
-    g.eps = f.norm_eps;
-    if (rms) { g.X = m.xg; g.ss_in = m.ss; g.n_part = n_part; }
-    else { g.X = m.x; g.gain = gain; g.beta = beta; }
+  auto normed = [&](GemmArgs& a, const Grp& q, const void* gain, const void* beta) {
+    a.R = q.R;
+    a.eps = f.norm_eps;
+    if (rms) { a.X = q.xg; a.ss_in = q.ss; a.n_part = n_part; }
+    else { a.X = q.x; a.gain = gain; a.beta = beta; }
   };
   // residual add that also prepares the input of the next norm
-  auto resid = [&](const void* W, const void* X, const void* bias, int K, const void* gain_next) {
-    GemmArgs o{};
-    o.R = R; o.W = W; o.X = X; o.bias = bias; o.K = K; o.N = d; o.out = m.x; o.ldo = d;
-    if (rms) { o.xg_out = m.xg; o.gain_next = gain_next; o.ss_out = m.ss; }
-    launch_gemm<T>(s, PRO_NONE, EPI_RESID, o);
+  auto resid = [&](const void* W, bool from_ffn, const void* bias, int K, const void* gain_next) {
+    for (int g = 0; g < n_groups; ++g) {
+      const Grp q = group(g);
+      GemmArgs o{};
+      o.R = q.R; o.W = W; o.X = from_ffn ? q.ffn : q.attn; o.bias = bias; o.K = K; o.N = d; o.out = q.x; o.ldo = d;
+      if (rms) { o.xg_out = q.xg; o.gain_next = gain_next; o.ss_out = q.ss; }
+      launch_gemm<T>(s, PRO_NONE, EPI_RESID, o);
+    }
     n_part = d / 16;
   };
   for (int li = 0; li < n_layers; ++li) {
     const LayerW& l = m.L[li];
-    GemmArgs g{};
-    g.R = R;
-    normed(g, l.ln1g, l.ln1b);
     // q, k, v projections (+ rotary) with k, v appended to the cache
-    g.W = l.wqkv; g.bias = l.bqkv; g.K = d; g.N = m.nq + 2 * m.nkv;
-    g.q_out = m.qbuf; g.nq = m.nq; g.nkv = m.nkv; g.kv_pool = l.kv; g.page_table = m.page_table;
-    g.page_size = m.page_size; g.n_kv_heads = f.n_kv_heads; g.d_head = f.d_head; g.row_pos = m.row_pos;
-    g.rope = m.rope;
-    launch_gemm<T>(s, pro, EPI_QKV, g);
-    AttnArgs a{};
-    a.q = m.qbuf; a.out = m.attn; a.kv_pool = l.kv; a.page_table = m.page_table; a.page_size = m.page_size; a.n_pages = m.n_pages;
-    a.row_pos = m.row_pos; a.R = R; a.H = f.n_heads; a.Hkv = f.n_kv_heads; a.cross = 0; a.kv_len = 0;
-    a.scale = (f.arch == SD_ARCH_T5DEC) ? 1.0f : 1.0f / sqrtf((float)f.d_head);
-    a.rel_bias = m.rel_bias; a.bucket_lut = m.bucket_lut; a.rel_buckets = f.rel_buckets;
-    launch_attn<T>(s, m, a);
-    resid(l.wo, m.attn, l.bo, m.nq, (f.arch == SD_ARCH_T5DEC) ? l.lncg : l.ln2g);
+    for (int g = 0; g < n_groups; ++g) {
+      const Grp q = group(g);
+      GemmArgs a{};
+      normed(a, q, l.ln1g, l.ln1b);
+      a.W = l.wqkv; a.bias = l.bqkv; a.K = d; a.N = m.nq + 2 * m.nkv;
+      a.q_out = q.qbuf; a.nq = m.nq; a.nkv = m.nkv; a.kv_pool = l.kv; a.page_table = m.page_table;
+      a.page_size = m.page_size; a.n_kv_heads = f.n_kv_heads; a.d_head = f.d_head; a.row_pos = q.row_pos;
+      a.rope = m.rope;
+      if (m.batch > 1) { a.row_seq = q.row_seq; a.pt_stride = m.n_pages; }
+      launch_gemm<T>(s, pro, EPI_QKV, a);
+    }
+    auto attention = [&](bool cross) {
+      for (int g = 0; g < n_groups; ++g) {
+        const Grp q = group(g);
+        AttnArgs a{};
+        a.q = q.qbuf; a.out = q.attn; a.kv_pool = l.kv; a.page_table = m.page_table; a.page_size = m.page_size; a.n_pages = m.n_pages;
+        a.row_pos = q.row_pos; a.R = rw.rps; a.H = f.n_heads; a.Hkv = f.n_kv_heads; a.cross = 0; a.kv_len = 0;
+        a.scale = (f.arch == SD_ARCH_T5DEC) ? 1.0f : 1.0f / sqrtf((float)f.d_head);
+        a.rel_bias = m.rel_bias; a.bucket_lut = m.bucket_lut; a.rel_buckets = f.rel_buckets;
+        a.seq0 = q.seq0; a.pt_stride = m.n_pages;
+        if (cross) { a.cross = 1; a.ck = l.cross_k; a.cv = l.cross_v; a.kv_len = f.enc_len; a.scale = 1.0f; a.rel_bias = nullptr; }
+        launch_attn<T>(s, m, a, q.ns);
+      }
+    };
+    attention(false);
+    resid(l.wo, false, l.bo, m.nq, (f.arch == SD_ARCH_T5DEC) ? l.lncg : l.ln2g);
     if (f.arch == SD_ARCH_T5DEC) {
-      GemmArgs cq{};
-      cq.R = R;
-      normed(cq, l.lncg, nullptr);
-      cq.W = l.cq; cq.K = d; cq.N = m.nq; cq.out = m.qbuf; cq.ldo = m.nq;
-      launch_gemm<T>(s, PRO_POST, EPI_STORE, cq);
-      AttnArgs ca = a;
-      ca.cross = 1; ca.ck = l.cross_k; ca.cv = l.cross_v; ca.kv_len = f.enc_len; ca.scale = 1.0f;
-      ca.rel_bias = nullptr;
-      launch_attn<T>(s, m, ca);
-      resid(l.co, m.attn, nullptr, m.nq, l.ln2g);
+      for (int g = 0; g < n_groups; ++g) {
+        const Grp q = group(g);
+        GemmArgs cq{};
+        normed(cq, q, l.lncg, nullptr);
+        cq.W = l.cq; cq.K = d; cq.N = m.nq; cq.out = q.qbuf; cq.ldo = m.nq;
+        launch_gemm<T>(s, PRO_POST, EPI_STORE, cq);
+      }
+      attention(true);
+      resid(l.co, false, nullptr, m.nq, l.ln2g);
     }
-    GemmArgs h{};
-    h.R = R;
-    normed(h, l.ln2g, l.ln2b);
-    h.K = d; h.N = f.d_ff; h.out = m.ffn; h.ldo = f.d_ff; h.W = l.w1;
-    if (f.arch == SD_ARCH_GPT) {
-      h.bias = l.b1;
-      launch_gemm<T>(s, PRO_LN, EPI_ACT, h);
-    } else {
-      h.W2 = l.wu; h.act = (f.arch == SD_ARCH_T5DEC) ? ACT_GELU : ACT_SILU;
-      const bool timed = c->time_ffn && &m == &c->p && 2 * li + 1 < (int)c->kev.size();
-      if (timed) hipEventRecord(c->kev[2 * li], s);
-      launch_gemm<T>(s, PRO_POST, EPI_GATED, h);
-      if (timed) hipEventRecord(c->kev[2 * li + 1], s);
+    for (int g = 0; g < n_groups; ++g) {
+      const Grp q = group(g);
+      GemmArgs h{};
+      normed(h, q, l.ln2g, l.ln2b);
+      h.K = d; h.N = f.d_ff; h.out = q.ffn; h.ldo = f.d_ff; h.W = l.w1;
+      if (f.arch == SD_ARCH_GPT) {
+        h.bias = l.b1;
+        launch_gemm<T>(s, PRO_LN, EPI_ACT, h);
+      } else {
+        h.W2 = l.wu; h.act = (f.arch == SD_ARCH_T5DEC) ? ACT_GELU : ACT_SILU;
+        const bool timed = c->time_ffn && &m == &c->p && g == 0 && 2 * li + 1 < (int)c->kev.size();
+        if (timed) hipEventRecord(c->kev[2 * li], s);
+        launch_gemm<T>(s, PRO_POST, EPI_GATED, h);
+        if (timed) hipEventRecord(c->kev[2 * li + 1], s);
+      }
     }
-    resid(l.w2, m.ffn, l.b2, f.d_ff, (li + 1 < n_layers) ? m.L[li + 1].ln1g : m.lnfg);
+    resid(l.w2, true, l.b2, f.d_ff, (li + 1 < n_layers) ? m.L[li + 1].ln1g : m.lnfg);
   }
   if (logits != nullptr) {
-    GemmArgs g{};
-    g.R = nrows;
-    normed(g, m.lnfg, m.lnfb);
-    g.X = static_cast<const char*>(g.X) + (size_t)row0 * d * (rms ? m.esz : sizeof(float));
-    if (rms) g.ss_in = m.ss + row0;
-    g.W = m.head; g.K = d; g.N = f.vocab; g.out = logits; g.ldo = f.vocab; g.scale = f.logit_scale;
-    launch_gemm<T>(s, pro, EPI_LOGITS, g);
+    for (int g = 0; g < n_groups; ++g) {
+      const Grp q = group(g);
+      GemmArgs a{};
+      normed(a, q, m.lnfg, m.lnfb);
+      a.W = m.head; a.K = d; a.N = f.vocab; a.out = logits; a.ldo = f.vocab; a.scale = f.logit_scale;
+      a.out_row = q.logit_row;
+      launch_gemm<T>(s, pro, EPI_LOGITS, a);
+    }
   }
 }
 
-void forward_any(sd_ctx* c, Model& m, int mode, int step, int R, int start, int row0, int nrows, float* logits) {
-  if (m.cfg.dtype == SD_BF16) forward<bf16>(c, m, mode, step, R, start, row0, nrows, logits);
-  else forward<float>(c, m, mode, step, R, start, row0, nrows, logits);
+void forward_any(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
+  if (m.cfg.dtype == SD_BF16) forward<bf16>(c, m, rw, logits);
+  else forward<float>(c, m, rw, logits);
 }
 
 // Cross-attention keys / values of every layer from the encoder output.
@@ -375,42 +435,45 @@ void cross_kv(sd_ctx* c, Model& m, const void* enc) {
       }
 }
 
-// The launch sequence of one run of Algorithm 1 (everything between the
-// upload of the step parameters and the download of the state).
+// The launch sequence of one run of Algorithm 1 for every sequence (everything between the
+// upload of the step parameters and the download of the states).
 void enqueue_step(sd_ctx* c, int gamma, bool profile) {
   hipStream_t s = c->stream;
-  const int V = c->p.cfg.vocab;
+  const int V = c->p.cfg.vocab, B = c->batch;
   if (profile) hipEventRecord(c->ev[0], s);
   for (int i = 0; i < gamma; ++i) {              // q_i <- Mq(prefix + x_<i), x_i ~ q_i
-    float* qrow = c->q_logits + (size_t)i * V;
-    if (i == 0) forward_any(c, c->q, ROWS_DRAFT_FIRST, 0, 2, 0, 1, 1, qrow);
-    else forward_any(c, c->q, ROWS_DRAFT_NEXT, i, 1, 0, 0, 1, qrow);
-    hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, s, qrow, V, c->d_params, i,
-                       c->d_state, 0, i);
+    if (i == 0) forward_any(c, c->q, Rows{ROWS_DRAFT_FIRST, 0, 2, 0, 0, B, gamma}, c->q_logits);
+    else forward_any(c, c->q, Rows{ROWS_DRAFT_NEXT, i, 1, 0, 0, B, gamma}, c->q_logits);
+    hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, s, c->q_logits + (size_t)i * V, V,
+                       c->d_params, i, c->d_state, 0, i, (size_t)gamma * V);
   }
   if (profile) hipEventRecord(c->ev[1], s);
   // p_1..p_{gamma+1} in one forward
   c->time_ffn = profile;
-  forward_any(c, c->p, ROWS_VERIFY, 0, gamma + 1, 0, 0, gamma + 1, c->p_logits);
+  forward_any(c, c->p, Rows{ROWS_VERIFY, 0, gamma + 1, 0, 0, B, gamma}, c->p_logits);
   c->time_ffn = false;
   if (profile) hipEventRecord(c->ev[2], s);
-  hipLaunchKernelGGL(spec_verify_kernel<0>, dim3(2 * gamma + 1, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
-                     c->q_logits, (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V,
-                     0.0f, 1.0f, 0.0, 0, 0.0f, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr,
-                     (float*)nullptr, c->d_state);
-  if (c->rt.flags & SD_FLAG_BETA)               // side output: beta_i of every guess, into the state
-    hipLaunchKernelGGL(spec_verify_kernel<3>, dim3(gamma, 1), dim3(SAMPLE_THREADS), 0, s, c->p_logits,
-                       c->q_logits, (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V,
-                       0.0f, 1.0f, 0.0, 0, 0.0f, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr,
-                       (float*)nullptr, c->d_state);
+#define SD_VERIFY(MODE, GRID)                                                                                        \
+  hipLaunchKernelGGL(spec_verify_kernel<MODE>, GRID, dim3(SAMPLE_THREADS), 0, s, c->p_logits, c->q_logits,             \
+                     (const int*)nullptr, (const float*)nullptr, (const float*)nullptr, gamma, V, 0.0f, 1.0f, 0.0, 0,  \
+                     0.0f, c->d_params, c->d_stats, c->d_counter, (int*)nullptr, (int*)nullptr, (float*)nullptr,       \
+                     c->d_state)
+  if (B * (2 * gamma + 1) <= 64) {              // few tickets: one launch
+    SD_VERIFY(0, dim3(2 * gamma + 1, B));
+  } else {                                       // many sequences: statistics, then one tail workgroup each
+    SD_VERIFY(1, dim3(2 * gamma + 1, B));
+    SD_VERIFY(2, dim3(1, B));
+  }
+  if (c->rt.flags & SD_FLAG_BETA) SD_VERIFY(3, dim3(gamma, B));   // side output: beta_i of every guess, into the states
+#undef SD_VERIFY
   if (profile) hipEventRecord(c->ev[3], s);
 }
 
 void enqueue_baseline(sd_ctx* c) {
-  const int V = c->p.cfg.vocab;
-  forward_any(c, c->p, ROWS_BASELINE, 0, 1, 0, 0, 1, c->p_logits);
-  hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
-                     c->d_params, 0, c->d_state, 1, 0);
+  const int V = c->p.cfg.vocab, B = c->batch;
+  forward_any(c, c->p, Rows{ROWS_BASELINE, 0, 1, 0, 0, B, 0}, c->p_logits);
+  hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
+                     c->d_params, 0, c->d_state, 1, 0, (size_t)V);
 }
 
 // ------------------------------------------------------------------ loading
@@ -488,8 +551,8 @@ sd_status load_model(hipStream_t s, Model& m, const sd_tensor* w, int n, std::st
   }
 #undef PUT
   // host-built tables
-  std::vector<int> pt(m.n_pages);
-  for (int i = 0; i < m.n_pages; ++i) pt[i] = i;
+  std::vector<int> pt((size_t)m.batch * m.n_pages);         // sequence b owns pages b * n_pages .. of every pool
+  for (size_t i = 0; i < pt.size(); ++i) pt[i] = (int)i;
   if (hipMemcpy(m.page_table, pt.data(), pt.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess) { err = "page table upload"; return SD_EHIP; }
   if (f.arch == SD_ARCH_T5DEC) {
     // causal distance -> bucket: one distance per bucket in the first half,
@@ -521,7 +584,7 @@ sd_status load_model(hipStream_t s, Model& m, const sd_tensor* w, int n, std::st
 }
 
 sd_status sync_state_to_host(sd_ctx* c) {
-  HIP_TRY(c, hipMemcpyAsync(c->h_state, c->d_state, sizeof(SeqState), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->h_state, c->d_state, (size_t)c->batch * sizeof(SeqState), hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   return SD_OK;
 }
@@ -550,6 +613,8 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
   if (!cfg_ok(*q_cfg, why)) return fail(nullptr, SD_EINVAL, "Mq config: " + why);
   if (!rt_ok(*rt, why)) return fail(nullptr, SD_EINVAL, "runtime config: " + why);
   if (p_cfg->vocab != q_cfg->vocab) return fail(nullptr, SD_EINVAL, "Mp and Mq must share the vocabulary");
+  if (rt->batch > 1 && (p_cfg->arch == SD_ARCH_T5DEC || q_cfg->arch == SD_ARCH_T5DEC))
+    return fail(nullptr, SD_EINVAL, "T5DEC models take one sequence (one encoder output per context)");
   if ((rt->max_gamma + 1) * (p_cfg->n_heads / p_cfg->n_kv_heads) > ATTN_MAX_RG ||
       2 * (q_cfg->n_heads / q_cfg->n_kv_heads) > ATTN_MAX_RG)
     return fail(nullptr, SD_EINVAL, "(max_gamma+1) x (query heads per kv head) exceeds the attention kernel's limit");
@@ -569,9 +634,13 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
     if (hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking) != hipSuccess) return bail(SD_EHIP, "stream creation failed");
     c->own_stream = true;
   }
-  if (hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(SeqState), hipHostMallocDefault) != hipSuccess ||
-      hipHostMalloc(reinterpret_cast<void**>(&c->h_params), sizeof(StepParams), hipHostMallocDefault) != hipSuccess)
+  const size_t B = (size_t)rt->batch;
+  c->len.assign(B, 0); c->last_tok.assign(B, -1); c->ready.assign(B, 0);
+  if (hipHostMalloc(reinterpret_cast<void**>(&c->h_state), B * sizeof(SeqState), hipHostMallocDefault) != hipSuccess ||
+      hipHostMalloc(reinterpret_cast<void**>(&c->h_params), B * sizeof(StepParams), hipHostMallocDefault) != hipSuccess)
     return bail(SD_EHIP, "pinned allocation failed");
+  std::memset(c->h_state, 0, B * sizeof(SeqState));
+  std::memset(c->h_params, 0, B * sizeof(StepParams));
   for (auto& e : c->ev) if (hipEventCreate(&e) != hipSuccess) return bail(SD_EHIP, "event creation failed");
   if (p_cfg->arch != SD_ARCH_GPT) {
     c->kev.assign(2 * (size_t)p_cfg->n_layers, nullptr);
@@ -591,7 +660,10 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
   st = (q_cfg->dtype == SD_BF16) ? load_model<bf16>(c->stream, c->q, q_w, n_q, err)
                                  : load_model<float>(c->stream, c->q, q_w, n_q, err);
   if (st != SD_OK) return bail(st, "Mq: " + err);
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, c->d_counter, 0u, (size_t)64);
+  {
+    const size_t n = B * SAMPLE_COUNTER_STRIDE;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->d_counter, 0u, n);
+  }
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e == hipSuccess) e = hipGetLastError();
   if (e != hipSuccess) return bail(SD_EHIP, std::string("load: ") + hipGetErrorString(e));
@@ -616,23 +688,25 @@ extern "C" const char* sd_last_error(const sd_ctx* c) { return c ? c->err.c_str(
 
 extern "C" sd_status sd_reset(sd_ctx* c, int32_t row) {
   if (!c) return SD_EINVAL;
-  if (row != 0 && row != -1) return fail(c, SD_EINVAL, "row must be 0 or -1");
-  c->state = 0; c->len = 0; c->last_tok = -1;
-  c->stats = sd_stats{};
+  if (row < -1 || row >= c->batch) return fail(c, SD_EINVAL, "row must be -1 or a sequence index");
+  for (int b = 0; b < c->batch; ++b)
+    if (row == -1 || row == b) { c->ready[b] = 0; c->len[b] = 0; c->last_tok[b] = -1; }
+  c->state = 0;
+  if (row == -1) c->stats = sd_stats{};
   return SD_OK;
 }
 
 extern "C" sd_status sd_prefill(sd_ctx* c, int32_t row, const int32_t* prompt, int32_t n,
                                 const void* enc_p, const void* enc_q) {
   if (!c) return SD_EINVAL;
-  if (row != 0 || !prompt || n < 1) return fail(c, SD_EINVAL, "row must be 0, prompt non-empty");
+  if (row < 0 || row >= c->batch || !prompt || n < 1) return fail(c, SD_EINVAL, "row must be a sequence index, prompt non-empty");
   const sd_model_cfg &pc = c->p.cfg, &qc = c->q.cfg;
   if ((pc.arch == SD_ARCH_T5DEC) != (enc_p != nullptr) || (qc.arch == SD_ARCH_T5DEC) != (enc_q != nullptr))
     return fail(c, SD_EINVAL, "encoder output must be given exactly for T5DEC models");
   const int room = std::min(pc.max_len, qc.max_len);
   if (n + c->rt.max_gamma + 1 > room) return fail(c, SD_ERANGE, "prompt + max_gamma + 1 exceeds max_len");
   for (int i = 0; i < n; ++i) if (prompt[i] < 0 || prompt[i] >= pc.vocab) return fail(c, SD_ERANGE, "token id out of range");
-  c->state = 0;
+  c->state = 0; c->ready[row] = 0;
   Model* ms[2] = {&c->p, &c->q};
   const void* encs[2] = {enc_p, enc_q};
   for (int k = 0; k < 2; ++k) {
@@ -644,16 +718,18 @@ extern "C" sd_status sd_prefill(sd_ctx* c, int32_t row, const int32_t* prompt, i
     }
     const int step = prefill_rows(m.cfg);
     for (int s0 = 0; s0 < n - 1; s0 += step)
-      forward_any(c, m, ROWS_PREFILL, 0, std::min(step, n - 1 - s0), s0, 0, 0, nullptr);
+      forward_any(c, m, Rows{ROWS_PREFILL, 0, std::min(step, n - 1 - s0), s0, row, 1, 0}, nullptr);
   }
   SeqState st{};
   st.len = n; st.last_tok = prompt[n - 1]; st.prev_tok = (n >= 2) ? prompt[n - 2] : 0;
   for (int i = 0; i < 16; ++i) { st.x[i] = 0; st.out[i] = -1; }
-  *c->h_state = st;
-  HIP_TRY(c, hipMemcpyAsync(c->d_state, c->h_state, sizeof(SeqState), hipMemcpyHostToDevice, c->stream));
+  c->h_state[row] = st;
+  HIP_TRY(c, hipMemcpyAsync(c->d_state + row, c->h_state + row, sizeof(SeqState), hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   HIP_TRY(c, hipGetLastError());
-  c->state = 1; c->len = n; c->last_tok = prompt[n - 1];
+  c->ready[row] = 1; c->len[row] = n; c->last_tok[row] = prompt[n - 1];
+  c->state = 1;
+  for (int b = 0; b < c->batch; ++b) if (!c->ready[b]) c->state = 0;      // READY once every sequence is prefilled
   return SD_OK;
 }
 
@@ -669,28 +745,36 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
   if (!c) return SD_EINVAL;
   if (!out_tokens || !out_n) return fail(c, SD_EINVAL, "null output");
   if (gamma < 1 || gamma > c->rt.max_gamma) return fail(c, SD_EINVAL, "gamma out of range");
-  if (c->state == 0) return fail(c, SD_ESTATE, "sd_step before sd_prefill");
+  const int B = c->batch;
+  if (c->state == 0) return fail(c, SD_ESTATE, "sd_step before every sequence was prefilled");
   if (c->state == 2) return fail(c, SD_ESTATE, "Mq cache is stale after sd_step_baseline: reset and prefill");
-  if (prefix && (prefix_len != c->len || prefix[prefix_len - 1] != c->last_tok))
+  if (prefix && B > 1) return fail(c, SD_EINVAL, "the prefix check is for single-sequence contexts");
+  if (prefix && (prefix_len != c->len[0] || prefix[prefix_len - 1] != c->last_tok[0]))
     return fail(c, SD_ESTATE, "prefix does not match the committed sequence");
-  sd_status st = check_uniforms(c, temperature, uniforms, 2 * gamma + 1);
+  const int nu = 2 * gamma + 1;
+  sd_status st = check_uniforms(c, temperature, uniforms, B * nu);
   if (st != SD_OK) return st;
-  if (c->len + gamma + 1 > std::min(c->p.cfg.max_len, c->q.cfg.max_len)) return fail(c, SD_ERANGE, "sequence would exceed max_len");
+  for (int b = 0; b < B; ++b)
+    if (c->len[b] + gamma + 1 > std::min(c->p.cfg.max_len, c->q.cfg.max_len)) return fail(c, SD_ERANGE, "sequence would exceed max_len");
 
-  c->h_params->temperature = temperature;
-  c->h_params->lenience = c->sampling.lenience;
-  c->h_params->log_lenience = std::log((double)c->sampling.lenience);
-  c->h_params->top_k = c->sampling.top_k; c->h_params->top_p = c->sampling.top_p;
-  for (int i = 0; i < 2 * gamma + 1; ++i) c->h_params->uniforms[i] = uniforms ? uniforms[i] : 0.5f;
+  for (int b = 0; b < B; ++b) {
+    StepParams& hp = c->h_params[b];
+    hp.temperature = temperature;
+    hp.lenience = c->sampling.lenience;
+    hp.log_lenience = std::log((double)c->sampling.lenience);
+    hp.top_k = c->sampling.top_k; hp.top_p = c->sampling.top_p;
+    for (int i = 0; i < nu; ++i) hp.uniforms[i] = uniforms ? uniforms[(size_t)b * nu + i] : 0.5f;
+  }
+  const size_t pbytes = (size_t)B * sizeof(StepParams), sbytes = (size_t)B * sizeof(SeqState);
   const bool profile = (c->rt.flags & SD_FLAG_PROFILE) != 0;
   const bool graph = (c->rt.flags & SD_FLAG_GRAPH) != 0 && !profile;
   if (graph) {
     if (!c->graphs[gamma]) {
       hipGraph_t g = nullptr;
       HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-      hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream);
+      hipMemcpyAsync(c->d_params, c->h_params, pbytes, hipMemcpyHostToDevice, c->stream);
       enqueue_step(c, gamma, false);
-      hipMemcpyAsync(c->h_state, c->d_state, sizeof(SeqState), hipMemcpyDeviceToHost, c->stream);
+      hipMemcpyAsync(c->h_state, c->d_state, sbytes, hipMemcpyDeviceToHost, c->stream);
       HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
       hipError_t e = hipGraphInstantiate(&c->graphs[gamma], g, nullptr, nullptr, 0);
       hipGraphDestroy(g);
@@ -699,27 +783,36 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
     HIP_TRY(c, hipGraphLaunch(c->graphs[gamma], c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
   } else {
-    HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, pbytes, hipMemcpyHostToDevice, c->stream));
     enqueue_step(c, gamma, profile);
     if ((st = sync_state_to_host(c)) != SD_OK) return st;
   }
   HIP_TRY(c, hipGetLastError());
-  const SeqState& hs = *c->h_state;
-  if (hs.n < 0 || hs.n > gamma || hs.len != c->len + hs.n + 1) return fail(c, SD_EHIP, "device state inconsistent after step");
-  *out_n = hs.n;
-  for (int i = 0; i <= gamma; ++i) out_tokens[i] = (i <= hs.n) ? hs.out[i] : -1;
-  c->len = hs.len; c->last_tok = hs.last_tok;
-  c->last_gamma = gamma; c->last_kind = 0;
-  c->stats.steps += 1; c->stats.tokens += hs.n + 1; c->stats.accepted += hs.n; c->stats.fallbacks = hs.fallbacks;
-  const int tested = std::min(hs.n + 1, gamma);          // guesses whose test decided something
-  c->stats.tested += tested;
-  c->tune_tested += tested; c->tune_accepted += hs.n;
-  if (c->rt.flags & SD_FLAG_BETA) {
-    double b = 0.0;
-    for (int i = 0; i < tested; ++i) b += (double)hs.beta[i];
-    c->stats.beta_sum += b; c->stats.beta_count += tested;
-    c->tune_beta_sum += b; c->tune_beta_count += tested;
+  for (int b = 0; b < B; ++b) {
+    const SeqState& hs = c->h_state[b];
+    if (hs.n < 0 || hs.n > gamma || hs.len != c->len[b] + hs.n + 1) return fail(c, SD_EHIP, "device state inconsistent after step");
   }
+  int64_t fallbacks = 0;
+  for (int b = 0; b < B; ++b) {
+    const SeqState& hs = c->h_state[b];
+    out_n[b] = hs.n;
+    for (int i = 0; i <= gamma; ++i) out_tokens[(size_t)b * (gamma + 1) + i] = (i <= hs.n) ? hs.out[i] : -1;
+    c->len[b] = hs.len; c->last_tok[b] = hs.last_tok;
+    c->stats.tokens += hs.n + 1; c->stats.accepted += hs.n;
+    fallbacks += hs.fallbacks;
+    const int tested = std::min(hs.n + 1, gamma);          // guesses whose test decided something
+    c->stats.tested += tested;
+    c->tune_tested += tested; c->tune_accepted += hs.n;
+    if (c->rt.flags & SD_FLAG_BETA) {
+      double bsum = 0.0;
+      for (int i = 0; i < tested; ++i) bsum += (double)hs.beta[i];
+      c->stats.beta_sum += bsum; c->stats.beta_count += tested;
+      c->tune_beta_sum += bsum; c->tune_beta_count += tested;
+    }
+  }
+  c->stats.fallbacks = fallbacks;
+  c->last_gamma = gamma; c->last_kind = 0;
+  c->stats.steps += 1;
   if (profile) {
     float a = 0, b = 0, d = 0;
     hipEventElapsedTime(&a, c->ev[0], c->ev[1]); hipEventElapsedTime(&b, c->ev[1], c->ev[2]);
@@ -736,21 +829,27 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
 extern "C" sd_status sd_step_baseline(sd_ctx* c, float temperature, const float* uniforms, int32_t* out_token) {
   if (!c) return SD_EINVAL;
   if (!out_token) return fail(c, SD_EINVAL, "null output");
-  if (c->state == 0) return fail(c, SD_ESTATE, "sd_step_baseline before sd_prefill");
-  sd_status st = check_uniforms(c, temperature, uniforms, 1);
+  const int B = c->batch;
+  if (c->state == 0) return fail(c, SD_ESTATE, "sd_step_baseline before every sequence was prefilled");
+  sd_status st = check_uniforms(c, temperature, uniforms, B);
   if (st != SD_OK) return st;
-  if (c->len + 1 > c->p.cfg.max_len) return fail(c, SD_ERANGE, "sequence would exceed max_len");
-  c->h_params->temperature = temperature;
-  c->h_params->lenience = 1.0f; c->h_params->log_lenience = 0.0;
-  c->h_params->top_k = c->sampling.top_k; c->h_params->top_p = c->sampling.top_p;
-  c->h_params->uniforms[0] = uniforms ? uniforms[0] : 0.5f;
+  for (int b = 0; b < B; ++b)
+    if (c->len[b] + 1 > c->p.cfg.max_len) return fail(c, SD_ERANGE, "sequence would exceed max_len");
+  for (int b = 0; b < B; ++b) {
+    StepParams& hp = c->h_params[b];
+    hp.temperature = temperature;
+    hp.lenience = 1.0f; hp.log_lenience = 0.0;
+    hp.top_k = c->sampling.top_k; hp.top_p = c->sampling.top_p;
+    hp.uniforms[0] = uniforms ? uniforms[b] : 0.5f;
+  }
+  const size_t pbytes = (size_t)B * sizeof(StepParams), sbytes = (size_t)B * sizeof(SeqState);
   if ((c->rt.flags & SD_FLAG_GRAPH) != 0) {
     if (!c->graph_baseline) {
       hipGraph_t g = nullptr;
       HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-      hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream);
+      hipMemcpyAsync(c->d_params, c->h_params, pbytes, hipMemcpyHostToDevice, c->stream);
       enqueue_baseline(c);
-      hipMemcpyAsync(c->h_state, c->d_state, sizeof(SeqState), hipMemcpyDeviceToHost, c->stream);
+      hipMemcpyAsync(c->h_state, c->d_state, sbytes, hipMemcpyDeviceToHost, c->stream);
       HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
       hipError_t e = hipGraphInstantiate(&c->graph_baseline, g, nullptr, nullptr, 0);
       hipGraphDestroy(g);
@@ -759,15 +858,18 @@ extern "C" sd_status sd_step_baseline(sd_ctx* c, float temperature, const float*
     HIP_TRY(c, hipGraphLaunch(c->graph_baseline, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
   } else {
-    HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, pbytes, hipMemcpyHostToDevice, c->stream));
     enqueue_baseline(c);
     if ((st = sync_state_to_host(c)) != SD_OK) return st;
   }
   HIP_TRY(c, hipGetLastError());
-  const SeqState& hs = *c->h_state;
-  if (hs.len != c->len + 1) return fail(c, SD_EHIP, "device state inconsistent after baseline step");
-  *out_token = hs.last_tok;
-  c->len = hs.len; c->last_tok = hs.last_tok; c->state = 2;
+  for (int b = 0; b < B; ++b)
+    if (c->h_state[b].len != c->len[b] + 1) return fail(c, SD_EHIP, "device state inconsistent after baseline step");
+  for (int b = 0; b < B; ++b) {
+    out_token[b] = c->h_state[b].last_tok;
+    c->len[b] = c->h_state[b].len; c->last_tok[b] = c->h_state[b].last_tok;
+  }
+  c->state = 2;
   c->last_kind = 2;
   return SD_OK;
 }
@@ -777,9 +879,10 @@ extern "C" sd_status sd_debug_logits(sd_ctx* c, int32_t which, float* host_out, 
   const size_t V = c->p.cfg.vocab;
   const float* src = nullptr;
   size_t rows = 0;
-  if (which == 0 && c->last_kind == 0) { src = c->p_logits; rows = c->last_gamma + 1; }
-  else if (which == 1 && c->last_kind == 0) { src = c->q_logits; rows = c->last_gamma; }
-  else if (which == 2 && c->last_kind == 2) { src = c->p_logits; rows = 1; }
+  const size_t B = (size_t)c->batch;
+  if (which == 0 && c->last_kind == 0) { src = c->p_logits; rows = B * (c->last_gamma + 1); }
+  else if (which == 1 && c->last_kind == 0) { src = c->q_logits; rows = B * c->last_gamma; }
+  else if (which == 2 && c->last_kind == 2) { src = c->p_logits; rows = B; }
   else return fail(c, SD_ESTATE, "no such logits from the last call");
   if (n > rows * V) return fail(c, SD_EINVAL, "more floats requested than the last call produced");
   HIP_TRY(c, hipMemcpy(host_out, src, n * sizeof(float), hipMemcpyDeviceToHost));
@@ -832,15 +935,20 @@ extern "C" sd_status sd_measure_cost(sd_ctx* c, int32_t reps, double* mq_us, dou
   if (!c || !mq_us || !mp_us) return SD_EINVAL;
   if (reps < 1 || reps > 1000) return fail(c, SD_EINVAL, "reps must be 1..1000");
   if (c->state != 1) return fail(c, SD_ESTATE, "sd_measure_cost needs a prefilled sequence with a valid Mq cache");
-  if (c->len + 2 > std::min(c->p.cfg.max_len, c->q.cfg.max_len)) return fail(c, SD_ERANGE, "no room behind the committed sequence");
-  const int V = c->p.cfg.vocab;
-  // step parameters for the draws: whatever temperature was used last is fine, the uniform must be valid
-  c->h_params->uniforms[0] = 0.5f; c->h_params->uniforms[1] = 0.5f;
-  if (!(c->h_params->temperature >= 0.0f)) c->h_params->temperature = 1.0f;
-  c->h_params->lenience = c->sampling.lenience;
-  c->h_params->log_lenience = std::log((double)c->sampling.lenience);
-  c->h_params->top_k = c->sampling.top_k; c->h_params->top_p = c->sampling.top_p;
-  HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, sizeof(StepParams), hipMemcpyHostToDevice, c->stream));
+  const int V = c->p.cfg.vocab, B = c->batch;
+  if (c->rt.max_gamma < 2) return fail(c, SD_EINVAL, "sd_measure_cost needs max_gamma >= 2 (it runs a second draft step)");
+  for (int b = 0; b < B; ++b)
+    if (c->len[b] + 2 > std::min(c->p.cfg.max_len, c->q.cfg.max_len)) return fail(c, SD_ERANGE, "no room behind the committed sequence");
+  // step parameters for the draws: whatever temperature was used last is fine, the uniforms must be valid
+  for (int b = 0; b < B; ++b) {
+    StepParams& hp = c->h_params[b];
+    hp.uniforms[0] = 0.5f; hp.uniforms[1] = 0.5f;
+    if (!(hp.temperature >= 0.0f)) hp.temperature = 1.0f;
+    hp.lenience = c->sampling.lenience;
+    hp.log_lenience = std::log((double)c->sampling.lenience);
+    hp.top_k = c->sampling.top_k; hp.top_p = c->sampling.top_p;
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->d_params, c->h_params, (size_t)B * sizeof(StepParams), hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   double us[2] = {0.0, 0.0};
   for (int which = 0; which < 2; ++which) {
@@ -848,13 +956,13 @@ extern "C" sd_status sd_measure_cost(sd_ctx* c, int32_t reps, double* mq_us, dou
     hipGraphExec_t ge = nullptr;
     HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
     if (which == 0) {      // a draft step that is not the first of an iteration: guess x_1 in, q_2 and x_2 out
-      forward_any(c, c->q, ROWS_DRAFT_NEXT, 1, 1, 0, 0, 1, c->q_logits + (size_t)V);
-      hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, c->stream, c->q_logits + (size_t)V, V,
-                         c->d_params, 1, c->d_state, 0, 1);
+      forward_any(c, c->q, Rows{ROWS_DRAFT_NEXT, 1, 1, 0, 0, B, 2}, c->q_logits);     // rows [seq][2][V], second of each
+      hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->q_logits + (size_t)V, V,
+                         c->d_params, 1, c->d_state, 0, 1, (size_t)2 * V);
     } else {               // standard decoding's forward and draw; the draw lands in a guess slot, nothing is committed
-      forward_any(c, c->p, ROWS_BASELINE, 0, 1, 0, 0, 1, c->p_logits);
-      hipLaunchKernelGGL(sample_row_kernel, dim3(1), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
-                         c->d_params, 0, c->d_state, 0, 1);
+      forward_any(c, c->p, Rows{ROWS_BASELINE, 0, 1, 0, 0, B, 0}, c->p_logits);
+      hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
+                         c->d_params, 0, c->d_state, 0, 1, (size_t)V);
     }
     HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
     hipError_t e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);

@@ -401,3 +401,90 @@ def test_top_k_and_nucleus_decoding_matches_oracle(top_k, top_p):
         z = sp.score([int(t) for t in prompt] + want[:j], 1)[0]
         assert 0 < tp < 1 and sampling.nucleus_margin(z, 1.0, top_k, tp) < 1e-4
     dec.close()
+
+
+# ----------------------------------------------------------------------------
+# several sequences at once: per-row prompts, uniforms, accept lengths, KV pages and roll-back
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("arch,dtype,batch,gamma", [
+    (T.GQA, "f32", 3, 4),       # 15 verify rows: one group
+    (T.GQA, "bf16", 5, 4),      # 25 verify rows: groups of 3 + 2 sequences
+    (T.GPT, "bf16", 16, 3),     # 64 verify rows: four groups; 32 rows in the first draft step
+    (T.GQA, "bf16", 4, 7),      # 8 rows per sequence: two sequences per group
+])
+def test_batched_decoding_equals_single_sequence_decoding(arch, dtype, batch, gamma):
+    """A row's arithmetic never depends on the other rows of a launch, so every sequence of a
+    batch must produce bit-identical logits, n and tokens to the same sequence decoded alone
+    (which the tests above hold against the oracle).  Prompts differ in length and content;
+    the first sequence has a one-token prompt (padding row in the first draft step)."""
+    cfg_p, w_p, cfg_q, w_q, _, _ = small_pair(arch, dtype)
+    V = cfg_p["vocab"]
+    prompts = [synth.random_tokens(100 + b, 1 + (11 * b) % 37, V) for b in range(batch)]
+    n_it = 8
+    U = synth.uniform_stream(77, n_it * batch * (2 * gamma + 1)).reshape(n_it, batch, -1)
+    for temperature in (1.0, 0.0):
+        dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=1, batch=batch)
+        for b in range(batch):
+            dec.prefill(prompts[b], row=b)
+        got, got_logits = [], []
+        for it in range(n_it):
+            got.append(dec.step(gamma, temperature, U[it]))
+            got_logits.append((dec.logits(0, batch * (gamma + 1)).reshape(batch, gamma + 1, V),
+                               dec.logits(1, batch * gamma).reshape(batch, gamma, V)))
+        dec.close()
+        accepted = 0
+        for b in range(batch):
+            one = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=1)
+            one.prefill(prompts[b])
+            for it in range(n_it):
+                n, toks = one.step(gamma, temperature, U[it, b])
+                assert (n, toks) == got[it][b], (b, it, (n, toks), got[it][b])
+                np.testing.assert_array_equal(one.logits(0, gamma + 1), got_logits[it][0][b])
+                np.testing.assert_array_equal(one.logits(1, gamma), got_logits[it][1][b])
+                accepted += n
+            one.close()
+        print(f"arch {arch} {dtype} batch {batch} gamma {gamma} T={temperature}: accepted {accepted} of {batch * n_it * gamma}")
+        assert accepted < batch * n_it * gamma
+
+
+def test_batched_tiny_pair_matches_oracle_per_row_with_reset_of_one_row():
+    """Three sequences of the tiny fp32 pair against independent oracle runs; half-way one
+    sequence is reset and prefilled with a new prompt while the others keep their state."""
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    batch, gamma = 3, 4
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=1, batch=batch)
+    prefixes = [[int(t) for t in synth.random_tokens(40 + b, 6 + 5 * b, cfg_p["vocab"])] for b in range(batch)]
+    scorers = [oracle_models(cfg_p, w_p, cfg_q, w_q) for _ in range(batch)]
+    for b in range(batch):
+        dec.prefill(prefixes[b], row=b)
+    U = synth.uniform_stream(12, 16 * batch * 9).reshape(16, batch, 9)
+    from paper_2211_17192_amd import binding
+    with pytest.raises(binding.SdError):
+        dec.step(gamma, 1.0, U[0], prefix=prefixes[0])          # the prefix check is single-sequence only
+    tolerated = 0
+    for it in range(12):
+        if it == 6:
+            dec.reset(row=1)
+            with pytest.raises(binding.SdError):
+                dec.step(gamma, 1.0, U[it])                      # row 1 is not prefilled
+            prefixes[1] = [int(t) for t in synth.random_tokens(90, 9, cfg_p["vocab"])]
+            scorers[1] = oracle_models(cfg_p, w_p, cfg_q, w_q)
+            dec.prefill(prefixes[1], row=1)
+        res = dec.step(gamma, 1.0, U[it])
+        for b in range(batch):
+            new_o, n_o, info = decode.speculative_decoding_step(scorers[b][0], scorers[b][1], prefixes[b], gamma, 1.0, U[it, b])
+            n_g, toks_g = res[b]
+            if new_o[len(prefixes[b]):] != toks_g:
+                assert np.min(info["margins"]) < 1e-3
+                tolerated += 1
+            prefixes[b] = prefixes[b] + toks_g
+    assert tolerated <= 1
+    # plain decoding for all rows afterwards
+    ub = synth.uniform_stream(13, 5 * batch).reshape(5, batch)
+    for i in range(5):
+        toks = dec.step_baseline(1.0, ub[i])
+        for b in range(batch):
+            want = decode.plain_decode(scorers[b][0], prefixes[b], 1, 1.0, [ub[i, b]])[-1]
+            assert toks[b] == want
+            prefixes[b].append(toks[b])
+    dec.close()
