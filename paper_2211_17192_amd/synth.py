@@ -263,6 +263,20 @@ def gpt_pair(device="cuda", seed: int = 2, emb_rms: float = 1.0, head_std: float
     return cfg_p, w_p, cfg_q, w_q
 
 
+def gqa8b_pair(device="cuda", seed: int = 6, max_len: int = 2336, emb_rms: float = 32.0,
+               head_std: float = 0.1, logit_scale: float = 1.0, q_logit_gain: float = 1.0):
+    """8B-class decoder-only target in bf16 (32 layers, d_model 4096, 32 query / 8 KV heads x 128,
+    d_ff 14336 SwiGLU, vocab 32000, rotary positions) with a 2-layer draft (d_model 1024,
+    8 heads x 128, d_ff 4096: the width is given, the rest is this build's choice), random init,
+    correlated like the other pairs.  max_len 2336 = 2048 context + 256 generated + slack."""
+    cfg_p = model_cfg(GQA, 32, 4096, 32, 14336, 32000, max_len, d_head=128, n_kv_heads=8,
+                      norm_eps=1e-5, dtype="bf16", logit_scale=logit_scale)
+    cfg_q = model_cfg(GQA, 2, 1024, 8, 4096, 32000, max_len, d_head=128, n_kv_heads=8,
+                      norm_eps=1e-5, dtype="bf16", logit_scale=logit_scale)
+    w_p, cfg_q, w_q = correlated_pair(cfg_p, cfg_q, seed, device, emb_rms, head_std, 0.02, q_logit_gain)
+    return cfg_p, w_p, cfg_q, w_q
+
+
 def model_bytes(cfg: dict) -> dict:
     """Bytes one forward has to read: layer + head weights (every row of them),
     and per cached position the self-attention keys / values."""

@@ -488,3 +488,83 @@ def test_batched_tiny_pair_matches_oracle_per_row_with_reset_of_one_row():
             assert toks[b] == want
             prefixes[b].append(toks[b])
     dec.close()
+
+
+def test_gqa8b_full_size_batch_matches_oracle_per_row():
+    """The batched 8B-class workload at full model size (Mp 32 layers, d_model 4096, 32 query /
+    8 KV heads x 128, d_ff 14336 SwiGLU, vocab 32000, rotary; Mq 2 layers, d_model 1024), four
+    sequences with prompts of 1, 5, 17 and 33 tokens (one to three KV pages), gamma = 4, graph
+    replay: every row's target and draft logits against the float64 oracle run on that sequence
+    alone (level M), and the oracle's Algorithm-1 arithmetic on the GPU's logits against the
+    GPU's n and tokens (level S).  The context is short because the oracle has to score it."""
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q = synth.gqa8b_pair("cuda", max_len=64)
+    host = (synth.to_numpy_weights(w_p), synth.to_numpy_weights(w_q))
+    batch, gamma = 4, 4
+    dec = binding.SpecDecoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=binding.SD_FLAG_GRAPH, batch=batch)
+    del w_p, w_q
+    torch.cuda.empty_cache()
+    mp = T.Transformer(T.ModelConfig(**cfg_p), host[0])
+    mq = T.Transformer(T.ModelConfig(**cfg_q), host[1])
+    V = cfg_p["vocab"]
+    prefixes = [[int(t) for t in synth.random_tokens(60 + b, n, V)] for b, n in enumerate((1, 5, 17, 33))]
+    scorers = [(T.CachedScorer(mp), T.CachedScorer(mq)) for _ in range(batch)]
+    for b in range(batch):
+        dec.prefill(prefixes[b], row=b)
+    U = synth.uniform_stream(31, 2 * batch * (2 * gamma + 1)).reshape(2, batch, -1)
+    worst, tolerated = 0.0, 0
+    for it in range(2):
+        res = dec.step(gamma, 1.0, U[it])
+        zp = dec.logits(0, batch * (gamma + 1)).astype(np.float64).reshape(batch, gamma + 1, V)
+        zq = dec.logits(1, batch * gamma).astype(np.float64).reshape(batch, gamma, V)
+        assert np.isfinite(zp).all() and np.isfinite(zq).all()
+        for b in range(batch):
+            n_g, toks_g = res[b]
+            x_s, n_s, t_s, info, p_rows, q_rows = level_s(zp[b], zq[b], U[it, b], gamma, 1.0)
+            if (n_g, toks_g) != (n_s, x_s[:n_s] + [t_s]):
+                k = min(n_g, n_s)
+                assert toks_g[:k] == x_s[:k] and n_g != n_s and info["margins"][k] < 1e-3, (it, b, n_g, n_s)
+                tolerated += 1
+            sp, sq = scorers[b]
+            zq_o = np.stack([sq.score(prefixes[b] + x_s[:i], 1)[0] for i in range(gamma)])
+            zp_o = sp.score(prefixes[b] + x_s, gamma + 1)
+            worst = max(worst, rel_err(zq[b], zq_o), rel_err(zp[b], zp_o))
+            assert worst <= TOL["bf16"], (it, b, worst)
+            prefixes[b] = prefixes[b] + toks_g
+    print(f"8B-class GQA pair, batch 4, gamma 4: worst logit error {worst:.2e}, tolerated {tolerated}")
+    assert tolerated <= 1
+    dec.close()
+
+
+@pytest.mark.parametrize("d_head,ctx", [(128, 600), (64, 1100), (32, 1300)])
+def test_long_context_spans_several_key_blocks(d_head, ctx):
+    """Contexts longer than one key block of the attention kernel (256 keys at d_head 128, 512
+    otherwise): the online softmax across blocks, with a ragged last block, two sequences of
+    different length, against the oracle (fp32 models, tight tolerance)."""
+    cfg = synth.model_cfg(T.GQA, 2, 4 * d_head, 4, 256, 512, ctx + 64, d_head=d_head, n_kv_heads=2,
+                          dtype="f32", logit_scale=4.0)
+    w = synth.random_weights(cfg, 9, w_std=0.1)
+    cfg_q, w_q = synth.truncated_noisy_copy(cfg, w, 1, 59, 0.02)
+    batch, gamma = 2, 3
+    dec = make_decoder(cfg, w, cfg_q, w_q, max_gamma=gamma, flags=1, batch=batch)
+    prefixes = [[int(t) for t in synth.random_tokens(70 + b, ctx - 250 * b, cfg["vocab"])] for b in range(batch)]
+    scorers = [oracle_models(cfg, w, cfg_q, w_q) for _ in range(batch)]
+    for b in range(batch):
+        dec.prefill(prefixes[b], row=b)
+    U = synth.uniform_stream(41, 3 * batch * (2 * gamma + 1)).reshape(3, batch, -1)
+    worst = 0.0
+    for it in range(3):
+        res = dec.step(gamma, 1.0, U[it])
+        zp = dec.logits(0, batch * (gamma + 1)).astype(np.float64).reshape(batch, gamma + 1, -1)
+        zq = dec.logits(1, batch * gamma).astype(np.float64).reshape(batch, gamma, -1)
+        for b in range(batch):
+            x_s, n_s, t_s, info, _, _ = level_s(zp[b], zq[b], U[it, b], gamma, 1.0)
+            assert res[b] == (n_s, x_s[:n_s] + [t_s]) or np.min(info["margins"]) < 1e-3
+            sp, sq = scorers[b]
+            zq_o = np.stack([sq.score(prefixes[b] + x_s[:i], 1)[0] for i in range(gamma)])
+            zp_o = sp.score(prefixes[b] + x_s, gamma + 1)
+            worst = max(worst, rel_err(zq[b], zq_o), rel_err(zp[b], zp_o))
+            prefixes[b] = prefixes[b] + res[b][1]
+    print(f"d_head {d_head}, context {ctx}: worst logit error {worst:.2e}")
+    assert worst <= TOL["f32"]
+    dec.close()
