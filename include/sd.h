@@ -228,6 +228,22 @@ sd_status sd_set_flags(sd_ctx* ctx, int32_t flags);
 sd_status sd_set_sampling(sd_ctx* ctx, const sd_sampling* opt);
 
 /*
+ * Section 3.6, negligible-cost approximation models: an n-gram table in place
+ * of Mq.  With a table set, the draft loop of sd_step does no Mq forward:
+ * the logits of guess x_i are the table row row_of[previous token] (a bigram
+ * model; the previous token is the last committed token for x_1, else x_{i-1});
+ * row_of == NULL selects row 0 for every context (a unigram model).  The rows
+ * then go through the same standardisation, acceptance test and adjusted
+ * distribution as Mq's logits would; c is the cost of a table lookup and a draw.
+ *   table  : dev, [n_rows, vocab] fp32 logits, caller-owned, must outlive its use
+ *   row_of : dev, [vocab] int32 row per previous token (values clamped to the table), or NULL
+ * table == NULL (with row_of NULL, n_rows 0) goes back to Mq; Mq's cache was not
+ * kept up meanwhile, so sd_step then needs sd_reset + sd_prefill first (SD_ESTATE).
+ * Mq must still be given to sd_load_models.  Synchronises the stream.
+ */
+sd_status sd_set_table_draft(sd_ctx* ctx, const float* table, const int32_t* row_of, int32_t n_rows);
+
+/*
  * Section 3.5 (choosing gamma): the integer gamma in 1..gamma_max that maximises
  * the expected walltime improvement of Theorem 3.8,
  *     (1 - alpha^(gamma+1)) / ((1 - alpha) (gamma c + 1)),

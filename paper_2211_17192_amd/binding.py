@@ -164,6 +164,8 @@ lib.sd_time_ffn_in.restype = C.c_int
 lib.sd_time_ffn_in.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
 lib.sd_set_sampling.restype = C.c_int
 lib.sd_set_sampling.argtypes = [C.c_void_p, C.POINTER(_Sampling)]
+lib.sd_set_table_draft.restype = C.c_int
+lib.sd_set_table_draft.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
 lib.sd_measure_cost.restype = C.c_int
 lib.sd_measure_cost.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 lib.sd_autotune_gamma.restype = C.c_int
@@ -287,6 +289,21 @@ class SpecDecoder:
     def set_sampling(self, lenience: float = 1.0, top_k: int = 0, top_p: float = 0.0):
         opt = _Sampling(float(lenience), int(top_k), float(top_p))
         self._check(lib.sd_set_sampling(self._ctx, C.byref(opt)))
+
+    def set_table_draft(self, table=None, row_of=None):
+        """Draft from an n-gram table (cuda fp32 [rows, vocab]; row_of: cuda int32 [vocab] or None
+        for a unigram model) instead of Mq; None goes back to Mq.  The tensors are kept alive here."""
+        if table is None:
+            self._check(lib.sd_set_table_draft(self._ctx, None, None, 0))
+            self._draft = None
+            return
+        assert table.is_cuda and table.is_contiguous() and table.dtype == torch.float32 and table.shape[1] == self.vocab
+        if row_of is not None:
+            assert row_of.is_cuda and row_of.is_contiguous() and row_of.dtype == torch.int32 and row_of.numel() == self.vocab
+        torch.cuda.synchronize()
+        self._check(lib.sd_set_table_draft(self._ctx, _ptr(table), _ptr(row_of) if row_of is not None else None,
+                                           int(table.shape[0])))
+        self._draft = (table, row_of)
 
     def measure_cost(self, reps: int = 20):
         """(microseconds of one Mq draft step, microseconds of one standard Mp decoding step)."""

@@ -85,6 +85,23 @@ static __global__ __launch_bounds__(256) void embed_kernel(
   }
 }
 
+// Negligible-cost approximation model (an n-gram table): the draft logits of guess `step`
+// of sequence b are the table row selected by the previous token (bigram; row_of == nullptr:
+// one row for every context, a unigram model).  grid = (slices, sequences); the row is
+// copied to dst + b * seq_stride, where the sampling kernels expect the draft's logits.
+static __global__ __launch_bounds__(256) void table_row_kernel(
+    const float* __restrict__ table, const int* __restrict__ row_of, int n_rows, int V,
+    const SeqState* __restrict__ st, int step, float* __restrict__ dst, size_t seq_stride) {
+  st += blockIdx.y;
+  int prev = (step == 0) ? st->last_tok : st->x[step - 1];
+  prev = min(max(prev, 0), V - 1);
+  int row = (row_of != nullptr) ? row_of[prev] : 0;
+  row = min(max(row, 0), n_rows - 1);
+  const float* src = table + (size_t)row * V;
+  float* out = dst + (size_t)blockIdx.y * seq_stride;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < V; i += gridDim.x * blockDim.x) out[i] = src[i];
+}
+
 static __global__ void fill_u32_kernel(unsigned int* p, unsigned int v, size_t n) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

@@ -176,6 +176,10 @@ struct sd_ctx {
   bool time_ffn = false;             // set while the verify forward of a profiled step is enqueued
   sd_stats stats{};
   sd_sampling sampling{1.0f, 0, 0.0f};
+  // negligible-cost draft: logits table in place of Mq's forward (caller-owned device memory)
+  const float* draft_table = nullptr;
+  const int* draft_row_of = nullptr;
+  int draft_rows = 0;
   // acceptance statistics for the choice of gamma: they describe the pair and the task, not one
   // sequence, so sd_reset leaves them alone
   int64_t tune_accepted = 0, tune_tested = 0, tune_beta_count = 0;
@@ -442,7 +446,10 @@ void enqueue_step(sd_ctx* c, int gamma, bool profile) {
   const int V = c->p.cfg.vocab, B = c->batch;
   if (profile) hipEventRecord(c->ev[0], s);
   for (int i = 0; i < gamma; ++i) {              // q_i <- Mq(prefix + x_<i), x_i ~ q_i
-    if (i == 0) forward_any(c, c->q, Rows{ROWS_DRAFT_FIRST, 0, 2, 0, 0, B, gamma}, c->q_logits);
+    if (c->draft_table)                          // table lookup instead of a forward
+      hipLaunchKernelGGL(table_row_kernel, dim3(std::min(32, (V + 255) / 256), B), dim3(256), 0, s, c->draft_table,
+                         c->draft_row_of, c->draft_rows, V, c->d_state, i, c->q_logits + (size_t)i * V, (size_t)gamma * V);
+    else if (i == 0) forward_any(c, c->q, Rows{ROWS_DRAFT_FIRST, 0, 2, 0, 0, B, gamma}, c->q_logits);
     else forward_any(c, c->q, Rows{ROWS_DRAFT_NEXT, i, 1, 0, 0, B, gamma}, c->q_logits);
     hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, s, c->q_logits + (size_t)i * V, V,
                        c->d_params, i, c->d_state, 0, i, (size_t)gamma * V);
@@ -747,7 +754,7 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
   if (gamma < 1 || gamma > c->rt.max_gamma) return fail(c, SD_EINVAL, "gamma out of range");
   const int B = c->batch;
   if (c->state == 0) return fail(c, SD_ESTATE, "sd_step before every sequence was prefilled");
-  if (c->state == 2) return fail(c, SD_ESTATE, "Mq cache is stale after sd_step_baseline: reset and prefill");
+  if (c->state == 2 && !c->draft_table) return fail(c, SD_ESTATE, "Mq cache is stale (after sd_step_baseline or table drafts): reset and prefill");
   if (prefix && B > 1) return fail(c, SD_EINVAL, "the prefix check is for single-sequence contexts");
   if (prefix && (prefix_len != c->len[0] || prefix[prefix_len - 1] != c->last_tok[0]))
     return fail(c, SD_ESTATE, "prefix does not match the committed sequence");
@@ -900,6 +907,19 @@ extern "C" sd_status sd_set_flags(sd_ctx* c, int32_t flags) {
   return SD_OK;
 }
 
+extern "C" sd_status sd_set_table_draft(sd_ctx* c, const float* table, const int32_t* row_of, int32_t n_rows) {
+  if (!c) return SD_EINVAL;
+  if (table != nullptr && n_rows < 1) return fail(c, SD_EINVAL, "a draft table needs at least one row");
+  if (table == nullptr && (row_of != nullptr || n_rows != 0)) return fail(c, SD_EINVAL, "no table: row_of must be NULL and n_rows 0");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (auto& g : c->graphs) if (g) { hipGraphExecDestroy(g); g = nullptr; }     // the captured draft loop changes
+  const bool was_table = c->draft_table != nullptr;
+  c->draft_table = table; c->draft_row_of = table ? row_of : nullptr; c->draft_rows = table ? n_rows : 0;
+  // table drafts leave Mq's cache behind: going back to Mq needs the sequences prefilled again
+  if (was_table && table == nullptr && c->state == 1) c->state = 2;
+  return SD_OK;
+}
+
 extern "C" sd_status sd_set_sampling(sd_ctx* c, const sd_sampling* opt) {
   if (!c || !opt) return SD_EINVAL;
   if (!(opt->lenience > 0.0f && opt->lenience <= 1.0f)) return fail(c, SD_EINVAL, "lenience must lie in (0, 1]");
@@ -935,6 +955,7 @@ extern "C" sd_status sd_measure_cost(sd_ctx* c, int32_t reps, double* mq_us, dou
   if (!c || !mq_us || !mp_us) return SD_EINVAL;
   if (reps < 1 || reps > 1000) return fail(c, SD_EINVAL, "reps must be 1..1000");
   if (c->state != 1) return fail(c, SD_ESTATE, "sd_measure_cost needs a prefilled sequence with a valid Mq cache");
+  if (c->draft_table) return fail(c, SD_ESTATE, "sd_measure_cost times Mq: clear the draft table first");
   const int V = c->p.cfg.vocab, B = c->batch;
   if (c->rt.max_gamma < 2) return fail(c, SD_EINVAL, "sd_measure_cost needs max_gamma >= 2 (it runs a second draft step)");
   for (int b = 0; b < B; ++b)

@@ -16,7 +16,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import decode, sampling, transformer as T
+from oracle import decode, drafts, sampling, transformer as T
 from paper_2211_17192_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -567,4 +567,52 @@ def test_long_context_spans_several_key_blocks(d_head, ctx):
             prefixes[b] = prefixes[b] + res[b][1]
     print(f"d_head {d_head}, context {ctx}: worst logit error {worst:.2e}")
     assert worst <= TOL["f32"]
+    dec.close()
+
+
+@pytest.mark.parametrize("kind", ["unigram", "bigram"])
+def test_table_drafts_match_oracle(kind):
+    """Section 3.6: an n-gram table in place of Mq.  Two sequences of the tiny fp32 target with a
+    unigram table (one row) or a bigram table (a row per previous token, shared by pairs of
+    tokens through row_of) against the oracle run with the same table as its approximation
+    model; afterwards going back to Mq needs a new prefill."""
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    V = cfg_p["vocab"]
+    batch, gamma = 2, 4
+    # the table approximates the target the way an n-gram model would: row r holds the target's own
+    # logits after the one-token context [2r] (+ noise), the unigram row is their mean
+    ref = oracle_models(cfg_p, w_p, cfg_q, w_q)[0]
+    rows = np.stack([ref.score([2 * r], 1)[0] for r in range(V // 2)]).astype(np.float32)
+    rows = torch.from_numpy(rows) + synth.counter_normal((V // 2, V), 202, 1.0).float()
+    if kind == "unigram":
+        table = rows.mean(dim=0, keepdim=True).contiguous()
+        row_of = None
+    else:
+        table = rows.contiguous()
+        row_of = (torch.arange(V, dtype=torch.int32) // 2)
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=1, batch=batch)
+    dec.set_table_draft(table.float().cuda(), None if row_of is None else row_of.cuda())
+    prefixes = [[int(t) for t in synth.random_tokens(50 + b, 4 + 9 * b, V)] for b in range(batch)]
+    targets = [oracle_models(cfg_p, w_p, cfg_q, w_q)[0] for _ in range(batch)]
+    tdraft = drafts.TableDraft(table.float().numpy(), None if row_of is None else row_of.numpy())
+    for b in range(batch):
+        dec.prefill(prefixes[b], row=b)
+    U = synth.uniform_stream(61, 20 * batch * 9).reshape(20, batch, 9)
+    tolerated, kept = 0, 0
+    for it in range(16):
+        res = dec.step(gamma, 1.0, U[it])
+        zq = dec.logits(1, batch * gamma).reshape(batch, gamma, V)
+        for b in range(batch):
+            new_o, n_o, info = decode.speculative_decoding_step(targets[b], tdraft, prefixes[b], gamma, 1.0, U[it, b])
+            np.testing.assert_array_equal(zq[b], info["q_logits"].astype(np.float32))   # the rows are copies of table rows
+            if new_o[len(prefixes[b]):] != res[b][1]:
+                assert np.min(info["margins"]) < 1e-3
+                tolerated += 1
+            kept += res[b][0]
+            prefixes[b] = prefixes[b] + res[b][1]
+    assert tolerated <= 1 and 0 < kept < 16 * batch * gamma
+    dec.set_table_draft(None)
+    with pytest.raises(binding.SdError):
+        dec.step(gamma, 1.0, U[16])                 # Mq's cache was not kept up
     dec.close()

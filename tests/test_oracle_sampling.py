@@ -13,7 +13,7 @@ import pytest
 import scipy.special
 import scipy.stats
 
-from oracle import analysis, decode, sampling
+from oracle import analysis, decode, drafts, sampling
 
 
 def grid(n):
@@ -331,6 +331,34 @@ def test_speculative_sampling_with_top_k_is_distributed_as_the_adjusted_p():
     # q keeps {1/2, 1/4} -> {2/3, 1/3} (draw threshold 8/12); token 0 is always dropped, token 1 always
     # kept; the residual {0, 1/12, 0, 7/12} normalises to {0, 1/8, 0, 7/8} (threshold 1/8)
     np.testing.assert_allclose(counts / counts.sum(), want, atol=1e-12)
+
+
+def test_table_drafts_leave_the_output_distribution_at_p():
+    """Section 3.6: a unigram or bigram table as the approximation model.  Whatever q is, the
+    first emitted token is distributed as p_1 and (given it was a kept guess) the second as
+    p_2 (appendix A.1); the acceptance rate is sum min(p, q) of the table row (Cor. 3.6)."""
+    mp, _ = table_models()
+    with np.errstate(divide="ignore"):
+        bigram = drafts.TableDraft(np.log(np.array([Q2[0], Q2[1], Q2[2], Q2[3]])), row_of=[0, 1, 2, 3])
+        unigram = drafts.TableDraft(np.log(np.array([Q1])))
+    np.testing.assert_array_equal(unigram.score([2, 0, 3], 2), np.log(np.array([Q1, Q1])))
+    with np.errstate(divide="ignore"):
+        np.testing.assert_array_equal(bigram.score([2, 0, 3], 2), np.log(np.array([Q2[0], Q2[3]])))
+    gd, gr, gs = grid(8), grid(16), grid(24)        # thresholds: draws k/8, tests 3/8 and 1/2, residual 1/6 and 1/8
+    # unigram, one guess: output ~ P1, acceptance rate = sum min(P1, Q1)
+    counts, kept = np.zeros(4), 0
+    for d, r, sv in itertools.product(gd, gr, gs):
+        out, n, _ = decode.speculative_decoding_step(mp, unigram, [0], 1, 1.0, [d, r, sv])
+        counts[out[1]] += 1
+        kept += n
+    np.testing.assert_allclose(counts / counts.sum(), P1, atol=1e-12)
+    assert abs(kept / counts.sum() - sampling.beta(P1, Q1)) < 1e-12
+    # bigram (context token 0 -> row Q2[0] = [1/2, 1/2, 0, 0]), target P1: output ~ P1 again
+    counts = np.zeros(4)
+    for d, r, sv in itertools.product(grid(2), gr, gs):
+        out, n, _ = decode.speculative_decoding_step(mp, bigram, [0], 1, 1.0, [d, r, sv])
+        counts[out[1]] += 1
+    np.testing.assert_allclose(counts / counts.sum(), P1, atol=1e-12)
 
 
 def test_uniform_validation():
