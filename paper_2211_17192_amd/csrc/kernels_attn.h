@@ -66,9 +66,10 @@ struct AttnArgs {
   const int* row_pos;       // [R]; self: causal limit of each row, < 0 = padding row
   int R, H, Hkv;
   int rows_per_wg;          // grid.y = ceil(R / rows_per_wg): rows are independent, no merge needed
-  // several sequences in one launch: grid.z = sequences, R rows each, one after the other in
-  // q / out / row_pos; sequence z uses the page table at page_table + (seq0 + z) * pt_stride
-  int seq0, pt_stride;
+  // several sequences in one launch: grid.z = sequences, R rows each; they sit in slabs of
+  // MAX_ROWS rows, spg whole sequences per slab (sequence z: slab z / spg, rows (z % spg) * R ..);
+  // sequence z uses the page table at page_table + (seq0 + z) * pt_stride
+  int seq0, pt_stride, spg;
   int cross;                // 1: cross-attention over kv_len keys, no mask, no bias
   int kv_len;
   float scale;
@@ -95,7 +96,7 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   // rows are independent: blockIdx.y takes rows [r0, r0 + R) of the launch
   const int rs = blockIdx.y * a.rows_per_wg;                   // first row within the sequence
   const int R = min(a.rows_per_wg, a.R - rs);
-  const int r0 = blockIdx.z * a.R + rs;                        // first row within the launch
+  const int r0 = ((int)blockIdx.z / a.spg) * MAX_ROWS + ((int)blockIdx.z % a.spg) * a.R + rs;   // first row within the launch
   const int* page_table = a.page_table + (size_t)(a.seq0 + blockIdx.z) * a.pt_stride;
   const int G = a.H / a.Hkv, RG = R * G;
 #ifdef SD_KTIME

@@ -71,6 +71,10 @@ struct GemmArgs {
   const int* row_seq;     // EPI_QKV: [R] sequence of each row; its page table starts at page_table + seq * pt_stride
   int pt_stride;
   const int* out_row;     // EPI_LOGITS: [R] row of `out` each input row goes to, < 0: dropped
+  // gemm_wide_kernel: nrt slabs of 16 rows, one after the other in every row-indexed
+  // buffer; slabs hold R rows each, the last one R_last; the partial-sum blocks of two
+  // slabs lie ss_stride floats apart
+  int nrt, R_last, ss_stride;
   const float* rope;      // [max_len][d_head/2][2] (cos, sin) or nullptr
 };
 
@@ -382,6 +386,301 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   // ---- software pipeline over the work list: the loads of chunk g+1 (possibly
   // the first chunk of the next tile) are in flight while chunk g is multiplied
   // and while a finished tile is reduced and written out ----
+  for (int g = 0; g < G; g += 2) {
+    before_prefetch(g);
+    if (g + 1 < G) load_chunk(b1, g + 1);
+    compute_chunk(b0, g);
+    if (g + 1 < G) {
+      before_prefetch(g + 1);
+      if (g + 2 < G) load_chunk(b0, g + 2);
+      compute_chunk(b1, g + 1);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// The same product for up to GEMM_WIDE_RT slabs of 16 rows in one launch (several
+// sequences decoded together give more than 16 rows).  Each weight fragment is
+// multiplied against the matching activation fragment of every slab, so the weights
+// are still streamed once; the activations are re-read per tile from L2 (a few KB
+// per KB of weights).  Same K split over wavefronts, same order of additions per
+// row as gemm_kernel: a row's result does not depend on the kernel it went through.
+// Shallower prefetch (GEMM_WIDE_U k-steps per chunk) because every chunk also holds
+// the activation fragments of all slabs.
+// ---------------------------------------------------------------------------
+constexpr int GEMM_WIDE_RT = 6;
+constexpr int GEMM_WIDE_U = 2;
+
+template <typename T, int PRO, int EPI>
+static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a) {
+  extern __shared__ float lds[];
+  constexpr int ND = (EPI == EPI_GATED) ? 2 : 1;
+  constexpr int U = GEMM_WIDE_U, RT = GEMM_WIDE_RT;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, S = blockDim.x >> 6;
+  const int j = lane & 15, kq = lane >> 4;
+  const int KS = a.K >> 5;
+  const int ks0 = min(KS, wave * a.ksteps_per_wave), ks1 = min(KS, ks0 + a.ksteps_per_wave);
+  const int nchunks = (a.ksteps_per_wave + U - 1) / U;
+  const int ntiles = a.N >> 4;
+  const int my_tiles = (ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+  float* part = lds;                                 // [2][S][ND][256], alternating per (tile, slab)
+  float* stat = lds + 2 * S * ND * 256;              // [S][16]
+  float* ybuf = stat + S * 16;                       // [256]
+  const bool epi_thread = tid < 256;
+  const int e_row = (tid >> 4) & 15, e_f = tid & 15;
+  const int nrt = a.nrt;
+  auto slab_rows = [&](int rt) { return (rt == nrt - 1) ? a.R_last : a.R; };
+
+  // per slab: clamped row of this lane (B side) and of this thread (epilogue side)
+  int jr[RT], er[RT];
+  bool jok[RT], eok[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int rc = min(rt, nrt - 1), rows = slab_rows(rc);
+    jr[rt] = rc * 16 + min(j, rows - 1);
+    er[rt] = rc * 16 + min(e_row, rows - 1);
+    jok[rt] = (rt < nrt) && (j < rows);
+    eok[rt] = (rt < nrt) && (e_row < rows);
+  }
+
+  // ---- PRO_LN: statistics of the fp32 rows, slab by slab ----
+  float mu[RT], rstd[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) { mu[rt] = 0.0f; rstd[rt] = 1.0f; }
+  if (PRO == PRO_LN) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const float* x = static_cast<const float*>(a.X) + (size_t)jr[rt] * a.K + kq * 8;
+      float s1 = 0.0f;
+      for (int ks = ks0; ks < ks1; ++ks) {
+        float v[8]; load8<float>(x + ks * 32, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s1 += v[e];
+      }
+      s1 = lane_combine<16>(s1, OpSumF()); s1 = lane_combine<32>(s1, OpSumF());
+      __syncthreads();
+      if (kq == 0) stat[wave * 16 + j] = s1;
+      __syncthreads();
+      float t = 0.0f;
+      for (int w = 0; w < S; ++w) t += stat[w * 16 + j];
+      mu[rt] = t / (float)a.K;
+      float s2 = 0.0f;
+      for (int ks = ks0; ks < ks1; ++ks) {
+        float v[8]; load8<float>(x + ks * 32, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float d = v[e] - mu[rt]; s2 += d * d; }
+      }
+      s2 = lane_combine<16>(s2, OpSumF()); s2 = lane_combine<32>(s2, OpSumF());
+      __syncthreads();
+      if (kq == 0) stat[wave * 16 + j] = s2;
+      __syncthreads();
+      float t2 = 0.0f;
+      for (int w = 0; w < S; ++w) t2 += stat[w * 16 + j];
+      rstd[rt] = 1.0f / sqrtf(t2 / (float)a.K + a.eps);
+    }
+    __syncthreads();
+  }
+
+  typedef typename Mma<T>::Frag Frag;
+  struct Buf { Frag fa[ND][U]; Frag fb[RT][U]; };
+
+  auto make_b = [&](int ks, bool valid, int rt) -> Frag {
+    const int k = ks * 32 + kq * 8;
+    if (PRO != PRO_LN) {
+      return Mma<T>::load(static_cast<const T*>(a.X) + (size_t)jr[rt] * a.K + k);
+    } else {
+      float v[8], g[8], bb[8];
+      load8<float>(static_cast<const float*>(a.X) + (size_t)jr[rt] * a.K + k, v);
+      load8<T>(static_cast<const T*>(a.gain) + k, g);
+      load8<T>(static_cast<const T*>(a.beta) + k, bb);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (v[e] - mu[rt]) * rstd[rt] * g[e] + bb[e];
+      return Mma<T>::select(valid && jok[rt], Mma<T>::from_floats(v));
+    }
+  };
+
+  const int ks_last = max(ks1 - 1, 0);
+  auto load_chunk = [&](Buf& b, int g) {
+    const int ti = g / nchunks, c = g - ti * nchunks;
+    const size_t tile = (size_t)blockIdx.x + (size_t)ti * gridDim.x;
+    const T* w0 = static_cast<const T*>(a.W) + (tile * KS) * 512 + lane * 8;
+    const T* w1 = (ND == 2) ? static_cast<const T*>(a.W2) + (tile * KS) * 512 + lane * 8 : nullptr;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ks = ks0 + c * U + u;
+      const int ksc = min(ks, ks_last);
+      b.fa[0][u] = Mma<T>::load_stream(w0 + (size_t)ksc * 512);
+      if (ND == 2) b.fa[ND - 1][u] = Mma<T>::load_stream(w1 + (size_t)ksc * 512);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) b.fb[rt][u] = make_b(ksc, ks < ks1, rt);
+    }
+  };
+
+  const int G = my_tiles * nchunks;
+  Buf b0, b1;
+  if (G > 0) load_chunk(b0, 0);
+
+  // ---- per slab, tile-independent epilogue inputs ----
+  float rs[RT];                                   // PRO_POST: 1 / rms of this thread's row
+  int e_pos[RT];
+  size_t e_kvbase[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) { rs[rt] = 1.0f; e_pos[rt] = -1; e_kvbase[rt] = 0; }
+  if (epi_thread) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int rc = min(rt, nrt - 1), row16 = er[rt] - rc * 16;
+      if (PRO == PRO_POST) {
+        const float* ss = a.ss_in + (size_t)rc * a.ss_stride;
+        float q = 0.0f;
+        for (int p = e_f; p < a.n_part; p += 16) q += ss[p * 16 + row16];
+        q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+        q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+        rs[rt] = 1.0f / sqrtf(q / (float)a.K + a.eps);
+      }
+      if (EPI == EPI_QKV) {
+        e_pos[rt] = eok[rt] ? a.row_pos[er[rt]] : -1;
+        const int pc = max(e_pos[rt], 0);
+        const int pt0 = (a.row_seq != nullptr) ? a.row_seq[er[rt]] * a.pt_stride : 0;
+        const int page = a.page_table[pt0 + pc / a.page_size], slot = pc % a.page_size;
+        e_kvbase[rt] = (size_t)page * 2 * a.n_kv_heads * a.page_size * a.d_head + (size_t)slot * a.d_head;
+      }
+    }
+  }
+
+  float pre_bias = 0.0f, pre_gain = 0.0f;
+  float pre_res[RT], pre_cos[RT], pre_sin[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) { pre_res[rt] = 0.0f; pre_cos[rt] = 1.0f; pre_sin[rt] = 0.0f; }
+  auto prefetch_epilogue = [&](int ti) {
+    if (!epi_thread) return;
+    const int n = ((int)blockIdx.x + ti * (int)gridDim.x) * 16 + e_f;
+    if (a.bias != nullptr) pre_bias = Store<T>::ld(static_cast<const T*>(a.bias) + n);
+    if (EPI == EPI_RESID) {
+      if (a.xg_out != nullptr) pre_gain = Store<T>::ld(static_cast<const T*>(a.gain_next) + n);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) pre_res[rt] = static_cast<const float*>(a.out)[(size_t)er[rt] * a.ldo + n];
+    }
+    if (EPI == EPI_QKV && a.rope != nullptr) {
+      const int nn = (n < a.nq) ? n : (n < a.nq + a.nkv ? n - a.nq : n - a.nq - a.nkv);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const float* cs = a.rope + ((size_t)max(e_pos[rt], 0) * (a.d_head >> 1) + ((nn % a.d_head) >> 1)) * 2;
+        pre_cos[rt] = cs[0]; pre_sin[rt] = cs[1];
+      }
+    }
+  };
+
+  f32x4 acc[ND][RT];
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) acc[d][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  int phase = 0;                                   // which half of `part` the next slab uses
+  auto finish_tile = [&](int ti) {
+    const int tile = (int)blockIdx.x + ti * (int)gridDim.x;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      if (rt < nrt) {                                // uniform over the workgroup
+        float* pt = part + (phase & 1) * S * ND * 256;
+        phase ^= 1;
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) pt[(wave * ND + d) * 256 + j * 16 + kq * 4 + r] = acc[d][rt][r];
+        }
+        __syncthreads();
+        if (epi_thread) {
+          const int t = tid, f = e_f, n = tile * 16 + f, row = rt * 16 + e_row;
+          float y[ND];
+#pragma unroll
+          for (int d = 0; d < ND; ++d) {
+            float s1 = 0.0f;
+            for (int w = 0; w < S; ++w) s1 += pt[(w * ND + d) * 256 + t];
+            y[d] = s1;
+          }
+          if (PRO == PRO_POST) {
+#pragma unroll
+            for (int d = 0; d < ND; ++d) y[d] *= rs[rt];
+          }
+          y[0] += pre_bias;
+          if (EPI == EPI_QKV) {
+            ybuf[t] = y[0];
+          } else if (EPI == EPI_RESID) {
+            float xn = 0.0f;
+            if (eok[rt]) {
+              xn = pre_res[rt] + y[0];
+              static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = xn;
+              if (a.xg_out != nullptr) Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * pre_gain);
+            }
+            if (a.ss_out != nullptr) {
+              float q = xn * xn;
+              q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+              q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+              if (f == 0) a.ss_out[(size_t)rt * a.ss_stride + tile * 16 + e_row] = q;
+            }
+          } else if (eok[rt]) {
+            if (EPI == EPI_STORE) {
+              Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
+            } else if (EPI == EPI_ACT) {
+              Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, gelu_tanh(y[0]));
+            } else if (EPI == EPI_GATED) {
+              const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
+              Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[ND - 1]);
+            } else if (EPI == EPI_LOGITS) {
+              const int orow = (a.out_row != nullptr) ? a.out_row[row] : row;
+              if (orow >= 0) static_cast<float*>(a.out)[(size_t)orow * a.ldo + n] = a.scale * y[0];
+            }
+          }
+        }
+        if (EPI == EPI_QKV) {
+          __syncthreads();
+          if (epi_thread && eok[rt]) {
+            const int t = tid, n = tile * 16 + e_f, row = rt * 16 + e_row;
+            float y = ybuf[t];
+            const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
+            const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
+            const int head = nn / a.d_head, d = nn % a.d_head;
+            if (a.rope != nullptr && (is_q || is_k) && e_pos[rt] >= 0) {
+              const float other = ybuf[t ^ 1];
+              y = (d & 1) ? (other * pre_sin[rt] + y * pre_cos[rt]) : (y * pre_cos[rt] - other * pre_sin[rt]);
+            }
+            if (is_q) {
+              Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
+            } else if (e_pos[rt] >= 0) {
+              const size_t idx = e_kvbase[rt] + ((size_t)(is_k ? 0 : 1) * a.n_kv_heads + head) * a.page_size * a.d_head + d;
+              Store<T>::st(static_cast<T*>(a.kv_pool) + idx, y);
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int d = 0; d < ND; ++d)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) acc[d][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  };
+
+  auto compute_chunk = [&](const Buf& b, int g) {
+    const int ti = g / nchunks, c = g - ti * nchunks;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool kvalid = (ks0 + c * U + u < ks1);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const Frag fb = (PRO == PRO_LN) ? b.fb[rt][u] : Mma<T>::select(kvalid && jok[rt], b.fb[rt][u]);
+        acc[0][rt] = Mma<T>::mma(b.fa[0][u], fb, acc[0][rt]);
+        if (ND == 2) acc[ND - 1][rt] = Mma<T>::mma(b.fa[ND - 1][u], fb, acc[ND - 1][rt]);
+      }
+    }
+    if (c == nchunks - 1) finish_tile(ti);
+  };
+  auto before_prefetch = [&](int g) {
+    const int ti = g / nchunks;
+    if (g - ti * nchunks == nchunks - 1) prefetch_epilogue(ti);
+  };
+
   for (int g = 0; g < G; g += 2) {
     before_prefetch(g);
     if (g + 1 < G) load_chunk(b1, g + 1);

@@ -20,8 +20,11 @@ enum {
 // For RMSNorm models the kernel also writes xg = x * gain of the first norm in
 // the storage type and the row's sum of squares (one partial: ss[0][r]).
 // Several sequences: the launch covers sequences seq0, seq0+1, ... with rps rows
-// each (row r belongs to sequence seq0 + r / rps); `st` is the array of sequence
-// states.  row_seq[r] (when given) receives the row's sequence, logit_row[r] the
+// each; they are laid out in slabs of MAX_ROWS rows holding spg whole sequences, so
+// workgroup b (sequence seq0 + b / rps) writes row (b / rps / spg) * MAX_ROWS +
+// (b / rps % spg) * rps + b % rps of x / xg / row_pos / ..., and the sum of squares of
+// its row into the slab's block of ss (ss_stride floats per slab); `st` is the array
+// of sequence states.  row_seq[r] (when given) receives the row's sequence, logit_row[r] the
 // row of the logits buffer its LM-head output belongs in (< 0: not needed):
 // p rows [seq][gamma+1], q rows [seq][gamma], one row per sequence for plain decoding.
 template <typename T>
@@ -30,10 +33,12 @@ static __global__ __launch_bounds__(256) void embed_kernel(
     const T* __restrict__ tok_emb, const T* __restrict__ pos_emb, int d, int vocab,
     float* __restrict__ x, int* __restrict__ row_pos, const T* __restrict__ gain_next,
     T* __restrict__ xg, float* __restrict__ ss,
-    int rps, int seq0, int gamma, int* __restrict__ row_seq, int* __restrict__ logit_row) {
+    int rps, int seq0, int gamma, int* __restrict__ row_seq, int* __restrict__ logit_row,
+    int spg, int ss_stride) {
   __shared__ float red[16];
-  const int r = blockIdx.x;
-  const int j = r % rps, seq = seq0 + r / rps;
+  const int j = (int)blockIdx.x % rps, sl = (int)blockIdx.x / rps, seq = seq0 + sl;
+  const int slab = sl / spg, r16 = (sl % spg) * rps + j;     // row within its slab
+  const int r = slab * MAX_ROWS + r16;
   st += seq;
   int tok, pos, lrow = -1;
   switch (mode) {
@@ -81,7 +86,7 @@ static __global__ __launch_bounds__(256) void embed_kernel(
   }
   if (ss) {
     q = block_reduce(q, red, OpSumF(), 0.0f);
-    if (threadIdx.x == 0) ss[r] = q;
+    if (threadIdx.x == 0) ss[(size_t)slab * ss_stride + r16] = q;
   }
 }
 

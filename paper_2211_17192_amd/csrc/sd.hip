@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <map>
 #include <new>
 #include <string>
@@ -241,6 +242,30 @@ void launch_gemm_t(hipStream_t s, GemmArgs a) {
   hipLaunchKernelGGL((gemm_kernel<T, PRO, EPI>), dim3(grid), dim3(64 * S), lds, s, a);
 }
 
+// Several 16-row slabs in one launch (a.nrt of them, set by the caller).
+template <typename T, int PRO, int EPI>
+void launch_gemm_wide_t(hipStream_t s, GemmArgs a) {
+  const int tiles = a.N / 16, KS = a.K / 32;
+  const int S = pick_waves(KS);                  // the same K split as the one-slab kernel: same sums
+  a.ksteps_per_wave = (KS + S - 1) / S;
+  const int ND = (EPI == EPI_GATED) ? 2 : 1;
+  const size_t lds = (size_t)(2 * S * ND * 256 + S * 16 + 256) * sizeof(float);
+  const int capacity = g_num_cus * std::max(1, 8 / S);
+  const int per_wg = (tiles + capacity - 1) / capacity;
+  const int grid = (tiles + per_wg - 1) / per_wg;
+  hipLaunchKernelGGL((gemm_wide_kernel<T, PRO, EPI>), dim3(grid), dim3(64 * S), lds, s, a);
+}
+
+template <typename T>
+void launch_gemm_wide(hipStream_t s, int pro, int epi, const GemmArgs& a) {
+#define SD_CASE(P, E) if (pro == P && epi == E) return launch_gemm_wide_t<T, P, E>(s, a)
+  SD_CASE(PRO_LN, EPI_QKV); SD_CASE(PRO_POST, EPI_QKV);
+  SD_CASE(PRO_NONE, EPI_RESID);
+  SD_CASE(PRO_LN, EPI_ACT); SD_CASE(PRO_POST, EPI_GATED);
+  SD_CASE(PRO_LN, EPI_LOGITS); SD_CASE(PRO_POST, EPI_LOGITS);
+#undef SD_CASE
+}
+
 template <typename T>
 void launch_gemm(hipStream_t s, int pro, int epi, const GemmArgs& a) {
 #define SD_CASE(P, E) if (pro == P && epi == E) return launch_gemm_t<T, P, E>(s, a)
@@ -319,14 +344,35 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
     q.row_pos = m.row_pos + off; q.row_seq = m.row_seq + off; q.logit_row = m.logit_row + off;
     return q;
   };
-  for (int g = 0; g < n_groups; ++g) {
-    const Grp q = group(g);
-    hipLaunchKernelGGL((embed_kernel<T>), dim3(q.R), dim3(256), 0, s, rw.mode, rw.step, c->d_state, m.prompt, rw.start,
-                       static_cast<const T*>(m.tok_emb), static_cast<const T*>(m.pos_emb), d, f.vocab, q.x,
+  {
+    const Grp q = group(0);                         // one launch: the kernel places each row in its slab
+    hipLaunchKernelGGL((embed_kernel<T>), dim3(rw.nseq * rw.rps), dim3(256), 0, s, rw.mode, rw.step, c->d_state, m.prompt,
+                       rw.start, static_cast<const T*>(m.tok_emb), static_cast<const T*>(m.pos_emb), d, f.vocab, q.x,
                        q.row_pos, static_cast<const T*>(rms ? m.L[0].ln1g : nullptr),
                        reinterpret_cast<T*>(rms ? q.xg : nullptr), rms ? q.ss : nullptr,
-                       rw.rps, q.seq0, rw.gamma, q.row_seq, q.logit_row);
+                       rw.rps, rw.seq0, rw.gamma, q.row_seq, q.logit_row, spg, (d / 16) * 16);
   }
+  // One GEMM over every group: groups are 16-row slabs one after the other in all row-indexed
+  // buffers, so up to GEMM_WIDE_RT of them go into one launch of the wide kernel (weights
+  // streamed once for all of them); a single group takes the one-slab kernel.
+  const int R_full = spg * rw.rps, R_tail = (rw.nseq - (n_groups - 1) * spg) * rw.rps;
+  auto gemm_groups = [&](int pro_, int epi_, const std::function<void(GemmArgs&, const Grp&)>& fill) {
+    if (n_groups == 1) {
+      GemmArgs a{};
+      fill(a, group(0));
+      launch_gemm<T>(s, pro_, epi_, a);
+      return;
+    }
+    for (int g0 = 0; g0 < n_groups; g0 += GEMM_WIDE_RT) {
+      GemmArgs a{};
+      fill(a, group(g0));
+      a.nrt = std::min(GEMM_WIDE_RT, n_groups - g0);
+      a.R = R_full;
+      a.R_last = (g0 + a.nrt == n_groups) ? R_tail : R_full;
+      a.ss_stride = (d / 16) * 16;
+      launch_gemm_wide<T>(s, pro_, epi_, a);
+    }
+  };
   int n_part = 1;                                   // partial sums of x^2 the next norm has to add
   // input of a normed GEMM: LayerNorm reads the fp32 rows, RMSNorm the pre-scaled rows + partials
   auto normed = [&](GemmArgs& a, const Grp& q, const void* gain, const void* beta) {
@@ -337,40 +383,34 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
   };
   // residual add that also prepares the input of the next norm
   auto resid = [&](const void* W, bool from_ffn, const void* bias, int K, const void* gain_next) {
-    for (int g = 0; g < n_groups; ++g) {
-      const Grp q = group(g);
-      GemmArgs o{};
+    gemm_groups(PRO_NONE, EPI_RESID, [&](GemmArgs& o, const Grp& q) {
       o.R = q.R; o.W = W; o.X = from_ffn ? q.ffn : q.attn; o.bias = bias; o.K = K; o.N = d; o.out = q.x; o.ldo = d;
       if (rms) { o.xg_out = q.xg; o.gain_next = gain_next; o.ss_out = q.ss; }
-      launch_gemm<T>(s, PRO_NONE, EPI_RESID, o);
-    }
+    });
     n_part = d / 16;
   };
   for (int li = 0; li < n_layers; ++li) {
     const LayerW& l = m.L[li];
     // q, k, v projections (+ rotary) with k, v appended to the cache
-    for (int g = 0; g < n_groups; ++g) {
-      const Grp q = group(g);
-      GemmArgs a{};
+    gemm_groups(pro, EPI_QKV, [&](GemmArgs& a, const Grp& q) {
       normed(a, q, l.ln1g, l.ln1b);
       a.W = l.wqkv; a.bias = l.bqkv; a.K = d; a.N = m.nq + 2 * m.nkv;
       a.q_out = q.qbuf; a.nq = m.nq; a.nkv = m.nkv; a.kv_pool = l.kv; a.page_table = m.page_table;
       a.page_size = m.page_size; a.n_kv_heads = f.n_kv_heads; a.d_head = f.d_head; a.row_pos = q.row_pos;
       a.rope = m.rope;
       if (m.batch > 1) { a.row_seq = q.row_seq; a.pt_stride = m.n_pages; }
-      launch_gemm<T>(s, pro, EPI_QKV, a);
-    }
+    });
     auto attention = [&](bool cross) {
-      for (int g = 0; g < n_groups; ++g) {
-        const Grp q = group(g);
+      {
+        const Grp q = group(0);                     // one launch over all sequences (grid.z)
         AttnArgs a{};
         a.q = q.qbuf; a.out = q.attn; a.kv_pool = l.kv; a.page_table = m.page_table; a.page_size = m.page_size; a.n_pages = m.n_pages;
         a.row_pos = q.row_pos; a.R = rw.rps; a.H = f.n_heads; a.Hkv = f.n_kv_heads; a.cross = 0; a.kv_len = 0;
         a.scale = (f.arch == SD_ARCH_T5DEC) ? 1.0f : 1.0f / sqrtf((float)f.d_head);
         a.rel_bias = m.rel_bias; a.bucket_lut = m.bucket_lut; a.rel_buckets = f.rel_buckets;
-        a.seq0 = q.seq0; a.pt_stride = m.n_pages;
+        a.seq0 = rw.seq0; a.pt_stride = m.n_pages; a.spg = spg;
         if (cross) { a.cross = 1; a.ck = l.cross_k; a.cv = l.cross_v; a.kv_len = f.enc_len; a.scale = 1.0f; a.rel_bias = nullptr; }
-        launch_attn<T>(s, m, a, q.ns);
+        launch_attn<T>(s, m, a, rw.nseq);
       }
     };
     attention(false);
@@ -386,33 +426,26 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       attention(true);
       resid(l.co, false, nullptr, m.nq, l.ln2g);
     }
-    for (int g = 0; g < n_groups; ++g) {
-      const Grp q = group(g);
-      GemmArgs h{};
-      normed(h, q, l.ln2g, l.ln2b);
-      h.K = d; h.N = f.d_ff; h.out = q.ffn; h.ldo = f.d_ff; h.W = l.w1;
-      if (f.arch == SD_ARCH_GPT) {
-        h.bias = l.b1;
-        launch_gemm<T>(s, PRO_LN, EPI_ACT, h);
-      } else {
-        h.W2 = l.wu; h.act = (f.arch == SD_ARCH_T5DEC) ? ACT_GELU : ACT_SILU;
-        const bool timed = c->time_ffn && &m == &c->p && g == 0 && 2 * li + 1 < (int)c->kev.size();
-        if (timed) hipEventRecord(c->kev[2 * li], s);
-        launch_gemm<T>(s, PRO_POST, EPI_GATED, h);
-        if (timed) hipEventRecord(c->kev[2 * li + 1], s);
-      }
+    {
+      const bool gpt = (f.arch == SD_ARCH_GPT);
+      const bool timed = !gpt && c->time_ffn && &m == &c->p && 2 * li + 1 < (int)c->kev.size();
+      if (timed) hipEventRecord(c->kev[2 * li], s);
+      gemm_groups(gpt ? PRO_LN : PRO_POST, gpt ? EPI_ACT : EPI_GATED, [&](GemmArgs& h, const Grp& q) {
+        normed(h, q, l.ln2g, l.ln2b);
+        h.K = d; h.N = f.d_ff; h.out = q.ffn; h.ldo = f.d_ff; h.W = l.w1;
+        if (gpt) h.bias = l.b1;
+        else { h.W2 = l.wu; h.act = (f.arch == SD_ARCH_T5DEC) ? ACT_GELU : ACT_SILU; }
+      });
+      if (timed) hipEventRecord(c->kev[2 * li + 1], s);
     }
     resid(l.w2, true, l.b2, f.d_ff, (li + 1 < n_layers) ? m.L[li + 1].ln1g : m.lnfg);
   }
   if (logits != nullptr) {
-    for (int g = 0; g < n_groups; ++g) {
-      const Grp q = group(g);
-      GemmArgs a{};
+    gemm_groups(pro, EPI_LOGITS, [&](GemmArgs& a, const Grp& q) {
       normed(a, q, m.lnfg, m.lnfb);
       a.W = m.head; a.K = d; a.N = f.vocab; a.out = logits; a.ldo = f.vocab; a.scale = f.logit_scale;
       a.out_row = q.logit_row;
-      launch_gemm<T>(s, pro, EPI_LOGITS, a);
-    }
+    });
   }
 }
 
