@@ -410,12 +410,18 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 // ---------------------------------------------------------------------------
 constexpr int GEMM_WIDE_RT = 6;
 constexpr int GEMM_WIDE_U = 2;
+constexpr int GEMM_WIDE_ES = GEMM_WIDE_RT / 2;      // slabs per epilogue thread (512 threads, 256 outputs per slab)
+
+// LDS of the wide kernel: the partial tiles of every wavefront and slab, and the QKV staging rows.
+__host__ __device__ constexpr size_t gemm_wide_lds_bytes(int S, int ND) {
+  return (size_t)(S * ND * GEMM_WIDE_RT * 256 + GEMM_WIDE_RT * 256 + S * 16 + GEMM_WIDE_RT * 16 * 4) * sizeof(float);
+}
 
 template <typename T, int PRO, int EPI>
 static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a) {
   extern __shared__ float lds[];
   constexpr int ND = (EPI == EPI_GATED) ? 2 : 1;
-  constexpr int U = GEMM_WIDE_U, RT = GEMM_WIDE_RT;
+  constexpr int U = GEMM_WIDE_U, RT = GEMM_WIDE_RT, ES = GEMM_WIDE_ES;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, S = blockDim.x >> 6;
   const int j = lane & 15, kq = lane >> 4;
   const int KS = a.K >> 5;
@@ -423,25 +429,28 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
   const int nchunks = (a.ksteps_per_wave + U - 1) / U;
   const int ntiles = a.N >> 4;
   const int my_tiles = (ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
-  float* part = lds;                                 // [2][S][ND][256], alternating per (tile, slab)
-  float* stat = lds + 2 * S * ND * 256;              // [S][16]
-  float* ybuf = stat + S * 16;                       // [256]
-  const bool epi_thread = tid < 256;
-  const int e_row = (tid >> 4) & 15, e_f = tid & 15;
+  float* part = lds;                                 // [S][ND][RT][256]
+  float* ybuf = part + S * ND * RT * 256;            // [RT][256]
+  float* stat = ybuf + RT * 256;                     // [S][16]
+  float* rs_s = stat + S * 16;                       // [RT * 16] 1 / rms of every row (PRO_POST)
+  int* pos_s = reinterpret_cast<int*>(rs_s + RT * 16);          // [RT * 16] position of every row (EPI_QKV)
+  unsigned long long* kvb_s = reinterpret_cast<unsigned long long*>(pos_s + RT * 16);   // [RT * 16] cache offset
   const int nrt = a.nrt;
   auto slab_rows = [&](int rt) { return (rt == nrt - 1) ? a.R_last : a.R; };
 
-  // per slab: clamped row of this lane (B side) and of this thread (epilogue side)
-  int jr[RT], er[RT];
-  bool jok[RT], eok[RT];
+  // B side: clamped row of this lane in every slab
+  int jr[RT];
+  bool jok[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     const int rc = min(rt, nrt - 1), rows = slab_rows(rc);
     jr[rt] = rc * 16 + min(j, rows - 1);
-    er[rt] = rc * 16 + min(e_row, rows - 1);
     jok[rt] = (rt < nrt) && (j < rows);
-    eok[rt] = (rt < nrt) && (e_row < rows);
   }
+  // Epilogue side: thread t owns output e = t % 256 (row e / 16, feature e % 16) of the slabs
+  // t / 256, t / 256 + blockDim / 256, ...
+  const int e_row = (tid >> 4) & 15, e_f = tid & 15, e_idx = tid & 255;
+  const int es_step = (int)blockDim.x >> 8, es0 = tid >> 8;          // 1 or 2; 0 or 1
 
   // ---- PRO_LN: statistics of the fp32 rows, slab by slab ----
   float mu[RT], rstd[RT];
@@ -478,12 +487,16 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
       for (int w = 0; w < S; ++w) t2 += stat[w * 16 + j];
       rstd[rt] = 1.0f / sqrtf(t2 / (float)a.K + a.eps);
     }
-    __syncthreads();
   }
 
   typedef typename Mma<T>::Frag Frag;
-  struct Buf { Frag fa[ND][U]; Frag fb[RT][U]; };
-
+  // A ring of U k-step slots: slot s holds the weight fragment(s) and the activation fragments of
+  // all slabs of one k-step.  Step q of this wavefront's work list is k-step ks0 + q % kpw of tile
+  // blockIdx.x + (q / kpw) * gridDim.x (kpw = k-steps per wavefront, padded steps are masked).
+  // Right after a slot is multiplied it is refilled with step q + U, so U k-steps of loads stay
+  // in flight across tile boundaries and epilogues.  All loads are unconditional (clamped
+  // addresses): a branch around a load would make the compiler drain the ring.
+  struct Slot { Frag fa[ND]; Frag fb[RT]; };
   auto make_b = [&](int ks, bool valid, int rt) -> Frag {
     const int k = ks * 32 + kq * 8;
     if (PRO != PRO_LN) {
@@ -499,76 +512,59 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
     }
   };
 
+
   const int ks_last = max(ks1 - 1, 0);
-  auto load_chunk = [&](Buf& b, int g) {
-    const int ti = g / nchunks, c = g - ti * nchunks;
+  const int kpw = a.ksteps_per_wave;
+  const int Q = my_tiles * kpw;                      // steps of this wavefront (the same for all)
+  auto load_step = [&](Slot& sl, int q) {
+    const int qc = min(q, max(Q - 1, 0));            // past the end: re-read the last step, never used
+    const int ti = qc / kpw, kk = qc - ti * kpw;
     const size_t tile = (size_t)blockIdx.x + (size_t)ti * gridDim.x;
-    const T* w0 = static_cast<const T*>(a.W) + (tile * KS) * 512 + lane * 8;
-    const T* w1 = (ND == 2) ? static_cast<const T*>(a.W2) + (tile * KS) * 512 + lane * 8 : nullptr;
+    const int ks = ks0 + kk, ksc = min(ks, ks_last);
+    sl.fa[0] = Mma<T>::load_stream(static_cast<const T*>(a.W) + (tile * KS + ksc) * 512 + lane * 8);
+    if (ND == 2) sl.fa[ND - 1] = Mma<T>::load_stream(static_cast<const T*>(a.W2) + (tile * KS + ksc) * 512 + lane * 8);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int ks = ks0 + c * U + u;
-      const int ksc = min(ks, ks_last);
-      b.fa[0][u] = Mma<T>::load_stream(w0 + (size_t)ksc * 512);
-      if (ND == 2) b.fa[ND - 1][u] = Mma<T>::load_stream(w1 + (size_t)ksc * 512);
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) b.fb[rt][u] = make_b(ksc, ks < ks1, rt);
-    }
+    for (int rt = 0; rt < RT; ++rt) sl.fb[rt] = make_b(ksc, ks < ks1, rt);
   };
 
-  const int G = my_tiles * nchunks;
-  Buf b0, b1;
-  if (G > 0) load_chunk(b0, 0);
+  Slot ring[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) load_step(ring[u], u);
 
-  // ---- per slab, tile-independent epilogue inputs ----
-  float rs[RT];                                   // PRO_POST: 1 / rms of this thread's row
-  int e_pos[RT];
-  size_t e_kvbase[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) { rs[rt] = 1.0f; e_pos[rt] = -1; e_kvbase[rt] = 0; }
-  if (epi_thread) {
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      const int rc = min(rt, nrt - 1), row16 = er[rt] - rc * 16;
-      if (PRO == PRO_POST) {
-        const float* ss = a.ss_in + (size_t)rc * a.ss_stride;
-        float q = 0.0f;
-        for (int p = e_f; p < a.n_part; p += 16) q += ss[p * 16 + row16];
-        q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
-        q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
-        rs[rt] = 1.0f / sqrtf(q / (float)a.K + a.eps);
-      }
-      if (EPI == EPI_QKV) {
-        e_pos[rt] = eok[rt] ? a.row_pos[er[rt]] : -1;
-        const int pc = max(e_pos[rt], 0);
-        const int pt0 = (a.row_seq != nullptr) ? a.row_seq[er[rt]] * a.pt_stride : 0;
-        const int page = a.page_table[pt0 + pc / a.page_size], slot = pc % a.page_size;
-        e_kvbase[rt] = (size_t)page * 2 * a.n_kv_heads * a.page_size * a.d_head + (size_t)slot * a.d_head;
-      }
+  // ---- per row, tile-independent epilogue inputs, kept in LDS ----
+  for (int r = tid >> 4; r < nrt * 16; r += (int)blockDim.x >> 4) {      // 16 lanes per row
+    const int rt = r >> 4, r16 = r & 15, rows = slab_rows(rt);
+    const int rc = rt * 16 + min(r16, rows - 1);                         // clamped: loads stay in bounds
+    if (PRO == PRO_POST) {
+      const float* ss = a.ss_in + (size_t)rt * a.ss_stride;
+      float q = 0.0f;
+      for (int p = e_f; p < a.n_part; p += 16) q += ss[p * 16 + (rc & 15)];
+      q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+      q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+      if (e_f == 0) rs_s[r] = 1.0f / sqrtf(q / (float)a.K + a.eps);
+    }
+    if (EPI == EPI_QKV && e_f == 0) {
+      const int pos = (r16 < rows) ? a.row_pos[rc] : -1;
+      const int pc = max(pos, 0);
+      const int pt0 = (a.row_seq != nullptr) ? a.row_seq[rc] * a.pt_stride : 0;
+      const int page = a.page_table[pt0 + pc / a.page_size], slot = pc % a.page_size;
+      pos_s[r] = pos;
+      kvb_s[r] = (unsigned long long)page * 2 * a.n_kv_heads * a.page_size * a.d_head + (unsigned long long)slot * a.d_head;
     }
   }
+  // (the first barrier of finish_tile orders these writes before their use)
 
+  // bias / gain of this thread's output feature in the tile being worked on: fetched at every
+  // step, without branches (absent vectors read the weights and are masked)
   float pre_bias = 0.0f, pre_gain = 0.0f;
-  float pre_res[RT], pre_cos[RT], pre_sin[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) { pre_res[rt] = 0.0f; pre_cos[rt] = 1.0f; pre_sin[rt] = 0.0f; }
+  const bool has_bias = a.bias != nullptr, has_gain = (EPI == EPI_RESID) && a.xg_out != nullptr;
+  const T* bias_p = has_bias ? static_cast<const T*>(a.bias) : static_cast<const T*>(a.W);
+  const T* gain_p = has_gain ? static_cast<const T*>(a.gain_next) : static_cast<const T*>(a.W);
   auto prefetch_epilogue = [&](int ti) {
-    if (!epi_thread) return;
     const int n = ((int)blockIdx.x + ti * (int)gridDim.x) * 16 + e_f;
-    if (a.bias != nullptr) pre_bias = Store<T>::ld(static_cast<const T*>(a.bias) + n);
-    if (EPI == EPI_RESID) {
-      if (a.xg_out != nullptr) pre_gain = Store<T>::ld(static_cast<const T*>(a.gain_next) + n);
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) pre_res[rt] = static_cast<const float*>(a.out)[(size_t)er[rt] * a.ldo + n];
-    }
-    if (EPI == EPI_QKV && a.rope != nullptr) {
-      const int nn = (n < a.nq) ? n : (n < a.nq + a.nkv ? n - a.nq : n - a.nq - a.nkv);
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        const float* cs = a.rope + ((size_t)max(e_pos[rt], 0) * (a.d_head >> 1) + ((nn % a.d_head) >> 1)) * 2;
-        pre_cos[rt] = cs[0]; pre_sin[rt] = cs[1];
-      }
-    }
+    const float b = Store<T>::ld(bias_p + n), g = Store<T>::ld(gain_p + n);
+    pre_bias = has_bias ? b : 0.0f;
+    pre_gain = has_gain ? g : 0.0f;
   };
 
   f32x4 acc[ND][RT];
@@ -577,118 +573,108 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) acc[d][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  int phase = 0;                                   // which half of `part` the next slab uses
+  // One barrier before the partial tiles are written (the previous tile's epilogue has read
+  // them), one after; every thread then finishes its outputs of its slabs.
   auto finish_tile = [&](int ti) {
     const int tile = (int)blockIdx.x + ti * (int)gridDim.x;
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      if (rt < nrt) {                                // uniform over the workgroup
-        float* pt = part + (phase & 1) * S * ND * 256;
-        phase ^= 1;
-#pragma unroll
-        for (int d = 0; d < ND; ++d) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) pt[(wave * ND + d) * 256 + j * 16 + kq * 4 + r] = acc[d][rt][r];
-        }
-        __syncthreads();
-        if (epi_thread) {
-          const int t = tid, f = e_f, n = tile * 16 + f, row = rt * 16 + e_row;
-          float y[ND];
-#pragma unroll
-          for (int d = 0; d < ND; ++d) {
-            float s1 = 0.0f;
-            for (int w = 0; w < S; ++w) s1 += pt[(w * ND + d) * 256 + t];
-            y[d] = s1;
-          }
-          if (PRO == PRO_POST) {
-#pragma unroll
-            for (int d = 0; d < ND; ++d) y[d] *= rs[rt];
-          }
-          y[0] += pre_bias;
-          if (EPI == EPI_QKV) {
-            ybuf[t] = y[0];
-          } else if (EPI == EPI_RESID) {
-            float xn = 0.0f;
-            if (eok[rt]) {
-              xn = pre_res[rt] + y[0];
-              static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = xn;
-              if (a.xg_out != nullptr) Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * pre_gain);
-            }
-            if (a.ss_out != nullptr) {
-              float q = xn * xn;
-              q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
-              q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
-              if (f == 0) a.ss_out[(size_t)rt * a.ss_stride + tile * 16 + e_row] = q;
-            }
-          } else if (eok[rt]) {
-            if (EPI == EPI_STORE) {
-              Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
-            } else if (EPI == EPI_ACT) {
-              Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, gelu_tanh(y[0]));
-            } else if (EPI == EPI_GATED) {
-              const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
-              Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[ND - 1]);
-            } else if (EPI == EPI_LOGITS) {
-              const int orow = (a.out_row != nullptr) ? a.out_row[row] : row;
-              if (orow >= 0) static_cast<float*>(a.out)[(size_t)orow * a.ldo + n] = a.scale * y[0];
-            }
-          }
-        }
-        if (EPI == EPI_QKV) {
-          __syncthreads();
-          if (epi_thread && eok[rt]) {
-            const int t = tid, n = tile * 16 + e_f, row = rt * 16 + e_row;
-            float y = ybuf[t];
-            const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
-            const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
-            const int head = nn / a.d_head, d = nn % a.d_head;
-            if (a.rope != nullptr && (is_q || is_k) && e_pos[rt] >= 0) {
-              const float other = ybuf[t ^ 1];
-              y = (d & 1) ? (other * pre_sin[rt] + y * pre_cos[rt]) : (y * pre_cos[rt] - other * pre_sin[rt]);
-            }
-            if (is_q) {
-              Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
-            } else if (e_pos[rt] >= 0) {
-              const size_t idx = e_kvbase[rt] + ((size_t)(is_k ? 0 : 1) * a.n_kv_heads + head) * a.page_size * a.d_head + d;
-              Store<T>::st(static_cast<T*>(a.kv_pool) + idx, y);
-            }
-          }
-        }
-      }
-    }
+    __syncthreads();
 #pragma unroll
     for (int d = 0; d < ND; ++d)
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) acc[d][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  };
-
-  auto compute_chunk = [&](const Buf& b, int g) {
-    const int ti = g / nchunks, c = g - ti * nchunks;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const bool kvalid = (ks0 + c * U + u < ks1);
-#pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        const Frag fb = (PRO == PRO_LN) ? b.fb[rt][u] : Mma<T>::select(kvalid && jok[rt], b.fb[rt][u]);
-        acc[0][rt] = Mma<T>::mma(b.fa[0][u], fb, acc[0][rt]);
-        if (ND == 2) acc[ND - 1][rt] = Mma<T>::mma(b.fa[ND - 1][u], fb, acc[ND - 1][rt]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[((wave * ND + d) * RT + rt) * 256 + j * 16 + kq * 4 + r] = acc[d][rt][r];
+        acc[d][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    __syncthreads();
+    const int f = e_f, n = tile * 16 + f;
+    for (int rt = es0; rt < nrt; rt += es_step) {
+      const int row = rt * 16 + e_row;
+      const bool ok = e_row < slab_rows(rt);
+      float y[ND];
+#pragma unroll
+      for (int d = 0; d < ND; ++d) {
+        float s1 = 0.0f;
+        for (int w = 0; w < S; ++w) s1 += part[((w * ND + d) * RT + rt) * 256 + e_idx];
+        y[d] = s1;
+      }
+      if (PRO == PRO_POST) {
+        const float r1 = rs_s[row];
+#pragma unroll
+        for (int d = 0; d < ND; ++d) y[d] *= r1;
+      }
+      y[0] += pre_bias;
+      if (EPI == EPI_QKV) {
+        ybuf[rt * 256 + e_idx] = y[0];
+      } else if (EPI == EPI_RESID) {
+        float xn = 0.0f;
+        if (ok) {
+          xn = static_cast<const float*>(a.out)[(size_t)row * a.ldo + n] + y[0];
+          static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = xn;
+          if (a.xg_out != nullptr) Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * pre_gain);
+        }
+        if (a.ss_out != nullptr) {
+          float q = xn * xn;
+          q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+          q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+          if (f == 0) a.ss_out[(size_t)rt * a.ss_stride + tile * 16 + e_row] = q;
+        }
+      } else if (ok) {
+        if (EPI == EPI_STORE) {
+          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
+        } else if (EPI == EPI_ACT) {
+          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, gelu_tanh(y[0]));
+        } else if (EPI == EPI_GATED) {
+          const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
+          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[ND - 1]);
+        } else if (EPI == EPI_LOGITS) {
+          const int orow = (a.out_row != nullptr) ? a.out_row[row] : row;
+          if (orow >= 0) static_cast<float*>(a.out)[(size_t)orow * a.ldo + n] = a.scale * y[0];
+        }
       }
     }
-    if (c == nchunks - 1) finish_tile(ti);
-  };
-  auto before_prefetch = [&](int g) {
-    const int ti = g / nchunks;
-    if (g - ti * nchunks == nchunks - 1) prefetch_epilogue(ti);
+    if (EPI == EPI_QKV) {
+      __syncthreads();
+      const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
+      const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
+      const int head = nn / a.d_head, d = nn % a.d_head;
+      for (int rt = es0; rt < nrt; rt += es_step) {
+        const int row = rt * 16 + e_row;
+        if (e_row < slab_rows(rt)) {
+          const int pos = pos_s[row];
+          float y = ybuf[rt * 256 + e_idx];
+          if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
+            const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
+            const float other = ybuf[rt * 256 + (e_idx ^ 1)];
+            y = (d & 1) ? (other * cs[1] + y * cs[0]) : (y * cs[0] - other * cs[1]);
+          }
+          if (is_q) {
+            Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
+          } else if (pos >= 0) {
+            const size_t idx = (size_t)kvb_s[row] + ((size_t)(is_k ? 0 : 1) * a.n_kv_heads + head) * a.page_size * a.d_head + d;
+            Store<T>::st(static_cast<T*>(a.kv_pool) + idx, y);
+          }
+        }
+      }
+    }
   };
 
-  for (int g = 0; g < G; g += 2) {
-    before_prefetch(g);
-    if (g + 1 < G) load_chunk(b1, g + 1);
-    compute_chunk(b0, g);
-    if (g + 1 < G) {
-      before_prefetch(g + 1);
-      if (g + 2 < G) load_chunk(b0, g + 2);
-      compute_chunk(b1, g + 1);
+  const int Qpad = (Q + U - 1) / U * U;
+  for (int q0 = 0; q0 < Qpad; q0 += U) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int q = q0 + u;
+      const int ti = min(q, max(Q - 1, 0)) / kpw, kk = q - ti * kpw;
+      const bool kvalid = (q < Q) && (ks0 + kk < ks1);
+      prefetch_epilogue(ti);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const Frag fb = (PRO == PRO_LN) ? Mma<T>::select(q < Q, ring[u].fb[rt]) : Mma<T>::select(kvalid && jok[rt], ring[u].fb[rt]);
+        acc[0][rt] = Mma<T>::mma(ring[u].fa[0], fb, acc[0][rt]);
+        if (ND == 2) acc[ND - 1][rt] = Mma<T>::mma(ring[u].fa[ND - 1], fb, acc[ND - 1][rt]);
+      }
+      load_step(ring[u], q + U);
+      if (q < Q && kk == kpw - 1) finish_tile(ti);
     }
   }
 }

@@ -249,11 +249,28 @@ void launch_gemm_wide_t(hipStream_t s, GemmArgs a) {
   const int S = pick_waves(KS);                  // the same K split as the one-slab kernel: same sums
   a.ksteps_per_wave = (KS + S - 1) / S;
   const int ND = (EPI == EPI_GATED) ? 2 : 1;
-  const size_t lds = (size_t)(2 * S * ND * 256 + S * 16 + 256) * sizeof(float);
-  const int capacity = g_num_cus * std::max(1, 8 / S);
-  const int per_wg = (tiles + capacity - 1) / capacity;
+  const size_t lds = gemm_wide_lds_bytes(S, ND);
+  // one resident workgroup per CU (the partial tiles of six slabs take most of its LDS)
+  const int per_wg = (tiles + g_num_cus - 1) / g_num_cus;
   const int grid = (tiles + per_wg - 1) / per_wg;
   hipLaunchKernelGGL((gemm_wide_kernel<T, PRO, EPI>), dim3(grid), dim3(64 * S), lds, s, a);
+}
+
+// The wide kernel's LDS exceeds the default 64 KB limit of dynamic LDS.
+template <typename T>
+hipError_t allow_wide_lds() {
+  hipError_t e = hipSuccess;
+#define SD_CASE(P, E)                                                                                          \
+  if (e == hipSuccess)                                                                                         \
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide_kernel<T, P, E>),                         \
+                            hipFuncAttributeMaxDynamicSharedMemorySize,                                       \
+                            (int)gemm_wide_lds_bytes(8, (E == EPI_GATED) ? 2 : 1))
+  SD_CASE(PRO_LN, EPI_QKV); SD_CASE(PRO_POST, EPI_QKV);
+  SD_CASE(PRO_NONE, EPI_RESID);
+  SD_CASE(PRO_LN, EPI_ACT); SD_CASE(PRO_POST, EPI_GATED);
+  SD_CASE(PRO_LN, EPI_LOGITS); SD_CASE(PRO_POST, EPI_LOGITS);
+#undef SD_CASE
+  return e;
 }
 
 template <typename T>
@@ -692,7 +709,9 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
       g_num_cus = cus;
   }
-  if (allow_big_lds<bf16>() != hipSuccess || allow_big_lds<float>() != hipSuccess) return bail(SD_EHIP, "cannot raise the LDS limit");
+  if (allow_big_lds<bf16>() != hipSuccess || allow_big_lds<float>() != hipSuccess ||
+      allow_wide_lds<bf16>() != hipSuccess || allow_wide_lds<float>() != hipSuccess)
+    return bail(SD_EHIP, "cannot raise the LDS limit");
   std::string err;
   sd_status st = (p_cfg->dtype == SD_BF16) ? load_model<bf16>(c->stream, c->p, p_w, n_p, err)
                                            : load_model<float>(c->stream, c->p, p_w, n_p, err);
