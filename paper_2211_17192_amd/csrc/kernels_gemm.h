@@ -400,45 +400,73 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 
 // ---------------------------------------------------------------------------
 // The same product for up to GEMM_WIDE_RT slabs of 16 rows in one launch (several
-// sequences decoded together give more than 16 rows).  Each weight fragment is
-// multiplied against the matching activation fragment of every slab, so the weights
-// are still streamed once; the activations are re-read per tile from L2 (a few KB
-// per KB of weights).  Same K split over wavefronts, same order of additions per
-// row as gemm_kernel: a row's result does not depend on the kernel it went through.
-// Shallower prefetch (GEMM_WIDE_U k-steps per chunk) because every chunk also holds
-// the activation fragments of all slabs.
+// sequences decoded together give more than 16 rows).  Same K split over wavefronts
+// and same order of additions per row as gemm_kernel: a row's result does not depend on
+// the kernel it went through.
+//
+// What bounds this kernel is not HBM but the traffic of activation fragments from L2:
+// every KB of weights needs a KB of activations per slab.  Two measures (a
+// micro-benchmark of the bare loop gave 1.4 TB/s of weights with six row-major fragments
+// per weight KB, 2.7 with the fragments contiguous, 3.9 with three contiguous ones):
+//  * the activations come in fragment order, Xf[K/32][GEMM_WIDE_RT][64 lanes][8]
+//    (rows_to_fragments_kernel writes it just before the launch), so a fragment is one
+//    contiguous KB instead of 16 rows x 64 B;
+//  * every fragment is used for two weight streams: the gate and up matrices of a gated
+//    FFN, else two neighbouring 16-feature tiles.
+// PRO_LN (LayerNorm prologue) still reads the fp32 rows directly.
+// Main loop: a ring of k-step slots refilled right after use; no branches around loads.
 // ---------------------------------------------------------------------------
 constexpr int GEMM_WIDE_RT = 6;
 constexpr int GEMM_WIDE_U = 2;
-constexpr int GEMM_WIDE_ES = GEMM_WIDE_RT / 2;      // slabs per epilogue thread (512 threads, 256 outputs per slab)
 
-// LDS of the wide kernel: the partial tiles of every wavefront and slab, and the QKV staging rows.
-__host__ __device__ constexpr size_t gemm_wide_lds_bytes(int S, int ND) {
-  return (size_t)(S * ND * GEMM_WIDE_RT * 256 + GEMM_WIDE_RT * 256 + S * 16 + GEMM_WIDE_RT * 16 * 4) * sizeof(float);
+// LDS of the wide kernel: the partial tiles of every wavefront, stream and slab, the QKV
+// staging rows, and per-row constants.
+__host__ __device__ constexpr size_t gemm_wide_lds_bytes(int S) {
+  return (size_t)(S * 2 * GEMM_WIDE_RT * 256 + 2 * GEMM_WIDE_RT * 256 + S * 16 + GEMM_WIDE_RT * 16 * 4) * sizeof(float);
+}
+
+// Row-major activations [nrt * 16][K] -> fragment order [K/32][GEMM_WIDE_RT][64][8].
+// One thread moves the 8 elements of one lane of one fragment.
+template <typename T>
+static __global__ __launch_bounds__(256) void rows_to_fragments_kernel(const T* __restrict__ X, T* __restrict__ Xf,
+                                                                      int nrt, int K) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = idx & 63, f = idx >> 6;
+  const int KS = K >> 5;
+  if (f >= KS * nrt) return;
+  const int ks = f / nrt, rt = f - ks * nrt;
+  const int j = lane & 15, kq = lane >> 4;
+  float v[8];
+  load8<T>(X + (size_t)(rt * 16 + j) * K + ks * 32 + kq * 8, v);
+  T* dst = Xf + (((size_t)ks * GEMM_WIDE_RT + rt) * 64 + lane) * 8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) Store<T>::st(dst + e, v[e]);
 }
 
 template <typename T, int PRO, int EPI>
 static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a) {
   extern __shared__ float lds[];
   constexpr int ND = (EPI == EPI_GATED) ? 2 : 1;
-  constexpr int U = GEMM_WIDE_U, RT = GEMM_WIDE_RT, ES = GEMM_WIDE_ES;
+  constexpr int U = GEMM_WIDE_U, RT = GEMM_WIDE_RT;   // a deeper ring (4 k-steps) measured the same
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, S = blockDim.x >> 6;
   const int j = lane & 15, kq = lane >> 4;
   const int KS = a.K >> 5;
   const int ks0 = min(KS, wave * a.ksteps_per_wave), ks1 = min(KS, ks0 + a.ksteps_per_wave);
-  const int nchunks = (a.ksteps_per_wave + U - 1) / U;
   const int ntiles = a.N >> 4;
-  const int my_tiles = (ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
-  float* part = lds;                                 // [S][ND][RT][256]
-  float* ybuf = part + S * ND * RT * 256;            // [RT][256]
-  float* stat = ybuf + RT * 256;                     // [S][16]
+  // work items: pairs of weight streams.  Gated FFN: (gate, up) of tile p; else tiles 2p, 2p+1.
+  const int npairs = (ND == 2) ? ntiles : (ntiles + 1) / 2;
+  const int my_pairs = (npairs - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+  auto stream_tile = [&](int pair, int st) { return (ND == 2) ? pair : 2 * pair + st; };
+  float* part = lds;                                 // [S][2][RT][256]
+  float* ybuf = part + S * 2 * RT * 256;             // [2][RT][256]
+  float* stat = ybuf + 2 * RT * 256;                 // [S][16]
   float* rs_s = stat + S * 16;                       // [RT * 16] 1 / rms of every row (PRO_POST)
   int* pos_s = reinterpret_cast<int*>(rs_s + RT * 16);          // [RT * 16] position of every row (EPI_QKV)
   unsigned long long* kvb_s = reinterpret_cast<unsigned long long*>(pos_s + RT * 16);   // [RT * 16] cache offset
   const int nrt = a.nrt;
   auto slab_rows = [&](int rt) { return (rt == nrt - 1) ? a.R_last : a.R; };
 
-  // B side: clamped row of this lane in every slab
+  // B side: clamped slab / row of this lane
   int jr[RT];
   bool jok[RT];
 #pragma unroll
@@ -448,7 +476,7 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
     jok[rt] = (rt < nrt) && (j < rows);
   }
   // Epilogue side: thread t owns output e = t % 256 (row e / 16, feature e % 16) of the slabs
-  // t / 256, t / 256 + blockDim / 256, ...
+  // t / 256, t / 256 + blockDim / 256, ... of both streams
   const int e_row = (tid >> 4) & 15, e_f = tid & 15, e_idx = tid & 255;
   const int es_step = (int)blockDim.x >> 8, es0 = tid >> 8;          // 1 or 2; 0 or 1
 
@@ -490,18 +518,13 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
   }
 
   typedef typename Mma<T>::Frag Frag;
-  // A ring of U k-step slots: slot s holds the weight fragment(s) and the activation fragments of
-  // all slabs of one k-step.  Step q of this wavefront's work list is k-step ks0 + q % kpw of tile
-  // blockIdx.x + (q / kpw) * gridDim.x (kpw = k-steps per wavefront, padded steps are masked).
-  // Right after a slot is multiplied it is refilled with step q + U, so U k-steps of loads stay
-  // in flight across tile boundaries and epilogues.  All loads are unconditional (clamped
-  // addresses): a branch around a load would make the compiler drain the ring.
-  struct Slot { Frag fa[ND]; Frag fb[RT]; };
+  struct Slot { Frag fa[2]; Frag fb[RT]; };
   auto make_b = [&](int ks, bool valid, int rt) -> Frag {
-    const int k = ks * 32 + kq * 8;
-    if (PRO != PRO_LN) {
-      return Mma<T>::load(static_cast<const T*>(a.X) + (size_t)jr[rt] * a.K + k);
+    if (PRO != PRO_LN) {             // fragment order: one contiguous KB per (k-step, slab)
+      const int rc = min(rt, nrt - 1);
+      return Mma<T>::load(static_cast<const T*>(a.X) + (((size_t)ks * RT + rc) * 64 + lane) * 8);
     } else {
+      const int k = ks * 32 + kq * 8;
       float v[8], g[8], bb[8];
       load8<float>(static_cast<const float*>(a.X) + (size_t)jr[rt] * a.K + k, v);
       load8<T>(static_cast<const T*>(a.gain) + k, g);
@@ -512,17 +535,17 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
     }
   };
 
-
   const int ks_last = max(ks1 - 1, 0);
   const int kpw = a.ksteps_per_wave;
-  const int Q = my_tiles * kpw;                      // steps of this wavefront (the same for all)
+  const int Q = my_pairs * kpw;                      // steps of this wavefront (the same for all)
   auto load_step = [&](Slot& sl, int q) {
     const int qc = min(q, max(Q - 1, 0));            // past the end: re-read the last step, never used
-    const int ti = qc / kpw, kk = qc - ti * kpw;
-    const size_t tile = (size_t)blockIdx.x + (size_t)ti * gridDim.x;
+    const int pi = qc / kpw, kk = qc - pi * kpw;
+    const int pair = (int)blockIdx.x + pi * (int)gridDim.x;
     const int ks = ks0 + kk, ksc = min(ks, ks_last);
-    sl.fa[0] = Mma<T>::load_stream(static_cast<const T*>(a.W) + (tile * KS + ksc) * 512 + lane * 8);
-    if (ND == 2) sl.fa[ND - 1] = Mma<T>::load_stream(static_cast<const T*>(a.W2) + (tile * KS + ksc) * 512 + lane * 8);
+    const size_t t0 = (size_t)stream_tile(pair, 0), t1 = (size_t)min(stream_tile(pair, 1), ntiles - 1);
+    sl.fa[0] = Mma<T>::load_stream(static_cast<const T*>(a.W) + (t0 * KS + ksc) * 512 + lane * 8);
+    sl.fa[1] = Mma<T>::load_stream(static_cast<const T*>(ND == 2 ? a.W2 : a.W) + (t1 * KS + ksc) * 512 + lane * 8);
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) sl.fb[rt] = make_b(ksc, ks < ks1, rt);
   };
@@ -552,107 +575,113 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
       kvb_s[r] = (unsigned long long)page * 2 * a.n_kv_heads * a.page_size * a.d_head + (unsigned long long)slot * a.d_head;
     }
   }
-  // (the first barrier of finish_tile orders these writes before their use)
+  // (the first barrier of finish_pair orders these writes before their use)
 
-  // bias / gain of this thread's output feature in the tile being worked on: fetched at every
-  // step, without branches (absent vectors read the weights and are masked)
-  float pre_bias = 0.0f, pre_gain = 0.0f;
   const bool has_bias = a.bias != nullptr, has_gain = (EPI == EPI_RESID) && a.xg_out != nullptr;
-  const T* bias_p = has_bias ? static_cast<const T*>(a.bias) : static_cast<const T*>(a.W);
-  const T* gain_p = has_gain ? static_cast<const T*>(a.gain_next) : static_cast<const T*>(a.W);
-  auto prefetch_epilogue = [&](int ti) {
-    const int n = ((int)blockIdx.x + ti * (int)gridDim.x) * 16 + e_f;
-    const float b = Store<T>::ld(bias_p + n), g = Store<T>::ld(gain_p + n);
-    pre_bias = has_bias ? b : 0.0f;
-    pre_gain = has_gain ? g : 0.0f;
-  };
 
-  f32x4 acc[ND][RT];
+  f32x4 acc[2][RT];
 #pragma unroll
-  for (int d = 0; d < ND; ++d)
+  for (int d = 0; d < 2; ++d)
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) acc[d][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // One barrier before the partial tiles are written (the previous tile's epilogue has read
+  // One barrier before the partial tiles are written (the previous pair's epilogue has read
   // them), one after; every thread then finishes its outputs of its slabs.
-  auto finish_tile = [&](int ti) {
-    const int tile = (int)blockIdx.x + ti * (int)gridDim.x;
+  auto finish_pair = [&](int pi) {
+    const int pair = (int)blockIdx.x + pi * (int)gridDim.x;
     __syncthreads();
 #pragma unroll
-    for (int d = 0; d < ND; ++d)
+    for (int d = 0; d < 2; ++d)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) part[((wave * ND + d) * RT + rt) * 256 + j * 16 + kq * 4 + r] = acc[d][rt][r];
+        for (int r = 0; r < 4; ++r) part[((wave * 2 + d) * RT + rt) * 256 + j * 16 + kq * 4 + r] = acc[d][rt][r];
         acc[d][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
     __syncthreads();
-    const int f = e_f, n = tile * 16 + f;
-    for (int rt = es0; rt < nrt; rt += es_step) {
-      const int row = rt * 16 + e_row;
-      const bool ok = e_row < slab_rows(rt);
-      float y[ND];
+    const int f = e_f;
+    constexpr int NOUT = (ND == 2) ? 1 : 2;         // output tiles of the pair
 #pragma unroll
-      for (int d = 0; d < ND; ++d) {
-        float s1 = 0.0f;
-        for (int w = 0; w < S; ++w) s1 += part[((w * ND + d) * RT + rt) * 256 + e_idx];
-        y[d] = s1;
-      }
-      if (PRO == PRO_POST) {
-        const float r1 = rs_s[row];
+    for (int o = 0; o < NOUT; ++o) {
+      const int tile = stream_tile(pair, o);
+      if (tile < ntiles) {                           // uniform over the workgroup
+        const int n = tile * 16 + f;
+        const float bias = has_bias ? Store<T>::ld(static_cast<const T*>(a.bias) + n) : 0.0f;
+        const float gain = has_gain ? Store<T>::ld(static_cast<const T*>(a.gain_next) + n) : 0.0f;
+        for (int rt = es0; rt < nrt; rt += es_step) {
+          const int row = rt * 16 + e_row;
+          const bool ok = e_row < slab_rows(rt);
+          float y[2];
 #pragma unroll
-        for (int d = 0; d < ND; ++d) y[d] *= r1;
-      }
-      y[0] += pre_bias;
-      if (EPI == EPI_QKV) {
-        ybuf[rt * 256 + e_idx] = y[0];
-      } else if (EPI == EPI_RESID) {
-        float xn = 0.0f;
-        if (ok) {
-          xn = static_cast<const float*>(a.out)[(size_t)row * a.ldo + n] + y[0];
-          static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = xn;
-          if (a.xg_out != nullptr) Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * pre_gain);
-        }
-        if (a.ss_out != nullptr) {
-          float q = xn * xn;
-          q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
-          q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
-          if (f == 0) a.ss_out[(size_t)rt * a.ss_stride + tile * 16 + e_row] = q;
-        }
-      } else if (ok) {
-        if (EPI == EPI_STORE) {
-          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
-        } else if (EPI == EPI_ACT) {
-          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, gelu_tanh(y[0]));
-        } else if (EPI == EPI_GATED) {
-          const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
-          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[ND - 1]);
-        } else if (EPI == EPI_LOGITS) {
-          const int orow = (a.out_row != nullptr) ? a.out_row[row] : row;
-          if (orow >= 0) static_cast<float*>(a.out)[(size_t)orow * a.ldo + n] = a.scale * y[0];
+          for (int d = 0; d < 2; ++d) {
+            float s1 = 0.0f;
+            const int st = (ND == 2) ? d : o;
+            for (int w = 0; w < S; ++w) s1 += part[((w * 2 + st) * RT + rt) * 256 + e_idx];
+            y[d] = s1;
+          }
+          if (PRO == PRO_POST) {
+            const float r1 = rs_s[row];
+            y[0] *= r1; y[1] *= r1;
+          }
+          y[0] += bias;
+          if (EPI == EPI_QKV) {
+            ybuf[(o * RT + rt) * 256 + e_idx] = y[0];
+          } else if (EPI == EPI_RESID) {
+            float xn = 0.0f;
+            if (ok) {
+              xn = static_cast<const float*>(a.out)[(size_t)row * a.ldo + n] + y[0];
+              static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = xn;
+              if (a.xg_out != nullptr) Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * gain);
+            }
+            if (a.ss_out != nullptr) {
+              float q = xn * xn;
+              q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+              q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+              if (f == 0) a.ss_out[(size_t)rt * a.ss_stride + tile * 16 + e_row] = q;
+            }
+          } else if (ok) {
+            if (EPI == EPI_STORE) {
+              Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
+            } else if (EPI == EPI_ACT) {
+              Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, gelu_tanh(y[0]));
+            } else if (EPI == EPI_GATED) {
+              const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
+              Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[1]);
+            } else if (EPI == EPI_LOGITS) {
+              const int orow = (a.out_row != nullptr) ? a.out_row[row] : row;
+              if (orow >= 0) static_cast<float*>(a.out)[(size_t)orow * a.ldo + n] = a.scale * y[0];
+            }
+          }
         }
       }
     }
     if (EPI == EPI_QKV) {
       __syncthreads();
-      const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
-      const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
-      const int head = nn / a.d_head, d = nn % a.d_head;
-      for (int rt = es0; rt < nrt; rt += es_step) {
-        const int row = rt * 16 + e_row;
-        if (e_row < slab_rows(rt)) {
-          const int pos = pos_s[row];
-          float y = ybuf[rt * 256 + e_idx];
-          if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
-            const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
-            const float other = ybuf[rt * 256 + (e_idx ^ 1)];
-            y = (d & 1) ? (other * cs[1] + y * cs[0]) : (y * cs[0] - other * cs[1]);
-          }
-          if (is_q) {
-            Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
-          } else if (pos >= 0) {
-            const size_t idx = (size_t)kvb_s[row] + ((size_t)(is_k ? 0 : 1) * a.n_kv_heads + head) * a.page_size * a.d_head + d;
-            Store<T>::st(static_cast<T*>(a.kv_pool) + idx, y);
+#pragma unroll
+      for (int o = 0; o < NOUT; ++o) {
+        const int tile = stream_tile(pair, o);
+        if (tile < ntiles) {
+          const int n = tile * 16 + f;
+          const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
+          const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
+          const int head = nn / a.d_head, d = nn % a.d_head;
+          for (int rt = es0; rt < nrt; rt += es_step) {
+            const int row = rt * 16 + e_row;
+            if (e_row < slab_rows(rt)) {
+              const int pos = pos_s[row];
+              float y = ybuf[(o * RT + rt) * 256 + e_idx];
+              if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
+                const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
+                const float other = ybuf[(o * RT + rt) * 256 + (e_idx ^ 1)];
+                y = (d & 1) ? (other * cs[1] + y * cs[0]) : (y * cs[0] - other * cs[1]);
+              }
+              if (is_q) {
+                Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
+              } else if (pos >= 0) {
+                const size_t idx = (size_t)kvb_s[row] + ((size_t)(is_k ? 0 : 1) * a.n_kv_heads + head) * a.page_size * a.d_head + d;
+                Store<T>::st(static_cast<T*>(a.kv_pool) + idx, y);
+              }
+            }
           }
         }
       }
@@ -664,17 +693,16 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int q = q0 + u;
-      const int ti = min(q, max(Q - 1, 0)) / kpw, kk = q - ti * kpw;
+      const int pi = min(q, max(Q - 1, 0)) / kpw, kk = q - pi * kpw;
       const bool kvalid = (q < Q) && (ks0 + kk < ks1);
-      prefetch_epilogue(ti);
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         const Frag fb = (PRO == PRO_LN) ? Mma<T>::select(q < Q, ring[u].fb[rt]) : Mma<T>::select(kvalid && jok[rt], ring[u].fb[rt]);
         acc[0][rt] = Mma<T>::mma(ring[u].fa[0], fb, acc[0][rt]);
-        if (ND == 2) acc[ND - 1][rt] = Mma<T>::mma(ring[u].fa[ND - 1], fb, acc[ND - 1][rt]);
+        acc[1][rt] = Mma<T>::mma(ring[u].fa[1], fb, acc[1][rt]);
       }
       load_step(ring[u], q + U);
-      if (q < Q && kk == kpw - 1) finish_tile(ti);
+      if (q < Q && kk == kpw - 1) finish_pair(pi);
     }
   }
 }

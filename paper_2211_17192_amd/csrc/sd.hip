@@ -4,6 +4,7 @@
 // The C ABI is declared and documented in include/sd.h.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -61,6 +62,7 @@ struct Model {
   int rows_cap = MAX_ROWS;     // activation rows: one group of MAX_ROWS rows per sequence at most
   int* page_table = nullptr;   // [batch][n_pages]
   int *row_seq = nullptr, *logit_row = nullptr;   // [rows_cap], written by the embedding kernel
+  void* xfrag = nullptr;       // activations of one wide GEMM in fragment order
   float* x = nullptr;
   void* xg = nullptr;          // x * gain of the next RMSNorm, storage type
   float* ss = nullptr;         // [d_model/16][16] partial sums of x^2
@@ -148,6 +150,7 @@ void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size, int ba
   m.row_pos = static_cast<int*>(A.take(rows * sizeof(int)));
   m.row_seq = static_cast<int*>(A.take(rows * sizeof(int)));
   m.logit_row = static_cast<int*>(A.take(rows * sizeof(int)));
+  if (batch > 1) m.xfrag = A.take((size_t)std::max({(size_t)d, (size_t)m.nq, ff}) * GEMM_WIDE_RT * 16 * e);
   m.prompt = static_cast<int*>(A.take((size_t)c.max_len * sizeof(int)));
 }
 
@@ -248,11 +251,12 @@ void launch_gemm_wide_t(hipStream_t s, GemmArgs a) {
   const int tiles = a.N / 16, KS = a.K / 32;
   const int S = pick_waves(KS);                  // the same K split as the one-slab kernel: same sums
   a.ksteps_per_wave = (KS + S - 1) / S;
-  const int ND = (EPI == EPI_GATED) ? 2 : 1;
-  const size_t lds = gemm_wide_lds_bytes(S, ND);
+  const size_t lds = gemm_wide_lds_bytes(S);
+  // work items are pairs of weight streams (gate + up of a tile, else two neighbouring tiles);
   // one resident workgroup per CU (the partial tiles of six slabs take most of its LDS)
-  const int per_wg = (tiles + g_num_cus - 1) / g_num_cus;
-  const int grid = (tiles + per_wg - 1) / per_wg;
+  const int pairs = (EPI == EPI_GATED) ? tiles : (tiles + 1) / 2;
+  const int per_wg = (pairs + g_num_cus - 1) / g_num_cus;
+  const int grid = (pairs + per_wg - 1) / per_wg;
   hipLaunchKernelGGL((gemm_wide_kernel<T, PRO, EPI>), dim3(grid), dim3(64 * S), lds, s, a);
 }
 
@@ -264,7 +268,7 @@ hipError_t allow_wide_lds() {
   if (e == hipSuccess)                                                                                         \
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide_kernel<T, P, E>),                         \
                             hipFuncAttributeMaxDynamicSharedMemorySize,                                       \
-                            (int)gemm_wide_lds_bytes(8, (E == EPI_GATED) ? 2 : 1))
+                            (int)gemm_wide_lds_bytes(8))
   SD_CASE(PRO_LN, EPI_QKV); SD_CASE(PRO_POST, EPI_QKV);
   SD_CASE(PRO_NONE, EPI_RESID);
   SD_CASE(PRO_LN, EPI_ACT); SD_CASE(PRO_POST, EPI_GATED);
@@ -387,6 +391,12 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       a.R = R_full;
       a.R_last = (g0 + a.nrt == n_groups) ? R_tail : R_full;
       a.ss_stride = (d / 16) * 16;
+      if (pro_ != PRO_LN) {                       // the wide kernel reads the activations in fragment order
+        const int frags = (a.K / 32) * a.nrt;
+        hipLaunchKernelGGL((rows_to_fragments_kernel<T>), dim3((frags * 64 + 255) / 256), dim3(256), 0, s,
+                           static_cast<const T*>(a.X), static_cast<T*>(m.xfrag), a.nrt, a.K);
+        a.X = m.xfrag;
+      }
       launch_gemm_wide<T>(s, pro_, epi_, a);
     }
   };
