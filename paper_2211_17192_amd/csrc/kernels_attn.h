@@ -70,6 +70,13 @@ struct AttnArgs {
   // MAX_ROWS rows, spg whole sequences per slab (sequence z: slab z / spg, rows (z % spg) * R ..);
   // sequence z uses the page table at page_table + (seq0 + z) * pt_stride
   int seq0, pt_stride, spg;
+  // long contexts: the keys of a (sequence, kv head) are cut into nsplit ranges of split_keys keys
+  // (a multiple of the key block) that different workgroups take (grid.y = row groups x nsplit);
+  // each leaves its running maximum, denominator and unnormalised output in `partial`
+  // ([sequence][kv head][split][ATTN_MAX_RG][d_head + 2] floats) and attn_merge_kernel combines
+  // them.  nsplit is fixed per model (from max_len), so the split never depends on the other rows.
+  int nsplit, split_keys;
+  float* partial;
   int cross;                // 1: cross-attention over kv_len keys, no mask, no bias
   int kv_len;
   float scale;
@@ -94,7 +101,8 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int hkv = blockIdx.x;
   // rows are independent: blockIdx.y takes rows [r0, r0 + R) of the launch
-  const int rs = blockIdx.y * a.rows_per_wg;                   // first row within the sequence
+  const int split = (a.nsplit > 1) ? (int)blockIdx.y % a.nsplit : 0;
+  const int rs = ((a.nsplit > 1) ? (int)blockIdx.y / a.nsplit : (int)blockIdx.y) * a.rows_per_wg;   // first row within the sequence
   const int R = min(a.rows_per_wg, a.R - rs);
   const int r0 = ((int)blockIdx.z / a.spg) * MAX_ROWS + ((int)blockIdx.z % a.spg) * a.R + rs;   // first row within the launch
   const int* page_table = a.page_table + (size_t)(a.seq0 + blockIdx.z) * a.pt_stride;
@@ -151,7 +159,14 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   const int kl_s = tid / LPK, part = tid % LPK;    // score phase: key within block, slice
   const int oct = tid % OCT, grp = tid / OCT;      // P*V phase: V slice, key group (KPT keys)
 
-  for (int k0 = 0; k0 < kv_len; k0 += KB) {
+  const int k_begin = split * a.split_keys;
+  if (a.nsplit > 1 && k_begin >= kv_len) {       // nothing in this key range yet: an empty partial
+    float* pp = a.partial + ((((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
+    if (tid < RG) { pp[(size_t)tid * (DH + 2) + DH] = -INFINITY; pp[(size_t)tid * (DH + 2) + DH + 1] = 0.0f; }
+    return;
+  }
+  if (a.nsplit > 1) kv_len = min(kv_len, k_begin + a.split_keys);
+  for (int k0 = (a.nsplit > 1) ? k_begin : 0; k0 < kv_len; k0 += KB) {
     const int nkeys = min(KB, kv_len - k0);
     // ---- issue every global load of this block.  Loads are unconditional
     //      (out-of-range keys re-read the last valid one and get probability 0):
@@ -274,6 +289,12 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
     SD_STAMP(4);
   }
 
+  if (a.nsplit > 1) {            // leave the partial result of this key range for the merge
+    float* pp = a.partial + ((((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
+    for (int i = tid; i < RG * DH; i += ATTN_THREADS) pp[(size_t)(i / DH) * (DH + 2) + i % DH] = acc_s[i];
+    if (tid < RG) { pp[(size_t)tid * (DH + 2) + DH] = m_s[tid]; pp[(size_t)tid * (DH + 2) + DH + 1] = l_s[tid]; }
+    return;
+  }
   T* og = static_cast<T*>(a.out);
   for (int i = tid; i < RG * DH; i += ATTN_THREADS) {
     const int rg = i / DH, d = i % DH, r = rg / G, h = hkv * G + rg % G;
@@ -281,6 +302,33 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
     Store<T>::st(og + (size_t)(r0 + r) * a.H * DH + h * DH + d, (L > 0.0f) ? acc_s[i] / L : 0.0f);
   }
   SD_STAMP(5);
+}
+
+// Combines the partial results of the key ranges of one (sequence, kv head): with
+// m = max m_s, the output is sum_s acc_s e^(m_s - m) / sum_s l_s e^(m_s - m), ranges taken in
+// order.  grid = (kv heads, 1, sequences), one thread per (row, query head, feature).
+template <typename T, int DH>
+static __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
+  const int hkv = blockIdx.x, G = a.H / a.Hkv, RG = a.R * G;
+  const int r_base = ((int)blockIdx.z / a.spg) * MAX_ROWS + ((int)blockIdx.z % a.spg) * a.R;
+  const float* pp = a.partial + (((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit) * ATTN_MAX_RG * (DH + 2);
+  T* og = static_cast<T*>(a.out);
+  for (int i = threadIdx.x; i < RG * DH; i += blockDim.x) {
+    const int rg = i / DH, d = i % DH, r = rg / G, h = hkv * G + rg % G;
+    float m = -INFINITY;
+    for (int sp = 0; sp < a.nsplit; ++sp) m = fmaxf(m, pp[((size_t)sp * ATTN_MAX_RG + rg) * (DH + 2) + DH]);
+    float L = 0.0f, o = 0.0f;
+    for (int sp = 0; sp < a.nsplit; ++sp) {
+      const float* q = pp + ((size_t)sp * ATTN_MAX_RG + rg) * (DH + 2);
+      const float ms = q[DH];
+      if (ms != -INFINITY) {                       // empty ranges left no output behind
+        const float w = __expf(ms - m);
+        L += q[DH + 1] * w;
+        o += q[d] * w;
+      }
+    }
+    Store<T>::st(og + (size_t)(r_base + r) * a.H * DH + h * DH + d, (L > 0.0f) ? o / L : 0.0f);
+  }
 }
 
 }  // namespace sd

@@ -63,6 +63,8 @@ struct Model {
   int* page_table = nullptr;   // [batch][n_pages]
   int *row_seq = nullptr, *logit_row = nullptr;   // [rows_cap], written by the embedding kernel
   void* xfrag = nullptr;       // activations of one wide GEMM in fragment order
+  int attn_nsplit = 1, attn_split_keys = 0;   // long contexts: key ranges per (sequence, kv head)
+  float* attn_partial = nullptr;
   float* x = nullptr;
   void* xg = nullptr;          // x * gain of the next RMSNorm, storage type
   float* ss = nullptr;         // [d_model/16][16] partial sums of x^2
@@ -150,6 +152,14 @@ void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size, int ba
   m.row_pos = static_cast<int*>(A.take(rows * sizeof(int)));
   m.row_seq = static_cast<int*>(A.take(rows * sizeof(int)));
   m.logit_row = static_cast<int*>(A.take(rows * sizeof(int)));
+  // contexts beyond 1024 positions: key ranges of 512 keys taken by different workgroups
+  m.attn_split_keys = 512;
+  m.attn_nsplit = (c.max_len > 1024) ? std::min(16, (c.max_len + m.attn_split_keys - 1) / m.attn_split_keys) : 1;
+  if (m.attn_nsplit > 1) {
+    m.attn_split_keys = ((c.max_len + m.attn_nsplit - 1) / m.attn_nsplit + 511) / 512 * 512;
+    m.attn_partial = static_cast<float*>(A.take((size_t)batch * c.n_kv_heads * m.attn_nsplit * ATTN_MAX_RG *
+                                                (c.d_head + 2) * sizeof(float)));
+  }
   if (batch > 1) m.xfrag = A.take((size_t)std::max({(size_t)d, (size_t)m.nq, ff}) * GEMM_WIDE_RT * 16 * e);
   m.prompt = static_cast<int*>(A.take((size_t)c.max_len * sizeof(int)));
 }
@@ -307,11 +317,20 @@ void launch_attn(hipStream_t s, const Model& m, AttnArgs a, int nseq) {
   const int G = a.H / a.Hkv, DH = m.cfg.d_head;
   // few kv heads leave most CUs idle: split the (independent) rows over more workgroups
   a.rows_per_wg = (nseq * a.Hkv * ((a.R + 1) / 2) <= g_num_cus) ? std::min(2, a.R) : a.R;
+  if (a.cross || m.attn_nsplit <= 1) { a.nsplit = 1; a.split_keys = 0; a.partial = nullptr; }
+  else { a.nsplit = m.attn_nsplit; a.split_keys = m.attn_split_keys; a.partial = m.attn_partial; }
+  if (a.nsplit > 1) a.rows_per_wg = a.R;          // the key ranges already spread the work
   const size_t lds = attn_lds_bytes(a.rows_per_wg * G, DH);
-  const dim3 grid(a.Hkv, (a.R + a.rows_per_wg - 1) / a.rows_per_wg, nseq), block(ATTN_THREADS);
+  const dim3 grid(a.Hkv, ((a.R + a.rows_per_wg - 1) / a.rows_per_wg) * a.nsplit, nseq), block(ATTN_THREADS);
   if (DH == 32) hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, lds, s, a);
   else if (DH == 64) hipLaunchKernelGGL((attn_kernel<T, 64>), grid, block, lds, s, a);
   else hipLaunchKernelGGL((attn_kernel<T, 128>), grid, block, lds, s, a);
+  if (a.nsplit > 1) {
+    const dim3 mg(a.Hkv, 1, nseq), mb(256);
+    if (DH == 32) hipLaunchKernelGGL((attn_merge_kernel<T, 32>), mg, mb, 0, s, a);
+    else if (DH == 64) hipLaunchKernelGGL((attn_merge_kernel<T, 64>), mg, mb, 0, s, a);
+    else hipLaunchKernelGGL((attn_merge_kernel<T, 128>), mg, mb, 0, s, a);
+  }
 }
 
 // The attention kernel keeps up to ATTN_MAX_RG query rows in more than 64 KB of LDS.

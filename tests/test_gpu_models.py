@@ -536,7 +536,7 @@ def test_gqa8b_full_size_batch_matches_oracle_per_row():
     dec.close()
 
 
-@pytest.mark.parametrize("d_head,ctx", [(128, 600), (64, 1100), (32, 1300)])
+@pytest.mark.parametrize("d_head,ctx", [(128, 600), (64, 1100), (32, 1300), (128, 1500)])
 def test_long_context_spans_several_key_blocks(d_head, ctx):
     """Contexts longer than one key block of the attention kernel (256 keys at d_head 128, 512
     otherwise): the online softmax across blocks, with a ragged last block, two sequences of
