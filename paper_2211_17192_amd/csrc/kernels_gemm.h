@@ -538,21 +538,26 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
   const int ks_last = max(ks1 - 1, 0);
   const int kpw = a.ksteps_per_wave;
   const int Q = my_pairs * kpw;                      // steps of this wavefront (the same for all)
-  auto load_step = [&](Slot& sl, int q) {
-    const int qc = min(q, max(Q - 1, 0));            // past the end: re-read the last step, never used
-    const int pi = qc / kpw, kk = qc - pi * kpw;
-    const int pair = (int)blockIdx.x + pi * (int)gridDim.x;
-    const int ks = ks0 + kk, ksc = min(ks, ks_last);
+  // cursor of the next step to load: pair index on this workgroup's list and k-step within the
+  // wavefront's K slice, advanced without divisions; past the end it stays on the last step
+  int l_pi = 0, l_kk = 0;
+  auto load_step = [&](Slot& sl) {
+    const int pair = (int)blockIdx.x + l_pi * (int)gridDim.x;
+    const int ks = ks0 + l_kk, ksc = min(ks, ks_last);
     const size_t t0 = (size_t)stream_tile(pair, 0), t1 = (size_t)min(stream_tile(pair, 1), ntiles - 1);
     sl.fa[0] = Mma<T>::load_stream(static_cast<const T*>(a.W) + (t0 * KS + ksc) * 512 + lane * 8);
     sl.fa[1] = Mma<T>::load_stream(static_cast<const T*>(ND == 2 ? a.W2 : a.W) + (t1 * KS + ksc) * 512 + lane * 8);
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) sl.fb[rt] = make_b(ksc, ks < ks1, rt);
+    const bool last = (l_pi == my_pairs - 1) && (l_kk == kpw - 1);
+    const bool wrap = (l_kk == kpw - 1) && !last;
+    l_kk = last ? l_kk : (wrap ? 0 : l_kk + 1);
+    l_pi = wrap ? l_pi + 1 : l_pi;
   };
 
   Slot ring[U];
 #pragma unroll
-  for (int u = 0; u < U; ++u) load_step(ring[u], u);
+  for (int u = 0; u < U; ++u) load_step(ring[u]);
 
   // ---- per row, tile-independent epilogue inputs, kept in LDS ----
   for (int r = tid >> 4; r < nrt * 16; r += (int)blockDim.x >> 4) {      // 16 lanes per row
@@ -689,20 +694,23 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
   };
 
   const int Qpad = (Q + U - 1) / U * U;
+  int c_pi = 0, c_kk = 0;                          // the step being multiplied
   for (int q0 = 0; q0 < Qpad; q0 += U) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int q = q0 + u;
-      const int pi = min(q, max(Q - 1, 0)) / kpw, kk = q - pi * kpw;
-      const bool kvalid = (q < Q) && (ks0 + kk < ks1);
+      const bool kvalid = (q < Q) && (ks0 + c_kk < ks1);
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         const Frag fb = (PRO == PRO_LN) ? Mma<T>::select(q < Q, ring[u].fb[rt]) : Mma<T>::select(kvalid && jok[rt], ring[u].fb[rt]);
         acc[0][rt] = Mma<T>::mma(ring[u].fa[0], fb, acc[0][rt]);
         acc[1][rt] = Mma<T>::mma(ring[u].fa[1], fb, acc[1][rt]);
       }
-      load_step(ring[u], q + U);
-      if (q < Q && kk == kpw - 1) finish_pair(pi);
+      load_step(ring[u]);
+      const bool tile_end = (q < Q) && (c_kk == kpw - 1);
+      if (tile_end) finish_pair(c_pi);
+      c_pi = tile_end ? c_pi + 1 : c_pi;
+      c_kk = (c_kk == kpw - 1) ? 0 : c_kk + 1;
     }
   }
 }
