@@ -616,3 +616,51 @@ def test_table_drafts_match_oracle(kind):
     with pytest.raises(binding.SdError):
         dec.step(gamma, 1.0, U[16])                 # Mq's cache was not kept up
     dec.close()
+
+
+def test_error_paths_of_the_options_and_of_batches():
+    """Argument checks of sd_set_sampling, sd_set_table_draft, sd_measure_cost and the batched
+    calls; a refused call changes nothing: the next step gives the tokens of an untouched run."""
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    V = cfg_p["vocab"]
+    U = synth.uniform_stream(5, 8 * 2 * 9).reshape(8, 2, 9)
+    prompts = [synth.random_tokens(7, 5, V), synth.random_tokens(8, 11, V)]
+
+    def fresh():
+        d = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=4, flags=1, batch=2)
+        for b in range(2):
+            d.prefill(prompts[b], row=b)
+        return d
+
+    ref = fresh()
+    want = [ref.step(4, 1.0, U[i]) for i in range(3)]
+    ref.close()
+    dec = fresh()
+    for kw in (dict(lenience=0.0), dict(lenience=1.5), dict(top_k=-1), dict(top_p=1.5), dict(top_p=-0.1)):
+        with pytest.raises(binding.SdError) as e:
+            dec.set_sampling(**kw)
+        assert e.value.status == binding.SD_EINVAL
+    with pytest.raises(binding.SdError):
+        dec.prefill(prompts[0], row=2)                               # no such sequence
+    with pytest.raises(binding.SdError):
+        dec.reset(row=5)
+    st = binding.lib.sd_set_table_draft(dec._ctx, None, None, 3)     # rows without a table
+    assert st == binding.SD_EINVAL
+    with pytest.raises(AssertionError):
+        dec.step(4, 1.0, U[0][:1])                                   # uniforms for one sequence only: the binding refuses
+    assert dec.step(4, 1.0, U[0]) == want[0]
+    mq_us, mp_us = dec.measure_cost(reps=3)                          # both sequences, commits nothing
+    assert mq_us > 0 and mp_us > 0
+    assert dec.step(4, 1.0, U[1]) == want[1]
+    table = torch.zeros(1, V, device="cuda")
+    dec.set_table_draft(table)
+    with pytest.raises(binding.SdError) as e:
+        dec.measure_cost(reps=3)                                     # times Mq: not with a table draft
+    assert e.value.status == binding.SD_ESTATE
+    dec.close()
+    with pytest.raises(binding.SdError):
+        make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=4, batch=65)
+    t5 = small_pair(T.T5DEC, "f32")
+    with pytest.raises(binding.SdError):
+        make_decoder(t5[0], t5[1], t5[2], t5[3], max_gamma=4, batch=2)   # one encoder output per context
