@@ -102,6 +102,17 @@ def main():
         gammas = gammas + [tuned["gamma"]]
         sweep(tuned["gamma"])
 
+    # argmax sampling (temperature 0): the same launches, another acceptance rate (section 2.2:
+    # acceptance then means "Mq's argmax is Mp's argmax")
+    per_gamma_t0 = {}
+    for gamma in gammas:
+        urows = synth.uniform_stream(300 + gamma, 512 * (2 * gamma + 1)).reshape(512, -1)
+        n_t0 = max(8, args.steps // 2)
+        timed_steps(dec, gamma, min(args.warmup, 4), 0.0, urows, enc_p, enc_q, torch)
+        secs, tokens, accepted, tested = timed_steps(dec, gamma, n_t0, 0.0, urows, enc_p, enc_q, torch)
+        per_gamma_t0[gamma] = {"tokens_per_s": tokens / secs, "ms_per_step": 1e3 * secs / n_t0,
+                               "tokens_per_step": tokens / n_t0, "alpha": accepted / max(tested, 1)}
+
     # plain Mp decoding: the denominator of the speedup.  One whole untimed sequence first: right
     # after the speculative runs the first ~100 plain steps are ~10 % slower than the steady state
     # (the chip's power management follows the change of load), which would flatter the speedup.
@@ -190,6 +201,7 @@ def main():
                                "temperature 1, 128 generated tokens per sequence",
                    "gamma": best, "temperature": TEMPERATURE, "gammas": gammas},
         "per_gamma": {str(g): per_gamma[g] for g in gammas},
+        "per_gamma_temperature0": {str(g): per_gamma_t0[g] for g in gammas},
         "autotune": {"gamma": tuned["gamma"], "alpha": tuned["alpha"], "c": tuned["c"],
                      "thm38_predicted_speedup": tuned["improvement"],
                      "measured_speedup": per_gamma[tuned["gamma"]]["tokens_per_s"] / (1e3 / base_ms)},
