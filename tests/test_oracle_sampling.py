@@ -361,6 +361,69 @@ def test_table_drafts_leave_the_output_distribution_at_p():
     np.testing.assert_allclose(counts / counts.sum(), P1, atol=1e-12)
 
 
+def test_copy_draft_match_rule_on_worked_contexts():
+    """Section 3.6, copying model: the last `match` tokens are looked up among their earlier
+    occurrences, the most recent one that has a successor wins (contexts worked by hand)."""
+    two = drafts.CopyDraft(8, 2)
+    assert two.copied_token([5, 6, 7, 5, 6]) == 7
+    assert two.copied_token([1, 2, 3, 1, 2, 4, 1, 2]) == 4          # occurrences at 0 (-> 3) and 3 (-> 4)
+    assert two.copied_token([7, 7, 7]) == 7                          # overlapping occurrence at 0
+    assert two.copied_token([7, 7]) is None                          # only the tail itself
+    assert two.copied_token([1, 2, 3, 2, 1]) is None
+    assert two.copied_token([4]) is None
+    one = drafts.CopyDraft(8, 1)
+    assert one.copied_token([3, 5, 3, 6, 3]) == 6
+    rows = two.score([5, 6, 7, 5, 6], 2)                             # contexts [5,6,7,5] and [5,6,7,5,6]
+    np.testing.assert_array_equal(rows[0], np.zeros(8))              # (7,5) never seen: uniform
+    assert rows[1][7] == 0.0 and np.all(np.isneginf(np.delete(rows[1], 7)))
+
+
+def test_copy_draft_leaves_the_output_distribution_at_p():
+    """A one-hot q on token x keeps x with probability p(x) (Cor. 3.6: sum min(p, q) = p(x)) and
+    otherwise draws from p with x removed, so the output is distributed as p (appendix A.1)."""
+    mp = TableScorer(lambda ctx: P2[ctx[-1]])
+    copy = drafts.CopyDraft(4, 2)
+    prefix = [0, 3, 1, 0, 3]                                         # copied guess 1; p = P2[3] = [1/8, 3/8, 1/4, 1/4]
+    counts, kept = np.zeros(4), 0
+    for d, r, sv in itertools.product(grid(2), grid(8), grid(10)):  # test threshold 3/8; residual [1/5, 0, 2/5, 2/5]
+        out, n, info = decode.speculative_decoding_step(mp, copy, prefix, 1, 1.0, [d, r, sv])
+        assert info["x"] == [1]
+        counts[out[len(prefix)]] += 1
+        kept += n
+    np.testing.assert_allclose(counts / counts.sum(), P2[3], atol=1e-12)
+    assert abs(kept / counts.sum() - 3 / 8) < 1e-12
+    # no earlier occurrence: the uniform model, acceptance rate sum min(p, 1/4)
+    counts, kept = np.zeros(4), 0
+    for d, r, sv in itertools.product(grid(4), grid(8), grid(8)):
+        out, n, _ = decode.speculative_decoding_step(mp, copy, [0, 1, 2], 1, 1.0, [d, r, sv])
+        counts[out[3]] += 1
+        kept += n
+    np.testing.assert_allclose(counts / counts.sum(), P2[2], atol=1e-12)
+    assert abs(kept / counts.sum() - sampling.beta(P2[2], [1 / 4] * 4)) < 1e-12
+    # ... or the fallback model when one is given
+    with np.errstate(divide="ignore"):
+        bigram = drafts.TableDraft(np.log(np.array([Q2[0], Q2[1], Q2[2], Q2[3]])), row_of=[0, 1, 2, 3])
+    both = drafts.CopyDraft(4, 2, fallback=bigram)
+    with np.errstate(divide="ignore"):
+        np.testing.assert_array_equal(both.score([0, 1, 2], 1)[0], np.log(np.array(Q2[2])))
+    assert both.score([0, 3, 1, 0, 3], 1)[0][1] == 0.0
+
+
+def test_copy_draft_on_a_periodic_target_keeps_every_guess():
+    """Closed form: when Mp continues a cycle with certainty and the context already holds one
+    period, every copied guess is Mp's own token, so each run of Algorithm 1 emits gamma + 1
+    tokens (the guesses extend the context they are matched in)."""
+    with np.errstate(divide="ignore"):
+        mp = TableScorer(lambda ctx: [1.0 if t == (ctx[-1] + 1) % 4 else 0.0 for t in range(4)])
+        copy = drafts.CopyDraft(4, 2)
+        for T in (0.0, 1.0):
+            rng = np.random.default_rng(5)
+            rows = (rng.uniform(0.01, 0.99, 7) for _ in range(10))
+            toks, recs = decode.speculative_decode(mp, copy, [0, 1, 2, 3, 0, 1], 12, 3, T, rows)
+            assert toks[6:] == [(2 + i) % 4 for i in range(12)]
+            assert [n for n, _, _ in recs] == [3, 3, 3]
+
+
 def test_uniform_validation():
     mp, mq = table_models()
     with pytest.raises(ValueError):
