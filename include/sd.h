@@ -244,6 +244,28 @@ sd_status sd_set_sampling(sd_ctx* ctx, const sd_sampling* opt);
 sd_status sd_set_table_draft(sd_ctx* ctx, const float* table, const int32_t* row_of, int32_t n_rows);
 
 /*
+ * Section 3.6, the parameter-less approximation model that copies from the
+ * context.  With match > 0 the draft loop of sd_step does no Mq forward: for
+ * each guess the context (the committed tokens of the sequence, then this
+ * iteration's earlier guesses) is searched for earlier occurrences of its own
+ * last `match` tokens; the most recent occurrence that has a successor decides,
+ * and the draft distribution is all mass on that successor.  Without an
+ * occurrence the draft is the table row of sd_set_table_draft when a table is
+ * set, else the uniform distribution (the random model that closes the
+ * section).  The paper names the idea only; this rule is this library's.
+ * The rows go through the same test and adjusted distribution as Mq's would:
+ * a copied guess x is kept with probability p(x).
+ * The token history lives on the device and is kept up by sd_prefill and by
+ * every step taken while match > 0; sequences that advanced with match == 0
+ * must be reset and prefilled before a copying step (SD_ESTATE).
+ *   match : tokens to match, 1..SD_MAX_COPY_MATCH; 0 goes back to the table
+ *           draft or Mq (Mq's cache is stale then, as for sd_set_table_draft)
+ * For T5DEC models the context is the decoder's tokens.  Synchronises the stream.
+ */
+#define SD_MAX_COPY_MATCH 8
+sd_status sd_set_copy_draft(sd_ctx* ctx, int32_t match);
+
+/*
  * Section 3.5 (choosing gamma): the integer gamma in 1..gamma_max that maximises
  * the expected walltime improvement of Theorem 3.8,
  *     (1 - alpha^(gamma+1)) / ((1 - alpha) (gamma c + 1)),

@@ -166,6 +166,8 @@ lib.sd_set_sampling.restype = C.c_int
 lib.sd_set_sampling.argtypes = [C.c_void_p, C.POINTER(_Sampling)]
 lib.sd_set_table_draft.restype = C.c_int
 lib.sd_set_table_draft.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+lib.sd_set_copy_draft.restype = C.c_int
+lib.sd_set_copy_draft.argtypes = [C.c_void_p, C.c_int32]
 lib.sd_measure_cost.restype = C.c_int
 lib.sd_measure_cost.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 lib.sd_autotune_gamma.restype = C.c_int
@@ -304,6 +306,11 @@ class SpecDecoder:
         self._check(lib.sd_set_table_draft(self._ctx, _ptr(table), _ptr(row_of) if row_of is not None else None,
                                            int(table.shape[0])))
         self._draft = (table, row_of)
+
+    def set_copy_draft(self, match: int = 0):
+        """Draft by copying from the context: the token after the most recent earlier occurrence
+        of the last `match` tokens (else the table draft / the uniform model); 0 turns it off."""
+        self._check(lib.sd_set_copy_draft(self._ctx, int(match)))
 
     def measure_cost(self, reps: int = 20):
         """(microseconds of one Mq draft step, microseconds of one standard Mp decoding step)."""

@@ -107,6 +107,60 @@ static __global__ __launch_bounds__(256) void table_row_kernel(
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < V; i += gridDim.x * blockDim.x) out[i] = src[i];
 }
 
+// Copying draft (section 3.6): the context is the committed tokens hist[0, len) of sequence b
+// followed by this iteration's guesses x[0, step).  Its last `match` tokens are searched among
+// their earlier occurrences; the most recent one that has a successor decides: the draft's
+// logits row is 0 at that successor and -inf elsewhere.  Without an occurrence the row is the
+// table row (as in table_row_kernel) or, with no table, all zeros: the uniform model.
+// grid = (slices, sequences); every workgroup repeats the search and writes its slice.
+static __global__ __launch_bounds__(256) void copy_row_kernel(
+    const int* __restrict__ hist, int hist_stride, int match, const float* __restrict__ table,
+    const int* __restrict__ row_of, int n_rows, int V, const SeqState* __restrict__ st, int step,
+    float* __restrict__ dst, size_t seq_stride) {
+  st += blockIdx.y;
+  const int* h = hist + (size_t)blockIdx.y * hist_stride;
+  const int L = min(max(st->len, 0), hist_stride), S = L + step;
+  auto tok = [&](int i) { return i < L ? h[i] : st->x[min(i - L, 15)]; };
+  __shared__ int found;
+  if (threadIdx.x == 0) found = -1;
+  __syncthreads();
+  int best = -1;
+  for (int j = threadIdx.x; j + match < S; j += blockDim.x) {      // occurrence at [j, j+match), successor j+match
+    bool same = true;
+    for (int t = 0; t < match; ++t) same = same && tok(j + t) == tok(S - match + t);
+    if (same) best = j;
+  }
+  if (best >= 0) atomicMax(&found, best);
+  __syncthreads();
+  float* out = dst + (size_t)blockIdx.y * seq_stride;
+  const int i0 = blockIdx.x * blockDim.x + threadIdx.x, di = gridDim.x * blockDim.x;
+  if (found >= 0) {
+    const int x = min(max(tok(found + match), 0), V - 1);
+    for (int i = i0; i < V; i += di) out[i] = (i == x) ? 0.0f : -INFINITY;
+  } else if (table != nullptr) {
+    int prev = (step == 0) ? st->last_tok : st->x[step - 1];
+    prev = min(max(prev, 0), V - 1);
+    int row = (row_of != nullptr) ? row_of[prev] : 0;
+    row = min(max(row, 0), n_rows - 1);
+    const float* src = table + (size_t)row * V;
+    for (int i = i0; i < V; i += di) out[i] = src[i];
+  } else {
+    for (int i = i0; i < V; i += di) out[i] = 0.0f;
+  }
+}
+
+// Keeps the token history that copy_row_kernel searches: after an iteration of Algorithm 1
+// (spec != 0) the n+1 emitted tokens, after a plain decoding step the one new token, at the
+// positions they were committed to.  grid = sequences, 32 threads.
+static __global__ void hist_append_kernel(int* __restrict__ hist, int hist_stride, const SeqState* __restrict__ st, int spec) {
+  st += blockIdx.x;
+  int* h = hist + (size_t)blockIdx.x * hist_stride;
+  const int L = st->len, t = threadIdx.x;
+  const int cnt = spec ? min(max(st->n, 0), 15) + 1 : 1;
+  const int pos = L - cnt + t;
+  if (t < cnt && pos >= 0 && pos < hist_stride) h[pos] = spec ? st->out[t] : st->last_tok;
+}
+
 static __global__ void fill_u32_kernel(unsigned int* p, unsigned int v, size_t n) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

@@ -194,6 +194,12 @@ struct sd_ctx {
   const float* draft_table = nullptr;
   const int* draft_row_of = nullptr;
   int draft_rows = 0;
+  // copying draft: the committed tokens of every sequence, [batch][hist_stride], kept on the
+  // device while copy_match > 0; hist_len = how many of them the device holds
+  int* d_hist = nullptr;
+  int hist_stride = 0, copy_match = 0;
+  std::vector<int> hist_len;
+  bool no_mq() const { return draft_table != nullptr || copy_match > 0; }
   // acceptance statistics for the choice of gamma: they describe the pair and the task, not one
   // sequence, so sd_reset leaves them alone
   int64_t tune_accepted = 0, tune_tested = 0, tune_beta_count = 0;
@@ -214,6 +220,8 @@ void plan_ctx(Arena& A, sd_ctx& c, const sd_model_cfg& pc, const sd_model_cfg& q
   c.q_logits = static_cast<float*>(A.take(B * rt.max_gamma * pc.vocab * sizeof(float)));         // [seq][gamma][V]
   c.d_stats = static_cast<RowStat*>(A.take(B * (2 * SD_MAX_GAMMA + 1) * sizeof(RowStat)));
   c.d_counter = static_cast<unsigned int*>(A.take(B * SAMPLE_COUNTER_STRIDE * sizeof(unsigned int)));
+  c.hist_stride = pc.max_len;
+  c.d_hist = static_cast<int*>(A.take(B * (size_t)pc.max_len * sizeof(int)));
 }
 
 bool rt_ok(const sd_runtime_cfg& rt, std::string& why) {
@@ -525,7 +533,11 @@ void enqueue_step(sd_ctx* c, int gamma, bool profile) {
   const int V = c->p.cfg.vocab, B = c->batch;
   if (profile) hipEventRecord(c->ev[0], s);
   for (int i = 0; i < gamma; ++i) {              // q_i <- Mq(prefix + x_<i), x_i ~ q_i
-    if (c->draft_table)                          // table lookup instead of a forward
+    if (c->copy_match > 0)                       // copied from the context, else the table / uniform
+      hipLaunchKernelGGL(copy_row_kernel, dim3(std::min(32, (V + 255) / 256), B), dim3(256), 0, s, c->d_hist, c->hist_stride,
+                         c->copy_match, c->draft_table, c->draft_row_of, c->draft_rows, V, c->d_state, i,
+                         c->q_logits + (size_t)i * V, (size_t)gamma * V);
+    else if (c->draft_table)                     // table lookup instead of a forward
       hipLaunchKernelGGL(table_row_kernel, dim3(std::min(32, (V + 255) / 256), B), dim3(256), 0, s, c->draft_table,
                          c->draft_row_of, c->draft_rows, V, c->d_state, i, c->q_logits + (size_t)i * V, (size_t)gamma * V);
     else if (i == 0) forward_any(c, c->q, Rows{ROWS_DRAFT_FIRST, 0, 2, 0, 0, B, gamma}, c->q_logits);
@@ -552,6 +564,7 @@ void enqueue_step(sd_ctx* c, int gamma, bool profile) {
   }
   if (c->rt.flags & SD_FLAG_BETA) SD_VERIFY(3, dim3(gamma, B));   // side output: beta_i of every guess, into the states
 #undef SD_VERIFY
+  if (c->copy_match > 0) hipLaunchKernelGGL(hist_append_kernel, dim3(B), dim3(32), 0, s, c->d_hist, c->hist_stride, c->d_state, 1);
   if (profile) hipEventRecord(c->ev[3], s);
 }
 
@@ -560,6 +573,7 @@ void enqueue_baseline(sd_ctx* c) {
   forward_any(c, c->p, Rows{ROWS_BASELINE, 0, 1, 0, 0, B, 0}, c->p_logits);
   hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
                      c->d_params, 0, c->d_state, 1, 0, (size_t)V);
+  if (c->copy_match > 0) hipLaunchKernelGGL(hist_append_kernel, dim3(B), dim3(32), 0, c->stream, c->d_hist, c->hist_stride, c->d_state, 0);
 }
 
 // ------------------------------------------------------------------ loading
@@ -721,7 +735,7 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
     c->own_stream = true;
   }
   const size_t B = (size_t)rt->batch;
-  c->len.assign(B, 0); c->last_tok.assign(B, -1); c->ready.assign(B, 0);
+  c->len.assign(B, 0); c->last_tok.assign(B, -1); c->ready.assign(B, 0); c->hist_len.assign(B, 0);
   if (hipHostMalloc(reinterpret_cast<void**>(&c->h_state), B * sizeof(SeqState), hipHostMallocDefault) != hipSuccess ||
       hipHostMalloc(reinterpret_cast<void**>(&c->h_params), B * sizeof(StepParams), hipHostMallocDefault) != hipSuccess)
     return bail(SD_EHIP, "pinned allocation failed");
@@ -778,7 +792,7 @@ extern "C" sd_status sd_reset(sd_ctx* c, int32_t row) {
   if (!c) return SD_EINVAL;
   if (row < -1 || row >= c->batch) return fail(c, SD_EINVAL, "row must be -1 or a sequence index");
   for (int b = 0; b < c->batch; ++b)
-    if (row == -1 || row == b) { c->ready[b] = 0; c->len[b] = 0; c->last_tok[b] = -1; }
+    if (row == -1 || row == b) { c->ready[b] = 0; c->len[b] = 0; c->last_tok[b] = -1; c->hist_len[b] = 0; }
   c->state = 0;
   if (row == -1) c->stats = sd_stats{};
   return SD_OK;
@@ -794,7 +808,7 @@ extern "C" sd_status sd_prefill(sd_ctx* c, int32_t row, const int32_t* prompt, i
   const int room = std::min(pc.max_len, qc.max_len);
   if (n + c->rt.max_gamma + 1 > room) return fail(c, SD_ERANGE, "prompt + max_gamma + 1 exceeds max_len");
   for (int i = 0; i < n; ++i) if (prompt[i] < 0 || prompt[i] >= pc.vocab) return fail(c, SD_ERANGE, "token id out of range");
-  c->state = 0; c->ready[row] = 0;
+  c->state = 0; c->ready[row] = 0; c->hist_len[row] = 0;
   Model* ms[2] = {&c->p, &c->q};
   const void* encs[2] = {enc_p, enc_q};
   for (int k = 0; k < 2; ++k) {
@@ -813,9 +827,10 @@ extern "C" sd_status sd_prefill(sd_ctx* c, int32_t row, const int32_t* prompt, i
   for (int i = 0; i < 16; ++i) { st.x[i] = 0; st.out[i] = -1; }
   c->h_state[row] = st;
   HIP_TRY(c, hipMemcpyAsync(c->d_state + row, c->h_state + row, sizeof(SeqState), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->d_hist + (size_t)row * c->hist_stride, prompt, (size_t)n * sizeof(int), hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   HIP_TRY(c, hipGetLastError());
-  c->ready[row] = 1; c->len[row] = n; c->last_tok[row] = prompt[n - 1];
+  c->ready[row] = 1; c->len[row] = n; c->last_tok[row] = prompt[n - 1]; c->hist_len[row] = n;
   c->state = 1;
   for (int b = 0; b < c->batch; ++b) if (!c->ready[b]) c->state = 0;      // READY once every sequence is prefilled
   return SD_OK;
@@ -835,7 +850,10 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
   if (gamma < 1 || gamma > c->rt.max_gamma) return fail(c, SD_EINVAL, "gamma out of range");
   const int B = c->batch;
   if (c->state == 0) return fail(c, SD_ESTATE, "sd_step before every sequence was prefilled");
-  if (c->state == 2 && !c->draft_table) return fail(c, SD_ESTATE, "Mq cache is stale (after sd_step_baseline or table drafts): reset and prefill");
+  if (c->state == 2 && !c->no_mq()) return fail(c, SD_ESTATE, "Mq cache is stale (after sd_step_baseline or drafts without Mq): reset and prefill");
+  if (c->copy_match > 0)
+    for (int b = 0; b < B; ++b)
+      if (c->hist_len[b] != c->len[b]) return fail(c, SD_ESTATE, "token history incomplete: choose the copying draft before prefill");
   if (prefix && B > 1) return fail(c, SD_EINVAL, "the prefix check is for single-sequence contexts");
   if (prefix && (prefix_len != c->len[0] || prefix[prefix_len - 1] != c->last_tok[0]))
     return fail(c, SD_ESTATE, "prefix does not match the committed sequence");
@@ -886,6 +904,7 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
     out_n[b] = hs.n;
     for (int i = 0; i <= gamma; ++i) out_tokens[(size_t)b * (gamma + 1) + i] = (i <= hs.n) ? hs.out[i] : -1;
     c->len[b] = hs.len; c->last_tok[b] = hs.last_tok;
+    if (c->copy_match > 0) c->hist_len[b] = hs.len;
     c->stats.tokens += hs.n + 1; c->stats.accepted += hs.n;
     fallbacks += hs.fallbacks;
     const int tested = std::min(hs.n + 1, gamma);          // guesses whose test decided something
@@ -955,6 +974,7 @@ extern "C" sd_status sd_step_baseline(sd_ctx* c, float temperature, const float*
     if (c->h_state[b].len != c->len[b] + 1) return fail(c, SD_EHIP, "device state inconsistent after baseline step");
   for (int b = 0; b < B; ++b) {
     out_token[b] = c->h_state[b].last_tok;
+    if (c->copy_match > 0 && c->hist_len[b] == c->len[b]) c->hist_len[b] = c->h_state[b].len;
     c->len[b] = c->h_state[b].len; c->last_tok[b] = c->h_state[b].last_tok;
   }
   c->state = 2;
@@ -994,10 +1014,22 @@ extern "C" sd_status sd_set_table_draft(sd_ctx* c, const float* table, const int
   if (table == nullptr && (row_of != nullptr || n_rows != 0)) return fail(c, SD_EINVAL, "no table: row_of must be NULL and n_rows 0");
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   for (auto& g : c->graphs) if (g) { hipGraphExecDestroy(g); g = nullptr; }     // the captured draft loop changes
-  const bool was_table = c->draft_table != nullptr;
+  const bool without = c->no_mq();
   c->draft_table = table; c->draft_row_of = table ? row_of : nullptr; c->draft_rows = table ? n_rows : 0;
-  // table drafts leave Mq's cache behind: going back to Mq needs the sequences prefilled again
-  if (was_table && table == nullptr && c->state == 1) c->state = 2;
+  // drafts without Mq leave its cache behind: going back to Mq needs the sequences prefilled again
+  if (without && !c->no_mq() && c->state == 1) c->state = 2;
+  return SD_OK;
+}
+
+extern "C" sd_status sd_set_copy_draft(sd_ctx* c, int32_t match) {
+  if (!c) return SD_EINVAL;
+  if (match < 0 || match > SD_MAX_COPY_MATCH) return fail(c, SD_EINVAL, "match must lie in [0, SD_MAX_COPY_MATCH]");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (auto& g : c->graphs) if (g) { hipGraphExecDestroy(g); g = nullptr; }     // the captured launches change
+  if (c->graph_baseline) { hipGraphExecDestroy(c->graph_baseline); c->graph_baseline = nullptr; }
+  const bool without = c->no_mq();
+  c->copy_match = match;
+  if (without && !c->no_mq() && c->state == 1) c->state = 2;
   return SD_OK;
 }
 
@@ -1036,7 +1068,7 @@ extern "C" sd_status sd_measure_cost(sd_ctx* c, int32_t reps, double* mq_us, dou
   if (!c || !mq_us || !mp_us) return SD_EINVAL;
   if (reps < 1 || reps > 1000) return fail(c, SD_EINVAL, "reps must be 1..1000");
   if (c->state != 1) return fail(c, SD_ESTATE, "sd_measure_cost needs a prefilled sequence with a valid Mq cache");
-  if (c->draft_table) return fail(c, SD_ESTATE, "sd_measure_cost times Mq: clear the draft table first");
+  if (c->no_mq()) return fail(c, SD_ESTATE, "sd_measure_cost times Mq: clear the table / copying draft first");
   const int V = c->p.cfg.vocab, B = c->batch;
   if (c->rt.max_gamma < 2) return fail(c, SD_EINVAL, "sd_measure_cost needs max_gamma >= 2 (it runs a second draft step)");
   for (int b = 0; b < B; ++b)

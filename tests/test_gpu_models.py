@@ -618,6 +618,95 @@ def test_table_drafts_match_oracle(kind):
     dec.close()
 
 
+@pytest.mark.parametrize("match,fallback,T", [(1, "uniform", 1.0), (2, "bigram", 1.0), (2, "uniform", 0.0)])
+def test_copy_drafts_match_oracle(match, fallback, T):
+    """Section 3.6: the model that copies from the context in place of Mq.  Two sequences of the
+    tiny fp32 target whose prompts use five token ids (so earlier occurrences exist), against
+    the oracle run with its own copying model; a plain decoding step in between and a new
+    prefill of one sequence must keep the token history on the device right."""
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    V = cfg_p["vocab"]
+    batch, gamma = 2, 4
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=1, batch=batch)
+    tdraft = None
+    if fallback == "bigram":
+        ref = oracle_models(cfg_p, w_p, cfg_q, w_q)[0]
+        rows = np.stack([ref.score([2 * r], 1)[0] for r in range(V // 2)]).astype(np.float32)
+        table = (torch.from_numpy(rows) + synth.counter_normal((V // 2, V), 203, 1.0).float()).contiguous()
+        row_of = torch.arange(V, dtype=torch.int32) // 2
+        dec.set_table_draft(table.cuda(), row_of.cuda())
+        tdraft = drafts.TableDraft(table.numpy(), row_of.numpy())
+    dec.set_copy_draft(match)
+    cdraft = drafts.CopyDraft(V, match, fallback=tdraft)
+    prefixes = [[int(t) % 5 for t in synth.random_tokens(70 + b, 12 + 7 * b, V)] for b in range(batch)]
+    targets = [oracle_models(cfg_p, w_p, cfg_q, w_q)[0] for _ in range(batch)]
+    for b in range(batch):
+        dec.prefill(prefixes[b], row=b)
+    U = synth.uniform_stream(62, 20 * batch * 9).reshape(20, batch, 9)
+    tolerated, kept, copied = 0, 0, 0
+    for it in range(14):
+        if it == 5:                                  # one standard decoding step: the history must follow
+            toks = dec.step_baseline(T, U[it, :, 0])
+            for b in range(batch):
+                want = decode.plain_decode(targets[b], prefixes[b], 1, T, [U[it, b, 0]])[-1]
+                assert toks[b] == want
+                prefixes[b] = prefixes[b] + [toks[b]]
+            continue
+        if it == 9:                                  # sequence 1 starts over with another prompt
+            dec.reset(row=1)
+            prefixes[1] = [int(t) % 5 for t in synth.random_tokens(77, 9, V)]
+            targets[1] = oracle_models(cfg_p, w_p, cfg_q, w_q)[0]
+            dec.prefill(prefixes[1], row=1)
+        res = dec.step(gamma, T, U[it])
+        zq = dec.logits(1, batch * gamma).reshape(batch, gamma, V)
+        for b in range(batch):
+            new_o, n_o, info = decode.speculative_decoding_step(targets[b], cdraft, prefixes[b], gamma, T, U[it, b])
+            np.testing.assert_array_equal(zq[b], info["q_logits"].astype(np.float32))   # one-hot, table or zero rows
+            copied += int(np.isneginf(zq[b]).any(axis=1).sum())
+            if new_o[len(prefixes[b]):] != res[b][1]:
+                assert T > 0 and np.min(info["margins"]) < 1e-3
+                tolerated += 1
+            kept += res[b][0]
+            prefixes[b] = prefixes[b] + res[b][1]
+    assert tolerated <= 1 and copied > 10 and kept < 13 * batch * gamma
+    dec.set_copy_draft(0)
+    if fallback == "uniform":
+        with pytest.raises(binding.SdError):
+            dec.step(gamma, T, U[14])               # back to Mq, whose cache was not kept up
+    else:
+        dec.step(gamma, T, U[14])                   # the table draft alone goes on
+    dec.close()
+
+
+def test_copy_draft_needs_the_whole_history():
+    """Steps taken without the copying draft do not record tokens: turning it on afterwards is
+    refused until the sequence is prefilled again; the match length is range-checked."""
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    V = cfg_p["vocab"]
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=4, flags=0)
+    prompt = synth.random_tokens(9, 6, V)
+    dec.prefill(prompt)
+    u = synth.uniform_stream(3, 3 * 9).reshape(3, 9)
+    for bad in (-1, 9):
+        with pytest.raises(binding.SdError) as e:
+            dec.set_copy_draft(bad)
+        assert e.value.status == binding.SD_EINVAL
+    dec.step(4, 1.0, u[0])                          # with Mq
+    dec.set_copy_draft(2)
+    with pytest.raises(binding.SdError) as e:
+        dec.step(4, 1.0, u[1])
+    assert e.value.status == binding.SD_ESTATE
+    with pytest.raises(binding.SdError):
+        dec.measure_cost(2)                         # times Mq, which this draft does not run
+    dec.reset()
+    dec.prefill(prompt)
+    n, toks = dec.step(4, 1.0, u[1])
+    assert 0 <= n <= 4 and len(toks) == n + 1
+    dec.close()
+
+
 def test_error_paths_of_the_options_and_of_batches():
     """Argument checks of sd_set_sampling, sd_set_table_draft, sd_measure_cost and the batched
     calls; a refused call changes nothing: the next step gives the tokens of an untouched run."""
