@@ -304,31 +304,275 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   SD_STAMP(5);
 }
 
-// Combines the partial results of the key ranges of one (sequence, kv head): with
-// m = max m_s, the output is sum_s acc_s e^(m_s - m) / sum_s l_s e^(m_s - m), ranges taken in
-// order.  grid = (kv heads, 1, sequences), one thread per (row, query head, feature).
-template <typename T, int DH>
-static __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnArgs a) {
-  const int hkv = blockIdx.x, G = a.H / a.Hkv, RG = a.R * G;
-  const int r_base = ((int)blockIdx.z / a.spg) * MAX_ROWS + ((int)blockIdx.z % a.spg) * a.R;
-  const float* pp = a.partial + (((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit) * ATTN_MAX_RG * (DH + 2);
-  T* og = static_cast<T*>(a.out);
-  for (int i = threadIdx.x; i < RG * DH; i += blockDim.x) {
-    const int rg = i / DH, d = i % DH, r = rg / G, h = hkv * G + rg % G;
-    float m = -INFINITY;
-    for (int sp = 0; sp < a.nsplit; ++sp) m = fmaxf(m, pp[((size_t)sp * ATTN_MAX_RG + rg) * (DH + 2) + DH]);
-    float L = 0.0f, o = 0.0f;
-    for (int sp = 0; sp < a.nsplit; ++sp) {
-      const float* q = pp + ((size_t)sp * ATTN_MAX_RG + rg) * (DH + 2);
-      const float ms = q[DH];
-      if (ms != -INFINITY) {                       // empty ranges left no output behind
-        const float w = __expf(ms - m);
-        L += q[DH + 1] * w;
-        o += q[d] * w;
+// Long contexts, bf16: the same key-range workgroups as attn_kernel with nsplit > 1, but the
+// two products run on the matrix cores, because with thousands of keys the vector ALUs, not
+// the loads, bound attn_kernel (gamma+1 rows x 4 query heads per kv head: about 1.3 M
+// multiply-adds per 256 keys).  A workgroup has four wavefronts that never synchronise inside
+// the key loop; each walks every fourth 32-key step of the range with its own running maximum,
+// denominator and output, all in registers:
+//   S^T = K Q^T   16x16x32 MFMA, A = 16 keys x 32 features straight from the cache rows,
+//                 B = the query rows (rows x heads of the kv head, zero-padded to 16 or 32),
+//                 kept in registers for the whole kernel.  Which features a lane holds is free
+//                 as long as both operands agree: lane (key, quarter kq) reads the contiguous
+//                 quarter kq of its key's row.  A lane ends up with the scores of one query
+//                 row for 8 keys, so the softmax needs two lane exchanges per step only.
+//   O^T = V^T P   A = 16 features x 32 keys: V is key-major in the cache, so every wavefront
+//                 transposes its 32 x d_head tile through a private LDS region (2-byte
+//                 writes, one 16-byte read per feature tile); B = the probabilities the lane
+//                 already holds, each as the sum of two bf16 numbers (two MFMAs).
+// The wavefronts' results are merged through LDS and left in `partial` for attn_merge_kernel
+// exactly as attn_kernel leaves them.  Every row's arithmetic is independent of the other rows.
+// dynamic LDS: max(4 x d_head x 32 bf16 staging, 4 x RG x (d_head + 2) floats for the merge).
+__device__ __forceinline__ bf16x8 ld_frag(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+__device__ __forceinline__ bf16x8 zero_frag() {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  return __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+}
+// D[m][n] += sum_k A[m][k] B[n][k]: lane (lane % 16, lane / 16) holds A[m][8 kq .. 8 kq + 8) and the
+// same of B; element r of the result is D[4 (lane / 16) + r][lane % 16]
+__device__ __forceinline__ f32x4 mma_bf16(const bf16x8& a, const bf16x8& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+constexpr int ATTN_LONG_WAVES = 4;
+constexpr float ATTN_LONG_SLACK = 6.0f;      // how far scores may outgrow the softmax reference point before it moves
+constexpr size_t attn_long_lds_bytes(int rg, int dh) {
+  const size_t stage = (size_t)ATTN_LONG_WAVES * dh * 32 * 2, merge = (size_t)ATTN_LONG_WAVES * rg * (dh + 2) * 4;
+  return stage > merge ? stage : merge;
+}
+
+template <int DH, int NRT>
+static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(const AttnArgs a) {
+  extern __shared__ float lds[];
+  __shared__ int s_pos[MAX_ROWS];
+  __shared__ int s_pt[ATTN_LDS_PAGES];
+  constexpr int KSQ = DH / 32;                     // k-steps of the score product
+  constexpr int DT = DH / 16;                      // 16-feature tiles of the output
+  constexpr int NW = ATTN_LONG_WAVES;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, kq = lane >> 4;
+  const int hkv = blockIdx.x;
+  const int split = (int)blockIdx.y % a.nsplit;
+  const int rs = ((int)blockIdx.y / a.nsplit) * a.rows_per_wg;
+  const int R = min(a.rows_per_wg, a.R - rs);
+  const int r0 = ((int)blockIdx.z / a.spg) * MAX_ROWS + ((int)blockIdx.z % a.spg) * a.R + rs;
+  const int* page_table = a.page_table + (size_t)(a.seq0 + blockIdx.z) * a.pt_stride;
+  const int G = a.H / a.Hkv, RG = R * G;
+  if (tid < MAX_ROWS) s_pos[tid] = (tid < R) ? a.row_pos[r0 + tid] : -1;
+  for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += 64 * NW) s_pt[i] = page_table[i];
+  __syncthreads();
+  int kv_len = 0;
+  for (int r = 0; r < R; ++r) kv_len = max(kv_len, s_pos[r] + 1);
+  const int k_begin = split * a.split_keys;
+  float* pp = a.partial + ((((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
+  if (k_begin >= kv_len) {                          // nothing in this key range yet: an empty partial
+    if (tid < RG) { pp[(size_t)tid * (DH + 2) + DH] = -INFINITY; pp[(size_t)tid * (DH + 2) + DH + 1] = 0.0f; }
+    return;
+  }
+  kv_len = min(kv_len, k_begin + a.split_keys);
+  const int page_shift = __ffs(a.page_size) - 1, page_mask = a.page_size - 1;
+  const bf16* pool = static_cast<const bf16*>(a.kv_pool);
+  auto row_ptr = [&](int key, int which) -> const bf16* {
+    const int page = s_pt[key >> page_shift], slot = key & page_mask;
+    return pool + ((((size_t)page * 2 + which) * a.Hkv + hkv) * a.page_size + slot) * DH;
+  };
+
+  // query rows of this lane: rg = rt * 16 + j; features kq * DH/4 + s * 8 .. + 8 in k-step s
+  bf16x8 qf[NRT][KSQ];
+  int pos[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    const int rg = rt * 16 + j;
+    const bool ok = rg < RG;
+    const int rgc = ok ? rg : 0;
+    pos[rt] = ok ? s_pos[rgc / G] : -1;
+    const bf16* qp = static_cast<const bf16*>(a.q) + (size_t)(r0 + rgc / G) * a.H * DH + (size_t)(hkv * G + rgc % G) * DH + kq * (DH / 4);
+#pragma unroll
+    for (int s = 0; s < KSQ; ++s) qf[rt][s] = ok ? ld_frag(qp + s * 8) : zero_frag();
+  }
+  float m_run[NRT], l_run[NRT];
+  f32x4 o[DT][NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    m_run[rt] = -INFINITY; l_run[rt] = 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  unsigned short* vt = reinterpret_cast<unsigned short*>(lds) + (size_t)wave * DH * 32;   // [DH][32 key places]
+  const int vkey = lane & 31, vhalf = lane >> 5;
+  // place of key 16 a + 4 q + i in a row of vt: 8 q + 4 a + i, so that quarter q reads 8 places in one piece
+  const int vplace = ((vkey >> 2) & 3) * 8 + (vkey >> 4) * 4 + (vkey & 3);
+
+  // The loads of a step are issued one step ahead, into the registers the previous step has
+  // just finished with (K after the score product, V after the transposition), so a
+  // wavefront's load latency overlaps its own arithmetic.
+  bf16x8 kf[2][KSQ];
+  bf16x8 vr[DH / 16];
+  auto load_k = [&](int kb) {                       // always issued: past the range every lane re-reads the last key
+    kb = min(kb, kv_len - 1);
+    const int nk = min(32, kv_len - kb);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      const bf16* kp = row_ptr(kb + min(kt * 16 + j, nk - 1), 0) + kq * (DH / 4);
+#pragma unroll
+      for (int s = 0; s < KSQ; ++s) kf[kt][s] = ld_frag(kp + s * 8);
+    }
+  };
+  auto load_v = [&](int kb) {
+    kb = min(kb, kv_len - 1);
+    const int nk = min(32, kv_len - kb);
+    const bf16* vp = row_ptr(kb + min(vkey, nk - 1), 1) + vhalf * (DH / 2);
+#pragma unroll
+    for (int c = 0; c < DH / 16; ++c) vr[c] = ld_frag(vp + c * 8);
+  };
+  const int kb0 = k_begin + wave * 32;
+  load_k(kb0); load_v(kb0);                         // out-of-range keys re-read the last valid one and get probability 0
+  for (int kb = kb0; kb < kv_len; kb += NW * 32) {
+    const int nkeys = min(32, kv_len - kb);
+    const int kb_next = kb + NW * 32;
+    // ---- scores: sc[kt][rt][r] = S[key kb + kt*16 + kq*4 + r][row rt*16 + j] ----
+    f32x4 sc[2][NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        sc[kt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KSQ; ++s) sc[kt][rt] = mma_bf16(kf[kt][s], qf[rt][s], sc[kt][rt]);
+      }
+    load_k(kb_next);                                 // no branch around loads: the compiler would wait for all of them
+    float p[2][NRT][4];
+    float f[NRT];
+    bool rescale = false;
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int kl = kt * 16 + kq * 4 + r;
+          const bool ok = kl < nkeys && kb + kl <= pos[rt];
+          p[kt][rt][r] = ok ? a.scale * sc[kt][rt][r] : -INFINITY;
+          mx = fmaxf(mx, p[kt][rt][r]);
+        }
+      mx = lane_combine<16>(mx, OpMaxF());
+      mx = lane_combine<32>(mx, OpMaxF());
+      // the reference point m_run only moves when the scores outgrow it by more than
+      // ATTN_LONG_SLACK: probabilities stay below e^slack, and most steps need no rescaling
+      const float m_new = (mx > m_run[rt] + ATTN_LONG_SLACK || m_run[rt] == -INFINITY) ? fmaxf(m_run[rt], mx) : m_run[rt];
+      f[rt] = (m_new == m_run[rt]) ? 1.0f : ((m_run[rt] == -INFINITY) ? 0.0f : __expf(m_run[rt] - m_new));
+      rescale = rescale || (f[rt] != 1.0f);
+      float sum = 0.0f;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float e = (p[kt][rt][r] == -INFINITY) ? 0.0f : __expf(p[kt][rt][r] - m_new);
+          p[kt][rt][r] = e;
+          sum += e;
+        }
+      l_run[rt] = l_run[rt] * f[rt] + sum;          // this lane's keys only; the quarters are added at the end
+      m_run[rt] = m_new;
+    }
+    // ---- V tile -> LDS, transposed ----
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");     // the reads of the previous step are done
+#pragma unroll
+    for (int c = 0; c < DH / 16; ++c) {
+      typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+      const u16x8 bits = __builtin_bit_cast(u16x8, vr[c]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vt[(vhalf * (DH / 2) + c * 8 + e) * 32 + vplace] = bits[e];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");     // writes land before this wavefront reads them back
+    load_v(kb_next);
+    // ---- O^T = f O^T + V^T P;  p as the sum of two bf16 numbers (16 mantissa bits): the
+    //      matrix cores have time to spare ----
+    bf16x8 pf[NRT], pl[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float v = p[e >> 2][rt][e & 3];
+        pf[rt][e] = (bf16)v;
+        pl[rt][e] = (bf16)(v - (float)pf[rt][e]);
+      }
+    if (__builtin_amdgcn_ballot_w64(rescale) != 0ull) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) o[dt][rt][r] *= f[rt];
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vt + (dt * 16 + j) * 32 + kq * 8);
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        o[dt][rt] = mma_bf16(vf, pl[rt], o[dt][rt]);
+        o[dt][rt] = mma_bf16(vf, pf[rt], o[dt][rt]);
       }
     }
-    Store<T>::st(og + (size_t)(r_base + r) * a.H * DH + h * DH + d, (L > 0.0f) ? o / L : 0.0f);
   }
+
+  // ---- merge the wavefronts: each leaves (m, l, O) of its keys in LDS ----
+  __syncthreads();                                  // staging region no longer in use
+  float* mg = lds + (size_t)wave * RG * (DH + 2);
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    float l = lane_combine<16>(l_run[rt], OpSumF());
+    l = lane_combine<32>(l, OpSumF());
+    const int rg = rt * 16 + j;
+    if (rg < RG) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mg[(size_t)rg * (DH + 2) + dt * 16 + kq * 4 + r] = o[dt][rt][r];
+      if (kq == 0) { mg[(size_t)rg * (DH + 2) + DH] = m_run[rt]; mg[(size_t)rg * (DH + 2) + DH + 1] = l; }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < RG * (DH + 2); i += 64 * NW) {
+    const int rg = i / (DH + 2), d = i % (DH + 2);
+    float m = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) m = fmaxf(m, lds[((size_t)w * RG + rg) * (DH + 2) + DH]);
+    float out = m;                                   // d == DH: the maximum itself
+    if (d != DH) {
+      out = 0.0f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {                 // wavefronts in order; d == DH + 1 sums the denominators
+        const float mw = lds[((size_t)w * RG + rg) * (DH + 2) + DH];
+        if (mw != -INFINITY) out += lds[((size_t)w * RG + rg) * (DH + 2) + d] * __expf(mw - m);
+      }
+    }
+    pp[i] = out;
+  }
+}
+
+// Combines the partial results of the key ranges of one (sequence, kv head): with
+// m = max m_s, the output is sum_s acc_s e^(m_s - m) / sum_s l_s e^(m_s - m), ranges taken in
+// order.  grid = (kv heads, rows x query heads of the kv head, sequences), one thread per feature.
+template <typename T, int DH>
+static __global__ __launch_bounds__(DH) void attn_merge_kernel(const AttnArgs a) {
+  const int hkv = blockIdx.x, G = a.H / a.Hkv, rg = blockIdx.y, d = threadIdx.x;
+  const int r_base = ((int)blockIdx.z / a.spg) * MAX_ROWS + ((int)blockIdx.z % a.spg) * a.R;
+  const float* pp = a.partial + ((((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit) * ATTN_MAX_RG + rg) * (DH + 2);
+  const size_t stride = (size_t)ATTN_MAX_RG * (DH + 2);
+  float m = -INFINITY;
+  for (int sp = 0; sp < a.nsplit; ++sp) m = fmaxf(m, pp[sp * stride + DH]);
+  float L = 0.0f, o = 0.0f;
+  for (int sp = 0; sp < a.nsplit; ++sp) {
+    const float* q = pp + sp * stride;
+    const float ms = q[DH];
+    if (ms != -INFINITY) {                         // empty ranges left no output behind
+      const float w = __expf(ms - m);
+      L += q[DH + 1] * w;
+      o += q[d] * w;
+    }
+  }
+  const int r = rg / G, h = hkv * G + rg % G;
+  Store<T>::st(static_cast<T*>(a.out) + (size_t)(r_base + r) * a.H * DH + h * DH + d, (L > 0.0f) ? o / L : 0.0f);
 }
 
 }  // namespace sd

@@ -12,6 +12,7 @@
 #include <map>
 #include <new>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/sd.h"
@@ -330,14 +331,23 @@ void launch_attn(hipStream_t s, const Model& m, AttnArgs a, int nseq) {
   if (a.nsplit > 1) a.rows_per_wg = a.R;          // the key ranges already spread the work
   const size_t lds = attn_lds_bytes(a.rows_per_wg * G, DH);
   const dim3 grid(a.Hkv, ((a.R + a.rows_per_wg - 1) / a.rows_per_wg) * a.nsplit, nseq), block(ATTN_THREADS);
-  if (DH == 32) hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, lds, s, a);
+  // long bf16 contexts without a position bias: the matrix-core variant of the key-range workgroups
+  if (std::is_same<T, bf16>::value && a.nsplit > 1 && a.rel_bias == nullptr && (DH == 64 || DH == 128)) {
+    const int RG = a.rows_per_wg * G;
+    const size_t ll = attn_long_lds_bytes(RG, DH);
+    const dim3 lb(64 * ATTN_LONG_WAVES);
+    if (DH == 64 && RG <= 16) hipLaunchKernelGGL((attn_long_kernel<64, 1>), grid, lb, ll, s, a);
+    else if (DH == 64) hipLaunchKernelGGL((attn_long_kernel<64, 2>), grid, lb, ll, s, a);
+    else if (RG <= 16) hipLaunchKernelGGL((attn_long_kernel<128, 1>), grid, lb, ll, s, a);
+    else hipLaunchKernelGGL((attn_long_kernel<128, 2>), grid, lb, ll, s, a);
+  } else if (DH == 32) hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, lds, s, a);
   else if (DH == 64) hipLaunchKernelGGL((attn_kernel<T, 64>), grid, block, lds, s, a);
   else hipLaunchKernelGGL((attn_kernel<T, 128>), grid, block, lds, s, a);
   if (a.nsplit > 1) {
-    const dim3 mg(a.Hkv, 1, nseq), mb(256);
-    if (DH == 32) hipLaunchKernelGGL((attn_merge_kernel<T, 32>), mg, mb, 0, s, a);
-    else if (DH == 64) hipLaunchKernelGGL((attn_merge_kernel<T, 64>), mg, mb, 0, s, a);
-    else hipLaunchKernelGGL((attn_merge_kernel<T, 128>), mg, mb, 0, s, a);
+    const dim3 mg(a.Hkv, a.R * G, nseq);
+    if (DH == 32) hipLaunchKernelGGL((attn_merge_kernel<T, 32>), mg, dim3(32), 0, s, a);
+    else if (DH == 64) hipLaunchKernelGGL((attn_merge_kernel<T, 64>), mg, dim3(64), 0, s, a);
+    else hipLaunchKernelGGL((attn_merge_kernel<T, 128>), mg, dim3(128), 0, s, a);
   }
 }
 

@@ -570,6 +570,55 @@ def test_long_context_spans_several_key_blocks(d_head, ctx):
     dec.close()
 
 
+@pytest.mark.parametrize("d_head,n_heads,n_kv,gamma,ctx", [(128, 8, 2, 4, 1500), (64, 4, 2, 3, 1100),
+                                                           (64, 8, 2, 5, 1200), (128, 2, 2, 3, 1300)])
+def test_long_context_bf16_matrix_core_attention(d_head, n_heads, n_kv, gamma, ctx):
+    """bf16 models with contexts beyond 1024 positions take the matrix-core attention kernel
+    (key ranges over workgroups, four wavefronts per range, merge).  (gamma+1) x (query heads per
+    kv head) = 20, 8, 24 (the most the kernels take) and 4 rows per kv head; two sequences of
+    different length, so ranges are full, ragged and empty; against the oracle.  The same
+    sequence decoded alone must give bit-identical logits: a row does not see its neighbours."""
+    cfg = synth.model_cfg(T.GQA, 2, n_heads * d_head, n_heads, 256, 512, ctx + 64, d_head=d_head, n_kv_heads=n_kv,
+                          dtype="bf16", logit_scale=4.0)
+    w = synth.random_weights(cfg, 9, w_std=0.1)
+    cfg_q, w_q = synth.truncated_noisy_copy(cfg, w, 1, 59, 0.02)
+    batch = 2
+    dec = make_decoder(cfg, w, cfg_q, w_q, max_gamma=gamma, flags=1, batch=batch)
+    solo = make_decoder(cfg, w, cfg_q, w_q, max_gamma=gamma, flags=1)
+    prefixes = [[int(t) for t in synth.random_tokens(70 + b, ctx - 700 * b, cfg["vocab"])] for b in range(batch)]
+    scorers = [oracle_models(cfg, w, cfg_q, w_q) for _ in range(batch)]
+    for b in range(batch):
+        dec.prefill(prefixes[b], row=b)
+    solo.prefill(prefixes[0])
+    U = synth.uniform_stream(41, 3 * batch * (2 * gamma + 1)).reshape(3, batch, -1)
+    worst = 0.0
+    for it in range(3):
+        res = dec.step(gamma, 1.0, U[it])
+        zp32 = dec.logits(0, batch * (gamma + 1)).reshape(batch, gamma + 1, -1)
+        zq32 = dec.logits(1, batch * gamma).reshape(batch, gamma, -1)
+        assert solo.step(gamma, 1.0, U[it, 0]) == res[0]
+        np.testing.assert_array_equal(solo.logits(0, gamma + 1), zp32[0])
+        np.testing.assert_array_equal(solo.logits(1, gamma), zq32[0])
+        zp, zq = zp32.astype(np.float64), zq32.astype(np.float64)
+        assert np.isfinite(zp).all() and np.isfinite(zq).all()
+        for b in range(batch):
+            x_s, n_s, t_s, info, _, _ = level_s(zp[b], zq[b], U[it, b], gamma, 1.0)
+            assert res[b] == (n_s, x_s[:n_s] + [t_s]) or np.min(info["margins"]) < 1e-3
+            sp, sq = scorers[b]
+            zq_o = np.stack([sq.score(prefixes[b] + x_s[:i], 1)[0] for i in range(gamma)])
+            zp_o = sp.score(prefixes[b] + x_s, gamma + 1)
+            worst = max(worst, rel_err(zq[b], zq_o), rel_err(zp[b], zp_o))
+            prefixes[b] = prefixes[b] + res[b][1]
+    print(f"bf16, d_head {d_head}, {n_heads}/{n_kv} heads, context {ctx}: worst logit error {worst:.2e}")
+    assert worst <= TOL["bf16"]
+    dec.step_baseline(1.0, U[0, :, 0])                    # one row per sequence through the same kernel
+    zb = dec.logits(2, batch).astype(np.float64)
+    for b in range(batch):
+        assert rel_err(zb[b], scorers[b][0].score(prefixes[b], 1)[0]) <= TOL["bf16"]
+    dec.close()
+    solo.close()
+
+
 @pytest.mark.parametrize("kind", ["unigram", "bigram"])
 def test_table_drafts_match_oracle(kind):
     """Section 3.6: an n-gram table in place of Mq.  Two sequences of the tiny fp32 target with a
