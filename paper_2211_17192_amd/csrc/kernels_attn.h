@@ -34,11 +34,18 @@ namespace sd {
 #ifdef SD_KTIME
 // Build-time instrumentation (off by default): block 0 accumulates the time it
 // spends in each phase, in ticks of the constant 100 MHz clock.
-__device__ unsigned long long g_ktime[64];
+__device__ unsigned long long g_ktime[96];   // [64, 96): attn_long_kernel
 #define SD_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) { const unsigned long long t_ = wall_clock64(); \
     atomicAdd(&g_ktime[kt_base + (i)], t_ - kt_last); kt_last = t_; } } while (0)
+// per-workgroup timeline of attn_long_kernel launches with 640 workgroups: start, end, HW_ID, XCC_ID
+__device__ unsigned long long g_wgtrace[640 * 4];
+#define SD_STAMPL(i) do { if (blockIdx.x == 0 && split == 0 && threadIdx.x == 0) { const unsigned long long t_ = wall_clock64(); \
+    atomicAdd(&g_ktime[64 + (i)], t_ - kt_last); kt_last = t_; } } while (0)
+#define SD_WAIT_VM8() __builtin_amdgcn_s_waitcnt(0x0F78)     // vmcnt(8): makes the load wait its own phase
 #else
 #define SD_STAMP(i) do { } while (0)
+#define SD_STAMPL(i) do { } while (0)
+#define SD_WAIT_VM8() do { } while (0)
 #endif
 
 constexpr int ATTN_THREADS = 1024;
@@ -313,16 +320,18 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
 //   S^T = K Q^T   16x16x32 MFMA, A = 16 keys x 32 features straight from the cache rows,
 //                 B = the query rows (rows x heads of the kv head, zero-padded to 16 or 32),
 //                 kept in registers for the whole kernel.  Which features a lane holds is free
-//                 as long as both operands agree: lane (key, quarter kq) reads the contiguous
-//                 quarter kq of its key's row.  A lane ends up with the scores of one query
-//                 row for 8 keys, so the softmax needs two lane exchanges per step only.
+//                 as long as both operands agree: in k-step s the four quarters of a key read
+//                 64 contiguous bytes of its row (features 32 s + 8 kq ..).  A lane ends up with
+//                 the scores of one query row for 8 keys, so the softmax needs two lane
+//                 exchanges per step only.
 //   O^T = V^T P   A = 16 features x 32 keys: V is key-major in the cache, so every wavefront
-//                 transposes its 32 x d_head tile through a private LDS region (2-byte
-//                 writes, one 16-byte read per feature tile); B = the probabilities the lane
+//                 copies its 32 x d_head tile into a private LDS region with fully coalesced
+//                 16-byte loads and reads the fragments back transposed, 2 bytes at a time;
+//                 B = the probabilities the lane
 //                 already holds, each as the sum of two bf16 numbers (two MFMAs).
 // The wavefronts' results are merged through LDS and left in `partial` for attn_merge_kernel
 // exactly as attn_kernel leaves them.  Every row's arithmetic is independent of the other rows.
-// dynamic LDS: max(4 x d_head x 32 bf16 staging, 4 x RG x (d_head + 2) floats for the merge).
+// dynamic LDS: max(4 x 32 x (d_head + 8) bf16 staging, 4 x RG x (d_head + 2) floats for the merge).
 __device__ __forceinline__ bf16x8 ld_frag(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
 __device__ __forceinline__ bf16x8 zero_frag() {
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -336,12 +345,12 @@ __device__ __forceinline__ f32x4 mma_bf16(const bf16x8& a, const bf16x8& b, f32x
 constexpr int ATTN_LONG_WAVES = 4;
 constexpr float ATTN_LONG_SLACK = 6.0f;      // how far scores may outgrow the softmax reference point before it moves
 constexpr size_t attn_long_lds_bytes(int rg, int dh) {
-  const size_t stage = (size_t)ATTN_LONG_WAVES * dh * 32 * 2, merge = (size_t)ATTN_LONG_WAVES * rg * (dh + 2) * 4;
+  const size_t stage = (size_t)ATTN_LONG_WAVES * 32 * (dh + 8) * 2, merge = (size_t)ATTN_LONG_WAVES * rg * (dh + 2) * 4;
   return stage > merge ? stage : merge;
 }
 
 template <int DH, int NRT>
-static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(const AttnArgs a) {
+static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kernel(const AttnArgs a) {
   extern __shared__ float lds[];
   __shared__ int s_pos[MAX_ROWS];
   __shared__ int s_pt[ATTN_LDS_PAGES];
@@ -351,21 +360,36 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, kq = lane >> 4;
   const int hkv = blockIdx.x;
-  const int split = (int)blockIdx.y % a.nsplit;
-  const int rs = ((int)blockIdx.y / a.nsplit) * a.rows_per_wg;
+  const int seq = blockIdx.y;                       // key ranges in z, the slowest index: the fullest ranges start first
+  const int split = (int)blockIdx.z % a.nsplit;
+  const int rs = ((int)blockIdx.z / a.nsplit) * a.rows_per_wg;
   const int R = min(a.rows_per_wg, a.R - rs);
-  const int r0 = ((int)blockIdx.z / a.spg) * MAX_ROWS + ((int)blockIdx.z % a.spg) * a.R + rs;
-  const int* page_table = a.page_table + (size_t)(a.seq0 + blockIdx.z) * a.pt_stride;
+  const int r0 = (seq / a.spg) * MAX_ROWS + (seq % a.spg) * a.R + rs;
+  const int* page_table = a.page_table + (size_t)(a.seq0 + seq) * a.pt_stride;
   const int G = a.H / a.Hkv, RG = R * G;
+#ifdef SD_KTIME
+  unsigned long long kt_last = wall_clock64();
+  if (blockIdx.x == 0 && split == 0 && threadIdx.x == 0) atomicAdd(&g_ktime[64 + 7], 1ull);
+  const unsigned wg_lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const bool wg_traced = gridDim.x * gridDim.y * gridDim.z == 640 && NRT == 2 && threadIdx.x == 0;
+  if (wg_traced) {
+    g_wgtrace[wg_lin * 4 + 0] = kt_last;
+    g_wgtrace[wg_lin * 4 + 2] = __builtin_amdgcn_s_getreg((31 << 11) | 4);
+    g_wgtrace[wg_lin * 4 + 3] = __builtin_amdgcn_s_getreg((31 << 11) | 20);
+  }
+#endif
   if (tid < MAX_ROWS) s_pos[tid] = (tid < R) ? a.row_pos[r0 + tid] : -1;
   for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += 64 * NW) s_pt[i] = page_table[i];
   __syncthreads();
   int kv_len = 0;
   for (int r = 0; r < R; ++r) kv_len = max(kv_len, s_pos[r] + 1);
   const int k_begin = split * a.split_keys;
-  float* pp = a.partial + ((((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
+  float* pp = a.partial + ((((size_t)seq * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
   if (k_begin >= kv_len) {                          // nothing in this key range yet: an empty partial
     if (tid < RG) { pp[(size_t)tid * (DH + 2) + DH] = -INFINITY; pp[(size_t)tid * (DH + 2) + DH + 1] = 0.0f; }
+#ifdef SD_KTIME
+    if (wg_traced) g_wgtrace[wg_lin * 4 + 1] = wall_clock64();
+#endif
     return;
   }
   kv_len = min(kv_len, k_begin + a.split_keys);
@@ -376,7 +400,7 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(
     return pool + ((((size_t)page * 2 + which) * a.Hkv + hkv) * a.page_size + slot) * DH;
   };
 
-  // query rows of this lane: rg = rt * 16 + j; features kq * DH/4 + s * 8 .. + 8 in k-step s
+  // query rows of this lane: rg = rt * 16 + j; features (4 s + kq) * 8 .. + 8 in k-step s
   bf16x8 qf[NRT][KSQ];
   int pos[NRT];
 #pragma unroll
@@ -385,9 +409,9 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(
     const bool ok = rg < RG;
     const int rgc = ok ? rg : 0;
     pos[rt] = ok ? s_pos[rgc / G] : -1;
-    const bf16* qp = static_cast<const bf16*>(a.q) + (size_t)(r0 + rgc / G) * a.H * DH + (size_t)(hkv * G + rgc % G) * DH + kq * (DH / 4);
+    const bf16* qp = static_cast<const bf16*>(a.q) + (size_t)(r0 + rgc / G) * a.H * DH + (size_t)(hkv * G + rgc % G) * DH + kq * 8;
 #pragma unroll
-    for (int s = 0; s < KSQ; ++s) qf[rt][s] = ok ? ld_frag(qp + s * 8) : zero_frag();
+    for (int s = 0; s < KSQ; ++s) qf[rt][s] = ok ? ld_frag(qp + s * 32) : zero_frag();
   }
   float m_run[NRT], l_run[NRT];
   f32x4 o[DT][NRT];
@@ -397,14 +421,15 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) o[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  unsigned short* vt = reinterpret_cast<unsigned short*>(lds) + (size_t)wave * DH * 32;   // [DH][32 key places]
-  const int vkey = lane & 31, vhalf = lane >> 5;
-  // place of key 16 a + 4 q + i in a row of vt: 8 q + 4 a + i, so that quarter q reads 8 places in one piece
-  const int vplace = ((vkey >> 2) & 3) * 8 + (vkey >> 4) * 4 + (vkey & 3);
+  // V tile of the step, row-major with padded rows: [32 keys][DH + 8] bf16.  The 16-byte writes of
+  // a load and the 2-byte reads of a fragment (16 features x 4 key groups) are both conflict-free.
+  constexpr int VRS = DH + 8, VKPL = 64 / (DH / 8);
+  unsigned short* vt = reinterpret_cast<unsigned short*>(lds) + (size_t)wave * 32 * VRS;
+  const int vpiece = lane % (DH / 8), vkey = lane / (DH / 8);
 
   // The loads of a step are issued one step ahead, into the registers the previous step has
-  // just finished with (K after the score product, V after the transposition), so a
-  // wavefront's load latency overlaps its own arithmetic.
+  // just finished with (V after its transposition at the top of the step, K after the score
+  // product), so a wavefront's load latency overlaps a whole step of its own arithmetic.
   bf16x8 kf[2][KSQ];
   bf16x8 vr[DH / 16];
   auto load_k = [&](int kb) {                       // always issued: past the range every lane re-reads the last key
@@ -412,23 +437,34 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(
     const int nk = min(32, kv_len - kb);
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
-      const bf16* kp = row_ptr(kb + min(kt * 16 + j, nk - 1), 0) + kq * (DH / 4);
+      const bf16* kp = row_ptr(kb + min(kt * 16 + j, nk - 1), 0) + kq * 8;
 #pragma unroll
-      for (int s = 0; s < KSQ; ++s) kf[kt][s] = ld_frag(kp + s * 8);
+      for (int s = 0; s < KSQ; ++s) kf[kt][s] = ld_frag(kp + s * 32);      // the four quarters read 64 contiguous bytes
     }
   };
-  auto load_v = [&](int kb) {
+  auto load_v = [&](int kb) {                       // load c: VKPL keys, each row read by DH/8 consecutive lanes
     kb = min(kb, kv_len - 1);
     const int nk = min(32, kv_len - kb);
-    const bf16* vp = row_ptr(kb + min(vkey, nk - 1), 1) + vhalf * (DH / 2);
 #pragma unroll
-    for (int c = 0; c < DH / 16; ++c) vr[c] = ld_frag(vp + c * 8);
+    for (int c = 0; c < DH / 16; ++c) vr[c] = ld_frag(row_ptr(kb + min(c * VKPL + vkey, nk - 1), 1) + vpiece * 8);
   };
   const int kb0 = k_begin + wave * 32;
+  SD_STAMPL(0);
   load_k(kb0); load_v(kb0);                         // out-of-range keys re-read the last valid one and get probability 0
   for (int kb = kb0; kb < kv_len; kb += NW * 32) {
     const int nkeys = min(32, kv_len - kb);
     const int kb_next = kb + NW * 32;
+    // ---- V tile -> LDS, transposed; then its registers take the next step's tile ----
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");     // the reads of the previous step are done
+    SD_STAMPL(1);
+    SD_WAIT_VM8();
+    SD_STAMPL(2);
+#pragma unroll
+    for (int c = 0; c < DH / 16; ++c) *reinterpret_cast<bf16x8*>(vt + (c * VKPL + vkey) * VRS + vpiece * 8) = vr[c];
+    load_v(kb_next);                                 // no branch around loads: the compiler would wait for all of them
+    SD_STAMPL(3);
+    SD_WAIT_VM8();
+    SD_STAMPL(4);
     // ---- scores: sc[kt][rt][r] = S[key kb + kt*16 + kq*4 + r][row rt*16 + j] ----
     f32x4 sc[2][NRT];
 #pragma unroll
@@ -439,7 +475,8 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(
 #pragma unroll
         for (int s = 0; s < KSQ; ++s) sc[kt][rt] = mma_bf16(kf[kt][s], qf[rt][s], sc[kt][rt]);
       }
-    load_k(kb_next);                                 // no branch around loads: the compiler would wait for all of them
+    SD_STAMPL(5);
+    load_k(kb_next);
     float p[2][NRT][4];
     float f[NRT];
     bool rescale = false;
@@ -474,17 +511,9 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(
       l_run[rt] = l_run[rt] * f[rt] + sum;          // this lane's keys only; the quarters are added at the end
       m_run[rt] = m_new;
     }
-    // ---- V tile -> LDS, transposed ----
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");     // the reads of the previous step are done
-#pragma unroll
-    for (int c = 0; c < DH / 16; ++c) {
-      typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
-      const u16x8 bits = __builtin_bit_cast(u16x8, vr[c]);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) vt[(vhalf * (DH / 2) + c * 8 + e) * 32 + vplace] = bits[e];
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");     // writes land before this wavefront reads them back
-    load_v(kb_next);
+    SD_STAMPL(6);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");     // this step's V tile has landed in LDS
+    SD_STAMPL(8);
     // ---- O^T = f O^T + V^T P;  p as the sum of two bf16 numbers (16 mantissa bits): the
     //      matrix cores have time to spare ----
     bf16x8 pf[NRT], pl[NRT];
@@ -506,13 +535,18 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(
     }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vt + (dt * 16 + j) * 32 + kq * 8);
+      typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+      u16x8 vb;                                      // V[key (e/4) 16 + 4 kq + e%4][feature dt 16 + j]
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vb[e] = vt[((e >> 2) * 16 + kq * 4 + (e & 3)) * VRS + dt * 16 + j];
+      const bf16x8 vf = __builtin_bit_cast(bf16x8, vb);
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt) {
         o[dt][rt] = mma_bf16(vf, pl[rt], o[dt][rt]);
         o[dt][rt] = mma_bf16(vf, pf[rt], o[dt][rt]);
       }
     }
+    SD_STAMPL(9);
   }
 
   // ---- merge the wavefronts: each leaves (m, l, O) of its keys in LDS ----
@@ -548,6 +582,10 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES) void attn_long_kernel(
     }
     pp[i] = out;
   }
+  SD_STAMPL(10);
+#ifdef SD_KTIME
+  if (wg_traced) g_wgtrace[wg_lin * 4 + 1] = wall_clock64();
+#endif
 }
 
 // Combines the partial results of the key ranges of one (sequence, kv head): with

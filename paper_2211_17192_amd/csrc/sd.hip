@@ -335,11 +335,11 @@ void launch_attn(hipStream_t s, const Model& m, AttnArgs a, int nseq) {
   if (std::is_same<T, bf16>::value && a.nsplit > 1 && a.rel_bias == nullptr && (DH == 64 || DH == 128)) {
     const int RG = a.rows_per_wg * G;
     const size_t ll = attn_long_lds_bytes(RG, DH);
-    const dim3 lb(64 * ATTN_LONG_WAVES);
-    if (DH == 64 && RG <= 16) hipLaunchKernelGGL((attn_long_kernel<64, 1>), grid, lb, ll, s, a);
-    else if (DH == 64) hipLaunchKernelGGL((attn_long_kernel<64, 2>), grid, lb, ll, s, a);
-    else if (RG <= 16) hipLaunchKernelGGL((attn_long_kernel<128, 1>), grid, lb, ll, s, a);
-    else hipLaunchKernelGGL((attn_long_kernel<128, 2>), grid, lb, ll, s, a);
+    const dim3 lb(64 * ATTN_LONG_WAVES), lg(grid.x, grid.z, grid.y);     // key ranges in z: the fullest ranges start first
+    if (DH == 64 && RG <= 16) hipLaunchKernelGGL((attn_long_kernel<64, 1>), lg, lb, ll, s, a);
+    else if (DH == 64) hipLaunchKernelGGL((attn_long_kernel<64, 2>), lg, lb, ll, s, a);
+    else if (RG <= 16) hipLaunchKernelGGL((attn_long_kernel<128, 1>), lg, lb, ll, s, a);
+    else hipLaunchKernelGGL((attn_long_kernel<128, 2>), lg, lb, ll, s, a);
   } else if (DH == 32) hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, lds, s, a);
   else if (DH == 64) hipLaunchKernelGGL((attn_kernel<T, 64>), grid, block, lds, s, a);
   else hipLaunchKernelGGL((attn_kernel<T, 128>), grid, block, lds, s, a);
@@ -1193,8 +1193,16 @@ extern "C" sd_status sd_get_stats(sd_ctx* c, sd_stats* out) {
 }
 
 #ifdef SD_KTIME
-extern "C" int sd_debug_ktime(unsigned long long* out64) {
-  return (int)hipMemcpyFromSymbol(out64, HIP_SYMBOL(sd::g_ktime), 64 * sizeof(unsigned long long));
+extern "C" int sd_debug_occupancy(int lds_bytes) {
+  int n = -1;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, sd::attn_long_kernel<128, 2>, 64 * sd::ATTN_LONG_WAVES, (size_t)lds_bytes) != hipSuccess) return -1;
+  return n;
+}
+extern "C" int sd_debug_wgtrace(unsigned long long* out2560) {
+  return (int)hipMemcpyFromSymbol(out2560, HIP_SYMBOL(sd::g_wgtrace), 2560 * sizeof(unsigned long long));
+}
+extern "C" int sd_debug_ktime(unsigned long long* out96) {
+  return (int)hipMemcpyFromSymbol(out96, HIP_SYMBOL(sd::g_ktime), 96 * sizeof(unsigned long long));
 }
 #endif
 
