@@ -76,6 +76,11 @@ struct GemmArgs {
   // slabs lie ss_stride floats apart
   int nrt, R_last, ss_stride;
   const float* rope;      // [max_len][d_head/2][2] (cos, sin) or nullptr
+  // gemm_split_kernel / gemm_split_finish_kernel: the K chunks' partial tiles,
+  // [nchunk][nrt][streams * N/16][64 lanes][4] floats, and the number of chunks
+  float* partial;
+  int nchunk;
+  const float* rs_in;     // PRO_POST: 1 / rms of every row, [nrt * 16] (rows_to_fragments_kernel writes it)
 };
 
 template <typename T> struct Mma;
@@ -426,10 +431,25 @@ __host__ __device__ constexpr size_t gemm_wide_lds_bytes(int S) {
 }
 
 // Row-major activations [nrt * 16][K] -> fragment order [K/32][GEMM_WIDE_RT][64][8].
-// One thread moves the 8 elements of one lane of one fragment.
+// One thread moves the 8 elements of one lane of one fragment.  With rs_out, the workgroups
+// nrt .. 2 nrt - 1 of the grid also leave 1 / rms of every row of slab (block - nrt) there, from
+// the partial sums of squares ss_in (added in gemm_kernel's order), for the split GEMM's
+// finish kernel.
 template <typename T>
 static __global__ __launch_bounds__(256) void rows_to_fragments_kernel(const T* __restrict__ X, T* __restrict__ Xf,
-                                                                      int nrt, int K) {
+                                                                      int nrt, int K, const float* __restrict__ ss_in,
+                                                                      int n_part, int ss_stride, float eps,
+                                                                      float* __restrict__ rs_out) {
+  if (rs_out != nullptr && (int)blockIdx.x >= nrt && (int)blockIdx.x < 2 * nrt) {
+    const int rt = (int)blockIdx.x - nrt, row = threadIdx.x >> 4, f = threadIdx.x & 15;
+    const float* ss = ss_in + (size_t)rt * ss_stride;
+    float q = 0.0f;
+#pragma unroll 8
+    for (int p = f; p < n_part; p += 16) q += ss[p * 16 + row];
+    q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+    q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+    if (f == 0) rs_out[rt * 16 + row] = 1.0f / sqrtf(q / (float)K + eps);
+  }
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
   const int lane = idx & 63, f = idx >> 6;
   const int KS = K >> 5;
@@ -733,6 +753,177 @@ static __global__ void retile_kernel(const T* __restrict__ src, T* __restrict__ 
   T* d = dst + i * 8;
 #pragma unroll
   for (int e = 0; e < 8; ++e) d[e] = s[e];
+}
+
+// ---------------------------------------------------------------------------
+// Several slabs, second design: the wavefronts of a workgroup share the activations.
+// gemm_wide_kernel splits K over the wavefronts of a workgroup, so every wavefront pulls its
+// own activation fragments from L2 (a KB per slab for every KB of weights), and that traffic
+// bounds it.  Here a workgroup takes one K chunk (the k-steps one wavefront of gemm_kernel
+// would take) of NW tiles, one per wavefront (two weight streams for a gated FFN: the
+// gate and up tiles; NW = 8, or 12 when that makes the grid fit the chip in one round): the chunk's activation fragments pass through LDS once per workgroup,
+// GEMM_SPLIT_SUB k-steps at a time, and serve all eight wavefronts; the weights of the next
+// pass are in flight meanwhile.  Each wavefront leaves the partial tile of its chunk in
+// global memory; gemm_split_finish_kernel adds the chunks in wavefront order and applies
+// the epilogue, so a row's sums are those of gemm_kernel, bit for bit.
+// grid = (ceil(tiles / NW), chunks); dynamic LDS = SUB * nrt fragments.
+template <typename T> struct SplitShape { static constexpr int SUB = 16 / (int)sizeof(T); };   // 8 k-steps of bf16, 4 of fp32: 1 KB per slab and k-step pair
+
+template <typename T, int NS, int NW>
+static __global__ __launch_bounds__(64 * NW) void gemm_split_kernel(const GemmArgs a) {
+  typedef typename Mma<T>::Frag Frag;
+  extern __shared__ float lds[];
+  Frag* xs = reinterpret_cast<Frag*>(lds);          // [SUB][nrt][64 lanes]
+  constexpr int SUB = SplitShape<T>::SUB, RT = GEMM_WIDE_RT;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int KS = a.K >> 5, ntiles = a.N >> 4, nrt = a.nrt;
+  const int chunk = blockIdx.y;
+  const int ks0 = min(KS, chunk * a.ksteps_per_wave), ks1 = min(KS, ks0 + a.ksteps_per_wave);
+  const int tile = (int)blockIdx.x * NW + wave, tilec = min(tile, ntiles - 1);
+  const int ks_last = max(ks1 - 1, 0);
+  const T* wbase[NS];
+  wbase[0] = static_cast<const T*>(a.W) + ((size_t)tilec * KS) * 512 + lane * 8;
+  if (NS == 2) wbase[NS - 1] = static_cast<const T*>(a.W2) + ((size_t)tilec * KS) * 512 + lane * 8;
+  const Frag* xf = reinterpret_cast<const Frag*>(a.X);            // [KS][RT][64 lanes]
+
+  f32x4 acc[NS][RT];
+#pragma unroll
+  for (int st = 0; st < NS; ++st)
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  Frag wf[NS][SUB];
+  auto load_w = [&](int ksb) {                       // unconditional, clamped: no branch around loads
+#pragma unroll
+    for (int st = 0; st < NS; ++st)
+#pragma unroll
+      for (int u = 0; u < SUB; ++u) wf[st][u] = Mma<T>::load_stream(wbase[st] + (size_t)min(ksb + u, ks_last) * 512);
+  };
+  // this thread's share of a pass's activation fragments (SUB * nrt * 64 of them over the workgroup)
+  constexpr int NT = 64 * NW, XPT = (SUB * RT * 64 + NT - 1) / NT;
+  Frag xr[XPT];
+  const int nfrag = SUB * nrt * 64;
+  auto load_x = [&](int ksb) {                       // unconditional, clamped
+#pragma unroll
+    for (int m = 0; m < XPT; ++m) {
+      const int i = min(tid + NT * m, nfrag - 1);
+      const int u = i / (nrt * 64), rem = i - u * (nrt * 64);
+      xr[m] = xf[(size_t)min(ksb + u, ks_last) * (RT * 64) + rem];
+    }
+  };
+  load_w(ks0);
+  load_x(ks0);
+  for (int ksb = ks0; ksb < ks1; ksb += SUB) {
+    __syncthreads();                                 // the previous pass has been multiplied
+#pragma unroll
+    for (int m = 0; m < XPT; ++m)
+      if (tid + NT * m < nfrag) xs[tid + NT * m] = xr[m];
+    __syncthreads();
+    Frag cur[NS][SUB];
+#pragma unroll
+    for (int st = 0; st < NS; ++st)
+#pragma unroll
+      for (int u = 0; u < SUB; ++u) cur[st][u] = wf[st][u];
+    load_w(ksb + SUB);                               // the next pass's weights and activations are in
+    load_x(ksb + SUB);                               // flight while this one is multiplied
+#pragma unroll
+    for (int u = 0; u < SUB; ++u) {
+      if (ksb + u < ks1) {                           // uniform; k-steps in order, as gemm_kernel takes them
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          if (rt < nrt) {
+            const Frag fb = xs[(u * nrt + rt) * 64 + lane];
+#pragma unroll
+            for (int st = 0; st < NS; ++st) acc[st][rt] = Mma<T>::mma(cur[st][u], fb, acc[st][rt]);
+          }
+        }
+      }
+    }
+  }
+  if (tile < ntiles) {
+#pragma unroll
+    for (int st = 0; st < NS; ++st)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+        if (rt < nrt)
+          *reinterpret_cast<f32x4*>(a.partial + ((((size_t)chunk * nrt + rt) * (NS * ntiles) + (size_t)st * ntiles + tile) * 64 + lane) * 4) = acc[st][rt];
+  }
+}
+
+// Adds the chunks' partial tiles in chunk order and applies the epilogue of one (tile, slab):
+// grid = (tiles, slabs), thread t = row * 16 + feature.  The partial tiles are requested first;
+// the row's constants (norm factor, cache position) arrive while they are on their way.
+template <typename T, int PRO, int EPI>
+static __global__ __launch_bounds__(256) void gemm_split_finish_kernel(const GemmArgs a) {
+  constexpr int ND = (EPI == EPI_GATED) ? 2 : 1;
+  const int tid = threadIdx.x, e_row = tid >> 4, f = tid & 15;
+  const int tile = blockIdx.x, rt = blockIdx.y, nrt = a.nrt, ntiles = a.N >> 4;
+  const int rows = (rt == nrt - 1) ? a.R_last : a.R;
+  const int row = rt * 16 + e_row, rc = rt * 16 + min(e_row, rows - 1);      // clamped: loads stay in bounds
+  const bool ok = e_row < rows;
+  const int n = tile * 16 + f;
+  // accumulator layout: lane (row, feature / 4) holds features 4 (lane / 16) + r of row lane % 16
+  const int pidx = (e_row + 16 * (f >> 2)) * 4 + (f & 3);
+  float pv[ND][8];                                   // at most 8 chunks
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int w = 0; w < 8; ++w)
+      pv[d][w] = a.partial[((((size_t)min(w, a.nchunk - 1) * nrt + rt) * (ND * ntiles) + (size_t)d * ntiles + tile) * 256) + pidx];
+  const float bias = (a.bias != nullptr) ? Store<T>::ld(static_cast<const T*>(a.bias) + n) : 0.0f;
+  const float r1 = (PRO == PRO_POST) ? a.rs_in[rc] : 1.0f;
+  float y[2] = {0.0f, 0.0f};
+#pragma unroll
+  for (int d = 0; d < ND; ++d) {
+    float s1 = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) if (w < a.nchunk) s1 += pv[d][w];
+    y[d] = s1;
+  }
+  if (PRO == PRO_POST) { y[0] *= r1; y[1] *= r1; }
+  y[0] += bias;
+  if (EPI == EPI_QKV) {
+    const int pos = ok ? a.row_pos[rc] : -1;
+    const bool is_q = n < a.nq, is_k = !is_q && n < a.nq + a.nkv;
+    const int nn = is_q ? n : (is_k ? n - a.nq : n - a.nq - a.nkv);
+    const int head = nn / a.d_head, d = nn % a.d_head;
+    float v = y[0];
+    const float other = __shfl_xor(v, 1, 64);        // the other half of the rotary pair: feature f ^ 1 of the same row
+    if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
+      const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
+      v = (d & 1) ? (other * cs[1] + v * cs[0]) : (v * cs[0] - other * cs[1]);
+    }
+    if (ok) {
+      if (is_q) {
+        Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, v);
+      } else if (pos >= 0) {
+        const int pt0 = (a.row_seq != nullptr) ? a.row_seq[rc] * a.pt_stride : 0;
+        const int page = a.page_table[pt0 + pos / a.page_size], slot = pos % a.page_size;
+        const size_t base = (size_t)page * 2 * a.n_kv_heads * a.page_size * a.d_head + (size_t)slot * a.d_head;
+        Store<T>::st(static_cast<T*>(a.kv_pool) + base + ((size_t)(is_k ? 0 : 1) * a.n_kv_heads + head) * a.page_size * a.d_head + d, v);
+      }
+    }
+  } else if (EPI == EPI_RESID) {
+    float xn = 0.0f;
+    if (ok) {
+      xn = static_cast<const float*>(a.out)[(size_t)row * a.ldo + n] + y[0];
+      static_cast<float*>(a.out)[(size_t)row * a.ldo + n] = xn;
+      if (a.xg_out != nullptr)
+        Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * Store<T>::ld(static_cast<const T*>(a.gain_next) + n));
+    }
+    if (a.ss_out != nullptr) {
+      float q = xn * xn;
+      q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+      q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+      if (f == 0) a.ss_out[(size_t)rt * a.ss_stride + tile * 16 + e_row] = q;
+    }
+  } else if (ok) {
+    if (EPI == EPI_STORE) {
+      Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, y[0]);
+    } else if (EPI == EPI_GATED) {
+      const float g = (a.act == ACT_GELU) ? gelu_tanh(y[0]) : silu(y[0]);
+      Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n, g * y[1]);
+    }
+  }
 }
 
 }  // namespace sd

@@ -64,6 +64,8 @@ struct Model {
   int* page_table = nullptr;   // [batch][n_pages]
   int *row_seq = nullptr, *logit_row = nullptr;   // [rows_cap], written by the embedding kernel
   void* xfrag = nullptr;       // activations of one wide GEMM in fragment order
+  float* wide_partial = nullptr;   // partial tiles of the K chunks of one split GEMM
+  float* wide_rs = nullptr;        // 1 / rms of the rows of one split GEMM
   int attn_nsplit = 1, attn_split_keys = 0;   // long contexts: key ranges per (sequence, kv head)
   float* attn_partial = nullptr;
   float* x = nullptr;
@@ -161,7 +163,12 @@ void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size, int ba
     m.attn_partial = static_cast<float*>(A.take((size_t)batch * c.n_kv_heads * m.attn_nsplit * ATTN_MAX_RG *
                                                 (c.d_head + 2) * sizeof(float)));
   }
-  if (batch > 1) m.xfrag = A.take((size_t)std::max({(size_t)d, (size_t)m.nq, ff}) * GEMM_WIDE_RT * 16 * e);
+  if (batch > 1) {
+    m.xfrag = A.take((size_t)std::max({(size_t)d, (size_t)m.nq, ff}) * GEMM_WIDE_RT * 16 * e);
+    const size_t tiles = std::max((size_t)d, (size_t)(m.nq + 2 * m.nkv)) / 16;    // the products split_ok() lets through
+    m.wide_partial = static_cast<float*>(A.take((size_t)8 * GEMM_WIDE_RT * tiles * 256 * sizeof(float)));
+    m.wide_rs = static_cast<float*>(A.take((size_t)GEMM_WIDE_RT * 16 * sizeof(float)));
+  }
   m.prompt = static_cast<int*>(A.take((size_t)c.max_len * sizeof(int)));
 }
 
@@ -277,6 +284,36 @@ void launch_gemm_wide_t(hipStream_t s, GemmArgs a) {
   const int per_wg = (pairs + g_num_cus - 1) / g_num_cus;
   const int grid = (pairs + per_wg - 1) / per_wg;
   hipLaunchKernelGGL((gemm_wide_kernel<T, PRO, EPI>), dim3(grid), dim3(64 * S), lds, s, a);
+}
+
+// Split design: K chunks over workgroups (the one-slab kernel's chunks), then the finish kernel.
+template <typename T, int PRO, int EPI>
+void launch_gemm_split_t(hipStream_t s, GemmArgs a, float* partial) {
+  const int tiles = a.N / 16, KS = a.K / 32;
+  const int S = pick_waves(KS);                  // the same K split as the one-slab kernel: same sums
+  a.ksteps_per_wave = (KS + S - 1) / S;
+  a.nchunk = S;
+  a.partial = partial;
+  constexpr int NS = (EPI == EPI_GATED) ? 2 : 1;
+  const size_t lds = (size_t)SplitShape<T>::SUB * a.nrt * 64 * 8 * sizeof(T);
+  // 8 tiles per workgroup, 12 when 8 would need a second round of workgroups and 12 does not
+  const bool wide12 = ((tiles + 7) / 8) * S > g_num_cus && ((tiles + 11) / 12) * S <= g_num_cus;
+  if (wide12) hipLaunchKernelGGL((gemm_split_kernel<T, NS, 12>), dim3((tiles + 11) / 12, S), dim3(768), lds, s, a);
+  else hipLaunchKernelGGL((gemm_split_kernel<T, NS, 8>), dim3((tiles + 7) / 8, S), dim3(512), lds, s, a);
+  hipLaunchKernelGGL((gemm_split_finish_kernel<T, PRO, EPI>), dim3(tiles, a.nrt), dim3(256), 0, s, a);
+}
+
+// Which products take the split design (activations in fragment order, RMSNorm or no norm).
+inline bool split_ok(int pro, int epi) {
+  // (a gated FFN's partial tiles are too many: 8 chunks x 2 streams x d_ff; it stays with gemm_wide_kernel)
+  return (pro == PRO_POST && epi == EPI_QKV) || (pro == PRO_NONE && epi == EPI_RESID);
+}
+
+template <typename T>
+void launch_gemm_split(hipStream_t s, int pro, int epi, const GemmArgs& a, float* partial) {
+#define SD_CASE(P, E) if (pro == P && epi == E) return launch_gemm_split_t<T, P, E>(s, a, partial)
+  SD_CASE(PRO_POST, EPI_QKV); SD_CASE(PRO_NONE, EPI_RESID); SD_CASE(PRO_POST, EPI_GATED);
+#undef SD_CASE
 }
 
 // The wide kernel's LDS exceeds the default 64 KB limit of dynamic LDS.
@@ -430,11 +467,16 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       a.ss_stride = (d / 16) * 16;
       if (pro_ != PRO_LN) {                       // the wide kernel reads the activations in fragment order
         const int frags = (a.K / 32) * a.nrt;
-        hipLaunchKernelGGL((rows_to_fragments_kernel<T>), dim3((frags * 64 + 255) / 256), dim3(256), 0, s,
-                           static_cast<const T*>(a.X), static_cast<T*>(m.xfrag), a.nrt, a.K);
+        const int blocks = (frags * 64 + 255) / 256;
+        const bool want_rs = pro_ == PRO_POST && split_ok(pro_, epi_) && blocks >= 2 * a.nrt;
+        hipLaunchKernelGGL((rows_to_fragments_kernel<T>), dim3(blocks), dim3(256), 0, s,
+                           static_cast<const T*>(a.X), static_cast<T*>(m.xfrag), a.nrt, a.K, a.ss_in, a.n_part,
+                           a.ss_stride, a.eps, want_rs ? m.wide_rs : nullptr);
         a.X = m.xfrag;
+        a.rs_in = want_rs ? m.wide_rs : nullptr;
       }
-      launch_gemm_wide<T>(s, pro_, epi_, a);
+      if (split_ok(pro_, epi_) && (pro_ != PRO_POST || a.rs_in != nullptr)) launch_gemm_split<T>(s, pro_, epi_, a, m.wide_partial);
+      else launch_gemm_wide<T>(s, pro_, epi_, a);
     }
   };
   int n_part = 1;                                   // partial sums of x^2 the next norm has to add

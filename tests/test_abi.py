@@ -28,9 +28,9 @@ def test_workspace_sizing_needs_no_gpu():
     rt = binding._RuntimeCfg(batch=1, max_gamma=4, page_size=16)
     n = binding.lib.sd_workspace_bytes(ctypes.byref(cp), ctypes.byref(cq), ctypes.byref(rt))
     assert 100_000 < n < 50_000_000
-    rt.batch = 4                                    # four sequences: four times the KV pages and activations
-    n4 = binding.lib.sd_workspace_bytes(ctypes.byref(cp), ctypes.byref(cq), ctypes.byref(rt))
-    assert n < n4 < 4 * n
+    rt.batch = 4                                    # four sequences: four times the KV pages and activations,
+    n4 = binding.lib.sd_workspace_bytes(ctypes.byref(cp), ctypes.byref(cq), ctypes.byref(rt))   # plus the batched GEMMs' scratch
+    assert n < n4 < 6 * n
     rt.batch = 65
     assert binding.lib.sd_workspace_bytes(ctypes.byref(cp), ctypes.byref(cq), ctypes.byref(rt)) == 0
     rt.batch, rt.max_gamma = 1, 16
