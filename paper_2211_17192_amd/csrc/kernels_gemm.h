@@ -926,4 +926,126 @@ static __global__ __launch_bounds__(256) void gemm_split_finish_kernel(const Gem
   }
 }
 
+// Gated FFN-in over several slabs: there are enough tiles to fill the chip without splitting K
+// over workgroups, and the partial tiles of a split would be many (chunks x 2 streams x d_ff).
+// A workgroup of four wavefronts takes four tiles (gate and up stream each) through ALL of K,
+// the activation fragments passing through LDS as in gemm_split_kernel; every wavefront keeps
+// gemm_kernel's sums: the k-steps of a chunk go into `acc` in order, and at a chunk's end `acc`
+// is added to the running total, chunks in order -- the additions gemm_kernel's epilogue
+// makes -- so the results stay bit-identical.  Epilogue out of registers: norm factor (from
+// rows_to_fragments_kernel), activation, product.  grid = ceil(tiles / 4).
+template <typename T>
+static __global__ __launch_bounds__(256, 2) void gemm_gated_wide_kernel(const GemmArgs a) {
+  typedef typename Mma<T>::Frag Frag;
+  extern __shared__ float lds[];
+  Frag* xs = reinterpret_cast<Frag*>(lds);          // [SUB][nrt][64 lanes]
+  constexpr int SUB = SplitShape<T>::SUB / 2, RT = GEMM_WIDE_RT, NT = 256;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, kq = lane >> 4;
+  const int KS = a.K >> 5, ntiles = a.N >> 4, nrt = a.nrt, kpw = a.ksteps_per_wave;
+  const int tile = (int)blockIdx.x * 4 + wave, tilec = min(tile, ntiles - 1);
+  const T* wbase[2];
+  wbase[0] = static_cast<const T*>(a.W) + ((size_t)tilec * KS) * 512 + lane * 8;
+  wbase[1] = static_cast<const T*>(a.W2) + ((size_t)tilec * KS) * 512 + lane * 8;
+  const Frag* xf = reinterpret_cast<const Frag*>(a.X);            // [KS][RT][64 lanes]
+
+  f32x4 acc[2][RT], total[2][RT];
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) { acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f}; total[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+  Frag wf[2][SUB];
+  auto load_w = [&](int ksb) {                       // unconditional, clamped: no branch around loads
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int u = 0; u < SUB; ++u) wf[st][u] = Mma<T>::load_stream(wbase[st] + (size_t)min(ksb + u, KS - 1) * 512);
+  };
+  constexpr int XPT = (SUB * RT * 64 + NT - 1) / NT;
+  Frag xr[XPT];
+  const int nfrag = SUB * nrt * 64;
+  auto load_x = [&](int ksb) {
+#pragma unroll
+    for (int m = 0; m < XPT; ++m) {
+      const int i = min(tid + NT * m, nfrag - 1);
+      const int u = i / (nrt * 64), rem = i - u * (nrt * 64);
+      xr[m] = xf[(size_t)min(ksb + u, KS - 1) * (RT * 64) + rem];
+    }
+  };
+  // a pass never crosses a chunk's end: its k-steps are [ksb, ksb + len)
+  auto pass_len = [&](int ksb) { return min(SUB, min(KS, (ksb / kpw + 1) * kpw) - ksb); };
+  load_w(0);
+  load_x(0);
+  int chunks_done = 0;
+  for (int ksb = 0; ksb < KS;) {
+    const int len = pass_len(ksb), next = ksb + len;
+    __syncthreads();                                 // the previous pass has been multiplied
+#pragma unroll
+    for (int m = 0; m < XPT; ++m)
+      if (tid + NT * m < nfrag) xs[tid + NT * m] = xr[m];
+    __syncthreads();
+    Frag cur[2][SUB];
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int u = 0; u < SUB; ++u) cur[st][u] = wf[st][u];
+    load_w(next);
+    load_x(next);
+#pragma unroll
+    for (int u = 0; u < SUB; ++u) {
+      if (u < len) {                                 // uniform
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          if (rt < nrt) {
+            const Frag fb = xs[(u * nrt + rt) * 64 + lane];
+            acc[0][rt] = Mma<T>::mma(cur[0][u], fb, acc[0][rt]);
+            acc[1][rt] = Mma<T>::mma(cur[1][u], fb, acc[1][rt]);
+          }
+        }
+      }
+    }
+    if (next == KS || next % kpw == 0) {             // the chunk is complete: add it, chunks in order
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) total[st][rt][r] += acc[st][rt][r];
+          acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+      ++chunks_done;
+    }
+    ksb = next;
+  }
+  for (; chunks_done < a.nchunk; ++chunks_done)      // chunks beyond K are empty in gemm_kernel too: it adds their zeros
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) total[st][rt][r] += 0.0f;
+
+  if (tile >= ntiles) return;
+  // accumulator layout: lane holds features 4 kq + r, r = 0..3, of row j
+  const int n0 = tile * 16 + kq * 4;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    if (rt < nrt) {
+      const int rows = (rt == nrt - 1) ? a.R_last : a.R;
+      if (j < rows) {
+        const int row = rt * 16 + j;
+        const float r1 = a.rs_in[row];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float y0 = total[0][rt][r] * r1;
+          const float y1 = total[1][rt][r] * r1;
+          y0 += (a.bias != nullptr) ? Store<T>::ld(static_cast<const T*>(a.bias) + n0 + r) : 0.0f;
+          const float g = (a.act == ACT_GELU) ? gelu_tanh(y0) : silu(y0);
+          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n0 + r, g * y1);
+        }
+      }
+    }
+  }
+}
+
 }  // namespace sd

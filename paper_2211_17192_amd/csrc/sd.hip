@@ -303,6 +303,17 @@ void launch_gemm_split_t(hipStream_t s, GemmArgs a, float* partial) {
   hipLaunchKernelGGL((gemm_split_finish_kernel<T, PRO, EPI>), dim3(tiles, a.nrt), dim3(256), 0, s, a);
 }
 
+// Gated FFN-in over several slabs: no split over workgroups, every wavefront walks all of K.
+template <typename T>
+void launch_gemm_gated_wide(hipStream_t s, GemmArgs a) {
+  const int tiles = a.N / 16, KS = a.K / 32;
+  const int S = pick_waves(KS);                  // the chunks whose sums the one-slab kernel adds
+  a.ksteps_per_wave = (KS + S - 1) / S;
+  a.nchunk = S;
+  const size_t lds = (size_t)(SplitShape<T>::SUB / 2) * a.nrt * 64 * 8 * sizeof(T);
+  hipLaunchKernelGGL((gemm_gated_wide_kernel<T>), dim3((tiles + 3) / 4), dim3(256), lds, s, a);
+}
+
 // Which products take the split design (activations in fragment order, RMSNorm or no norm).
 inline bool split_ok(int pro, int epi) {
   // (a gated FFN's partial tiles are too many: 8 chunks x 2 streams x d_ff; it stays with gemm_wide_kernel)
@@ -468,14 +479,15 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       if (pro_ != PRO_LN) {                       // the wide kernel reads the activations in fragment order
         const int frags = (a.K / 32) * a.nrt;
         const int blocks = (frags * 64 + 255) / 256;
-        const bool want_rs = pro_ == PRO_POST && split_ok(pro_, epi_) && blocks >= 2 * a.nrt;
+        const bool want_rs = pro_ == PRO_POST && (split_ok(pro_, epi_) || epi_ == EPI_GATED) && blocks >= 2 * a.nrt;
         hipLaunchKernelGGL((rows_to_fragments_kernel<T>), dim3(blocks), dim3(256), 0, s,
                            static_cast<const T*>(a.X), static_cast<T*>(m.xfrag), a.nrt, a.K, a.ss_in, a.n_part,
                            a.ss_stride, a.eps, want_rs ? m.wide_rs : nullptr);
         a.X = m.xfrag;
         a.rs_in = want_rs ? m.wide_rs : nullptr;
       }
-      if (split_ok(pro_, epi_) && (pro_ != PRO_POST || a.rs_in != nullptr)) launch_gemm_split<T>(s, pro_, epi_, a, m.wide_partial);
+      if (pro_ == PRO_POST && epi_ == EPI_GATED && a.rs_in != nullptr) launch_gemm_gated_wide<T>(s, a);
+      else if (split_ok(pro_, epi_) && (pro_ != PRO_POST || a.rs_in != nullptr)) launch_gemm_split<T>(s, pro_, epi_, a, m.wide_partial);
       else launch_gemm_wide<T>(s, pro_, epi_, a);
     }
   };
