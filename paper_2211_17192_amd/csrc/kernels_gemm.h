@@ -932,39 +932,42 @@ static __global__ __launch_bounds__(256) void gemm_split_finish_kernel(const Gem
 // the activation fragments passing through LDS as in gemm_split_kernel; every wavefront keeps
 // gemm_kernel's sums: the k-steps of a chunk go into `acc` in order, and at a chunk's end `acc`
 // is added to the running total, chunks in order -- the additions gemm_kernel's epilogue
-// makes -- so the results stay bit-identical.  Epilogue out of registers: norm factor (from
-// rows_to_fragments_kernel), activation, product.  grid = ceil(tiles / 4).
+// makes -- so the results stay bit-identical.  One workgroup per CU has to cover the memory
+// latency alone, so a pass is GEMM_GATED_SUB k-steps deep: a weight register is reloaded for the
+// next pass right after its multiply (no second copy), and the running totals live in LDS to
+// make room.  Epilogue out of registers: norm factor (from rows_to_fragments_kernel),
+// activation, product.  grid = ceil(tiles / 4);
+// dynamic LDS = SUB * nrt fragments + 4 x 2 x GEMM_WIDE_RT x 256 floats.
+constexpr int GEMM_GATED_NW = 4;
+template <typename T> __host__ __device__ constexpr size_t gemm_gated_lds_bytes(int nrt) {
+  return (size_t)SplitShape<T>::SUB * nrt * 64 * 8 * sizeof(T) + (size_t)GEMM_GATED_NW * 2 * GEMM_WIDE_RT * 256 * sizeof(float);
+}
 template <typename T>
-static __global__ __launch_bounds__(256, 2) void gemm_gated_wide_kernel(const GemmArgs a) {
+static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_kernel(const GemmArgs a) {
   typedef typename Mma<T>::Frag Frag;
   extern __shared__ float lds[];
-  Frag* xs = reinterpret_cast<Frag*>(lds);          // [SUB][nrt][64 lanes]
-  constexpr int SUB = SplitShape<T>::SUB / 2, RT = GEMM_WIDE_RT, NT = 256;
+  constexpr int SUB = SplitShape<T>::SUB, RT = GEMM_WIDE_RT, NW = GEMM_GATED_NW, NT = 64 * NW;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, kq = lane >> 4;
   const int KS = a.K >> 5, ntiles = a.N >> 4, nrt = a.nrt, kpw = a.ksteps_per_wave;
-  const int tile = (int)blockIdx.x * 4 + wave, tilec = min(tile, ntiles - 1);
+  f32x4* tot = reinterpret_cast<f32x4*>(lds) + (size_t)wave * 2 * RT * 64 + lane;   // [2][RT] x 64 lanes, this lane's
+  Frag* xs = reinterpret_cast<Frag*>(lds + NW * 2 * RT * 256);                      // [SUB][nrt][64 lanes]
+  const int tile = (int)blockIdx.x * NW + wave, tilec = min(tile, ntiles - 1);
   const T* wbase[2];
   wbase[0] = static_cast<const T*>(a.W) + ((size_t)tilec * KS) * 512 + lane * 8;
   wbase[1] = static_cast<const T*>(a.W2) + ((size_t)tilec * KS) * 512 + lane * 8;
   const Frag* xf = reinterpret_cast<const Frag*>(a.X);            // [KS][RT][64 lanes]
 
-  f32x4 acc[2][RT], total[2][RT];
+  f32x4 acc[2][RT];
 #pragma unroll
   for (int st = 0; st < 2; ++st)
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) { acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f}; total[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int rt = 0; rt < RT; ++rt) { acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f}; tot[(st * RT + rt) * 64] = f32x4{0.f, 0.f, 0.f, 0.f}; }
   Frag wf[2][SUB];
-  auto load_w = [&](int ksb) {                       // unconditional, clamped: no branch around loads
-#pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-      for (int u = 0; u < SUB; ++u) wf[st][u] = Mma<T>::load_stream(wbase[st] + (size_t)min(ksb + u, KS - 1) * 512);
-  };
   constexpr int XPT = (SUB * RT * 64 + NT - 1) / NT;
   Frag xr[XPT];
   const int nfrag = SUB * nrt * 64;
-  auto load_x = [&](int ksb) {
+  auto load_x = [&](int ksb) {                       // unconditional, clamped: no branch around loads
 #pragma unroll
     for (int m = 0; m < XPT; ++m) {
       const int i = min(tid + NT * m, nfrag - 1);
@@ -974,7 +977,10 @@ static __global__ __launch_bounds__(256, 2) void gemm_gated_wide_kernel(const Ge
   };
   // a pass never crosses a chunk's end: its k-steps are [ksb, ksb + len)
   auto pass_len = [&](int ksb) { return min(SUB, min(KS, (ksb / kpw + 1) * kpw) - ksb); };
-  load_w(0);
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int u = 0; u < SUB; ++u) wf[st][u] = Mma<T>::load_stream(wbase[st] + (size_t)min(u, KS - 1) * 512);
   load_x(0);
   int chunks_done = 0;
   for (int ksb = 0; ksb < KS;) {
@@ -984,12 +990,6 @@ static __global__ __launch_bounds__(256, 2) void gemm_gated_wide_kernel(const Ge
     for (int m = 0; m < XPT; ++m)
       if (tid + NT * m < nfrag) xs[tid + NT * m] = xr[m];
     __syncthreads();
-    Frag cur[2][SUB];
-#pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-      for (int u = 0; u < SUB; ++u) cur[st][u] = wf[st][u];
-    load_w(next);
     load_x(next);
 #pragma unroll
     for (int u = 0; u < SUB; ++u) {
@@ -998,33 +998,30 @@ static __global__ __launch_bounds__(256, 2) void gemm_gated_wide_kernel(const Ge
         for (int rt = 0; rt < RT; ++rt) {
           if (rt < nrt) {
             const Frag fb = xs[(u * nrt + rt) * 64 + lane];
-            acc[0][rt] = Mma<T>::mma(cur[0][u], fb, acc[0][rt]);
-            acc[1][rt] = Mma<T>::mma(cur[1][u], fb, acc[1][rt]);
+            acc[0][rt] = Mma<T>::mma(wf[0][u], fb, acc[0][rt]);
+            acc[1][rt] = Mma<T>::mma(wf[1][u], fb, acc[1][rt]);
           }
         }
       }
+      // this register's next k-step is on its way while the rest of the pass is multiplied
+      wf[0][u] = Mma<T>::load_stream(wbase[0] + (size_t)min(next + u, KS - 1) * 512);
+      wf[1][u] = Mma<T>::load_stream(wbase[1] + (size_t)min(next + u, KS - 1) * 512);
     }
     if (next == KS || next % kpw == 0) {             // the chunk is complete: add it, chunks in order
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
+          f32x4 t = tot[(st * RT + rt) * 64];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) total[st][rt][r] += acc[st][rt][r];
+          for (int r = 0; r < 4; ++r) t[r] += acc[st][rt][r];
+          tot[(st * RT + rt) * 64] = t;
           acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
       ++chunks_done;
     }
     ksb = next;
   }
-  for (; chunks_done < a.nchunk; ++chunks_done)      // chunks beyond K are empty in gemm_kernel too: it adds their zeros
-#pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) total[st][rt][r] += 0.0f;
-
   if (tile >= ntiles) return;
   // accumulator layout: lane holds features 4 kq + r, r = 0..3, of row j
   const int n0 = tile * 16 + kq * 4;
@@ -1035,10 +1032,14 @@ static __global__ __launch_bounds__(256, 2) void gemm_gated_wide_kernel(const Ge
       if (j < rows) {
         const int row = rt * 16 + j;
         const float r1 = a.rs_in[row];
+        f32x4 t0 = tot[rt * 64], t1 = tot[(RT + rt) * 64];
+        for (int c = chunks_done; c < a.nchunk; ++c)      // chunks beyond K are empty in gemm_kernel too: it adds their zeros
+#pragma unroll
+          for (int r = 0; r < 4; ++r) { t0[r] += 0.0f; t1[r] += 0.0f; }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          float y0 = total[0][rt][r] * r1;
-          const float y1 = total[1][rt][r] * r1;
+          float y0 = t0[r] * r1;
+          const float y1 = t1[r] * r1;
           y0 += (a.bias != nullptr) ? Store<T>::ld(static_cast<const T*>(a.bias) + n0 + r) : 0.0f;
           const float g = (a.act == ACT_GELU) ? gelu_tanh(y0) : silu(y0);
           Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n0 + r, g * y1);

@@ -310,8 +310,8 @@ void launch_gemm_gated_wide(hipStream_t s, GemmArgs a) {
   const int S = pick_waves(KS);                  // the chunks whose sums the one-slab kernel adds
   a.ksteps_per_wave = (KS + S - 1) / S;
   a.nchunk = S;
-  const size_t lds = (size_t)(SplitShape<T>::SUB / 2) * a.nrt * 64 * 8 * sizeof(T);
-  hipLaunchKernelGGL((gemm_gated_wide_kernel<T>), dim3((tiles + 3) / 4), dim3(256), lds, s, a);
+  hipLaunchKernelGGL((gemm_gated_wide_kernel<T>), dim3((tiles + GEMM_GATED_NW - 1) / GEMM_GATED_NW), dim3(64 * GEMM_GATED_NW),
+                     gemm_gated_lds_bytes<T>(a.nrt), s, a);
 }
 
 // Which products take the split design (activations in fragment order, RMSNorm or no norm).
@@ -330,7 +330,8 @@ void launch_gemm_split(hipStream_t s, int pro, int epi, const GemmArgs& a, float
 // The wide kernel's LDS exceeds the default 64 KB limit of dynamic LDS.
 template <typename T>
 hipError_t allow_wide_lds() {
-  hipError_t e = hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_gated_wide_kernel<T>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_gated_lds_bytes<T>(GEMM_WIDE_RT));
 #define SD_CASE(P, E)                                                                                          \
   if (e == hipSuccess)                                                                                         \
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide_kernel<T, P, E>),                         \
