@@ -63,9 +63,14 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a 256 MiB device-to-device copy (reference for the profiler's byte counters)")
+    ap.add_argument("--workload", type=str, default="t5xxl", choices=["t5xxl", "gqa8b-batch16"],
+                    help="t5xxl: the headline configuration (default); gqa8b-batch16: the batched 8B-class "
+                         "configuration (16 sequences, 2048-token contexts, gamma 4), a side measurement")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (nothing here uses a second GPU)")
+    if args.workload == "gqa8b-batch16":
+        return batched_gqa8b(args)
 
     import numpy as np
     import torch
@@ -212,6 +217,50 @@ def main():
     }
     print(json.dumps(out), flush=True)
     dec.close()
+
+
+def batched_gqa8b(args, batch=16, ctx=2048, gamma=4):
+    """Side measurement: the batched 8B-class pair (32-layer GQA target, 2-layer draft, bf16), every
+    sequence with a ctx-token context written by a real prefill; Algorithm-1 iterations against plain
+    decoding steps of the same batch.  One JSON line; no CPU leg (the oracle needs minutes per row here)."""
+    import torch
+    from paper_2211_17192_amd import binding, synth
+    cfg_p, w_p, cfg_q, w_q = synth.gqa8b_pair("cuda")
+    dec = binding.SpecDecoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=binding.SD_FLAG_GRAPH, batch=batch)
+    del w_p, w_q
+    torch.cuda.empty_cache()
+    for b in range(batch):
+        dec.prefill(synth.random_tokens(300 + b, ctx, cfg_p["vocab"]), row=b)
+    steps, warm = min(args.steps, 40), min(args.warmup, 4)
+    U = synth.uniform_stream(9, (steps + warm) * batch * (2 * gamma + 1)).reshape(steps + warm, batch, -1)
+    for i in range(warm):
+        dec.step(gamma, TEMPERATURE, U[i])
+    torch.cuda.synchronize()
+    t0, tokens = time.perf_counter(), 0
+    for i in range(steps):
+        tokens += sum(n + 1 for n, _ in dec.step(gamma, TEMPERATURE, U[warm + i]))
+    torch.cuda.synchronize()
+    secs = time.perf_counter() - t0
+    st = dec.stats()
+    ub = synth.uniform_stream(7, (steps + 2) * batch).reshape(steps + 2, batch)
+    for i in range(2):
+        dec.step_baseline(TEMPERATURE, ub[i])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        dec.step_baseline(TEMPERATURE, ub[2 + i])
+    torch.cuda.synchronize()
+    plain = time.perf_counter() - t0
+    dec.close()
+    print(json.dumps({
+        "metric": "tokens_per_s", "value": tokens / secs, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": 1e3 * secs / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "gqa8b-batch16: 8B-class GQA target + 2-layer draft, 16 sequences, "
+                               f"{ctx}-token contexts, gamma {gamma}, temperature {TEMPERATURE}"},
+        "tokens_per_step": tokens / steps, "alpha": st["accepted"] / max(st["tested"], 1),
+        "plain_decode_tokens_per_s": batch * steps / plain, "plain_decode_ms_per_step": 1e3 * plain / steps,
+        "speedup_over_plain": (tokens / secs) / (batch * steps / plain)}))
 
 
 def cpu_baseline(cfg_p, cfg_q, host_w, synth):
