@@ -131,10 +131,31 @@ template <> struct Mma<float> {
   }
 };
 
+// The same row must come out bit-identical from every kernel that can compute it (one slab or
+// several), so the arithmetic of the epilogues and of the LayerNorm prologue is written once and
+// with floating-point contraction off: left to itself the compiler fuses a multiply and an add
+// into an FMA in one kernel and not in another, and the last bit of a rotated key then differs.
 __device__ __forceinline__ float gelu_tanh(float x) {
+#pragma clang fp contract(off)
   return 0.5f * x * (1.0f + tanhf(0.7978845608028654f * (x + 0.044715f * x * x * x)));
 }
-__device__ __forceinline__ float silu(float x) { return x / (1.0f + expf(-x)); }
+__device__ __forceinline__ float silu(float x) {
+#pragma clang fp contract(off)
+  return x / (1.0f + expf(-x));
+}
+// rotary embedding of one element: y with its pair partner `other`, (cos, sin) of the position
+__device__ __forceinline__ float rope_rotate(float y, float other, float c, float sn, bool odd) {
+#pragma clang fp contract(off)
+  const float yc = y * c, os = other * sn;
+  return odd ? (os + yc) : (yc - os);
+}
+// LayerNorm of one element
+__device__ __forceinline__ float ln_apply(float v, float mu, float rstd, float g, float b) {
+#pragma clang fp contract(off)
+  const float n = (v - mu) * rstd;
+  const float ng = n * g;
+  return ng + b;
+}
 
 #ifndef SD_EXP_UNROLL
 #define SD_EXP_UNROLL 8
@@ -214,7 +235,7 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
       load8<T>(static_cast<const T*>(a.gain) + k, g);
       load8<T>(static_cast<const T*>(a.beta) + k, bb);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = (v[e] - mu) * rstd * g[e] + bb[e];
+      for (int e = 0; e < 8; ++e) v[e] = ln_apply(v[e], mu, rstd, g[e], bb[e]);
       return Mma<T>::select(valid && row_ok, Mma<T>::from_floats(v));
     }
   };
@@ -358,7 +379,7 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         const int head = nn / a.d_head, d = nn % a.d_head;
         if (a.rope != nullptr && (is_q || is_k) && e_pos >= 0) {
           const float other = ybuf[t ^ 1];
-          y = (d & 1) ? (other * pre_sin + y * pre_cos) : (y * pre_cos - other * pre_sin);
+          y = rope_rotate(y, other, pre_cos, pre_sin, (d & 1) != 0);
         }
         if (is_q) {
           Store<T>::st(static_cast<T*>(a.q_out) + (size_t)e_row * a.nq + n, y);
@@ -550,7 +571,7 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
       load8<T>(static_cast<const T*>(a.gain) + k, g);
       load8<T>(static_cast<const T*>(a.beta) + k, bb);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = (v[e] - mu[rt]) * rstd[rt] * g[e] + bb[e];
+      for (int e = 0; e < 8; ++e) v[e] = ln_apply(v[e], mu[rt], rstd[rt], g[e], bb[e]);
       return Mma<T>::select(valid && jok[rt], Mma<T>::from_floats(v));
     }
   };
@@ -698,7 +719,7 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
               if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
                 const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
                 const float other = ybuf[(o * RT + rt) * 256 + (e_idx ^ 1)];
-                y = (d & 1) ? (other * cs[1] + y * cs[0]) : (y * cs[0] - other * cs[1]);
+                y = rope_rotate(y, other, cs[0], cs[1], (d & 1) != 0);
               }
               if (is_q) {
                 Store<T>::st(static_cast<T*>(a.q_out) + (size_t)row * a.nq + n, y);
@@ -890,7 +911,7 @@ static __global__ __launch_bounds__(256) void gemm_split_finish_kernel(const Gem
     const float other = __shfl_xor(v, 1, 64);        // the other half of the rotary pair: feature f ^ 1 of the same row
     if (a.rope != nullptr && (is_q || is_k) && pos >= 0) {
       const float* cs = a.rope + ((size_t)pos * (a.d_head >> 1) + (d >> 1)) * 2;
-      v = (d & 1) ? (other * cs[1] + v * cs[0]) : (v * cs[0] - other * cs[1]);
+      v = rope_rotate(v, other, cs[0], cs[1], (d & 1) != 0);
     }
     if (ok) {
       if (is_q) {

@@ -411,6 +411,8 @@ def test_top_k_and_nucleus_decoding_matches_oracle(top_k, top_p):
     (T.GQA, "bf16", 5, 4),      # 25 verify rows: groups of 3 + 2 sequences
     (T.GPT, "bf16", 16, 3),     # 64 verify rows: four groups; 32 rows in the first draft step
     (T.GQA, "bf16", 4, 7),      # 8 rows per sequence: two sequences per group
+    (T.GQA, "bf16", 16, 4),     # 80 verify rows: six groups, the last with one sequence (RMSNorm: split / gated GEMMs)
+    (T.GQA, "f32", 11, 4),      # 55 verify rows: groups of 3 + 3 + 3 + 2 sequences, fp32 fragments
 ])
 def test_batched_decoding_equals_single_sequence_decoding(arch, dtype, batch, gamma):
     """A row's arithmetic never depends on the other rows of a launch, so every sequence of a
