@@ -413,6 +413,8 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
 #pragma unroll
     for (int s = 0; s < KSQ; ++s) qf[rt][s] = ok ? ld_frag(qp + s * 32) : zero_frag();
   }
+  int pos_min = 0x7fffffff;                         // a step whose keys all lie at or below it needs no mask
+  for (int r = 0; r < R; ++r) pos_min = min(pos_min, s_pos[r]);
   float m_run[NRT], l_run[NRT];
   f32x4 o[DT][NRT];
 #pragma unroll
@@ -432,12 +434,18 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
   // product), so a wavefront's load latency overlaps a whole step of its own arithmetic.
   bf16x8 kf[2][KSQ];
   bf16x8 vr[DH / 16];
-  auto load_k = [&](int kb) {                       // always issued: past the range every lane re-reads the last key
+  // A step's 32 keys start at a multiple of 32 and pages hold a multiple of 16 keys, so keys 0..15
+  // of the step are consecutive slots of one page and keys 16..31 of one page: two table lookups
+  // per step and operand instead of one per load.  (Past the range kb is clamped and every lane
+  // re-reads key kb itself, slot 0 of the first half.)
+  auto load_k = [&](int kb) {                       // always issued
     kb = min(kb, kv_len - 1);
     const int nk = min(32, kv_len - kb);
+    const bf16* half[2] = {row_ptr(kb, 0), row_ptr(min(kb + 16, kv_len - 1), 0)};
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
-      const bf16* kp = row_ptr(kb + min(kt * 16 + j, nk - 1), 0) + kq * 8;
+      const int kk = min(kt * 16 + j, nk - 1);
+      const bf16* kp = ((kk < 16) ? half[0] + kk * DH : half[1] + (kk - 16) * DH) + kq * 8;
 #pragma unroll
       for (int s = 0; s < KSQ; ++s) kf[kt][s] = ld_frag(kp + s * 32);      // the four quarters read 64 contiguous bytes
     }
@@ -445,8 +453,12 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
   auto load_v = [&](int kb) {                       // load c: VKPL keys, each row read by DH/8 consecutive lanes
     kb = min(kb, kv_len - 1);
     const int nk = min(32, kv_len - kb);
+    const bf16* half[2] = {row_ptr(kb, 1), row_ptr(min(kb + 16, kv_len - 1), 1)};
 #pragma unroll
-    for (int c = 0; c < DH / 16; ++c) vr[c] = ld_frag(row_ptr(kb + min(c * VKPL + vkey, nk - 1), 1) + vpiece * 8);
+    for (int c = 0; c < DH / 16; ++c) {
+      const int kk = min(c * VKPL + vkey, nk - 1);
+      vr[c] = ld_frag(((kk < 16) ? half[0] + kk * DH : half[1] + (kk - 16) * DH) + vpiece * 8);
+    }
   };
   const int kb0 = k_begin + wave * 32;
   SD_STAMPL(0);
@@ -480,18 +492,29 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
     float p[2][NRT][4];
     float f[NRT];
     bool rescale = false;
+    const bool all_visible = nkeys == 32 && kb + 31 <= pos_min;     // uniform
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
       float mx = -INFINITY;
+      if (all_visible) {
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int kl = kt * 16 + kq * 4 + r;
-          const bool ok = kl < nkeys && kb + kl <= pos[rt];
-          p[kt][rt][r] = ok ? a.scale * sc[kt][rt][r] : -INFINITY;
-          mx = fmaxf(mx, p[kt][rt][r]);
-        }
+          for (int r = 0; r < 4; ++r) {
+            p[kt][rt][r] = a.scale * sc[kt][rt][r];
+            mx = fmaxf(mx, p[kt][rt][r]);
+          }
+      } else {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int kl = kt * 16 + kq * 4 + r;
+            const bool ok = kl < nkeys && kb + kl <= pos[rt];
+            p[kt][rt][r] = ok ? a.scale * sc[kt][rt][r] : -INFINITY;
+            mx = fmaxf(mx, p[kt][rt][r]);
+          }
+      }
       mx = lane_combine<16>(mx, OpMaxF());
       mx = lane_combine<32>(mx, OpMaxF());
       // the reference point m_run only moves when the scores outgrow it by more than
