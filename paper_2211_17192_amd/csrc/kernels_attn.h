@@ -73,10 +73,9 @@ struct AttnArgs {
   const int* row_pos;       // [R]; self: causal limit of each row, < 0 = padding row
   int R, H, Hkv;
   int rows_per_wg;          // grid.y = ceil(R / rows_per_wg): rows are independent, no merge needed
-  // several sequences in one launch: grid.z = sequences, R rows each; they sit in slabs of
-  // MAX_ROWS rows, spg whole sequences per slab (sequence z: slab z / spg, rows (z % spg) * R ..);
-  // sequence z uses the page table at page_table + (seq0 + z) * pt_stride
-  int seq0, pt_stride, spg;
+  // several sequences in one launch: grid.z = sequences, R rows each, one after the other
+  // (sequence z: rows z * R ..); sequence z uses the page table at page_table + (seq0 + z) * pt_stride
+  int seq0, pt_stride;
   // long contexts: the keys of a (sequence, kv head) are cut into nsplit ranges of split_keys keys
   // (a multiple of the key block) that different workgroups take (grid.y = row groups x nsplit);
   // each leaves its running maximum, denominator and unnormalised output in `partial`
@@ -111,7 +110,7 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   const int split = (a.nsplit > 1) ? (int)blockIdx.y % a.nsplit : 0;
   const int rs = ((a.nsplit > 1) ? (int)blockIdx.y / a.nsplit : (int)blockIdx.y) * a.rows_per_wg;   // first row within the sequence
   const int R = min(a.rows_per_wg, a.R - rs);
-  const int r0 = ((int)blockIdx.z / a.spg) * MAX_ROWS + ((int)blockIdx.z % a.spg) * a.R + rs;   // first row within the launch
+  const int r0 = (int)blockIdx.z * a.R + rs;      // first row within the launch
   const int* page_table = a.page_table + (size_t)(a.seq0 + blockIdx.z) * a.pt_stride;
   const int G = a.H / a.Hkv, RG = R * G;
 #ifdef SD_KTIME
@@ -364,7 +363,7 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
   const int split = (int)blockIdx.z % a.nsplit;
   const int rs = ((int)blockIdx.z / a.nsplit) * a.rows_per_wg;
   const int R = min(a.rows_per_wg, a.R - rs);
-  const int r0 = (seq / a.spg) * MAX_ROWS + (seq % a.spg) * a.R + rs;
+  const int r0 = seq * a.R + rs;
   const int* page_table = a.page_table + (size_t)(a.seq0 + seq) * a.pt_stride;
   const int G = a.H / a.Hkv, RG = R * G;
 #ifdef SD_KTIME
@@ -617,7 +616,7 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
 template <typename T, int DH>
 static __global__ __launch_bounds__(DH) void attn_merge_kernel(const AttnArgs a) {
   const int hkv = blockIdx.x, G = a.H / a.Hkv, rg = blockIdx.y, d = threadIdx.x;
-  const int r_base = ((int)blockIdx.z / a.spg) * MAX_ROWS + ((int)blockIdx.z % a.spg) * a.R;
+  const int r_base = (int)blockIdx.z * a.R;
   const float* pp = a.partial + ((((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit) * ATTN_MAX_RG + rg) * (DH + 2);
   const size_t stride = (size_t)ATTN_MAX_RG * (DH + 2);
   float m = -INFINITY;

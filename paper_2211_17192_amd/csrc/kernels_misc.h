@@ -20,10 +20,9 @@ enum {
 // For RMSNorm models the kernel also writes xg = x * gain of the first norm in
 // the storage type and the row's sum of squares (one partial: ss[0][r]).
 // Several sequences: the launch covers sequences seq0, seq0+1, ... with rps rows
-// each; they are laid out in slabs of MAX_ROWS rows holding spg whole sequences, so
-// workgroup b (sequence seq0 + b / rps) writes row (b / rps / spg) * MAX_ROWS +
-// (b / rps % spg) * rps + b % rps of x / xg / row_pos / ..., and the sum of squares of
-// its row into the slab's block of ss (ss_stride floats per slab); `st` is the array
+// each, one after the other: workgroup b (sequence seq0 + b / rps) writes row b of
+// x / xg / row_pos / ..., and the sum of squares of its row into the block of ss that
+// belongs to the row's slab of MAX_ROWS rows (ss_stride floats per slab); `st` is the array
 // of sequence states.  row_seq[r] (when given) receives the row's sequence, logit_row[r] the
 // row of the logits buffer its LM-head output belongs in (< 0: not needed):
 // p rows [seq][gamma+1], q rows [seq][gamma], one row per sequence for plain decoding.
@@ -34,11 +33,10 @@ static __global__ __launch_bounds__(256) void embed_kernel(
     float* __restrict__ x, int* __restrict__ row_pos, const T* __restrict__ gain_next,
     T* __restrict__ xg, float* __restrict__ ss,
     int rps, int seq0, int gamma, int* __restrict__ row_seq, int* __restrict__ logit_row,
-    int spg, int ss_stride) {
+    int ss_stride) {
   __shared__ float red[16];
   const int j = (int)blockIdx.x % rps, sl = (int)blockIdx.x / rps, seq = seq0 + sl;
-  const int slab = sl / spg, r16 = (sl % spg) * rps + j;     // row within its slab
-  const int r = slab * MAX_ROWS + r16;
+  const int r = blockIdx.x, slab = r / MAX_ROWS, r16 = r % MAX_ROWS;     // row, its slab, row within the slab
   st += seq;
   int tok, pos, lrow = -1;
   switch (mode) {

@@ -421,9 +421,9 @@ struct Rows { int mode, step, rps, start, seq0, nseq, gamma; };
 
 // One forward of model m; with `logits` the LM head runs on every row and each row's
 // output goes where the embedding kernel's row map says (or nowhere).
-// The kernels take at most MAX_ROWS rows, so the sequences are cut into groups of
-// MAX_ROWS / rps whole sequences; every operation is launched once per group (each launch
-// streams the operation's weights again: more than one group costs bandwidth, not correctness).
+// The rows of the sequences lie one after the other (sequence s: rows s * rps ..) and are cut into
+// slabs ("groups") of MAX_ROWS rows for the GEMMs; a sequence may straddle two slabs, which no
+// kernel minds: every row carries its own position, sequence and output row.
 template <typename T>
 void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
   hipStream_t s = c->stream;
@@ -433,14 +433,12 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
   const bool rms = (f.arch != SD_ARCH_GPT);
   const int pro = rms ? PRO_POST : PRO_LN;
   const int n_layers = (int)m.L.size();
-  const int spg = std::max(1, MAX_ROWS / rw.rps);                  // sequences per group
-  const int n_groups = (rw.nseq + spg - 1) / spg;
-  struct Grp { int seq0, ns, R; float* x; char* xg; float* ss; char *qbuf, *attn, *ffn; int *row_pos, *row_seq, *logit_row; };
+  const int rows_total = rw.nseq * rw.rps;
+  const int n_groups = (rows_total + MAX_ROWS - 1) / MAX_ROWS;
+  struct Grp { int R; float* x; char* xg; float* ss; char *qbuf, *attn, *ffn; int *row_pos, *row_seq, *logit_row; };
   auto group = [&](int g) {
     Grp q;
-    q.seq0 = rw.seq0 + g * spg;
-    q.ns = std::min(spg, rw.seq0 + rw.nseq - q.seq0);
-    q.R = q.ns * rw.rps;
+    q.R = std::min(MAX_ROWS, rows_total - g * MAX_ROWS);
     const size_t off = (size_t)g * MAX_ROWS;
     q.x = m.x + off * d;
     q.xg = static_cast<char*>(m.xg) + off * d * e;
@@ -457,12 +455,12 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
                        rw.start, static_cast<const T*>(m.tok_emb), static_cast<const T*>(m.pos_emb), d, f.vocab, q.x,
                        q.row_pos, static_cast<const T*>(rms ? m.L[0].ln1g : nullptr),
                        reinterpret_cast<T*>(rms ? q.xg : nullptr), rms ? q.ss : nullptr,
-                       rw.rps, rw.seq0, rw.gamma, q.row_seq, q.logit_row, spg, (d / 16) * 16);
+                       rw.rps, rw.seq0, rw.gamma, q.row_seq, q.logit_row, (d / 16) * 16);
   }
   // One GEMM over every group: groups are 16-row slabs one after the other in all row-indexed
   // buffers, so up to GEMM_WIDE_RT of them go into one launch of the wide kernel (weights
   // streamed once for all of them); a single group takes the one-slab kernel.
-  const int R_full = spg * rw.rps, R_tail = (rw.nseq - (n_groups - 1) * spg) * rw.rps;
+  const int R_full = MAX_ROWS, R_tail = rows_total - (n_groups - 1) * MAX_ROWS;
   auto gemm_groups = [&](int pro_, int epi_, const std::function<void(GemmArgs&, const Grp&)>& fill) {
     if (n_groups == 1) {
       GemmArgs a{};
@@ -527,7 +525,7 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
         a.row_pos = q.row_pos; a.R = rw.rps; a.H = f.n_heads; a.Hkv = f.n_kv_heads; a.cross = 0; a.kv_len = 0;
         a.scale = (f.arch == SD_ARCH_T5DEC) ? 1.0f : 1.0f / sqrtf((float)f.d_head);
         a.rel_bias = m.rel_bias; a.bucket_lut = m.bucket_lut; a.rel_buckets = f.rel_buckets;
-        a.seq0 = rw.seq0; a.pt_stride = m.n_pages; a.spg = spg;
+        a.seq0 = rw.seq0; a.pt_stride = m.n_pages;
         if (cross) { a.cross = 1; a.ck = l.cross_k; a.cv = l.cross_v; a.kv_len = f.enc_len; a.scale = 1.0f; a.rel_bias = nullptr; }
         launch_attn<T>(s, m, a, rw.nseq);
       }
