@@ -81,6 +81,9 @@ struct GemmArgs {
   float* partial;
   int nchunk;
   const float* rs_in;     // PRO_POST: 1 / rms of every row, [nrt * 16] (rows_to_fragments_kernel writes it)
+  // gemm_gated_wide_kernel: when set, the output goes here in fragment order
+  // ([N/32][GEMM_WIDE_RT][64 lanes][8], what the FFN-out product reads) instead of row-major into `out`
+  void* out_frag;
 };
 
 template <typename T> struct Mma;
@@ -1063,7 +1066,10 @@ static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_ker
           const float y1 = t1[r] * r1;
           y0 += (a.bias != nullptr) ? Store<T>::ld(static_cast<const T*>(a.bias) + n0 + r) : 0.0f;
           const float g = (a.act == ACT_GELU) ? gelu_tanh(y0) : silu(y0);
-          Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n0 + r, g * y1);
+          if (a.out_frag != nullptr)     // element (row, n): k-step n / 32, lane (row % 16) + 16 ((n % 32) / 8), element n % 8
+            Store<T>::st(static_cast<T*>(a.out_frag) + ((((size_t)((n0 + r) >> 5) * RT + rt) * 64 + j + 16 * (((n0 + r) & 31) >> 3)) * 8 + ((n0 + r) & 7)), g * y1);
+          else
+            Store<T>::st(static_cast<T*>(a.out) + (size_t)row * a.ldo + n0 + r, g * y1);
         }
       }
     }

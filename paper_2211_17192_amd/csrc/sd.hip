@@ -66,6 +66,7 @@ struct Model {
   void* xfrag = nullptr;       // activations of one wide GEMM in fragment order
   float* wide_partial = nullptr;   // partial tiles of the K chunks of one split GEMM
   float* wide_rs = nullptr;        // 1 / rms of the rows of one split GEMM
+  void* xfrag2 = nullptr;          // a batched kernel's output that the next product reads, in fragment order
   int attn_nsplit = 1, attn_split_keys = 0;   // long contexts: key ranges per (sequence, kv head)
   float* attn_partial = nullptr;
   float* x = nullptr;
@@ -168,6 +169,7 @@ void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size, int ba
     const size_t tiles = std::max((size_t)d, (size_t)(m.nq + 2 * m.nkv)) / 16;    // the products split_ok() lets through
     m.wide_partial = static_cast<float*>(A.take((size_t)8 * GEMM_WIDE_RT * tiles * 256 * sizeof(float)));
     m.wide_rs = static_cast<float*>(A.take((size_t)GEMM_WIDE_RT * 16 * sizeof(float)));
+    m.xfrag2 = A.take((size_t)std::max({(size_t)d, (size_t)m.nq, ff}) * GEMM_WIDE_RT * 16 * e);
   }
   m.prompt = static_cast<int*>(A.take((size_t)c.max_len * sizeof(int)));
 }
@@ -461,6 +463,9 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
   // buffers, so up to GEMM_WIDE_RT of them go into one launch of the wide kernel (weights
   // streamed once for all of them); a single group takes the one-slab kernel.
   const int R_full = MAX_ROWS, R_tail = rows_total - (n_groups - 1) * MAX_ROWS;
+  // frag_in: the producer left this product's activations in fragment order already (one launch only)
+  const void* frag_in = nullptr;
+  bool out_frag_next = false, produced_frag = false;   // ask the gated kernel for fragment-order output / it complied
   auto gemm_groups = [&](int pro_, int epi_, const std::function<void(GemmArgs&, const Grp&)>& fill) {
     if (n_groups == 1) {
       GemmArgs a{};
@@ -475,7 +480,9 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       a.R = R_full;
       a.R_last = (g0 + a.nrt == n_groups) ? R_tail : R_full;
       a.ss_stride = (d / 16) * 16;
-      if (pro_ != PRO_LN) {                       // the wide kernel reads the activations in fragment order
+      if (frag_in != nullptr && pro_ == PRO_NONE && n_groups <= GEMM_WIDE_RT) {
+        a.X = frag_in;
+      } else if (pro_ != PRO_LN) {                // the wide kernel reads the activations in fragment order
         const int frags = (a.K / 32) * a.nrt;
         const int blocks = (frags * 64 + 255) / 256;
         const bool want_rs = pro_ == PRO_POST && (split_ok(pro_, epi_) || epi_ == EPI_GATED) && blocks >= 2 * a.nrt;
@@ -485,7 +492,10 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
         a.X = m.xfrag;
         a.rs_in = want_rs ? m.wide_rs : nullptr;
       }
-      if (pro_ == PRO_POST && epi_ == EPI_GATED && a.rs_in != nullptr) launch_gemm_gated_wide<T>(s, a);
+      if (pro_ == PRO_POST && epi_ == EPI_GATED && a.rs_in != nullptr) {
+        if (out_frag_next && n_groups <= GEMM_WIDE_RT) { a.out_frag = m.xfrag2; produced_frag = true; }
+        launch_gemm_gated_wide<T>(s, a);
+      }
       else if (split_ok(pro_, epi_) && (pro_ != PRO_POST || a.rs_in != nullptr)) launch_gemm_split<T>(s, pro_, epi_, a, m.wide_partial);
       else launch_gemm_wide<T>(s, pro_, epi_, a);
     }
@@ -547,6 +557,7 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       const bool gpt = (f.arch == SD_ARCH_GPT);
       const bool timed = !gpt && c->time_ffn && &m == &c->p && 2 * li + 1 < (int)c->kev.size();
       if (timed) hipEventRecord(c->kev[2 * li], s);
+      out_frag_next = true;                        // the FFN-out product reads fragments: skip its re-tile
       gemm_groups(gpt ? PRO_LN : PRO_POST, gpt ? EPI_ACT : EPI_GATED, [&](GemmArgs& h, const Grp& q) {
         normed(h, q, l.ln2g, l.ln2b);
         h.K = d; h.N = f.d_ff; h.out = q.ffn; h.ldo = f.d_ff; h.W = l.w1;
@@ -555,7 +566,11 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       });
       if (timed) hipEventRecord(c->kev[2 * li + 1], s);
     }
+    out_frag_next = false;
+    frag_in = produced_frag ? m.xfrag2 : nullptr;
+    produced_frag = false;
     resid(l.w2, true, l.b2, f.d_ff, (li + 1 < n_layers) ? m.L[li + 1].ln1g : m.lnfg);
+    frag_in = nullptr;
   }
   if (logits != nullptr) {
     gemm_groups(pro, EPI_LOGITS, [&](GemmArgs& a, const Grp& q) {
