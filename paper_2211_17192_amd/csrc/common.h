@@ -17,6 +17,10 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 // Device-resident decoding state of one sequence (section 2.3 / Algorithm 1:
 // the committed prefix is summarised by its length and last two tokens; x
 // holds the guesses of the running iteration).
+// Slabs of MAX_ROWS rows one batched GEMM launch takes; also the slab count of the fragment-order
+// activation buffers ([K/32][GEMM_WIDE_RT][64 lanes][8]) that the producing kernels may write directly.
+constexpr int GEMM_WIDE_RT = 6;
+
 struct SeqState {
   int32_t len;                 // committed tokens
   int32_t last_tok;            // token at position len-1
@@ -125,6 +129,18 @@ __device__ __forceinline__ V lane_combine(V v, Op op) {
     for (int i = 0; i < Words<V>::N; ++i) { const u32x2 r = half_swap<OFF>(w[i]); x[i] = r.x; y[i] = r.y; }
     return op(Words<V>::join(x), Words<V>::join(y));
   }
+}
+
+// The value that lane 0 of this lane's row of 16 holds.  (After the four in-row steps of a sum every
+// lane holds a total, but the rotation of the OFF == 4 step gives the quads two different
+// association orders; code that must agree bit for bit with code that reads lane 0's total
+// takes lane 0's too.)
+__device__ __forceinline__ float row_first(float v) {
+  const int w = __builtin_bit_cast(int, v);
+  const int a = __builtin_amdgcn_readlane(w, 0), b = __builtin_amdgcn_readlane(w, 16);
+  const int c = __builtin_amdgcn_readlane(w, 32), d = __builtin_amdgcn_readlane(w, 48);
+  const int lane = (int)(threadIdx.x & 63);
+  return __builtin_bit_cast(float, lane < 16 ? a : (lane < 32 ? b : (lane < 48 ? c : d)));
 }
 
 // All 64 lanes get op over the wavefront (op must be commutative; the

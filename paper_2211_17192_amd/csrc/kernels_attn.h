@@ -83,6 +83,10 @@ struct AttnArgs {
   // them.  nsplit is fixed per model (from max_len), so the split never depends on the other rows.
   int nsplit, split_keys;
   float* partial;
+  // attn_merge_kernel: when set, the merged output goes here in the batched GEMMs' fragment order
+  // ([H * d_head / 32][GEMM_WIDE_RT][64 lanes][8]: element (row, n) at k-step n / 32, slab row / 16,
+  // lane (row % 16) + 16 ((n % 32) / 8), element n % 8) instead of row-major into `out`
+  void* out_frag;
   int cross;                // 1: cross-attention over kv_len keys, no mask, no bias
   int kv_len;
   float scale;
@@ -632,7 +636,13 @@ static __global__ __launch_bounds__(DH) void attn_merge_kernel(const AttnArgs a)
     }
   }
   const int r = rg / G, h = hkv * G + rg % G;
-  Store<T>::st(static_cast<T*>(a.out) + (size_t)(r_base + r) * a.H * DH + h * DH + d, (L > 0.0f) ? o / L : 0.0f);
+  const float res = (L > 0.0f) ? o / L : 0.0f;
+  if (a.out_frag != nullptr) {
+    const int row = r_base + r, n = h * DH + d;
+    Store<T>::st(static_cast<T*>(a.out_frag) + ((((size_t)(n >> 5) * GEMM_WIDE_RT + (row >> 4)) * 64 + (row & 15) + 16 * ((n & 31) >> 3)) * 8 + (n & 7)), res);
+  } else {
+    Store<T>::st(static_cast<T*>(a.out) + (size_t)(r_base + r) * a.H * DH + h * DH + d, res);
+  }
 }
 
 }  // namespace sd

@@ -152,6 +152,19 @@ __device__ __forceinline__ float rope_rotate(float y, float other, float c, floa
   const float yc = y * c, os = other * sn;
   return odd ? (os + yc) : (yc - os);
 }
+// a square that stays a product: the sums of squares behind the norms must not depend on whether
+// the compiler fuses the square into the addition that follows it
+__device__ __forceinline__ float square(float x) {
+#pragma clang fp contract(off)
+  const float q = x * x;
+  return q;
+}
+// variance accumulation of the LayerNorm prologue
+__device__ __forceinline__ float add_square(float acc, float x) {
+#pragma clang fp contract(off)
+  const float q = x * x;
+  return acc + q;
+}
 // LayerNorm of one element
 __device__ __forceinline__ float ln_apply(float v, float mu, float rstd, float g, float b) {
 #pragma clang fp contract(off)
@@ -210,7 +223,7 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     for (int ks = ks0; ks < ks1; ++ks) {
       float v[8]; load8<float>(x + ks * 32, v);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { const float d = v[e] - mu; s2 += d * d; }
+      for (int e = 0; e < 8; ++e) s2 = add_square(s2, v[e] - mu);
     }
     s2 = lane_combine<16>(s2, OpSumF()); s2 = lane_combine<32>(s2, OpSumF());
     if (kq == 0) stat[wave * 16 + j] = s2;
@@ -334,6 +347,7 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         for (int p = f + 16 * GEMM_PART_REGS; p < a.n_part; p += 16) q += a.ss_in[p * 16 + e_rowc];
         q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
         q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+        q = row_first(q);                          // the total the batched kernels use: the first lane's
         const float rs = 1.0f / sqrtf(q / (float)a.K + a.eps);
 #pragma unroll
         for (int d = 0; d < ND; ++d) y[d] *= rs;
@@ -349,7 +363,7 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
           if (a.xg_out != nullptr) Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * pre_gain);
         }
         if (a.ss_out != nullptr) {
-          float q = xn * xn;
+          float q = square(xn);
           q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
           q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
           if (f == 0) a.ss_out[tile * 16 + row] = q;
@@ -445,7 +459,6 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 // PRO_LN (LayerNorm prologue) still reads the fp32 rows directly.
 // Main loop: a ring of k-step slots refilled right after use; no branches around loads.
 // ---------------------------------------------------------------------------
-constexpr int GEMM_WIDE_RT = 6;
 constexpr int GEMM_WIDE_U = 2;
 
 // LDS of the wide kernel: the partial tiles of every wavefront, stream and slab, the QKV
@@ -549,7 +562,7 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
       for (int ks = ks0; ks < ks1; ++ks) {
         float v[8]; load8<float>(x + ks * 32, v);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { const float d = v[e] - mu[rt]; s2 += d * d; }
+        for (int e = 0; e < 8; ++e) s2 = add_square(s2, v[e] - mu[rt]);
       }
       s2 = lane_combine<16>(s2, OpSumF()); s2 = lane_combine<32>(s2, OpSumF());
       __syncthreads();
@@ -683,7 +696,7 @@ static __global__ __launch_bounds__(512) void gemm_wide_kernel(const GemmArgs a)
               if (a.xg_out != nullptr) Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * gain);
             }
             if (a.ss_out != nullptr) {
-              float q = xn * xn;
+              float q = square(xn);
               q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
               q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
               if (f == 0) a.ss_out[(size_t)rt * a.ss_stride + tile * 16 + e_row] = q;
@@ -935,7 +948,7 @@ static __global__ __launch_bounds__(256) void gemm_split_finish_kernel(const Gem
         Store<T>::st(static_cast<T*>(a.xg_out) + (size_t)row * a.ldo + n, xn * Store<T>::ld(static_cast<const T*>(a.gain_next) + n));
     }
     if (a.ss_out != nullptr) {
-      float q = xn * xn;
+      float q = square(xn);
       q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
       q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
       if (f == 0) a.ss_out[(size_t)rt * a.ss_stride + tile * 16 + e_row] = q;
@@ -966,7 +979,9 @@ constexpr int GEMM_GATED_NW = 4;
 template <typename T> __host__ __device__ constexpr size_t gemm_gated_lds_bytes(int nrt) {
   return (size_t)SplitShape<T>::SUB * nrt * 64 * 8 * sizeof(T) + (size_t)GEMM_GATED_NW * 2 * GEMM_WIDE_RT * 256 * sizeof(float);
 }
-template <typename T>
+// EPI == EPI_LOGITS: the same walk for the LM head; a wavefront's two streams are the tiles 2 t and
+// 2 t + 1 of the one weight matrix, the epilogue scales and routes the rows (out_row).
+template <typename T, int EPI>
 static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_kernel(const GemmArgs a) {
   typedef typename Mma<T>::Frag Frag;
   extern __shared__ float lds[];
@@ -976,10 +991,13 @@ static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_ker
   const int KS = a.K >> 5, ntiles = a.N >> 4, nrt = a.nrt, kpw = a.ksteps_per_wave;
   f32x4* tot = reinterpret_cast<f32x4*>(lds) + (size_t)wave * 2 * RT * 64 + lane;   // [2][RT] x 64 lanes, this lane's
   Frag* xs = reinterpret_cast<Frag*>(lds + NW * 2 * RT * 256);                      // [SUB][nrt][64 lanes]
-  const int tile = (int)blockIdx.x * NW + wave, tilec = min(tile, ntiles - 1);
+  // work item = pair of streams: (gate, up) of tile `item`, or tiles 2 item and 2 item + 1
+  const int nitems = (EPI == EPI_GATED) ? ntiles : (ntiles + 1) / 2;
+  const int item = (int)blockIdx.x * NW + wave, itemc = min(item, nitems - 1);
+  const int tile0 = (EPI == EPI_GATED) ? itemc : 2 * itemc, tile1 = (EPI == EPI_GATED) ? itemc : min(2 * itemc + 1, ntiles - 1);
   const T* wbase[2];
-  wbase[0] = static_cast<const T*>(a.W) + ((size_t)tilec * KS) * 512 + lane * 8;
-  wbase[1] = static_cast<const T*>(a.W2) + ((size_t)tilec * KS) * 512 + lane * 8;
+  wbase[0] = static_cast<const T*>(a.W) + ((size_t)tile0 * KS) * 512 + lane * 8;
+  wbase[1] = static_cast<const T*>((EPI == EPI_GATED) ? a.W2 : a.W) + ((size_t)tile1 * KS) * 512 + lane * 8;
   const Frag* xf = reinterpret_cast<const Frag*>(a.X);            // [KS][RT][64 lanes]
 
   f32x4 acc[2][RT];
@@ -1046,9 +1064,9 @@ static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_ker
     }
     ksb = next;
   }
-  if (tile >= ntiles) return;
+  if (item >= nitems) return;
   // accumulator layout: lane holds features 4 kq + r, r = 0..3, of row j
-  const int n0 = tile * 16 + kq * 4;
+  const int n0 = tile0 * 16 + kq * 4;
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     if (rt < nrt) {
@@ -1060,6 +1078,23 @@ static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_ker
         for (int c = chunks_done; c < a.nchunk; ++c)      // chunks beyond K are empty in gemm_kernel too: it adds their zeros
 #pragma unroll
           for (int r = 0; r < 4; ++r) { t0[r] += 0.0f; t1[r] += 0.0f; }
+        if (EPI == EPI_LOGITS) {
+          const int orow = (a.out_row != nullptr) ? a.out_row[row] : row;
+          if (orow >= 0) {
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+              if (st == 1 && 2 * item + 1 >= ntiles) break;          // an odd number of tiles: no second stream
+              const int n1 = (2 * item + st) * 16 + kq * 4;
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                float y = (st ? t1[r] : t0[r]) * r1;
+                y += (a.bias != nullptr) ? Store<T>::ld(static_cast<const T*>(a.bias) + n1 + r) : 0.0f;
+                static_cast<float*>(a.out)[(size_t)orow * a.ldo + n1 + r] = a.scale * y;
+              }
+            }
+          }
+          continue;
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           float y0 = t0[r] * r1;

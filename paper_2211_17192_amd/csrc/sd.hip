@@ -306,13 +306,13 @@ void launch_gemm_split_t(hipStream_t s, GemmArgs a, float* partial) {
 }
 
 // Gated FFN-in over several slabs: no split over workgroups, every wavefront walks all of K.
-template <typename T>
+template <typename T, int EPI>
 void launch_gemm_gated_wide(hipStream_t s, GemmArgs a) {
-  const int tiles = a.N / 16, KS = a.K / 32;
+  const int tiles = (EPI == EPI_GATED) ? a.N / 16 : (a.N / 16 + 1) / 2, KS = a.K / 32;
   const int S = pick_waves(KS);                  // the chunks whose sums the one-slab kernel adds
   a.ksteps_per_wave = (KS + S - 1) / S;
   a.nchunk = S;
-  hipLaunchKernelGGL((gemm_gated_wide_kernel<T>), dim3((tiles + GEMM_GATED_NW - 1) / GEMM_GATED_NW), dim3(64 * GEMM_GATED_NW),
+  hipLaunchKernelGGL((gemm_gated_wide_kernel<T, EPI>), dim3((tiles + GEMM_GATED_NW - 1) / GEMM_GATED_NW), dim3(64 * GEMM_GATED_NW),
                      gemm_gated_lds_bytes<T>(a.nrt), s, a);
 }
 
@@ -332,8 +332,10 @@ void launch_gemm_split(hipStream_t s, int pro, int epi, const GemmArgs& a, float
 // The wide kernel's LDS exceeds the default 64 KB limit of dynamic LDS.
 template <typename T>
 hipError_t allow_wide_lds() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_gated_wide_kernel<T>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_gated_wide_kernel<T, EPI_GATED>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_gated_lds_bytes<T>(GEMM_WIDE_RT));
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_gated_wide_kernel<T, EPI_LOGITS>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_gated_lds_bytes<T>(GEMM_WIDE_RT));
 #define SD_CASE(P, E)                                                                                          \
   if (e == hipSuccess)                                                                                         \
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide_kernel<T, P, E>),                         \
@@ -485,7 +487,7 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       } else if (pro_ != PRO_LN) {                // the wide kernel reads the activations in fragment order
         const int frags = (a.K / 32) * a.nrt;
         const int blocks = (frags * 64 + 255) / 256;
-        const bool want_rs = pro_ == PRO_POST && (split_ok(pro_, epi_) || epi_ == EPI_GATED) && blocks >= 2 * a.nrt;
+        const bool want_rs = pro_ == PRO_POST && (split_ok(pro_, epi_) || epi_ == EPI_GATED || epi_ == EPI_LOGITS) && blocks >= 2 * a.nrt;
         hipLaunchKernelGGL((rows_to_fragments_kernel<T>), dim3(blocks), dim3(256), 0, s,
                            static_cast<const T*>(a.X), static_cast<T*>(m.xfrag), a.nrt, a.K, a.ss_in, a.n_part,
                            a.ss_stride, a.eps, want_rs ? m.wide_rs : nullptr);
@@ -494,7 +496,9 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       }
       if (pro_ == PRO_POST && epi_ == EPI_GATED && a.rs_in != nullptr) {
         if (out_frag_next && n_groups <= GEMM_WIDE_RT) { a.out_frag = m.xfrag2; produced_frag = true; }
-        launch_gemm_gated_wide<T>(s, a);
+        launch_gemm_gated_wide<T, EPI_GATED>(s, a);
+      } else if (pro_ == PRO_POST && epi_ == EPI_LOGITS && a.rs_in != nullptr) {
+        launch_gemm_gated_wide<T, EPI_LOGITS>(s, a);
       }
       else if (split_ok(pro_, epi_) && (pro_ != PRO_POST || a.rs_in != nullptr)) launch_gemm_split<T>(s, pro_, epi_, a, m.wide_partial);
       else launch_gemm_wide<T>(s, pro_, epi_, a);
@@ -537,11 +541,17 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
         a.rel_bias = m.rel_bias; a.bucket_lut = m.bucket_lut; a.rel_buckets = f.rel_buckets;
         a.seq0 = rw.seq0; a.pt_stride = m.n_pages;
         if (cross) { a.cross = 1; a.ck = l.cross_k; a.cv = l.cross_v; a.kv_len = f.enc_len; a.scale = 1.0f; a.rel_bias = nullptr; }
+        // long contexts end in the merge kernel, which can leave its output in fragment order for
+        // the batched O projection (no re-tile)
+        if (!cross && m.attn_nsplit > 1 && n_groups > 1 && n_groups <= GEMM_WIDE_RT) { a.out_frag = m.xfrag2; produced_frag = true; }
         launch_attn<T>(s, m, a, rw.nseq);
       }
     };
     attention(false);
+    frag_in = produced_frag ? m.xfrag2 : nullptr;
+    produced_frag = false;
     resid(l.wo, false, l.bo, m.nq, (f.arch == SD_ARCH_T5DEC) ? l.lncg : l.ln2g);
+    frag_in = nullptr;
     if (f.arch == SD_ARCH_T5DEC) {
       for (int g = 0; g < n_groups; ++g) {
         const Grp q = group(g);

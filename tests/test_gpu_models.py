@@ -572,22 +572,24 @@ def test_long_context_spans_several_key_blocks(d_head, ctx):
     dec.close()
 
 
-@pytest.mark.parametrize("d_head,n_heads,n_kv,gamma,ctx", [(128, 8, 2, 4, 1500), (64, 4, 2, 3, 1100),
-                                                           (64, 8, 2, 5, 1200), (128, 2, 2, 3, 1300)])
-def test_long_context_bf16_matrix_core_attention(d_head, n_heads, n_kv, gamma, ctx):
+@pytest.mark.parametrize("d_head,n_heads,n_kv,gamma,ctx,batch", [(128, 8, 2, 4, 1500, 2), (64, 4, 2, 3, 1100, 2),
+                                                                 (64, 8, 2, 5, 1200, 2), (128, 2, 2, 3, 1300, 2),
+                                                                 (64, 4, 2, 4, 1100, 5)])
+def test_long_context_bf16_matrix_core_attention(d_head, n_heads, n_kv, gamma, ctx, batch):
     """bf16 models with contexts beyond 1024 positions take the matrix-core attention kernel
     (key ranges over workgroups, four wavefronts per range, merge).  (gamma+1) x (query heads per
     kv head) = 20, 8, 24 (the most the kernels take) and 4 rows per kv head; two sequences of
     different length, so ranges are full, ragged and empty; against the oracle.  The same
-    sequence decoded alone must give bit-identical logits: a row does not see its neighbours."""
+    sequence decoded alone must give bit-identical logits: a row does not see its neighbours.
+    The last case has five sequences (25 verify rows in two slabs): the batched GEMMs, whose O
+    projection reads the merge kernel's output in fragment order."""
     cfg = synth.model_cfg(T.GQA, 2, n_heads * d_head, n_heads, 256, 512, ctx + 64, d_head=d_head, n_kv_heads=n_kv,
                           dtype="bf16", logit_scale=4.0)
     w = synth.random_weights(cfg, 9, w_std=0.1)
     cfg_q, w_q = synth.truncated_noisy_copy(cfg, w, 1, 59, 0.02)
-    batch = 2
     dec = make_decoder(cfg, w, cfg_q, w_q, max_gamma=gamma, flags=1, batch=batch)
     solo = make_decoder(cfg, w, cfg_q, w_q, max_gamma=gamma, flags=1)
-    prefixes = [[int(t) for t in synth.random_tokens(70 + b, ctx - 700 * b, cfg["vocab"])] for b in range(batch)]
+    prefixes = [[int(t) for t in synth.random_tokens(70 + b, ctx - 700 * (b % 2) - 13 * b, cfg["vocab"])] for b in range(batch)]
     scorers = [oracle_models(cfg, w, cfg_q, w_q) for _ in range(batch)]
     for b in range(batch):
         dec.prefill(prefixes[b], row=b)
