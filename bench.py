@@ -222,7 +222,7 @@ def main():
 def batched_gqa8b(args, batch=16, ctx=2048):
     """Side measurement: the batched 8B-class pair (32-layer GQA target, 2-layer draft, bf16), every
     sequence with a ctx-token context written by a real prefill; Algorithm-1 iterations (gamma = 3 and
-    4 unless --gammas says otherwise; 3 fills the 16-row slabs of the batched kernels exactly) against
+    4 unless --gammas says otherwise) against
     plain decoding steps of the same batch.  One JSON line; `value` is the best gamma's rate.  No CPU
     leg (the oracle needs minutes per row here)."""
     import torch
