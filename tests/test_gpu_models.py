@@ -408,11 +408,12 @@ def test_top_k_and_nucleus_decoding_matches_oracle(top_k, top_p):
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("arch,dtype,batch,gamma", [
     (T.GQA, "f32", 3, 4),       # 15 verify rows: one group
-    (T.GQA, "bf16", 5, 4),      # 25 verify rows: groups of 3 + 2 sequences
+    (T.GQA, "bf16", 5, 4),      # 25 verify rows: two slabs, the fourth sequence straddles them
     (T.GPT, "bf16", 16, 3),     # 64 verify rows: four groups; 32 rows in the first draft step
     (T.GQA, "bf16", 4, 7),      # 8 rows per sequence: two sequences per group
-    (T.GQA, "bf16", 16, 4),     # 80 verify rows: six groups, the last with one sequence (RMSNorm: split / gated GEMMs)
-    (T.GQA, "f32", 11, 4),      # 55 verify rows: groups of 3 + 3 + 3 + 2 sequences, fp32 fragments
+    (T.GQA, "bf16", 16, 4),     # 80 verify rows: five full slabs (RMSNorm: split / gated GEMMs)
+    (T.GQA, "f32", 11, 4),      # 55 verify rows in four slabs, fp32 fragments
+    (T.GQA, "bf16", 24, 4),     # 120 verify rows: eight slabs, two launches per batched GEMM
 ])
 def test_batched_decoding_equals_single_sequence_decoding(arch, dtype, batch, gamma):
     """A row's arithmetic never depends on the other rows of a launch, so every sequence of a
