@@ -804,7 +804,7 @@ static __global__ void retile_kernel(const T* __restrict__ src, T* __restrict__ 
 // global memory; gemm_split_finish_kernel adds the chunks in wavefront order and applies
 // the epilogue, so a row's sums are those of gemm_kernel, bit for bit.
 // grid = (ceil(tiles / NW), chunks); dynamic LDS = SUB * nrt fragments.
-template <typename T> struct SplitShape { static constexpr int SUB = 16 / (int)sizeof(T); };   // 8 k-steps of bf16, 4 of fp32: 1 KB per slab and k-step pair
+template <typename T> struct SplitShape { static constexpr int SUB = 16 / (int)sizeof(T); };   // k-steps per pass: 8 of bf16, 4 of fp32 (8 KB of activation fragments per slab)
 
 template <typename T, int NS, int NW>
 static __global__ __launch_bounds__(64 * NW) void gemm_split_kernel(const GemmArgs a) {
