@@ -799,8 +799,8 @@ static __global__ void retile_kernel(const T* __restrict__ src, T* __restrict__ 
 // bounds it.  Here a workgroup takes one K chunk (the k-steps one wavefront of gemm_kernel
 // would take) of NW tiles, one per wavefront (two weight streams for a gated FFN: the
 // gate and up tiles; NW = 8, or 12 when that makes the grid fit the chip in one round): the chunk's activation fragments pass through LDS once per workgroup,
-// GEMM_SPLIT_SUB k-steps at a time, and serve all eight wavefronts; the weights of the next
-// pass are in flight meanwhile.  Each wavefront leaves the partial tile of its chunk in
+// SplitShape<T>::SUB k-steps at a time, and serve all its wavefronts; a weight register is
+// reloaded for the next pass right after its multiply.  Each wavefront leaves the partial tile of its chunk in
 // global memory; gemm_split_finish_kernel adds the chunks in wavefront order and applies
 // the epilogue, so a row's sums are those of gemm_kernel, bit for bit.
 // grid = (ceil(tiles / NW), chunks); dynamic LDS = SUB * nrt fragments.
@@ -828,18 +828,17 @@ static __global__ __launch_bounds__(64 * NW) void gemm_split_kernel(const GemmAr
   for (int st = 0; st < NS; ++st)
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // All loads are unconditional and clamped: no branch around loads.
   Frag wf[NS][SUB];
-  auto load_w = [&](int ksb) {                       // unconditional, clamped: no branch around loads
 #pragma unroll
-    for (int st = 0; st < NS; ++st)
+  for (int st = 0; st < NS; ++st)
 #pragma unroll
-      for (int u = 0; u < SUB; ++u) wf[st][u] = Mma<T>::load_stream(wbase[st] + (size_t)min(ksb + u, ks_last) * 512);
-  };
+    for (int u = 0; u < SUB; ++u) wf[st][u] = Mma<T>::load_stream(wbase[st] + (size_t)min(ks0 + u, ks_last) * 512);
   // this thread's share of a pass's activation fragments (SUB * nrt * 64 of them over the workgroup)
   constexpr int NT = 64 * NW, XPT = (SUB * RT * 64 + NT - 1) / NT;
   Frag xr[XPT];
   const int nfrag = SUB * nrt * 64;
-  auto load_x = [&](int ksb) {                       // unconditional, clamped
+  auto load_x = [&](int ksb) {
 #pragma unroll
     for (int m = 0; m < XPT; ++m) {
       const int i = min(tid + NT * m, nfrag - 1);
@@ -847,7 +846,6 @@ static __global__ __launch_bounds__(64 * NW) void gemm_split_kernel(const GemmAr
       xr[m] = xf[(size_t)min(ksb + u, ks_last) * (RT * 64) + rem];
     }
   };
-  load_w(ks0);
   load_x(ks0);
   for (int ksb = ks0; ksb < ks1; ksb += SUB) {
     __syncthreads();                                 // the previous pass has been multiplied
@@ -855,13 +853,7 @@ static __global__ __launch_bounds__(64 * NW) void gemm_split_kernel(const GemmAr
     for (int m = 0; m < XPT; ++m)
       if (tid + NT * m < nfrag) xs[tid + NT * m] = xr[m];
     __syncthreads();
-    Frag cur[NS][SUB];
-#pragma unroll
-    for (int st = 0; st < NS; ++st)
-#pragma unroll
-      for (int u = 0; u < SUB; ++u) cur[st][u] = wf[st][u];
-    load_w(ksb + SUB);                               // the next pass's weights and activations are in
-    load_x(ksb + SUB);                               // flight while this one is multiplied
+    load_x(ksb + SUB);                               // the next pass's activations are in flight while this one is multiplied
 #pragma unroll
     for (int u = 0; u < SUB; ++u) {
       if (ksb + u < ks1) {                           // uniform; k-steps in order, as gemm_kernel takes them
@@ -870,10 +862,13 @@ static __global__ __launch_bounds__(64 * NW) void gemm_split_kernel(const GemmAr
           if (rt < nrt) {
             const Frag fb = xs[(u * nrt + rt) * 64 + lane];
 #pragma unroll
-            for (int st = 0; st < NS; ++st) acc[st][rt] = Mma<T>::mma(cur[st][u], fb, acc[st][rt]);
+            for (int st = 0; st < NS; ++st) acc[st][rt] = Mma<T>::mma(wf[st][u], fb, acc[st][rt]);
           }
         }
       }
+      // this register's k-step of the next pass is on its way while the rest of this pass is multiplied
+#pragma unroll
+      for (int st = 0; st < NS; ++st) wf[st][u] = Mma<T>::load_stream(wbase[st] + (size_t)min(ksb + SUB + u, ks_last) * 512);
     }
   }
   if (tile < ntiles) {
