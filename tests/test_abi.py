@@ -62,3 +62,14 @@ def test_choose_gamma_matches_brute_force_and_the_papers_rule():
     g = ctypes.c_int32(0)
     for bad in ((1.0, 0.1, 5), (-0.1, 0.1, 5), (0.5, -1.0, 5), (0.5, 0.1, 0), (float("nan"), 0.1, 5)):
         assert binding.lib.sd_choose_gamma(bad[0], bad[1], bad[2], ctypes.byref(g), None) == binding.SD_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu_and_unknown_workloads():
+    """bench.py runs on one GPU only and says so; its command line is checked before anything
+    touches a GPU."""
+    import subprocess, sys, os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "nope"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "invalid choice" in r.stderr
