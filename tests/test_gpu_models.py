@@ -414,6 +414,7 @@ def test_top_k_and_nucleus_decoding_matches_oracle(top_k, top_p):
     (T.GQA, "bf16", 16, 4),     # 80 verify rows: five full slabs (RMSNorm: split / gated GEMMs)
     (T.GQA, "f32", 11, 4),      # 55 verify rows in four slabs, fp32 fragments
     (T.GQA, "bf16", 24, 4),     # 120 verify rows: eight slabs, two launches per batched GEMM
+    (T.GQA, "bf16", 64, 2),     # the most sequences a context takes: 192 verify rows, 128 in the first draft step
 ])
 def test_batched_decoding_equals_single_sequence_decoding(arch, dtype, batch, gamma):
     """A row's arithmetic never depends on the other rows of a launch, so every sequence of a
