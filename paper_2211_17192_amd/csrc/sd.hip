@@ -1270,6 +1270,9 @@ extern "C" sd_status sd_get_stats(sd_ctx* c, sd_stats* out) {
   return SD_OK;
 }
 
+// Instrumented build only (-DSD_KTIME, never the product library): read-outs of the runtime's
+// occupancy estimate for the long-context attention kernel, of its per-workgroup timeline and of
+// the attention kernels' phase timers.
 #ifdef SD_KTIME
 extern "C" int sd_debug_occupancy(int lds_bytes) {
   int n = -1;
