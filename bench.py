@@ -63,6 +63,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a 256 MiB device-to-device copy (reference for the profiler's byte counters)")
+    ap.add_argument("--ctx", type=int, default=2048, help="gqa8b-batch16: tokens of context per sequence")
     ap.add_argument("--workload", type=str, default="t5xxl", choices=["t5xxl", "gqa8b-batch16"],
                     help="t5xxl: the headline configuration (default); gqa8b-batch16: the batched 8B-class "
                          "configuration (16 sequences, 2048-token contexts, gamma 4), a side measurement")
@@ -70,7 +71,7 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (nothing here uses a second GPU)")
     if args.workload == "gqa8b-batch16":
-        return batched_gqa8b(args)
+        return batched_gqa8b(args, ctx=args.ctx)
 
     import numpy as np
     import torch
@@ -239,6 +240,7 @@ def batched_gqa8b(args, batch=16, ctx=2048):
         dec.reset()
         for b in range(batch):
             dec.prefill(prompts[b], row=b)
+            print(f"gamma {gamma}: prefilled {b + 1} of {batch} sequences", file=sys.stderr, flush=True)
         U = synth.uniform_stream(9, (steps + warm) * batch * (2 * gamma + 1)).reshape(steps + warm, batch, -1)
         for i in range(warm):
             dec.step(gamma, TEMPERATURE, U[i])
