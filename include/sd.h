@@ -44,6 +44,10 @@ typedef enum { SD_F32 = 0, SD_BF16 = 1 } sd_dtype;
 enum { SD_ARCH_GPT = 0, SD_ARCH_T5DEC = 1, SD_ARCH_GQA = 2 };
 enum { SD_MAX_GAMMA = 15 };       /* a sequence contributes at most SD_MAX_GAMMA+1 rows to a forward */
 enum { SD_MAX_BATCH = 64 };       /* sequences decoded together */
+enum { SD_ATTN_MAX_ROWS_X_GROUP = 24 };  /* the attention kernels keep (query rows) x (query heads per KV head)
+                                     <= 24 rows per KV head: sd_load_models refuses (max_gamma + 1) x
+                                     (n_heads / n_kv_heads) beyond it (SD_EINVAL), e.g. 4 query heads per
+                                     KV head allow max_gamma <= 5 */
 
 /* Flags of sd_runtime_cfg.flags */
 enum {
@@ -131,7 +135,9 @@ typedef struct {
   int32_t page_size;        /* KV-cache page, positions; power of two, >= 16 */
   void*   workspace;        /* dev, 256-byte aligned, caller-owned, outlives the context */
   size_t  workspace_bytes;
-  void*   stream;           /* hipStream_t, or NULL for the default stream */
+  void*   stream;           /* hipStream_t every call enqueues on (default priority, capturable: not the
+                               legacy default stream), or NULL: the context creates a non-blocking stream
+                               of its own and destroys it in sd_free */
   int32_t flags;
 } sd_runtime_cfg;
 
@@ -310,6 +316,25 @@ sd_status sd_autotune_gamma(sd_ctx* ctx, int32_t reps, int32_t* gamma, double* a
  * multiplies are whatever the last forward left; it overwrites Mp's FFN scratch
  * rows, nothing else.  Synchronous. */
 sd_status sd_time_ffn_in(sd_ctx* ctx, int32_t rows, int32_t reps, double* us_per_launch);
+
+/* Measurement: the time of one whole forward inside a replayed graph, with chosen launches left
+ * out, so that a launch's share of the forward is the difference of two calls (kernels of a graph
+ * run back to back, so the difference is that launch's duration in its real surroundings).
+ *   which    : 0 = Mp over `rows` rows (1 = the standard decoding step of section 1, r > 1 = the
+ *              scoring of r - 1 guesses, section 2.3), rows <= max_gamma + 1;
+ *              1 = Mq, rows 1 (a draft step) or 2 (the first draft step of an iteration)
+ *   skip_ops : SD_OP_* bits: the launches of these kinds are not recorded (their outputs keep
+ *              whatever the last forward left, so the remaining launches do the same work)
+ *   reps     : graph replays between the two HIP events, 1..1000
+ *   us_per_forward : host output, microseconds per replay.
+ * Writes cache rows beyond the committed sequence and the logits buffers only; commits nothing.
+ * SD_ESTATE unless every sequence is prefilled.  Synchronous. */
+enum {
+  SD_OP_QKV = 1, SD_OP_ATTN = 2, SD_OP_O = 4, SD_OP_CROSS_Q = 8, SD_OP_CROSS_ATTN = 16, SD_OP_CROSS_O = 32,
+  SD_OP_FFN_IN = 64, SD_OP_FFN_OUT = 128, SD_OP_HEAD = 256, SD_OP_ALL = 511
+};
+sd_status sd_time_forward(sd_ctx* ctx, int32_t which, int32_t rows, int32_t skip_ops, int32_t reps,
+                          double* us_per_forward);
 
 /*
  * The accept / resample part of Algorithm 1 on explicit logits, for `rows`

@@ -162,6 +162,10 @@ lib.sd_set_flags.restype = C.c_int
 lib.sd_set_flags.argtypes = [C.c_void_p, C.c_int32]
 lib.sd_time_ffn_in.restype = C.c_int
 lib.sd_time_ffn_in.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
+lib.sd_time_forward.restype = C.c_int
+lib.sd_time_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
+SD_OP = {"qkv": 1, "attn": 2, "o": 4, "cross_q": 8, "cross_attn": 16, "cross_o": 32, "ffn_in": 64, "ffn_out": 128,
+         "head": 256}
 lib.sd_set_sampling.restype = C.c_int
 lib.sd_set_sampling.argtypes = [C.c_void_p, C.POINTER(_Sampling)]
 lib.sd_set_table_draft.restype = C.c_int
@@ -283,6 +287,13 @@ class SpecDecoder:
         """Mean duration (microseconds) of one launch of Mp's FFN-in GEMM over `rows` rows."""
         us = C.c_double(0.0)
         self._check(lib.sd_time_ffn_in(self._ctx, int(rows), int(reps), C.byref(us)))
+        return us.value
+
+    def time_forward(self, which: int, rows: int, skip_ops: int = 0, reps: int = 20) -> float:
+        """Microseconds of one graph-replayed forward of Mp (which 0) or Mq (1) over `rows` rows with
+        the launches in skip_ops (SD_OP bits) left out."""
+        us = C.c_double(0.0)
+        self._check(lib.sd_time_forward(self._ctx, int(which), int(rows), int(skip_ops), int(reps), C.byref(us)))
         return us.value
 
     def set_flags(self, flags: int):

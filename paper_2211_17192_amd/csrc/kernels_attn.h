@@ -31,22 +31,6 @@
 
 namespace sd {
 
-#ifdef SD_KTIME
-// Build-time instrumentation (off by default): block 0 accumulates the time it
-// spends in each phase, in ticks of the constant 100 MHz clock.
-__device__ unsigned long long g_ktime[96];   // [64, 96): attn_long_kernel
-#define SD_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) { const unsigned long long t_ = wall_clock64(); \
-    atomicAdd(&g_ktime[kt_base + (i)], t_ - kt_last); kt_last = t_; } } while (0)
-// per-workgroup timeline of attn_long_kernel launches with 640 workgroups: start, end, HW_ID, XCC_ID
-__device__ unsigned long long g_wgtrace[640 * 4];
-#define SD_STAMPL(i) do { if (blockIdx.x == 0 && split == 0 && threadIdx.x == 0) { const unsigned long long t_ = wall_clock64(); \
-    atomicAdd(&g_ktime[64 + (i)], t_ - kt_last); kt_last = t_; } } while (0)
-#define SD_WAIT_VM8() __builtin_amdgcn_s_waitcnt(0x0F78)     // vmcnt(8): makes the load wait its own phase
-#else
-#define SD_STAMP(i) do { } while (0)
-#define SD_STAMPL(i) do { } while (0)
-#define SD_WAIT_VM8() do { } while (0)
-#endif
 
 constexpr int ATTN_THREADS = 1024;
 constexpr int ATTN_LDS_PAGES = 1024;       // page-table entries cached in LDS
@@ -117,11 +101,6 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   const int r0 = (int)blockIdx.z * a.R + rs;      // first row within the launch
   const int* page_table = a.page_table + (size_t)(a.seq0 + blockIdx.z) * a.pt_stride;
   const int G = a.H / a.Hkv, RG = R * G;
-#ifdef SD_KTIME
-  const int kt_base = (a.cross ? 8 : 0) + (R > 1 ? 16 : 0) + (a.Hkv > 8 ? 32 : 0);
-  unsigned long long kt_last = wall_clock64();
-  if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&g_ktime[kt_base + 7], 1ull);
-#endif
 
   if (tid < MAX_ROWS) s_pos[tid] = (tid < R) ? (a.cross ? 0 : a.row_pos[r0 + tid]) : -1;
   if (!a.cross) for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += ATTN_THREADS) s_pt[i] = page_table[i];
@@ -150,7 +129,6 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   }
   if (tid < RG) { m_s[tid] = -INFINITY; l_s[tid] = 0.0f; }
   __syncthreads();
-  SD_STAMP(0);
   int kv_len = a.kv_len;
   if (!a.cross) {
     int mx = -1;
@@ -222,9 +200,7 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
         s_s[rg * KB + kl_s] = sc;
       }
     }
-    SD_STAMP(1);
     __syncthreads();
-    SD_STAMP(2);
 
     // ---- online softmax: one wavefront per row ----
     for (int rg = wave; rg < RG; rg += NW) {
@@ -251,7 +227,6 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
       }
     }
     __syncthreads();
-    SD_STAMP(3);
 
     // ---- P * V out of registers, RPP rows per pass ----
     for (int rb = 0; rb < RG; rb += RPP) {
@@ -296,7 +271,6 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
       }
       __syncthreads();
     }
-    SD_STAMP(4);
   }
 
   if (a.nsplit > 1) {            // leave the partial result of this key range for the merge
@@ -311,7 +285,6 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
     const float L = l_s[rg];
     Store<T>::st(og + (size_t)(r0 + r) * a.H * DH + h * DH + d, (L > 0.0f) ? acc_s[i] / L : 0.0f);
   }
-  SD_STAMP(5);
 }
 
 // Long contexts, bf16: the same key-range workgroups as attn_kernel with nsplit > 1, but the
@@ -370,17 +343,6 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
   const int r0 = seq * a.R + rs;
   const int* page_table = a.page_table + (size_t)(a.seq0 + seq) * a.pt_stride;
   const int G = a.H / a.Hkv, RG = R * G;
-#ifdef SD_KTIME
-  unsigned long long kt_last = wall_clock64();
-  if (blockIdx.x == 0 && split == 0 && threadIdx.x == 0) atomicAdd(&g_ktime[64 + 7], 1ull);
-  const unsigned wg_lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-  const bool wg_traced = gridDim.x * gridDim.y * gridDim.z == 640 && NRT == 2 && threadIdx.x == 0;
-  if (wg_traced) {
-    g_wgtrace[wg_lin * 4 + 0] = kt_last;
-    g_wgtrace[wg_lin * 4 + 2] = __builtin_amdgcn_s_getreg((31 << 11) | 4);
-    g_wgtrace[wg_lin * 4 + 3] = __builtin_amdgcn_s_getreg((31 << 11) | 20);
-  }
-#endif
   if (tid < MAX_ROWS) s_pos[tid] = (tid < R) ? a.row_pos[r0 + tid] : -1;
   for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += 64 * NW) s_pt[i] = page_table[i];
   __syncthreads();
@@ -390,9 +352,6 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
   float* pp = a.partial + ((((size_t)seq * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
   if (k_begin >= kv_len) {                          // nothing in this key range yet: an empty partial
     if (tid < RG) { pp[(size_t)tid * (DH + 2) + DH] = -INFINITY; pp[(size_t)tid * (DH + 2) + DH + 1] = 0.0f; }
-#ifdef SD_KTIME
-    if (wg_traced) g_wgtrace[wg_lin * 4 + 1] = wall_clock64();
-#endif
     return;
   }
   kv_len = min(kv_len, k_begin + a.split_keys);
@@ -464,22 +423,15 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
     }
   };
   const int kb0 = k_begin + wave * 32;
-  SD_STAMPL(0);
   load_k(kb0); load_v(kb0);                         // out-of-range keys re-read the last valid one and get probability 0
   for (int kb = kb0; kb < kv_len; kb += NW * 32) {
     const int nkeys = min(32, kv_len - kb);
     const int kb_next = kb + NW * 32;
     // ---- V tile -> LDS, transposed; then its registers take the next step's tile ----
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");     // the reads of the previous step are done
-    SD_STAMPL(1);
-    SD_WAIT_VM8();
-    SD_STAMPL(2);
 #pragma unroll
     for (int c = 0; c < DH / 16; ++c) *reinterpret_cast<bf16x8*>(vt + (c * VKPL + vkey) * VRS + vpiece * 8) = vr[c];
     load_v(kb_next);                                 // no branch around loads: the compiler would wait for all of them
-    SD_STAMPL(3);
-    SD_WAIT_VM8();
-    SD_STAMPL(4);
     // ---- scores: sc[kt][rt][r] = S[key kb + kt*16 + kq*4 + r][row rt*16 + j] ----
     f32x4 sc[2][NRT];
 #pragma unroll
@@ -490,7 +442,6 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
 #pragma unroll
         for (int s = 0; s < KSQ; ++s) sc[kt][rt] = mma_bf16(kf[kt][s], qf[rt][s], sc[kt][rt]);
       }
-    SD_STAMPL(5);
     load_k(kb_next);
     float p[2][NRT][4];
     float f[NRT];
@@ -537,9 +488,7 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
       l_run[rt] = l_run[rt] * f[rt] + sum;          // this lane's keys only; the quarters are added at the end
       m_run[rt] = m_new;
     }
-    SD_STAMPL(6);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");     // this step's V tile has landed in LDS
-    SD_STAMPL(8);
     // ---- O^T = f O^T + V^T P;  p as the sum of two bf16 numbers (16 mantissa bits): the
     //      matrix cores have time to spare ----
     bf16x8 pf[NRT], pl[NRT];
@@ -572,7 +521,6 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
         o[dt][rt] = mma_bf16(vf, pf[rt], o[dt][rt]);
       }
     }
-    SD_STAMPL(9);
   }
 
   // ---- merge the wavefronts: each leaves (m, l, O) of its keys in LDS ----
@@ -608,10 +556,6 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
     }
     pp[i] = out;
   }
-  SD_STAMPL(10);
-#ifdef SD_KTIME
-  if (wg_traced) g_wgtrace[wg_lin * 4 + 1] = wall_clock64();
-#endif
 }
 
 // Combines the partial results of the key ranges of one (sequence, kv head): with

@@ -26,6 +26,7 @@ namespace {
 using namespace sd;
 
 thread_local std::string g_load_error;
+static_assert(sd::ATTN_MAX_RG == SD_ATTN_MAX_ROWS_X_GROUP, "sd.h states the attention kernels' row limit");
 int g_num_cus = 256;                 // compute units of the device, read at load
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
@@ -190,14 +191,18 @@ struct sd_ctx {
   StepParams* h_params = nullptr;    // pinned
   int batch = 1;
   // host mirror of the sequences
-  int state = 0;                     // 0 not all rows prefilled, 1 READY, 2 Mq cache stale (after baseline steps)
-  std::vector<int> len, last_tok, ready;
+  // per sequence: prefilled?  Mq cache behind the committed tokens (after plain decoding steps or
+  // steps whose drafts did not come from Mq; only that sequence's prefill brings it back)?
+  std::vector<int> len, last_tok, ready, mq_stale;
+  bool all_ready() const { for (int r : ready) if (!r) return false; return true; }
+  bool any_stale() const { for (int m : mq_stale) if (m) return true; return false; }
   int last_gamma = 0, last_kind = -1;   // for sd_debug_logits
   hipGraphExec_t graphs[SD_MAX_GAMMA + 1] = {};
   hipGraphExec_t graph_baseline = nullptr;
   hipEvent_t ev[4] = {};
   std::vector<hipEvent_t> kev;       // 2 per Mp layer: around the gated FFN-in GEMM (SD_FLAG_PROFILE)
   bool time_ffn = false;             // set while the verify forward of a profiled step is enqueued
+  int skip_ops = 0;                  // sd_time_forward: SD_OP_* launches left out of the forward being recorded
   sd_stats stats{};
   sd_sampling sampling{1.0f, 0, 0.0f};
   // negligible-cost draft: logits table in place of Mq's forward (caller-owned device memory)
@@ -405,12 +410,21 @@ void launch_attn(hipStream_t s, const Model& m, AttnArgs a, int nseq) {
 }
 
 // The attention kernel keeps up to ATTN_MAX_RG query rows in more than 64 KB of LDS.
+// Each instantiation gets the most it can ask for, ATTN_MAX_RG query rows at its own d_head (the
+// reduction buffer [16 wavefronts][rows per pass][d_head] makes d_head 64 the largest).
+constexpr size_t ATTN_STATIC_LDS = MAX_ROWS * 4 + ATTN_LDS_PAGES * 4 + 4 * 64 * 4 + ATTN_LDS_DIST;   // the kernel's __shared__ arrays
+constexpr size_t LDS_PER_CU = 160 * 1024;
+template <typename T, int DH>
+hipError_t allow_attn_lds() {
+  const size_t bytes = attn_lds_bytes(ATTN_MAX_RG, DH);
+  if (bytes + ATTN_STATIC_LDS > LDS_PER_CU) return hipErrorInvalidValue;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, DH>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
 template <typename T>
 hipError_t allow_big_lds() {
-  const int bytes = (int)attn_lds_bytes(ATTN_MAX_RG, 128);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, 32>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, 128>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  hipError_t e = allow_attn_lds<T, 32>();
+  if (e == hipSuccess) e = allow_attn_lds<T, 64>();
+  if (e == hipSuccess) e = allow_attn_lds<T, 128>();
   return e;
 }
 
@@ -437,6 +451,7 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
   const bool rms = (f.arch != SD_ARCH_GPT);
   const int pro = rms ? PRO_POST : PRO_LN;
   const int n_layers = (int)m.L.size();
+  const int skip = c->skip_ops;                     // measurement only (sd_time_forward); 0 in every decoding call
   const int rows_total = rw.nseq * rw.rps;
   const int n_groups = (rows_total + MAX_ROWS - 1) / MAX_ROWS;
   struct Grp { int R; float* x; char* xg; float* ss; char *qbuf, *attn, *ffn; int *row_pos, *row_seq, *logit_row; };
@@ -523,7 +538,7 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
   for (int li = 0; li < n_layers; ++li) {
     const LayerW& l = m.L[li];
     // q, k, v projections (+ rotary) with k, v appended to the cache
-    gemm_groups(pro, EPI_QKV, [&](GemmArgs& a, const Grp& q) {
+    if (!(skip & SD_OP_QKV)) gemm_groups(pro, EPI_QKV, [&](GemmArgs& a, const Grp& q) {
       normed(a, q, l.ln1g, l.ln1b);
       a.W = l.wqkv; a.bias = l.bqkv; a.K = d; a.N = m.nq + 2 * m.nkv;
       a.q_out = q.qbuf; a.nq = m.nq; a.nkv = m.nkv; a.kv_pool = l.kv; a.page_table = m.page_table;
@@ -547,28 +562,29 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
         launch_attn<T>(s, m, a, rw.nseq);
       }
     };
-    attention(false);
+    if (!(skip & SD_OP_ATTN)) attention(false);
     frag_in = produced_frag ? m.xfrag2 : nullptr;
     produced_frag = false;
-    resid(l.wo, false, l.bo, m.nq, (f.arch == SD_ARCH_T5DEC) ? l.lncg : l.ln2g);
+    if (!(skip & SD_OP_O)) resid(l.wo, false, l.bo, m.nq, (f.arch == SD_ARCH_T5DEC) ? l.lncg : l.ln2g);
+    else n_part = d / 16;
     frag_in = nullptr;
     if (f.arch == SD_ARCH_T5DEC) {
-      for (int g = 0; g < n_groups; ++g) {
+      for (int g = 0; g < n_groups && !(skip & SD_OP_CROSS_Q); ++g) {
         const Grp q = group(g);
         GemmArgs cq{};
         normed(cq, q, l.lncg, nullptr);
         cq.W = l.cq; cq.K = d; cq.N = m.nq; cq.out = q.qbuf; cq.ldo = m.nq;
         launch_gemm<T>(s, PRO_POST, EPI_STORE, cq);
       }
-      attention(true);
-      resid(l.co, false, nullptr, m.nq, l.ln2g);
+      if (!(skip & SD_OP_CROSS_ATTN)) attention(true);
+      if (!(skip & SD_OP_CROSS_O)) resid(l.co, false, nullptr, m.nq, l.ln2g);
     }
     {
       const bool gpt = (f.arch == SD_ARCH_GPT);
       const bool timed = !gpt && c->time_ffn && &m == &c->p && 2 * li + 1 < (int)c->kev.size();
       if (timed) hipEventRecord(c->kev[2 * li], s);
       out_frag_next = true;                        // the FFN-out product reads fragments: skip its re-tile
-      gemm_groups(gpt ? PRO_LN : PRO_POST, gpt ? EPI_ACT : EPI_GATED, [&](GemmArgs& h, const Grp& q) {
+      if (!(skip & SD_OP_FFN_IN)) gemm_groups(gpt ? PRO_LN : PRO_POST, gpt ? EPI_ACT : EPI_GATED, [&](GemmArgs& h, const Grp& q) {
         normed(h, q, l.ln2g, l.ln2b);
         h.K = d; h.N = f.d_ff; h.out = q.ffn; h.ldo = f.d_ff; h.W = l.w1;
         if (gpt) h.bias = l.b1;
@@ -579,10 +595,11 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
     out_frag_next = false;
     frag_in = produced_frag ? m.xfrag2 : nullptr;
     produced_frag = false;
-    resid(l.w2, true, l.b2, f.d_ff, (li + 1 < n_layers) ? m.L[li + 1].ln1g : m.lnfg);
+    if (!(skip & SD_OP_FFN_OUT)) resid(l.w2, true, l.b2, f.d_ff, (li + 1 < n_layers) ? m.L[li + 1].ln1g : m.lnfg);
+    else n_part = d / 16;
     frag_in = nullptr;
   }
-  if (logits != nullptr) {
+  if (logits != nullptr && !(skip & SD_OP_HEAD)) {
     gemm_groups(pro, EPI_LOGITS, [&](GemmArgs& a, const Grp& q) {
       normed(a, q, m.lnfg, m.lnfb);
       a.W = m.head; a.K = d; a.N = f.vocab; a.out = logits; a.ldo = f.vocab; a.scale = f.logit_scale;
@@ -777,6 +794,32 @@ sd_status sync_state_to_host(sd_ctx* c) {
   return SD_OK;
 }
 
+// Records what `enqueue` puts on the context's stream into an executable graph.  Whatever fails,
+// the stream has left capture mode when this returns and *exec is a valid graph or nullptr.
+template <typename F>
+sd_status capture_graph(sd_ctx* c, hipGraphExec_t* exec, F&& enqueue) {
+  hipGraph_t g = nullptr;
+  *exec = nullptr;
+  HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+  enqueue();
+  hipError_t e = hipStreamEndCapture(c->stream, &g);     // ends the capture also when it reports an error
+  if (e == hipSuccess) e = hipGraphInstantiate(exec, g, nullptr, nullptr, 0);
+  if (g) hipGraphDestroy(g);
+  if (e != hipSuccess) {
+    *exec = nullptr;
+    (void)hipGetLastError();
+    return fail(c, SD_EHIP, std::string("graph capture / instantiate: ") + hipGetErrorString(e));
+  }
+  return SD_OK;
+}
+
+// The device and the host disagree about a sequence after a launch: nothing can be trusted any
+// more, so every sequence has to be reset and prefilled before the next step.
+sd_status poisoned(sd_ctx* c, const char* what) {
+  for (auto& r : c->ready) r = 0;
+  return fail(c, SD_EHIP, std::string(what) + ": reset and prefill every sequence");
+}
+
 }  // namespace
 
 // ====================================================================== C ABI
@@ -818,12 +861,12 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
   plan_ctx(A, *c, *p_cfg, *q_cfg, *rt);
   auto bail = [&](sd_status s, const std::string& m) { sd_free(c); return fail(nullptr, s, m); };
   if (rt->stream) c->stream = static_cast<hipStream_t>(rt->stream);
-  else {
+  else {                       // a stream of the context's own (not the legacy default stream, which cannot be captured)
     if (hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking) != hipSuccess) return bail(SD_EHIP, "stream creation failed");
     c->own_stream = true;
   }
   const size_t B = (size_t)rt->batch;
-  c->len.assign(B, 0); c->last_tok.assign(B, -1); c->ready.assign(B, 0); c->hist_len.assign(B, 0);
+  c->len.assign(B, 0); c->last_tok.assign(B, -1); c->ready.assign(B, 0); c->hist_len.assign(B, 0); c->mq_stale.assign(B, 0);
   if (hipHostMalloc(reinterpret_cast<void**>(&c->h_state), B * sizeof(SeqState), hipHostMallocDefault) != hipSuccess ||
       hipHostMalloc(reinterpret_cast<void**>(&c->h_params), B * sizeof(StepParams), hipHostMallocDefault) != hipSuccess)
     return bail(SD_EHIP, "pinned allocation failed");
@@ -881,7 +924,6 @@ extern "C" sd_status sd_reset(sd_ctx* c, int32_t row) {
   if (row < -1 || row >= c->batch) return fail(c, SD_EINVAL, "row must be -1 or a sequence index");
   for (int b = 0; b < c->batch; ++b)
     if (row == -1 || row == b) { c->ready[b] = 0; c->len[b] = 0; c->last_tok[b] = -1; c->hist_len[b] = 0; }
-  c->state = 0;
   if (row == -1) c->stats = sd_stats{};
   return SD_OK;
 }
@@ -896,7 +938,7 @@ extern "C" sd_status sd_prefill(sd_ctx* c, int32_t row, const int32_t* prompt, i
   const int room = std::min(pc.max_len, qc.max_len);
   if (n + c->rt.max_gamma + 1 > room) return fail(c, SD_ERANGE, "prompt + max_gamma + 1 exceeds max_len");
   for (int i = 0; i < n; ++i) if (prompt[i] < 0 || prompt[i] >= pc.vocab) return fail(c, SD_ERANGE, "token id out of range");
-  c->state = 0; c->ready[row] = 0; c->hist_len[row] = 0;
+  c->ready[row] = 0; c->hist_len[row] = 0;
   Model* ms[2] = {&c->p, &c->q};
   const void* encs[2] = {enc_p, enc_q};
   for (int k = 0; k < 2; ++k) {
@@ -919,8 +961,7 @@ extern "C" sd_status sd_prefill(sd_ctx* c, int32_t row, const int32_t* prompt, i
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   HIP_TRY(c, hipGetLastError());
   c->ready[row] = 1; c->len[row] = n; c->last_tok[row] = prompt[n - 1]; c->hist_len[row] = n;
-  c->state = 1;
-  for (int b = 0; b < c->batch; ++b) if (!c->ready[b]) c->state = 0;      // READY once every sequence is prefilled
+  c->mq_stale[row] = 0;                             // both caches were just filled for this sequence
   return SD_OK;
 }
 
@@ -937,8 +978,8 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
   if (!out_tokens || !out_n) return fail(c, SD_EINVAL, "null output");
   if (gamma < 1 || gamma > c->rt.max_gamma) return fail(c, SD_EINVAL, "gamma out of range");
   const int B = c->batch;
-  if (c->state == 0) return fail(c, SD_ESTATE, "sd_step before every sequence was prefilled");
-  if (c->state == 2 && !c->no_mq()) return fail(c, SD_ESTATE, "Mq cache is stale (after sd_step_baseline or drafts without Mq): reset and prefill");
+  if (!c->all_ready()) return fail(c, SD_ESTATE, "sd_step before every sequence was prefilled");
+  if (!c->no_mq() && c->any_stale()) return fail(c, SD_ESTATE, "Mq cache is stale (after sd_step_baseline or drafts without Mq): reset and prefill");
   if (c->copy_match > 0)
     for (int b = 0; b < B; ++b)
       if (c->hist_len[b] != c->len[b]) return fail(c, SD_ESTATE, "token history incomplete: choose the copying draft before prefill");
@@ -964,15 +1005,12 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
   const bool graph = (c->rt.flags & SD_FLAG_GRAPH) != 0 && !profile;
   if (graph) {
     if (!c->graphs[gamma]) {
-      hipGraph_t g = nullptr;
-      HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-      hipMemcpyAsync(c->d_params, c->h_params, pbytes, hipMemcpyHostToDevice, c->stream);
-      enqueue_step(c, gamma, false);
-      hipMemcpyAsync(c->h_state, c->d_state, sbytes, hipMemcpyDeviceToHost, c->stream);
-      HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
-      hipError_t e = hipGraphInstantiate(&c->graphs[gamma], g, nullptr, nullptr, 0);
-      hipGraphDestroy(g);
-      if (e != hipSuccess) { c->graphs[gamma] = nullptr; return fail(c, SD_EHIP, std::string("graph instantiate: ") + hipGetErrorString(e)); }
+      st = capture_graph(c, &c->graphs[gamma], [&] {
+        hipMemcpyAsync(c->d_params, c->h_params, pbytes, hipMemcpyHostToDevice, c->stream);
+        enqueue_step(c, gamma, false);
+        hipMemcpyAsync(c->h_state, c->d_state, sbytes, hipMemcpyDeviceToHost, c->stream);
+      });
+      if (st != SD_OK) return st;
     }
     HIP_TRY(c, hipGraphLaunch(c->graphs[gamma], c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -984,7 +1022,7 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
   HIP_TRY(c, hipGetLastError());
   for (int b = 0; b < B; ++b) {
     const SeqState& hs = c->h_state[b];
-    if (hs.n < 0 || hs.n > gamma || hs.len != c->len[b] + hs.n + 1) return fail(c, SD_EHIP, "device state inconsistent after step");
+    if (hs.n < 0 || hs.n > gamma || hs.len != c->len[b] + hs.n + 1) return poisoned(c, "device state inconsistent after step");
   }
   int64_t fallbacks = 0;
   for (int b = 0; b < B; ++b) {
@@ -1006,6 +1044,7 @@ extern "C" sd_status sd_step(sd_ctx* c, const int32_t* prefix, int32_t prefix_le
     }
   }
   c->stats.fallbacks = fallbacks;
+  if (c->no_mq()) c->mq_stale.assign((size_t)B, 1);      // Mq did not see these tokens
   c->last_gamma = gamma; c->last_kind = 0;
   c->stats.steps += 1;
   if (profile) {
@@ -1025,7 +1064,7 @@ extern "C" sd_status sd_step_baseline(sd_ctx* c, float temperature, const float*
   if (!c) return SD_EINVAL;
   if (!out_token) return fail(c, SD_EINVAL, "null output");
   const int B = c->batch;
-  if (c->state == 0) return fail(c, SD_ESTATE, "sd_step_baseline before every sequence was prefilled");
+  if (!c->all_ready()) return fail(c, SD_ESTATE, "sd_step_baseline before every sequence was prefilled");
   sd_status st = check_uniforms(c, temperature, uniforms, B);
   if (st != SD_OK) return st;
   for (int b = 0; b < B; ++b)
@@ -1040,15 +1079,12 @@ extern "C" sd_status sd_step_baseline(sd_ctx* c, float temperature, const float*
   const size_t pbytes = (size_t)B * sizeof(StepParams), sbytes = (size_t)B * sizeof(SeqState);
   if ((c->rt.flags & SD_FLAG_GRAPH) != 0) {
     if (!c->graph_baseline) {
-      hipGraph_t g = nullptr;
-      HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-      hipMemcpyAsync(c->d_params, c->h_params, pbytes, hipMemcpyHostToDevice, c->stream);
-      enqueue_baseline(c);
-      hipMemcpyAsync(c->h_state, c->d_state, sbytes, hipMemcpyDeviceToHost, c->stream);
-      HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
-      hipError_t e = hipGraphInstantiate(&c->graph_baseline, g, nullptr, nullptr, 0);
-      hipGraphDestroy(g);
-      if (e != hipSuccess) { c->graph_baseline = nullptr; return fail(c, SD_EHIP, std::string("graph instantiate: ") + hipGetErrorString(e)); }
+      st = capture_graph(c, &c->graph_baseline, [&] {
+        hipMemcpyAsync(c->d_params, c->h_params, pbytes, hipMemcpyHostToDevice, c->stream);
+        enqueue_baseline(c);
+        hipMemcpyAsync(c->h_state, c->d_state, sbytes, hipMemcpyDeviceToHost, c->stream);
+      });
+      if (st != SD_OK) return st;
     }
     HIP_TRY(c, hipGraphLaunch(c->graph_baseline, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1059,13 +1095,13 @@ extern "C" sd_status sd_step_baseline(sd_ctx* c, float temperature, const float*
   }
   HIP_TRY(c, hipGetLastError());
   for (int b = 0; b < B; ++b)
-    if (c->h_state[b].len != c->len[b] + 1) return fail(c, SD_EHIP, "device state inconsistent after baseline step");
+    if (c->h_state[b].len != c->len[b] + 1) return poisoned(c, "device state inconsistent after baseline step");
   for (int b = 0; b < B; ++b) {
     out_token[b] = c->h_state[b].last_tok;
     if (c->copy_match > 0 && c->hist_len[b] == c->len[b]) c->hist_len[b] = c->h_state[b].len;
     c->len[b] = c->h_state[b].len; c->last_tok[b] = c->h_state[b].last_tok;
   }
-  c->state = 2;
+  c->mq_stale.assign((size_t)B, 1);
   c->last_kind = 2;
   return SD_OK;
 }
@@ -1102,10 +1138,8 @@ extern "C" sd_status sd_set_table_draft(sd_ctx* c, const float* table, const int
   if (table == nullptr && (row_of != nullptr || n_rows != 0)) return fail(c, SD_EINVAL, "no table: row_of must be NULL and n_rows 0");
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   for (auto& g : c->graphs) if (g) { hipGraphExecDestroy(g); g = nullptr; }     // the captured draft loop changes
-  const bool without = c->no_mq();
+  // (steps taken without Mq mark the sequences' Mq caches stale: going back to Mq needs them prefilled again)
   c->draft_table = table; c->draft_row_of = table ? row_of : nullptr; c->draft_rows = table ? n_rows : 0;
-  // drafts without Mq leave its cache behind: going back to Mq needs the sequences prefilled again
-  if (without && !c->no_mq() && c->state == 1) c->state = 2;
   return SD_OK;
 }
 
@@ -1115,9 +1149,7 @@ extern "C" sd_status sd_set_copy_draft(sd_ctx* c, int32_t match) {
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   for (auto& g : c->graphs) if (g) { hipGraphExecDestroy(g); g = nullptr; }     // the captured launches change
   if (c->graph_baseline) { hipGraphExecDestroy(c->graph_baseline); c->graph_baseline = nullptr; }
-  const bool without = c->no_mq();
   c->copy_match = match;
-  if (without && !c->no_mq() && c->state == 1) c->state = 2;
   return SD_OK;
 }
 
@@ -1155,7 +1187,7 @@ extern "C" sd_status sd_choose_gamma(double alpha, double cost, int32_t gamma_ma
 extern "C" sd_status sd_measure_cost(sd_ctx* c, int32_t reps, double* mq_us, double* mp_us) {
   if (!c || !mq_us || !mp_us) return SD_EINVAL;
   if (reps < 1 || reps > 1000) return fail(c, SD_EINVAL, "reps must be 1..1000");
-  if (c->state != 1) return fail(c, SD_ESTATE, "sd_measure_cost needs a prefilled sequence with a valid Mq cache");
+  if (!c->all_ready() || c->any_stale()) return fail(c, SD_ESTATE, "sd_measure_cost needs a prefilled sequence with a valid Mq cache");
   if (c->no_mq()) return fail(c, SD_ESTATE, "sd_measure_cost times Mq: clear the table / copying draft first");
   const int V = c->p.cfg.vocab, B = c->batch;
   if (c->rt.max_gamma < 2) return fail(c, SD_EINVAL, "sd_measure_cost needs max_gamma >= 2 (it runs a second draft step)");
@@ -1174,22 +1206,20 @@ extern "C" sd_status sd_measure_cost(sd_ctx* c, int32_t reps, double* mq_us, dou
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   double us[2] = {0.0, 0.0};
   for (int which = 0; which < 2; ++which) {
-    hipGraph_t g = nullptr;
     hipGraphExec_t ge = nullptr;
-    HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-    if (which == 0) {      // a draft step that is not the first of an iteration: guess x_1 in, q_2 and x_2 out
-      forward_any(c, c->q, Rows{ROWS_DRAFT_NEXT, 1, 1, 0, 0, B, 2}, c->q_logits);     // rows [seq][2][V], second of each
-      hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->q_logits + (size_t)V, V,
-                         c->d_params, 1, c->d_state, 0, 1, (size_t)2 * V);
-    } else {               // standard decoding's forward and draw; the draw lands in a guess slot, nothing is committed
-      forward_any(c, c->p, Rows{ROWS_BASELINE, 0, 1, 0, 0, B, 0}, c->p_logits);
-      hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
-                         c->d_params, 0, c->d_state, 0, 1, (size_t)V);
-    }
-    HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
-    hipError_t e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
-    hipGraphDestroy(g);
-    if (e != hipSuccess) return fail(c, SD_EHIP, std::string("graph instantiate: ") + hipGetErrorString(e));
+    const sd_status cs = capture_graph(c, &ge, [&] {
+      if (which == 0) {      // a draft step that is not the first of an iteration: guess x_1 in, q_2 and x_2 out
+        forward_any(c, c->q, Rows{ROWS_DRAFT_NEXT, 1, 1, 0, 0, B, 2}, c->q_logits);     // rows [seq][2][V], second of each
+        hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->q_logits + (size_t)V, V,
+                           c->d_params, 1, c->d_state, 0, 1, (size_t)2 * V);
+      } else {               // standard decoding's forward and draw; the draw lands in a guess slot, nothing is committed
+        forward_any(c, c->p, Rows{ROWS_BASELINE, 0, 1, 0, 0, B, 0}, c->p_logits);
+        hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
+                           c->d_params, 0, c->d_state, 0, 1, (size_t)V);
+      }
+    });
+    if (cs != SD_OK) return cs;
+    hipError_t e = hipSuccess;
     hipGraphLaunch(ge, c->stream);                       // warm-up
     hipEventRecord(c->ev[0], c->stream);
     for (int i = 0; i < reps; ++i) hipGraphLaunch(ge, c->stream);
@@ -1230,9 +1260,8 @@ extern "C" sd_status sd_time_ffn_in(sd_ctx* c, int32_t rows, int32_t reps, doubl
   Model& m = c->p;
   const sd_model_cfg& f = m.cfg;
   const bool rms = f.arch != SD_ARCH_GPT;
-  hipGraph_t g = nullptr;
   hipGraphExec_t ge = nullptr;
-  HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+  const sd_status cs = capture_graph(c, &ge, [&] {
   for (const LayerW& l : m.L) {
     GemmArgs h{};
     h.R = rows; h.eps = f.norm_eps; h.K = f.d_model; h.N = f.d_ff; h.out = m.ffn; h.ldo = f.d_ff; h.W = l.w1;
@@ -1247,10 +1276,9 @@ extern "C" sd_status sd_time_ffn_in(sd_ctx* c, int32_t rows, int32_t reps, doubl
       else launch_gemm<float>(c->stream, PRO_LN, EPI_ACT, h);
     }
   }
-  HIP_TRY(c, hipStreamEndCapture(c->stream, &g));
-  hipError_t e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
-  hipGraphDestroy(g);
-  if (e != hipSuccess) return fail(c, SD_EHIP, std::string("graph instantiate: ") + hipGetErrorString(e));
+  });
+  if (cs != SD_OK) return cs;
+  hipError_t e = hipSuccess;
   hipGraphLaunch(ge, c->stream);                       // warm-up
   hipEventRecord(c->ev[0], c->stream);
   for (int i = 0; i < reps; ++i) hipGraphLaunch(ge, c->stream);
@@ -1264,27 +1292,47 @@ extern "C" sd_status sd_time_ffn_in(sd_ctx* c, int32_t rows, int32_t reps, doubl
   return SD_OK;
 }
 
+extern "C" sd_status sd_time_forward(sd_ctx* c, int32_t which, int32_t rows, int32_t skip_ops, int32_t reps,
+                                     double* us_per_forward) {
+  if (!c || !us_per_forward) return SD_EINVAL;
+  if (which < 0 || which > 1 || reps < 1 || reps > 1000 || (skip_ops & ~SD_OP_ALL)) return fail(c, SD_EINVAL, "which must be 0 / 1, reps 1..1000, skip_ops a set of SD_OP_* bits");
+  const int B = c->batch;
+  const int max_rows = (which == 0) ? c->rt.max_gamma + 1 : 2;
+  if (rows < 1 || rows > max_rows) return fail(c, SD_EINVAL, "rows must be 1..max_gamma+1 for Mp, 1..2 for Mq");
+  if (!c->all_ready() || (which == 1 && c->any_stale())) return fail(c, SD_ESTATE, "sd_time_forward needs every sequence prefilled (and a valid Mq cache to time Mq)");
+  for (int b = 0; b < B; ++b)
+    if (c->len[b] + rows > std::min(c->p.cfg.max_len, c->q.cfg.max_len)) return fail(c, SD_ERANGE, "no room behind the committed sequence");
+  hipGraphExec_t ge = nullptr;
+  c->skip_ops = skip_ops;
+  const sd_status cs = capture_graph(c, &ge, [&] {
+    if (which == 0) {
+      if (rows == 1) forward_any(c, c->p, Rows{ROWS_BASELINE, 0, 1, 0, 0, B, 0}, c->p_logits);
+      else forward_any(c, c->p, Rows{ROWS_VERIFY, 0, rows, 0, 0, B, rows - 1}, c->p_logits);
+    } else {
+      if (rows == 1) forward_any(c, c->q, Rows{ROWS_DRAFT_NEXT, 1, 1, 0, 0, B, 2}, c->q_logits);
+      else forward_any(c, c->q, Rows{ROWS_DRAFT_FIRST, 0, 2, 0, 0, B, 2}, c->q_logits);
+    }
+  });
+  c->skip_ops = 0;
+  if (cs != SD_OK) return cs;
+  hipGraphLaunch(ge, c->stream);                       // warm-up
+  hipEventRecord(c->ev[0], c->stream);
+  for (int i = 0; i < reps; ++i) hipGraphLaunch(ge, c->stream);
+  hipEventRecord(c->ev[1], c->stream);
+  hipError_t e = hipStreamSynchronize(c->stream);
+  float ms = 0.0f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, c->ev[0], c->ev[1]);
+  hipGraphExecDestroy(ge);
+  c->last_kind = -1;                                   // the logits buffers no longer hold a step's rows
+  if (e != hipSuccess) return fail(c, SD_EHIP, std::string("sd_time_forward: ") + hipGetErrorString(e));
+  *us_per_forward = 1e3 * (double)ms / (double)reps;
+  return SD_OK;
+}
+
 extern "C" sd_status sd_get_stats(sd_ctx* c, sd_stats* out) {
   if (!c || !out) return SD_EINVAL;
   *out = c->stats;
   return SD_OK;
 }
-
-// Instrumented build only (-DSD_KTIME, never the product library): read-outs of the runtime's
-// occupancy estimate for the long-context attention kernel, of its per-workgroup timeline and of
-// the attention kernels' phase timers.
-#ifdef SD_KTIME
-extern "C" int sd_debug_occupancy(int lds_bytes) {
-  int n = -1;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, sd::attn_long_kernel<128, 2>, 64 * sd::ATTN_LONG_WAVES, (size_t)lds_bytes) != hipSuccess) return -1;
-  return n;
-}
-extern "C" int sd_debug_wgtrace(unsigned long long* out2560) {
-  return (int)hipMemcpyFromSymbol(out2560, HIP_SYMBOL(sd::g_wgtrace), 2560 * sizeof(unsigned long long));
-}
-extern "C" int sd_debug_ktime(unsigned long long* out96) {
-  return (int)hipMemcpyFromSymbol(out96, HIP_SYMBOL(sd::g_ktime), 96 * sizeof(unsigned long long));
-}
-#endif
 
 #include "spec_sample_api.hip"

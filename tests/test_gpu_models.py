@@ -574,6 +574,55 @@ def test_long_context_spans_several_key_blocks(d_head, ctx):
     dec.close()
 
 
+def test_fp32_long_context_with_the_most_rows_per_kv_head():
+    """d_head 64 with 4 query heads per KV head at gamma = 5 in a long (key-range) context: 24
+    (row, head) pairs per KV head in one workgroup, the attention kernel's largest LDS request
+    (its reduction buffer is biggest at d_head 64).  fp32, against the oracle."""
+    cfg = synth.model_cfg(T.GQA, 2, 8 * 64, 8, 256, 512, 1100 + 64, d_head=64, n_kv_heads=2, dtype="f32", logit_scale=4.0)
+    w = synth.random_weights(cfg, 9, w_std=0.1)
+    cfg_q, w_q = synth.truncated_noisy_copy(cfg, w, 1, 59, 0.02)
+    gamma = 5
+    dec = make_decoder(cfg, w, cfg_q, w_q, max_gamma=gamma, flags=1)
+    sp, sq = oracle_models(cfg, w, cfg_q, w_q)
+    prompt = synth.random_tokens(73, 1100, cfg["vocab"])
+    dec.prefill(prompt)
+    toks, tol, worst, _ = run_pair(dec, sp, sq, prompt, 10, gamma, 1.0, 43, "f32", False)
+    print(f"fp32 d_head 64, 8/2 heads, gamma 5, context 1100: worst logit error {worst}, tolerated {tol}")
+    assert tol["accept"] + tol["draw"] <= 1
+    dec.close()
+
+
+def test_single_row_prefill_does_not_clear_the_other_rows_stale_draft_caches():
+    """After a plain decoding step Mq's cache lags behind for every sequence; resetting and
+    prefilling one of them must not make sd_step acceptable again: the others are still stale."""
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q = synth.tiny_pair()
+    V = cfg_p["vocab"]
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=4, flags=1, batch=2)
+    prompts = [synth.random_tokens(7, 5, V), synth.random_tokens(8, 11, V)]
+    for b in range(2):
+        dec.prefill(prompts[b], row=b)
+    U = synth.uniform_stream(5, 4 * 2 * 9).reshape(4, 2, 9)
+    dec.step(4, 1.0, U[0])
+    dec.step_baseline(1.0, U[1, :, 0])
+    dec.reset(row=0)
+    with pytest.raises(binding.SdError) as e:
+        dec.step(4, 1.0, U[2])
+    assert e.value.status == binding.SD_ESTATE                      # row 0 not prefilled
+    dec.prefill(prompts[0], row=0)
+    with pytest.raises(binding.SdError) as e:
+        dec.step(4, 1.0, U[2])
+    assert e.value.status == binding.SD_ESTATE                      # row 1's Mq cache is still stale
+    with pytest.raises(binding.SdError) as e:
+        dec.measure_cost(2)
+    assert e.value.status == binding.SD_ESTATE
+    dec.reset(row=1)
+    dec.prefill(prompts[1], row=1)
+    res = dec.step(4, 1.0, U[2])                                    # every sequence fresh again
+    assert all(len(t) == n + 1 for n, t in res)
+    dec.close()
+
+
 @pytest.mark.parametrize("d_head,n_heads,n_kv,gamma,ctx,batch", [(128, 8, 2, 4, 1500, 2), (64, 4, 2, 3, 1100, 2),
                                                                  (64, 8, 2, 5, 1200, 2), (128, 2, 2, 3, 1300, 2),
                                                                  (64, 4, 2, 4, 1100, 5)])
