@@ -18,10 +18,21 @@ import torch
 
 from oracle import decode, drafts, sampling, transformer as T
 from paper_2211_17192_amd import synth
+from pairs import row_rel_err as rel_err, small_pair, unrounded
 
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+# bf16 GPU logits against the oracle with every activation rounding switched off (the model the
+# torch-library test pins at 1e-9): the bf16 oracle's own distance from it (bounded per block type
+# in tests/test_oracle_transformer.py) plus the bf16 tolerance.  Independent of where either side
+# places its roundings.
+TOL_VS_UNROUNDED = 4.5e-2
+# Draw disagreements against the INDEPENDENT oracle run (fp32 pairs): there the two sides' CDFs
+# differ themselves (logits agree to 1e-4 of a row's scale, probabilities to about 1e-3), so a
+# draw is excused when its uniform lies within 1e-3 CDF units of an edge of the GPU token's
+# interval.  Level S (the oracle's arithmetic on the GPU's own logits) keeps 1e-5.
+E2E_DRAW_TOL = 1e-3
 
 
 def oracle_models(cfg_p, w_p, cfg_q, w_q, enc_p=None, enc_q=None):
@@ -31,10 +42,6 @@ def oracle_models(cfg_p, w_p, cfg_q, w_q, enc_p=None, enc_q=None):
         mp.set_encoder_output(synth.to_numpy_weights({"e": enc_p})["e"])
         mq.set_encoder_output(synth.to_numpy_weights({"e": enc_q})["e"])
     return T.CachedScorer(mp), T.CachedScorer(mq)
-
-
-def rel_err(got, ref):
-    return float(np.max(np.abs(got - ref), axis=-1).max() / np.abs(ref).max())
 
 
 def level_s(zp, zq, u, gamma, temperature):
@@ -47,14 +54,67 @@ def level_s(zp, zq, u, gamma, temperature):
     return x, n, t, info, p_rows, q_rows
 
 
-def run_pair(dec, sp, sq, prompt, n_new, gamma, temperature, useed, dtype, end_to_end):
+def check_level_s(n_g, toks_g, zp, zq, u, gamma, temperature, tolerated, where=""):
+    """The oracle's Algorithm-1 arithmetic on the GPU's own logits must give the GPU's n and tokens.
+    A disagreement has to be explained by the very decision at which the two part: a draft draw or
+    the final draw whose uniform lies within 1e-5 of an edge of the GPU token's CDF interval, or the
+    first acceptance test they decide differently, with |r - p/q| < 1e-3.  Counts it in
+    `tolerated`; returns the oracle's guesses."""
+    x_s, n_s, t_s, info, p_rows, q_rows = level_s(zp, zq, u, gamma, temperature)
+    expect = x_s[:n_s] + [t_s]
+    if (n_g, toks_g) == (n_s, expect):
+        return x_s
+    if temperature == 0:
+        raise AssertionError(f"{where}: argmax decoding must agree exactly: {n_g, toks_g} vs {n_s, expect}")
+    k = min(n_g, n_s)
+    if toks_g[:k] != x_s[:k]:                       # a draft draw flipped: must be an edge case
+        j = next(i for i in range(k) if toks_g[i] != x_s[i])
+        assert sampling.icdf_edge_distance(q_rows[j], u[j], toks_g[j]) < 1e-5, (where, "draft draw", j)
+        tolerated["draw"] += 1
+    elif n_g != n_s:                                # the test of guess k+1 went the other way
+        if n_g > k and toks_g[k] != x_s[k]:         # ... because the GPU drew another guess there
+            assert sampling.icdf_edge_distance(q_rows[k], u[k], toks_g[k]) < 1e-5, (where, "draft draw", k)
+            tolerated["draw"] += 1
+        else:
+            assert info["margins"][k] < 1e-3, (where, n_g, n_s, info["margins"])
+            tolerated["accept"] += 1
+    else:
+        w = p_rows[n_s] if n_s == gamma else sampling.adjusted_distribution(p_rows[n_s], q_rows[n_s])
+        assert sampling.icdf_edge_distance(w, u[2 * gamma], toks_g[-1]) < 1e-5, (where, "final draw")
+        tolerated["draw"] += 1
+    return x_s
+
+
+def excuse_e2e(info, u, gamma, n_g, toks_g, n_o, toks_o, lenience=1.0):
+    """The GPU's (n, tokens) differ from the independent oracle run's: the decision at which they
+    part must be a close one.  Returns "accept" or "draw", else raises."""
+    assert (n_g, toks_g) != (n_o, toks_o)
+    assert info["margins"] is not None, "argmax decoding has no close decisions"
+    x = info["x"]
+    k = min(n_g, n_o)
+    for i in range(k):
+        if toks_g[i] != x[i]:
+            assert sampling.icdf_edge_distance(info["q_rows"][i], u[i], toks_g[i]) < E2E_DRAW_TOL, ("draft draw", i)
+            return "draw"
+    if n_g != n_o:
+        if n_g > k and toks_g[k] != x[k]:
+            assert sampling.icdf_edge_distance(info["q_rows"][k], u[k], toks_g[k]) < E2E_DRAW_TOL, ("draft draw", k)
+            return "draw"
+        assert info["margins"][k] < 1e-3, (n_g, n_o, k, info["margins"])
+        return "accept"
+    w = info["p_rows"][n_o] if n_o == gamma else sampling.adjusted_distribution(info["p_rows"][n_o], lenience * info["q_rows"][n_o])
+    assert sampling.icdf_edge_distance(w, u[2 * gamma], toks_g[-1]) < E2E_DRAW_TOL, "final draw"
+    return "draw"
+
+
+def run_pair(dec, sp, sq, prompt, n_new, gamma, temperature, useed, dtype, end_to_end, unrounded_scorers=None):
     """Decode n_new tokens on the GPU, checking every iteration.  Returns
     (gpu tokens, counts of tolerated events, worst logit errors, mean accepted)."""
     prefix = [int(t) for t in prompt]
     target = len(prefix) + n_new
     urows = synth.uniform_stream(useed, 400 * (2 * gamma + 1)).reshape(400, -1)
     tolerated = {"accept": 0, "draw": 0, "e2e": 0}
-    worst = {"p": 0.0, "q": 0.0}
+    worst = {"p": 0.0, "q": 0.0, "p_unrounded": 0.0, "q_unrounded": 0.0}
     acc = []
     it = 0
     while len(prefix) < target:
@@ -64,34 +124,23 @@ def run_pair(dec, sp, sq, prompt, n_new, gamma, temperature, useed, dtype, end_t
         zq = dec.logits(1, gamma).astype(np.float64)
         assert np.isfinite(zp).all() and np.isfinite(zq).all()
         # ---- level S
-        x_s, n_s, t_s, info, p_rows, q_rows = level_s(zp, zq, u, gamma, temperature)
-        expect = x_s[:n_s] + [t_s]
-        if (n_g, toks_g) != (n_s, expect):
-            if temperature == 0:
-                raise AssertionError(f"argmax decoding must agree exactly: {n_g, toks_g} vs {n_s, expect}")
-            k = min(n_g, n_s)
-            if toks_g[:k] != x_s[:k]:               # a draft draw flipped: must be an edge case
-                j = next(i for i in range(k) if toks_g[i] != x_s[i])
-                assert sampling.icdf_edge_distance(q_rows[j], u[j], toks_g[j]) < 1e-5
-                tolerated["draw"] += 1
-            elif n_g != n_s:
-                assert info["margins"][k] < 1e-3, (it, n_g, n_s, info["margins"])
-                tolerated["accept"] += 1
-            else:
-                w = p_rows[n_s] if n_s == gamma else sampling.adjusted_distribution(p_rows[n_s], q_rows[n_s])
-                assert sampling.icdf_edge_distance(w, u[2 * gamma], toks_g[-1]) < 1e-5
-                tolerated["draw"] += 1
+        x_s = check_level_s(n_g, toks_g, zp, zq, u, gamma, temperature, tolerated, f"iteration {it}")
         # ---- level M: oracle logits for the same prefix and the same guesses
         zq_o = np.stack([sq.score(prefix + x_s[:i], 1)[0] for i in range(gamma)])
         zp_o = sp.score(prefix + x_s, gamma + 1)
         worst["q"] = max(worst["q"], rel_err(zq, zq_o))
         worst["p"] = max(worst["p"], rel_err(zp, zp_o))
         assert worst["q"] <= TOL[dtype] and worst["p"] <= TOL[dtype], (it, worst)
+        if unrounded_scorers is not None:           # bf16: also against the model without any activation rounding
+            up, uq = unrounded_scorers
+            worst["q_unrounded"] = max(worst["q_unrounded"], rel_err(zq, np.stack([uq.score(prefix + x_s[:i], 1)[0] for i in range(gamma)])))
+            worst["p_unrounded"] = max(worst["p_unrounded"], rel_err(zp, up.score(prefix + x_s, gamma + 1)))
+            assert max(worst["q_unrounded"], worst["p_unrounded"]) <= TOL_VS_UNROUNDED, (it, worst)
         # ---- end to end against the independent oracle (fp32 only)
         if end_to_end:
             new_o, n_o, info_o = decode.speculative_decoding_step(sp, sq, prefix, gamma, temperature, u)
             if new_o[len(prefix):] != toks_g:
-                assert temperature > 0
+                excuse_e2e(info_o, u, gamma, n_g, toks_g, n_o, new_o[len(prefix):])
                 tolerated["e2e"] += 1
         acc.append(n_g)
         prefix = prefix + toks_g
@@ -130,25 +179,6 @@ def test_tiny_fp32_pair_matches_oracle(temperature, flags):
     dec.close()
 
 
-def small_pair(arch, dtype, seed=3):
-    kw = dict(dtype=dtype, logit_scale=4.0)
-    if arch == T.GPT:
-        cfg = synth.model_cfg(T.GPT, 3, 64, 2, 128, 512, 160, **kw)
-    elif arch == T.T5DEC:
-        cfg = synth.model_cfg(T.T5DEC, 3, 64, 2, 96, 512, 160, enc_len=40, norm_eps=1e-6, **kw)
-    else:
-        cfg = synth.model_cfg(T.GQA, 3, 128, 4, 160, 512, 160, d_head=32, n_kv_heads=2, **kw)
-    # bf16: smaller weights keep the toy model out of the regime where one flipped bf16
-    # rounding of an attention output moves a logit by more than the 2e-2 tolerance
-    w = synth.random_weights(cfg, seed, w_std=0.1 if dtype == "f32" else 0.06)
-    cfg_q, w_q = synth.truncated_noisy_copy(cfg, w, 1, seed + 50, 0.02)
-    enc_p = enc_q = None
-    if arch == T.T5DEC:
-        enc_p = synth.counter_normal((cfg["enc_len"], cfg["d_model"]), 91, 1.0).to(w["head"].dtype)
-        enc_q = enc_p.clone()
-    return cfg, w, cfg_q, w_q, enc_p, enc_q
-
-
 @pytest.mark.parametrize("arch", [T.GPT, T.T5DEC, T.GQA])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_small_pairs_all_block_types(arch, dtype):
@@ -156,13 +186,15 @@ def test_small_pairs_all_block_types(arch, dtype):
     attention chunks with a ragged tail, gamma = 5, graph replay on."""
     cfg_p, w_p, cfg_q, w_q, enc_p, enc_q = small_pair(arch, dtype)
     sp, sq = oracle_models(cfg_p, w_p, cfg_q, w_q, enc_p, enc_q)
+    # bf16: a second oracle pair with every activation rounding switched off
+    un = oracle_models(unrounded(cfg_p), w_p, unrounded(cfg_q), w_q, enc_p, enc_q) if dtype == "bf16" else None
     prompt = synth.random_tokens(21, 70, cfg_p["vocab"])
     dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=7, flags=1)
     dec.prefill(prompt, None if enc_p is None else enc_p.cuda(), None if enc_q is None else enc_q.cuda())
     for temperature, gamma, useed in ((1.0, 5, 4), (0.0, 3, 5), (0.7, 7, 6)):
         dec.reset()
         dec.prefill(prompt, None if enc_p is None else enc_p.cuda(), None if enc_q is None else enc_q.cuda())
-        toks, tol, worst, mean_n = run_pair(dec, sp, sq, prompt, 24, gamma, temperature, useed, dtype, dtype == "f32")
+        toks, tol, worst, mean_n = run_pair(dec, sp, sq, prompt, 24, gamma, temperature, useed, dtype, dtype == "f32", un)
         print(f"arch {arch} {dtype} T={temperature} gamma={gamma}: worst logit error {worst}, tolerated {tol}, mean n {mean_n:.2f}")
         assert tol["accept"] + tol["draw"] <= 1, tol
     dec.close()
@@ -254,26 +286,71 @@ def test_gpt_pair_bf16_all_gammas():
     dec.close()
 
 
-def test_t5xxl_full_size_iteration_matches_oracle():
-    """The headline workload at full size (Mp 24 layers, d_model 4096, d_ff 10240,
-    vocab 32128, 512 encoder positions; Mq 6 layers, d_model 512), in the launch
-    configuration bench.py times (graph replay, gamma = 5, temperature 1): the first
-    eight tokens from the start token, all gamma+1 target rows and gamma draft rows
-    of logits against the float64 oracle (level M), and the oracle's Algorithm-1
-    arithmetic on the GPU's logits against the GPU's tokens (level S)."""
+def _t5xxl_full_size():
+    """The headline pair at full size on the GPU (graph replay, the launch configuration bench.py
+    times) and its oracle models on the host: (decoder, bf16 oracle pair, unrounded oracle pair,
+    encoder outputs)."""
     from paper_2211_17192_amd import binding
     cfg_p, w_p, cfg_q, w_q, enc_p, enc_q = synth.t5xxl_pair("cuda")
     host = (synth.to_numpy_weights(w_p), synth.to_numpy_weights(w_q), synth.to_numpy_weights({"p": enc_p, "q": enc_q}))
     dec = binding.SpecDecoder(cfg_p, w_p, cfg_q, w_q, max_gamma=7, flags=binding.SD_FLAG_GRAPH)
     del w_p, w_q
     torch.cuda.empty_cache()
-    mp = T.Transformer(T.ModelConfig(**cfg_p), host[0])
-    mq = T.Transformer(T.ModelConfig(**cfg_q), host[1])
-    mp.set_encoder_output(host[2]["p"]); mq.set_encoder_output(host[2]["q"])
+
+    def models(cp, cq):
+        mp, mq = T.Transformer(T.ModelConfig(**cp), host[0]), T.Transformer(T.ModelConfig(**cq), host[1])
+        mp.set_encoder_output(host[2]["p"]); mq.set_encoder_output(host[2]["q"])
+        return mp, mq
+    return dec, cfg_p, models(cfg_p, cfg_q), models(unrounded(cfg_p), unrounded(cfg_q)), enc_p, enc_q
+
+
+def test_t5xxl_full_size_iteration_matches_oracle():
+    """The headline workload at full size (Mp 24 layers, d_model 4096, d_ff 10240,
+    vocab 32128, 512 encoder positions; Mq 6 layers, d_model 512), in the launch
+    configuration bench.py times (graph replay, gamma = 5, temperature 1): the first
+    eight tokens from the start token, all gamma+1 target rows and gamma draft rows
+    of logits against the float64 oracle (level M) and against the oracle with every
+    activation rounding switched off, and the oracle's Algorithm-1 arithmetic on the
+    GPU's logits against the GPU's tokens (level S)."""
+    dec, cfg_p, (mp, mq), (mp_un, mq_un), enc_p, enc_q = _t5xxl_full_size()
     dec.prefill([0], enc_p, enc_q)
-    toks, tol, worst, mean_n = run_pair(dec, T.CachedScorer(mp), T.CachedScorer(mq), [0], 8, 5, 1.0, 21, "bf16", False)
+    toks, tol, worst, mean_n = run_pair(dec, T.CachedScorer(mp), T.CachedScorer(mq), [0], 8, 5, 1.0, 21, "bf16", False,
+                                        (T.CachedScorer(mp_un), T.CachedScorer(mq_un)))
     print(f"T5-XXL-shaped pair, gamma=5: worst logit error {worst}, tolerated {tol}, mean n {mean_n:.2f}")
     assert tol["accept"] + tol["draw"] <= 1, tol
+    dec.close()
+
+
+def test_t5xxl_full_size_other_headline_cells():
+    """The other cells of the headline run at full size, all behind a 100-token decoder context
+    (self-attention over more than a hundred cached positions, rows in the seventh KV page):
+    gamma = 7 and gamma = 3 at temperature 1 against the oracle at both levels, and argmax
+    sampling (temperature 0) at gamma = 3 / 5 / 7: speculative decoding must emit exactly the
+    tokens of the library's own plain argmax decoding (section 2.2 / the abstract: identical
+    outputs), and its first tokens are checked against the oracle's argmax as well."""
+    dec, cfg_p, (mp, mq), _, enc_p, enc_q = _t5xxl_full_size()
+    prompt = [0] + [int(t) for t in synth.random_tokens(33, 99, cfg_p["vocab"])]
+    sp, sq = T.CachedScorer(mp), T.CachedScorer(mq)
+    for gamma, n_new, useed in ((7, 8, 22), (3, 4, 23)):
+        dec.reset(); dec.prefill(prompt, enc_p, enc_q)
+        toks, tol, worst, mean_n = run_pair(dec, sp, sq, prompt, n_new, gamma, 1.0, useed, "bf16", False)
+        print(f"T5-XXL-shaped pair, 100-token context, gamma={gamma}: worst logit error {worst}, tolerated {tol}, mean n {mean_n:.2f}")
+        assert tol["accept"] + tol["draw"] <= 1, tol
+    # temperature 0
+    dec.reset(); dec.prefill(prompt, enc_p, enc_q)
+    plain = [dec.step_baseline(0.0) for _ in range(24)]
+    for gamma in (3, 5, 7):
+        dec.reset(); dec.prefill(prompt, enc_p, enc_q)
+        spec, kept, its = [], 0, 0
+        while len(spec) < 24:
+            n, t = dec.step(gamma, 0.0, None, prefix=prompt + spec)
+            spec += t; kept += n; its += 1
+        assert spec[:24] == plain, (gamma, spec[:24], plain)
+        print(f"T5-XXL-shaped pair, temperature 0, gamma={gamma}: 24 tokens identical to plain decoding, {kept} guesses kept in {its} iterations")
+    # the first argmax tokens against the oracle (a near-tie of the two largest logits may differ in bf16)
+    z = sp.score(prompt, 1)[0]
+    top2 = np.sort(z)[-2:]
+    assert plain[0] == int(np.argmax(z)) or (top2[1] - top2[0]) < 2e-2 * np.abs(z).max()
     dec.close()
 
 
@@ -305,7 +382,8 @@ def test_lenient_decoding_and_beta_statistics_match_oracle(temperature, lenience
         n_g, toks_g = dec.step(gamma, temperature, u, prefix=prefix)
         new_o, n_o, info = decode.speculative_decoding_step(sp, sq, prefix, gamma, temperature, u, lenience)
         if new_o[len(prefix):] != toks_g:
-            assert temperature > 0 and info["margins"] is not None and np.min(info["margins"]) < 1e-3
+            assert temperature > 0
+            excuse_e2e(info, u, gamma, n_g, toks_g, n_o, new_o[len(prefix):], lenience=l64)
             mismatches += 1
             break                                   # the sequences part ways at a tolerated decision
         tested = min(n_o + 1, gamma)
@@ -380,10 +458,13 @@ def test_top_k_and_nucleus_decoding_matches_oracle(top_k, top_p):
         n_g, toks_g = dec.step(gamma, 1.0, u, prefix=prefix)
         new_o, n_o, info = decode.speculative_decoding_step(sp, sq, prefix, gamma, 1.0, u, 1.0, top_k, tp)
         if new_o[len(prefix):] != toks_g:
-            # explained by a near-threshold acceptance test or a nucleus boundary next to top_p
-            rows = list(info["p_logits"]) + list(info["q_logits"])
+            # explained by the decision at which the two part: a close acceptance test or draw, or a
+            # nucleus boundary next to top_p in one of the rows used up to that decision
+            k = min(n_g, n_o)
+            rows = list(info["p_logits"][:k + 1]) + list(info["q_logits"][:min(k, gamma - 1) + 1])
             near = min(sampling.nucleus_margin(z, 1.0, top_k, tp) for z in rows) if 0 < tp < 1 else 1.0
-            assert np.min(info["margins"]) < 1e-3 or near < 1e-4, (it, toks_g, new_o[len(prefix):])
+            if not near < 1e-4:
+                excuse_e2e(info, u, gamma, n_g, toks_g, n_o, new_o[len(prefix):])
             broke += 1
             break
         for i in range(gamma):                       # every guess lies in q's kept set
@@ -479,7 +560,7 @@ def test_batched_tiny_pair_matches_oracle_per_row_with_reset_of_one_row():
             new_o, n_o, info = decode.speculative_decoding_step(scorers[b][0], scorers[b][1], prefixes[b], gamma, 1.0, U[it, b])
             n_g, toks_g = res[b]
             if new_o[len(prefixes[b]):] != toks_g:
-                assert np.min(info["margins"]) < 1e-3
+                excuse_e2e(info, U[it, b], gamma, n_g, toks_g, n_o, new_o[len(prefixes[b]):])
                 tolerated += 1
             prefixes[b] = prefixes[b] + toks_g
     assert tolerated <= 1
@@ -513,10 +594,13 @@ def test_gqa8b_full_size_batch_matches_oracle_per_row():
     V = cfg_p["vocab"]
     prefixes = [[int(t) for t in synth.random_tokens(60 + b, n, V)] for b, n in enumerate((1, 5, 17, 33))]
     scorers = [(T.CachedScorer(mp), T.CachedScorer(mq)) for _ in range(batch)]
+    mp_un = T.Transformer(T.ModelConfig(**unrounded(cfg_p)), host[0])
+    mq_un = T.Transformer(T.ModelConfig(**unrounded(cfg_q)), host[1])
+    un_scorers = {b: (T.CachedScorer(mp_un), T.CachedScorer(mq_un)) for b in (0, 3)}
     for b in range(batch):
         dec.prefill(prefixes[b], row=b)
     U = synth.uniform_stream(31, 2 * batch * (2 * gamma + 1)).reshape(2, batch, -1)
-    worst, tolerated = 0.0, 0
+    worst, worst_un, tol_s = 0.0, 0.0, {"accept": 0, "draw": 0}
     for it in range(2):
         res = dec.step(gamma, 1.0, U[it])
         zp = dec.logits(0, batch * (gamma + 1)).astype(np.float64).reshape(batch, gamma + 1, V)
@@ -524,19 +608,20 @@ def test_gqa8b_full_size_batch_matches_oracle_per_row():
         assert np.isfinite(zp).all() and np.isfinite(zq).all()
         for b in range(batch):
             n_g, toks_g = res[b]
-            x_s, n_s, t_s, info, p_rows, q_rows = level_s(zp[b], zq[b], U[it, b], gamma, 1.0)
-            if (n_g, toks_g) != (n_s, x_s[:n_s] + [t_s]):
-                k = min(n_g, n_s)
-                assert toks_g[:k] == x_s[:k] and n_g != n_s and info["margins"][k] < 1e-3, (it, b, n_g, n_s)
-                tolerated += 1
+            x_s = check_level_s(n_g, toks_g, zp[b], zq[b], U[it, b], gamma, 1.0, tol_s, f"iteration {it} row {b}")
             sp, sq = scorers[b]
             zq_o = np.stack([sq.score(prefixes[b] + x_s[:i], 1)[0] for i in range(gamma)])
             zp_o = sp.score(prefixes[b] + x_s, gamma + 1)
             worst = max(worst, rel_err(zq[b], zq_o), rel_err(zp[b], zp_o))
             assert worst <= TOL["bf16"], (it, b, worst)
+            if b in (0, 3):      # shortest and longest context: also against the model without activation rounding
+                up, uq = un_scorers[b]
+                worst_un = max(worst_un, rel_err(zq[b], np.stack([uq.score(prefixes[b] + x_s[:i], 1)[0] for i in range(gamma)])),
+                               rel_err(zp[b], up.score(prefixes[b] + x_s, gamma + 1)))
+                assert worst_un <= TOL_VS_UNROUNDED, (it, b, worst_un)
             prefixes[b] = prefixes[b] + toks_g
-    print(f"8B-class GQA pair, batch 4, gamma 4: worst logit error {worst:.2e}, tolerated {tolerated}")
-    assert tolerated <= 1
+    print(f"8B-class GQA pair, batch 4, gamma 4: worst logit error {worst:.2e} (vs the unrounded model {worst_un:.2e}), tolerated {tol_s}")
+    assert tol_s["accept"] + tol_s["draw"] <= 1
     dec.close()
 
 
@@ -556,21 +641,20 @@ def test_long_context_spans_several_key_blocks(d_head, ctx):
     for b in range(batch):
         dec.prefill(prefixes[b], row=b)
     U = synth.uniform_stream(41, 3 * batch * (2 * gamma + 1)).reshape(3, batch, -1)
-    worst = 0.0
+    worst, tolerated = 0.0, {"accept": 0, "draw": 0}
     for it in range(3):
         res = dec.step(gamma, 1.0, U[it])
         zp = dec.logits(0, batch * (gamma + 1)).astype(np.float64).reshape(batch, gamma + 1, -1)
         zq = dec.logits(1, batch * gamma).astype(np.float64).reshape(batch, gamma, -1)
         for b in range(batch):
-            x_s, n_s, t_s, info, _, _ = level_s(zp[b], zq[b], U[it, b], gamma, 1.0)
-            assert res[b] == (n_s, x_s[:n_s] + [t_s]) or np.min(info["margins"]) < 1e-3
+            x_s = check_level_s(res[b][0], res[b][1], zp[b], zq[b], U[it, b], gamma, 1.0, tolerated, f"iteration {it} row {b}")
             sp, sq = scorers[b]
             zq_o = np.stack([sq.score(prefixes[b] + x_s[:i], 1)[0] for i in range(gamma)])
             zp_o = sp.score(prefixes[b] + x_s, gamma + 1)
             worst = max(worst, rel_err(zq[b], zq_o), rel_err(zp[b], zp_o))
             prefixes[b] = prefixes[b] + res[b][1]
-    print(f"d_head {d_head}, context {ctx}: worst logit error {worst:.2e}")
-    assert worst <= TOL["f32"]
+    print(f"d_head {d_head}, context {ctx}: worst logit error {worst:.2e}, tolerated {tolerated}")
+    assert worst <= TOL["f32"] and tolerated["accept"] + tolerated["draw"] <= 1
     dec.close()
 
 
@@ -646,7 +730,7 @@ def test_long_context_bf16_matrix_core_attention(d_head, n_heads, n_kv, gamma, c
         dec.prefill(prefixes[b], row=b)
     solo.prefill(prefixes[0])
     U = synth.uniform_stream(41, 3 * batch * (2 * gamma + 1)).reshape(3, batch, -1)
-    worst = 0.0
+    worst, tolerated = 0.0, {"accept": 0, "draw": 0}
     for it in range(3):
         res = dec.step(gamma, 1.0, U[it])
         zp32 = dec.logits(0, batch * (gamma + 1)).reshape(batch, gamma + 1, -1)
@@ -657,15 +741,14 @@ def test_long_context_bf16_matrix_core_attention(d_head, n_heads, n_kv, gamma, c
         zp, zq = zp32.astype(np.float64), zq32.astype(np.float64)
         assert np.isfinite(zp).all() and np.isfinite(zq).all()
         for b in range(batch):
-            x_s, n_s, t_s, info, _, _ = level_s(zp[b], zq[b], U[it, b], gamma, 1.0)
-            assert res[b] == (n_s, x_s[:n_s] + [t_s]) or np.min(info["margins"]) < 1e-3
+            x_s = check_level_s(res[b][0], res[b][1], zp[b], zq[b], U[it, b], gamma, 1.0, tolerated, f"iteration {it} row {b}")
             sp, sq = scorers[b]
             zq_o = np.stack([sq.score(prefixes[b] + x_s[:i], 1)[0] for i in range(gamma)])
             zp_o = sp.score(prefixes[b] + x_s, gamma + 1)
             worst = max(worst, rel_err(zq[b], zq_o), rel_err(zp[b], zp_o))
             prefixes[b] = prefixes[b] + res[b][1]
-    print(f"bf16, d_head {d_head}, {n_heads}/{n_kv} heads, context {ctx}: worst logit error {worst:.2e}")
-    assert worst <= TOL["bf16"]
+    print(f"bf16, d_head {d_head}, {n_heads}/{n_kv} heads, context {ctx}: worst logit error {worst:.2e}, tolerated {tolerated}")
+    assert worst <= TOL["bf16"] and tolerated["accept"] + tolerated["draw"] <= 1
     dec.step_baseline(1.0, U[0, :, 0])                    # one row per sequence through the same kernel
     zb = dec.logits(2, batch).astype(np.float64)
     for b in range(batch):
@@ -711,7 +794,7 @@ def test_table_drafts_match_oracle(kind):
             new_o, n_o, info = decode.speculative_decoding_step(targets[b], tdraft, prefixes[b], gamma, 1.0, U[it, b])
             np.testing.assert_array_equal(zq[b], info["q_logits"].astype(np.float32))   # the rows are copies of table rows
             if new_o[len(prefixes[b]):] != res[b][1]:
-                assert np.min(info["margins"]) < 1e-3
+                excuse_e2e(info, U[it, b], gamma, res[b][0], res[b][1], n_o, new_o[len(prefixes[b]):])
                 tolerated += 1
             kept += res[b][0]
             prefixes[b] = prefixes[b] + res[b][1]
@@ -769,7 +852,8 @@ def test_copy_drafts_match_oracle(match, fallback, T):
             np.testing.assert_array_equal(zq[b], info["q_logits"].astype(np.float32))   # one-hot, table or zero rows
             copied += int(np.isneginf(zq[b]).any(axis=1).sum())
             if new_o[len(prefixes[b]):] != res[b][1]:
-                assert T > 0 and np.min(info["margins"]) < 1e-3
+                assert T > 0
+                excuse_e2e(info, U[it, b], gamma, res[b][0], res[b][1], n_o, new_o[len(prefixes[b]):])
                 tolerated += 1
             kept += res[b][0]
             prefixes[b] = prefixes[b] + res[b][1]

@@ -50,9 +50,13 @@ def run_case(rows, gamma, vocab, sigma, seed, temperature):
 
 @pytest.mark.parametrize("sigma", [0.5, 1.0, 2.0])
 def test_spec_sample_matches_oracle_full_vocab(sigma):
-    tol, n = run_case(16, 7, 32128, sigma, seed=int(sigma * 10), temperature=1.0)
-    assert tol <= 1
+    """The isolated-sampler workload as configured: 64 independent rows, vocabulary 32128,
+    gamma = 7, target logits N(0, 3^2), draft = target + N(0, sigma^2), through plain
+    sd_spec_sample (64 x 15 statistics workgroups, then one tail workgroup per row)."""
+    tol, n = run_case(64, 7, 32128, sigma, seed=int(sigma * 10), temperature=1.0)
+    assert tol <= 2
     assert n.min() >= 0 and n.max() <= 7
+    print(f"sigma {sigma}: mean accepted {n.mean():.2f} of 7, tolerated {tol}")
 
 
 @pytest.mark.parametrize("rows,gamma,vocab,temperature", [

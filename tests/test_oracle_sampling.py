@@ -430,3 +430,51 @@ def test_uniform_validation():
         decode.speculative_decoding_step(mp, mq, [0], 1, 1.0, [0.0, 0.5, 0.5])
     with pytest.raises(ValueError):
         decode.speculative_decoding_step(mp, mq, [0], 2, 1.0, [0.5, 0.5, 0.5])
+
+
+def test_icdf_edge_distance_on_hand_worked_cdfs():
+    """The helper that decides which draw disagreements the GPU tests excuse.  Weights (1, 1, 2)
+    have the CDF edges 0.25, 0.5, 1: token 1 owns [0.25, 0.5)."""
+    w = [1.0, 1.0, 2.0]
+    assert sampling.icdf_edge_distance(w, 0.3, 1) == pytest.approx(0.05)      # nearer edge 0.25
+    assert sampling.icdf_edge_distance(w, 0.45, 1) == pytest.approx(0.05)     # nearer edge 0.5
+    assert sampling.icdf_edge_distance(w, 0.2, 0) == pytest.approx(0.05)      # token 0: edges 0 and 0.25
+    assert sampling.icdf_edge_distance(w, 0.9, 2) == pytest.approx(0.1)
+    assert sampling.icdf_edge_distance([4.0, 4.0, 8.0], 0.3, 1) == pytest.approx(0.05)   # scale-free
+    # a zero-weight token has an empty interval: its distance is the distance to that single edge
+    assert sampling.icdf_edge_distance([1.0, 0.0, 1.0], 0.6, 1) == pytest.approx(0.1)
+    # meaning: moving u by more than the distance towards the nearer edge changes the drawn token,
+    # moving it by less does not
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        w = rng.random(9) + 0.01
+        u = float(rng.random() * 0.98 + 0.01)
+        k = sampling.icdf(w, u)
+        d = sampling.icdf_edge_distance(w, u, k)
+        c = np.concatenate([[0.0], np.cumsum(w) / np.sum(w)])
+        assert c[k] <= u < c[k + 1] and d == pytest.approx(min(u - c[k], c[k + 1] - u))
+        towards = -1.0 if (u - c[k]) <= (c[k + 1] - u) else 1.0
+        assert sampling.icdf(w, u + towards * 0.5 * d) == k
+        moved = u + towards * (d + 1e-9)
+        if 0.0 < moved < 1.0:
+            assert sampling.icdf(w, moved) != k
+
+
+def test_nucleus_margin_on_hand_worked_rows():
+    """The helper that recognises rows whose nucleus could legitimately come out differently in
+    fp32.  Probabilities (0.5, 0.3, 0.2): the descending cumulative mass passes 0.5, 0.8, 1."""
+    z = np.log([0.3, 0.5, 0.2])
+    assert sampling.nucleus_margin(z, 1.0, 0, 0.75) == pytest.approx(0.05)    # |0.8 - 0.75|
+    assert sampling.nucleus_margin(z, 1.0, 0, 0.55) == pytest.approx(0.05)    # |0.5 - 0.55|
+    assert sampling.nucleus_margin(z, 1.0, 0, 0.8) == pytest.approx(0.0, abs=1e-15)
+    # after top-2 the masses are 0.625, 0.375: cumulative 0.625, 1
+    assert sampling.nucleus_margin(z, 1.0, 2, 0.6) == pytest.approx(0.025)
+    # temperature 0.5 squares the probabilities: (0.25, 0.09, 0.04) / 0.38
+    assert sampling.nucleus_margin(z, 0.5, 0, 0.9) == pytest.approx(abs(0.34 / 0.38 - 0.9))
+    # meaning: the kept set of standardise() changes exactly where the margin reaches zero
+    kept = lambda top_p: int(np.count_nonzero(sampling.standardise(z, 1.0, 0, top_p)))
+    assert (kept(0.8 - 1e-9), kept(0.8 + 1e-9)) == (2, 3)
+    assert (kept(0.5 - 1e-9), kept(0.5 + 1e-9)) == (1, 2)
+    for top_p in (0.3, 0.6, 0.79, 0.81, 0.95):
+        m = sampling.nucleus_margin(z, 1.0, 0, top_p)
+        assert m > 0 and kept(top_p - 0.5 * m) == kept(top_p) == kept(top_p + 0.5 * m)

@@ -40,9 +40,13 @@ def build(arch, dtype="f32", seed=3, w_std=0.25):
     return cfg, w, m, enc
 
 
-def torch_reference(cfg, w, tokens, enc):
-    """Full-prefix forward in float64 with torch library routines."""
+def torch_reference(cfg, w, tokens, enc, rnd=None):
+    """Full-prefix forward in float64 with torch library routines.  rnd (optional) is applied
+    where a textbook mixed-precision implementation stores a tensor in the storage type: the
+    fully normed rows, q / k / v, the attention output, the MLP hidden activation."""
     c = cfg
+    if rnd is None:
+        rnd = lambda t: t
     W = {k: v.double() for k, v in w.items()}
     tok = torch.as_tensor(np.asarray(tokens), dtype=torch.long)
     n = tok.numel()
@@ -53,8 +57,8 @@ def torch_reference(cfg, w, tokens, enc):
 
     def norm(x, p):
         if c["arch"] == T.GPT:
-            return F.layer_norm(x, (d,), W[p + ".g"], W[p + ".b"], c["norm_eps"])
-        return x * torch.rsqrt(x.pow(2).mean(-1, keepdim=True) + c["norm_eps"]) * W[p + ".g"]
+            return rnd(F.layer_norm(x, (d,), W[p + ".g"], W[p + ".b"], c["norm_eps"]))
+        return rnd(x * torch.rsqrt(x.pow(2).mean(-1, keepdim=True) + c["norm_eps"]) * W[p + ".g"])
 
     causal = torch.ones(n, n, dtype=torch.bool).tril()
     mask = torch.zeros(n, n, dtype=torch.float64).masked_fill(~causal, float("-inf"))
@@ -90,27 +94,29 @@ def torch_reference(cfg, w, tokens, enc):
                 z = torch.view_as_complex(t.reshape(*t.shape[:-1], dh // 2, 2).contiguous()) * rot
                 return torch.view_as_real(z).reshape(t.shape)
             q, k = rope(q), rope(k)
+        q, k, v = rnd(q), rnd(k), rnd(v)
+        if c["arch"] == T.GQA:
             k = k.repeat_interleave(H // Hk, 0)
             v = v.repeat_interleave(H // Hk, 0)
         scale = 1.0 if c["arch"] == T.T5DEC else 1.0 / math.sqrt(dh)
         a = F.scaled_dot_product_attention(q[None], k[None], v[None], attn_mask=mask, scale=scale)[0]
-        a = a.transpose(0, 1).reshape(n, H * dh)
+        a = rnd(a.transpose(0, 1).reshape(n, H * dh))
         x = x + F.linear(a, W[p + ".wo"], b(".bo"))
         if c["arch"] == T.T5DEC:
             e = enc.double()
             hc = norm(x, p + ".lnc")
-            qc = F.linear(hc, W[p + ".cq"]).view(n, H, dh).transpose(0, 1)
-            kc = F.linear(e, W[p + ".ck"]).view(-1, H, dh).transpose(0, 1)
-            vc = F.linear(e, W[p + ".cv"]).view(-1, H, dh).transpose(0, 1)
+            qc = rnd(F.linear(hc, W[p + ".cq"])).view(n, H, dh).transpose(0, 1)
+            kc = rnd(F.linear(e, W[p + ".ck"])).view(-1, H, dh).transpose(0, 1)
+            vc = rnd(F.linear(e, W[p + ".cv"])).view(-1, H, dh).transpose(0, 1)
             ac = F.scaled_dot_product_attention(qc[None], kc[None], vc[None], scale=1.0)[0]
-            x = x + F.linear(ac.transpose(0, 1).reshape(n, H * dh), W[p + ".co"])
+            x = x + F.linear(rnd(ac.transpose(0, 1).reshape(n, H * dh)), W[p + ".co"])
         h2 = norm(x, p + ".ln2")
         if c["arch"] == T.GPT:
-            f = F.gelu(F.linear(h2, W[p + ".w1"], W[p + ".b1"]), approximate="tanh")
+            f = rnd(F.gelu(F.linear(h2, W[p + ".w1"], W[p + ".b1"]), approximate="tanh"))
             x = x + F.linear(f, W[p + ".w2"], W[p + ".b2"])
         else:
             act = (lambda t: F.gelu(t, approximate="tanh")) if c["arch"] == T.T5DEC else F.silu
-            f = act(F.linear(h2, W[p + ".wg"])) * F.linear(h2, W[p + ".wu"])
+            f = rnd(act(F.linear(h2, W[p + ".wg"])) * F.linear(h2, W[p + ".wu"]))
             x = x + F.linear(f, W[p + ".w2"])
     return (c["logit_scale"] * F.linear(norm(x, "lnf"), W["head"])).numpy()
 
@@ -140,6 +146,79 @@ def test_cached_blockwise_and_rowwise_forwards_agree(arch, dtype):
     # stale rows beyond the current position are ignored and overwritten (rollback)
     again = m.forward(tokens[9:12], 9, cache)
     np.testing.assert_allclose(again, full[9:12], rtol=1e-10, atol=1e-10)
+
+
+# Bounds (per row: max |difference| / max |logit|) that the bf16 precision model has to keep on the
+# small pairs the GPU tests decode, per block type.  Measured over seeds 3-5 and an 80-token
+# sequence: GPT 6.0e-3, T5DEC 1.6e-2, GQA 8.9e-3 against the unrounded model.
+BF16_GAP_BOUND = {T.GPT: 1.0e-2, T.T5DEC: 2.2e-2, T.GQA: 1.4e-2}
+
+
+def _bf16_small_models(arch, seed, w_std=None):
+    from pairs import small_pair, unrounded
+    cfg, w, _, _, enc, _ = small_pair(arch, "bf16", seed, w_std)
+    wn = synth.to_numpy_weights(w)
+    mb = T.Transformer(T.ModelConfig(**cfg), wn)
+    mf = T.Transformer(T.ModelConfig(**unrounded(cfg)), wn)
+    if enc is not None:
+        e = synth.to_numpy_weights({"e": enc})["e"]
+        mb.set_encoder_output(e)
+        mf.set_encoder_output(e)
+    return cfg, w, enc, mb, mf
+
+
+@pytest.mark.parametrize("arch", [T.GPT, T.T5DEC, T.GQA])
+def test_bf16_precision_model_stays_close_to_the_unrounded_model(arch):
+    """The bf16 model is the fp32-pinned model plus roundings R(.) of activations.  Where the
+    R's sit is this build's convention (the paper fixes no model internals, section 2.1), so it is
+    pinned by its effect: on the same bf16-valued weights the rounded model must stay within a
+    small, stated distance of (a) the very same code with every R switched off, which the
+    torch-library test above pins at 1e-9, and (b) an independent torch evaluation that rounds
+    where a textbook mixed-precision implementation would (the fully normed rows, not x * gain).
+    A rounding in a place where its error accumulates (the residual stream, a sum of squares, the
+    logits of a peaked row) or a scale applied on the wrong side of a rounding widens the gap
+    beyond the bound; and the gap must not vanish either: the R's have to be there."""
+    from pairs import row_rel_err
+    worst_f, worst_t = 0.0, 0.0
+    for seed in (3, 4, 5):
+        cfg, w, enc, mb, mf = _bf16_small_models(arch, seed)
+        toks = synth.random_tokens(21 + seed, 80, cfg["vocab"])
+        zb = mb.forward(toks, 0, T.KVCache(mb.cfg))
+        zf = mf.forward(toks, 0, T.KVCache(mf.cfg))
+        zt = torch_reference(cfg, w, toks, enc, rnd=lambda t: t.to(torch.bfloat16).double())
+        worst_f = max(worst_f, row_rel_err(zb, zf))
+        worst_t = max(worst_t, row_rel_err(zb, zt))
+        assert row_rel_err(zb, zf) > 2e-4                 # the roundings are applied
+    print(f"arch {arch}: bf16 model vs unrounded {worst_f:.2e}, vs textbook rounding points {worst_t:.2e}")
+    assert worst_f <= BF16_GAP_BOUND[arch]
+    assert worst_t <= BF16_GAP_BOUND[arch]
+
+
+def test_bf16_kv_cache_and_cross_keys_hold_bf16_values():
+    """k, v (after the rotary rotation) and the cross-attention keys / values are rounded before
+    they are stored: every cached number is exactly representable in bf16."""
+    for arch in (T.T5DEC, T.GQA):
+        cfg, w, enc, mb, _ = _bf16_small_models(arch, 3)
+        cache = T.KVCache(mb.cfg)
+        mb.forward(synth.random_tokens(2, 12, cfg["vocab"]), 0, cache)
+        for a in (cache.k[:, :12], cache.v[:, :12]):
+            assert np.abs(a).max() > 0 and np.array_equal(T.bf16_round(a), a)
+        if arch == T.T5DEC:
+            for a in mb.cross_k + mb.cross_v:
+                assert np.array_equal(T.bf16_round(a), a)
+
+
+def test_t5dec_toy_model_is_ill_conditioned_in_bf16_at_weight_scale_0_1():
+    """Why the small bf16 pairs use weights of scale 0.06: at 0.1 the T5DEC toy model (unscaled
+    attention scores) amplifies bf16 rounding until the rounded and the unrounded evaluation OF THE
+    SAME ORACLE differ by several times the 2e-2 tolerance that bf16 logits are compared at, so a
+    comparison between two bf16 implementations would measure the model's conditioning, not an
+    implementation."""
+    from pairs import row_rel_err
+    cfg, w, enc, mb, mf = _bf16_small_models(T.T5DEC, 3, w_std=0.1)
+    toks = synth.random_tokens(24, 80, cfg["vocab"])
+    gap = row_rel_err(mb.forward(toks, 0, T.KVCache(mb.cfg)), mf.forward(toks, 0, T.KVCache(mf.cfg)))
+    assert gap > 4e-2, gap
 
 
 def test_cached_scorer_rolls_back_on_divergent_prefix():
