@@ -364,6 +364,28 @@ sd_status sd_spec_sample(const float* p_logits, const float* q_logits, const int
                          int32_t* out_n, int32_t* out_t,
                          void* scratch, void* stream);
 
+
+/*
+ * sd_spec_sample_ex for callers that cannot allocate device memory or pass a
+ * scratch buffer: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels and same results; the
+ * scratch (tickets and row statistics, 250 KB) is a fixed array in device
+ * memory that the library holds on every GPU it runs on until the process ends.
+ * The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine) and clears the tickets it uses with a small fill kernel, so it may
+ * be recorded into a graph.
+ *   rows <= SD_SPEC_SAMPLE_STATIC_MAX_ROWS, else SD_ERANGE (sd_last_error(NULL)
+ *   says so); other argument errors as for sd_spec_sample_ex.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one
+ * GPU (different streams, different threads) race and give undefined results;
+ * calls on one stream are ordered and safe.  Asynchronous on `stream`.
+ */
+enum { SD_SPEC_SAMPLE_STATIC_MAX_ROWS = 256 };
+sd_status sd_spec_sample_static(const float* p_logits, const float* q_logits, const int32_t* x,
+                                const float* r, const float* s, int32_t rows, int32_t gamma,
+                                int32_t vocab, float temperature, const sd_sampling* opt,
+                                int32_t* out_n, int32_t* out_t, float* beta, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

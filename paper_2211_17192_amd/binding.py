@@ -57,6 +57,11 @@ lib.sd_spec_sample_ex.restype = C.c_int
 lib.sd_spec_sample_ex.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                                      C.POINTER(_Sampling), C.c_void_p, C.c_void_p, C.c_void_p,
                                                      C.c_void_p, C.c_void_p]
+lib.sd_spec_sample_static.restype = C.c_int
+lib.sd_spec_sample_static.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                                         C.POINTER(_Sampling), C.c_void_p, C.c_void_p, C.c_void_p,
+                                                         C.c_void_p]
+SD_SPEC_SAMPLE_STATIC_MAX_ROWS = 256
 lib.sd_choose_gamma.restype = C.c_int
 lib.sd_choose_gamma.argtypes = [C.c_double, C.c_double, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
 
@@ -106,6 +111,27 @@ def spec_sample(p_logits, q_logits, x, r, s, temperature: float, scratch=None, o
                                    _ptr(beta) if beta is not None else None, _ptr(scratch), _stream())
     if st != SD_OK:
         raise SdError(st, "sd_spec_sample")
+    return out_n, out_t
+
+
+def spec_sample_static(p_logits, q_logits, x, r, s, temperature: float, out_n, out_t, lenience=None, beta=None,
+                       top_k=0, top_p=0.0):
+    """sd_spec_sample_static: as spec_sample, with the library's own fixed scratch array.  The
+    outputs are the caller's tensors (nothing is allocated here either)."""
+    rows, g1, V = p_logits.shape
+    gamma = g1 - 1
+    for t_, dt in ((p_logits, torch.float32), (q_logits, torch.float32), (x, torch.int32), (out_n, torch.int32),
+                   (out_t, torch.int32)):
+        assert t_.is_cuda and t_.is_contiguous() and t_.dtype == dt
+    assert q_logits.shape == (rows, gamma, V) and x.shape == (rows, gamma) and out_n.numel() == rows and out_t.numel() == rows
+    if beta is not None:
+        assert beta.is_cuda and beta.is_contiguous() and beta.dtype == torch.float32 and beta.shape == (rows, gamma)
+    opt = _Sampling(1.0 if lenience is None else float(lenience), int(top_k), float(top_p))
+    st = lib.sd_spec_sample_static(_ptr(p_logits), _ptr(q_logits), _ptr(x), _ptr(r), _ptr(s), rows, gamma, V,
+                                   float(temperature), C.byref(opt), _ptr(out_n), _ptr(out_t),
+                                   _ptr(beta) if beta is not None else None, _stream())
+    if st != SD_OK:
+        raise SdError(st, (lib.sd_last_error(None) or b"").decode())
     return out_n, out_t
 
 
