@@ -230,6 +230,19 @@ def main():
                          "frac_of_hbm_peak": op_bytes[name] / us / 1e3 / HBM_PEAK_GBPS,
                          "launches_per_forward": 1 if name == "head" else L}
 
+    # the draft model's step, launch by launch, the same way (a draft step that is not an iteration's first)
+    draft_us = dec.time_forward(1, 1, 0, reps=30)
+    bytes_q_ops = {"qkv": 3 * cfg_q["n_heads"] * cfg_q["d_head"] * cfg_q["d_model"] * 2, "attn": 2 * cfg_q["n_heads"] * cfg_q["d_head"] * 2 * ctx_len,
+                   "o": cfg_q["d_model"] * cfg_q["n_heads"] * cfg_q["d_head"] * 2, "cross_q": cfg_q["n_heads"] * cfg_q["d_head"] * cfg_q["d_model"] * 2,
+                   "cross_attn": 2 * cfg_q["enc_len"] * cfg_q["n_heads"] * cfg_q["d_head"] * 2, "cross_o": cfg_q["d_model"] * cfg_q["n_heads"] * cfg_q["d_head"] * 2,
+                   "ffn_in": 2 * cfg_q["d_ff"] * cfg_q["d_model"] * 2, "ffn_out": cfg_q["d_model"] * cfg_q["d_ff"] * 2, "head": V * cfg_q["d_model"] * 2}
+    draft_kernels = {}
+    for name, bit in binding.SD_OP.items():
+        us = (draft_us - dec.time_forward(1, 1, bit, reps=30)) / (1 if name == "head" else cfg_q["n_layers"])
+        draft_kernels[name] = {"bytes": bytes_q_ops[name], "us": us, "launches_per_forward": 1 if name == "head" else cfg_q["n_layers"]}
+    # what the chip gives a kernel that only reads (the GEMMs' access shape, no arithmetic)
+    ceiling_GBps = dec.stream_read_GBps(0, reps=5)
+
     # phase timing with HIP events on the library's stream (eager launches; a few % slower than the graph)
     dec.set_flags(binding.SD_FLAG_PROFILE)
     prof = {}
@@ -314,6 +327,9 @@ def main():
         "speedup_vs_plain": res["speedup_vs_plain"],
         "verify_GBps": res["verify_GBps"], "verify_frac_of_hbm_peak": res["verify_frac_of_hbm_peak"],
         "verify_kernels": {"rows": best + 1, "context": ctx_len, "forward_us": full_us, "per_launch": kernels},
+        "draft_kernels": {"rows": 1, "context": ctx_len, "forward_us": draft_us, "per_launch": draft_kernels},
+        "hbm_read_ceiling_GBps": ceiling_GBps, "hbm_read_ceiling_frac_of_peak": ceiling_GBps / HBM_PEAK_GBPS,
+        "verify_frac_of_read_ceiling": res["verify_GBps"] / ceiling_GBps,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

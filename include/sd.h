@@ -336,6 +336,14 @@ enum {
 sd_status sd_time_forward(sd_ctx* ctx, int32_t which, int32_t rows, int32_t skip_ops, int32_t reps,
                           double* us_per_forward);
 
+/* Measurement: what this chip delivers to a kernel that does nothing but read (the ceiling the
+ * weight-streaming GEMMs of section 3.4's memory-bound regime can approach).  One pass reads the
+ * whole resident weight block of Mp (which = 0) or Mq (1) exactly once with one persistent
+ * 512-thread workgroup per compute unit, 1 KB per wavefront and load, 8 KB in flight per
+ * wavefront: the GEMMs' access shape without their arithmetic.  reps passes between two HIP
+ * events; us_per_pass, bytes_per_pass: host outputs.  Reads only.  Synchronous. */
+sd_status sd_time_stream_read(sd_ctx* ctx, int32_t which, int32_t reps, double* us_per_pass, double* bytes_per_pass);
+
 /*
  * The accept / resample part of Algorithm 1 on explicit logits, for `rows`
  * independent sequences:  n = number of guesses before the first

@@ -192,6 +192,8 @@ lib.sd_time_forward.restype = C.c_int
 lib.sd_time_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
 SD_OP = {"qkv": 1, "attn": 2, "o": 4, "cross_q": 8, "cross_attn": 16, "cross_o": 32, "ffn_in": 64, "ffn_out": 128,
          "head": 256}
+lib.sd_time_stream_read.restype = C.c_int
+lib.sd_time_stream_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 lib.sd_set_sampling.restype = C.c_int
 lib.sd_set_sampling.argtypes = [C.c_void_p, C.POINTER(_Sampling)]
 lib.sd_set_table_draft.restype = C.c_int
@@ -321,6 +323,12 @@ class SpecDecoder:
         us = C.c_double(0.0)
         self._check(lib.sd_time_forward(self._ctx, int(which), int(rows), int(skip_ops), int(reps), C.byref(us)))
         return us.value
+
+    def stream_read_GBps(self, which: int = 0, reps: int = 10) -> float:
+        """GB/s of a pure read of the model's resident weights (the chip's ceiling for the GEMMs' access shape)."""
+        us, nb = C.c_double(0.0), C.c_double(0.0)
+        self._check(lib.sd_time_stream_read(self._ctx, int(which), int(reps), C.byref(us), C.byref(nb)))
+        return nb.value / us.value / 1e3
 
     def set_flags(self, flags: int):
         self._check(lib.sd_set_flags(self._ctx, int(flags)))

@@ -177,7 +177,8 @@ __device__ __forceinline__ float ln_apply(float v, float mu, float rstd, float g
 #define SD_EXP_UNROLL 8
 #endif
 constexpr int GEMM_UNROLL = SD_EXP_UNROLL;
-constexpr int GEMM_PART_REGS = 16;          // partial sums of x^2 held in registers: n_part <= 256
+constexpr int GEMM_PART_REGS = 16;          // partial sums of x^2 an epilogue thread adds from LDS: 16 x 16 tiles
+constexpr int GEMM_PART_STAGE = 16 * GEMM_PART_REGS;   // tiles whose partial sums are staged in LDS (d_model <= 4096)
 
 // Launched with 4 or 8 wavefronts; threads 0..255 (t = row * 16 + feature) run the epilogue.
 template <typename T, int PRO, int EPI>
@@ -276,18 +277,28 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
 
   const int G = my_tiles * nchunks;
   Buf b0, b1;
-  if (G > 0) load_chunk(b0, 0);
-
-  // ---- values the epilogue needs that do not depend on the tile ----
-  float sp[GEMM_PART_REGS];                      // PRO_POST: partial sums p = e_f, e_f + 16, ...
+  // ---- PRO_POST: 1 / rms of every row, once per workgroup.  The producer left one partial sum
+  // of x^2 per 16-feature tile and row ([n_part][16] floats, written by n_part different
+  // workgroups).  Thread t of the four epilogue wavefronts fetches block t with four 16-byte
+  // loads that go straight into LDS (no registers; the whole array crosses the memory system once
+  // per workgroup, 1 KB per wavefront and load); epilogue thread (row, f) then adds the partials
+  // f, f + 16, ... in ascending order and the 16 lanes of the row: the order the batched kernels
+  // use too.  (Letting every epilogue thread load its 16 partials itself, 64 bytes apart, made 256
+  // workgroups send a thousand requests each to the same 256 cache lines: 1.3 us per launch.)
+  // The loads go out ahead of the weights, so that the in-order return of loads does not hold the
+  // weight stream back, and are read under the barrier the first tile's end needs anyway.
+  // LDS layout: load i of wavefront w fills ssb[(4 i + w) * 256 ..] with one 16-byte piece per
+  // lane: partial (p, row) sits at (((row / 4) * 4 + p / 64) * 64 + p % 64) * 4 + row % 4.
+  float rs_row = 1.0f;
+  float* ssb = ybuf + 256;                       // GEMM_PART_STAGE * 16 floats
   if (PRO == PRO_POST && epi_thread) {
+    const float* blk = a.ss_in + (size_t)min(tid, a.n_part - 1) * 16;
 #pragma unroll
-    for (int u = 0; u < GEMM_PART_REGS; ++u) {
-      const int p = e_f + 16 * u;
-      const float v = a.ss_in[min(p, a.n_part - 1) * 16 + e_rowc];
-      sp[u] = (p < a.n_part) ? v : 0.0f;
-    }
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(blk + 4 * i),
+                                       (__attribute__((address_space(3))) void*)(ssb + (4 * i + wave) * 256), 16, 0, 0);
   }
+  if (G > 0) load_chunk(b0, 0);
   int e_pos = -1;
   size_t e_kvbase = 0;                            // EPI_QKV: cache offset of this row's page / slot
   if (EPI == EPI_QKV && epi_thread) {
@@ -333,6 +344,21 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     __syncthreads();
     if (epi_thread) {
       const int t = tid, row = e_row, f = e_f, n = tile * 16 + f;
+      if (PRO == PRO_POST && ti == 0) {
+        float q = 0.0f;
+#pragma unroll
+        for (int u = 0; u < GEMM_PART_REGS; ++u) {
+          const int p = e_f + 16 * u;
+          const int pc = min(p, a.n_part - 1);
+          const float v = ssb[((((e_row >> 2) << 2) + (pc >> 6)) * 64 + (pc & 63)) * 4 + (e_row & 3)];
+          q += (p < a.n_part) ? v : 0.0f;
+        }
+        for (int p = e_f + 16 * GEMM_PART_REGS; p < a.n_part; p += 16) q += a.ss_in[p * 16 + e_rowc];
+        q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+        q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+        q = row_first(q);                          // the total the batched kernels use: the first lane's
+        rs_row = 1.0f / sqrtf(q / (float)a.K + a.eps);
+      }
       float y[ND];
 #pragma unroll
       for (int d = 0; d < ND; ++d) {
@@ -341,16 +367,8 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
         y[d] = s;
       }
       if (PRO == PRO_POST) {
-        float q = 0.0f;
 #pragma unroll
-        for (int u = 0; u < GEMM_PART_REGS; ++u) q += sp[u];
-        for (int p = f + 16 * GEMM_PART_REGS; p < a.n_part; p += 16) q += a.ss_in[p * 16 + e_rowc];
-        q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
-        q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
-        q = row_first(q);                          // the total the batched kernels use: the first lane's
-        const float rs = 1.0f / sqrtf(q / (float)a.K + a.eps);
-#pragma unroll
-        for (int d = 0; d < ND; ++d) y[d] *= rs;
+        for (int d = 0; d < ND; ++d) y[d] *= rs_row;
       }
       y[0] += pre_bias;
       if (EPI == EPI_QKV) {

@@ -159,6 +159,31 @@ static __global__ void hist_append_kernel(int* __restrict__ hist, int hist_strid
   if (t < cnt && pos >= 0 && pos < hist_stride) h[pos] = spec ? st->out[t] : st->last_tok;
 }
 
+// Pure streaming read (measurement): the grid's wavefronts walk the buffer in the GEMMs' access
+// shape, 1 KB per wavefront and load, `depth` KB in flight per wavefront, every byte exactly once
+// (n_blocks 1-KB blocks, wavefront w of W takes blocks w, w + W, ... in runs of `run` blocks).
+// The sum lands in *sink only if it equals a value it cannot have, so the loads are not removed.
+static __global__ __launch_bounds__(512) void stream_read_kernel(const f32x4* __restrict__ src, size_t n_blocks, float* sink) {
+  const int lane = threadIdx.x & 63;
+  const size_t W = (size_t)gridDim.x * (blockDim.x >> 6), w = (size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const size_t per_wave = (n_blocks + W - 1) / W;            // consecutive blocks per wavefront
+  const size_t b0 = w * per_wave, b1 = (b0 + per_wave < n_blocks) ? b0 + per_wave : n_blocks;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  constexpr int U = 8;
+  for (size_t b = b0; b < b1; b += U) {
+    f32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {                            // unconditional loads, out-of-range ones re-read the last block
+      const size_t bb = (b + u < b1) ? b + u : b1 - 1;
+      v[u] = __builtin_nontemporal_load(src + bb * 64 + lane);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (b + u < b1) acc += v[u];
+  }
+  if (acc.x + acc.y + acc.z + acc.w == 1.2345e-31f) *sink = acc.x;
+}
+
 static __global__ void fill_u32_kernel(unsigned int* p, unsigned int v, size_t n) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

@@ -269,7 +269,7 @@ void launch_gemm_t(hipStream_t s, GemmArgs a) {
   const int S = pick_waves(KS);
   a.ksteps_per_wave = (KS + S - 1) / S;
   const int ND = (EPI == EPI_GATED) ? 2 : 1;
-  const size_t lds = (size_t)(2 * S * ND * 256 + S * 16 + 256) * sizeof(float);
+  const size_t lds = (size_t)(2 * S * ND * 256 + S * 16 + 256 + (PRO == PRO_POST ? GEMM_PART_STAGE * 16 : 0)) * sizeof(float);
   // one resident workgroup of 8 wavefronts per CU (more only when they are smaller), each
   // taking the same number of tiles
   const int capacity = g_num_cus * std::max(1, 8 / S);
@@ -1326,6 +1326,31 @@ extern "C" sd_status sd_time_forward(sd_ctx* c, int32_t which, int32_t rows, int
   c->last_kind = -1;                                   // the logits buffers no longer hold a step's rows
   if (e != hipSuccess) return fail(c, SD_EHIP, std::string("sd_time_forward: ") + hipGetErrorString(e));
   *us_per_forward = 1e3 * (double)ms / (double)reps;
+  return SD_OK;
+}
+
+extern "C" sd_status sd_time_stream_read(sd_ctx* c, int32_t which, int32_t reps, double* us_per_pass, double* bytes_per_pass) {
+  if (!c || !us_per_pass || !bytes_per_pass) return SD_EINVAL;
+  if (which < 0 || which > 1 || reps < 1 || reps > 1000) return fail(c, SD_EINVAL, "which must be 0 / 1, reps 1..1000");
+  const Model& m = which ? c->q : c->p;
+  // the model's weights as the library holds them: from the output table to the end of the last layer's weights
+  const char* lo = static_cast<const char*>(m.head);
+  const LayerW& last = m.L.back();
+  const char* hi = static_cast<const char*>(last.kv);
+  if (hi <= lo) return fail(c, SD_EINVAL, "unexpected workspace layout");
+  const size_t n_blocks = (size_t)(hi - lo) / 1024;
+  float* sink = reinterpret_cast<float*>(c->d_counter);      // never written: the kernel's condition cannot hold
+  hipLaunchKernelGGL(stream_read_kernel, dim3(g_num_cus), dim3(512), 0, c->stream, reinterpret_cast<const f32x4*>(lo), n_blocks, sink);
+  hipEventRecord(c->ev[0], c->stream);
+  for (int i = 0; i < reps; ++i)
+    hipLaunchKernelGGL(stream_read_kernel, dim3(g_num_cus), dim3(512), 0, c->stream, reinterpret_cast<const f32x4*>(lo), n_blocks, sink);
+  hipEventRecord(c->ev[1], c->stream);
+  hipError_t e = hipStreamSynchronize(c->stream);
+  float ms = 0.0f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, c->ev[0], c->ev[1]);
+  if (e != hipSuccess) return fail(c, SD_EHIP, std::string("sd_time_stream_read: ") + hipGetErrorString(e));
+  *us_per_pass = 1e3 * (double)ms / (double)reps;
+  *bytes_per_pass = (double)n_blocks * 1024.0;
   return SD_OK;
 }
 
