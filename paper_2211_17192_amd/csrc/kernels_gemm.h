@@ -173,19 +173,22 @@ __device__ __forceinline__ float ln_apply(float v, float mu, float rstd, float g
   return ng + b;
 }
 
-#ifndef SD_EXP_UNROLL
-#define SD_EXP_UNROLL 8
-#endif
-constexpr int GEMM_UNROLL = SD_EXP_UNROLL;
+// k-steps per chunk of the software pipeline (a chunk's loads go out together, unconditionally:
+// k-steps beyond a wavefront's slice re-read its last one).  8 for long K-slices; a wavefront
+// whose whole slice is 4 k-steps or fewer (d_model 512 over 4 wavefronts) takes chunks of 4, so
+// that half of its loads are not duplicates: 7 % off the small draft model's forward.
+constexpr int GEMM_UNROLL = 8;
+constexpr int GEMM_UNROLL_SHORT = 4;
 constexpr int GEMM_PART_REGS = 16;          // partial sums of x^2 an epilogue thread adds from LDS: 16 x 16 tiles
 constexpr int GEMM_PART_STAGE = 16 * GEMM_PART_REGS;   // tiles whose partial sums are staged in LDS (d_model <= 4096)
 
 // Launched with 4 or 8 wavefronts; threads 0..255 (t = row * 16 + feature) run the epilogue.
-template <typename T, int PRO, int EPI>
+// U: k-steps per chunk (GEMM_UNROLL or GEMM_UNROLL_SHORT; it changes what is in flight, never the
+// order of a row's additions).
+template <typename T, int PRO, int EPI, int U = GEMM_UNROLL>
 static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   extern __shared__ float lds[];
   constexpr int ND = (EPI == EPI_GATED) ? 2 : 1;
-  constexpr int U = GEMM_UNROLL;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, S = blockDim.x >> 6;
   const int j = lane & 15, kq = lane >> 4;           // B side: row j, k-quarter kq
   const int KS = a.K >> 5;

@@ -275,7 +275,10 @@ void launch_gemm_t(hipStream_t s, GemmArgs a) {
   const int capacity = g_num_cus * std::max(1, 8 / S);
   const int per_wg = (tiles + capacity - 1) / capacity;
   const int grid = (tiles + per_wg - 1) / per_wg;
-  hipLaunchKernelGGL((gemm_kernel<T, PRO, EPI>), dim3(grid), dim3(64 * S), lds, s, a);
+  if (a.ksteps_per_wave <= GEMM_UNROLL_SHORT)
+    hipLaunchKernelGGL((gemm_kernel<T, PRO, EPI, GEMM_UNROLL_SHORT>), dim3(grid), dim3(64 * S), lds, s, a);
+  else
+    hipLaunchKernelGGL((gemm_kernel<T, PRO, EPI, GEMM_UNROLL>), dim3(grid), dim3(64 * S), lds, s, a);
 }
 
 // Several 16-row slabs in one launch (a.nrt of them, set by the caller).
