@@ -5,9 +5,9 @@
 // QKV projection just before) or to a fixed block of encoder keys
 // (cross-attention).
 //
-// One workgroup of 1024 threads owns one kv head (and a few of the query rows:
+// One workgroup of 256, 512 or 1024 threads owns one kv head (and a few of the query rows:
 // rows are independent, so splitting them needs no merge) and walks its keys in blocks
-// (512 keys, 256 for d_head 128) with an online softmax (running max m,
+// (one key per 2 threads, per 4 for d_head 128) with an online softmax (running max m,
 // denominator l, unnormalised output O per row).  There is no split over
 // workgroups and therefore no cross-workgroup merge: device-scope atomics cost
 // about a quarter of a microsecond each on this chip when they queue on one
@@ -32,19 +32,17 @@
 namespace sd {
 
 
-constexpr int ATTN_THREADS = 1024;
-constexpr int ATTN_LDS_PAGES = 1024;       // page-table entries cached in LDS
 constexpr int ATTN_LDS_DIST = 4096;        // causal distances whose bias bucket is cached in LDS
 constexpr int ATTN_MAX_RG = 24;            // query rows x heads per kv head that fit in LDS
 
-// KB keys per block; LPK lanes per key and DP head-dim elements per lane in the
-// score phase; KPT consecutive keys per thread in the P*V phase; RPP rows per
-// P*V pass (bounds the LDS reduction buffer [16 waves][RPP][DH] to 64 KB).
+// LPK lanes per key and DP head-dim elements per lane in the score phase (a workgroup of THREADS
+// threads takes THREADS / LPK keys per block); KPT consecutive keys per thread in the P*V phase;
+// RPP rows per P*V pass (bounds the LDS reduction buffer [wavefronts][RPP][DH] to 64 KB).
 template <int DH> struct AttnShape;
-template <> struct AttnShape<32>  { static constexpr int KB = 512, LPK = 2, DP = 16, KPT = 2, RPP = 16; };
-template <> struct AttnShape<64>  { static constexpr int KB = 512, LPK = 2, DP = 32, KPT = 4, RPP = 16; };
-template <> struct AttnShape<128> { static constexpr int KB = 256, LPK = 4, DP = 32, KPT = 4, RPP = 8; };
-constexpr int attn_block_keys(int dh) { return dh == 128 ? 256 : 512; }
+template <> struct AttnShape<32>  { static constexpr int LPK = 2, DP = 16, KPT = 2, RPP = 16; };
+template <> struct AttnShape<64>  { static constexpr int LPK = 2, DP = 32, KPT = 4, RPP = 16; };
+template <> struct AttnShape<128> { static constexpr int LPK = 4, DP = 32, KPT = 4, RPP = 8; };
+constexpr int attn_block_keys(int dh, int threads = 1024) { return threads / (dh == 128 ? 4 : 2); }
 constexpr int attn_rows_per_pass(int dh) { return dh == 128 ? 8 : 16; }
 
 struct AttnArgs {
@@ -53,9 +51,10 @@ struct AttnArgs {
   const void* kv_pool;      // self: this layer's pages
   const void* ck; const void* cv;   // cross: T [H][kv_len][dh] each
   const int* page_table;
-  int page_size, n_pages;   // page_size a power of two, n_pages <= ATTN_LDS_PAGES
+  int page_size, n_pages;   // page_size a power of two >= 16; n_pages entries per sequence in page_table
   const int* row_pos;       // [R]; self: causal limit of each row, < 0 = padding row
   int R, H, Hkv;
+  int G, g_mul;             // query heads per kv head; 65536 / G + 1: x / G == (x * g_mul) >> 16 for x < 1024
   int rows_per_wg;          // grid.y = ceil(R / rows_per_wg): rows are independent, no merge needed
   // several sequences in one launch: grid.z = sequences, R rows each, one after the other
   // (sequence z: rows z * R ..); sequence z uses the page table at page_table + (seq0 + z) * pt_stride
@@ -75,24 +74,37 @@ struct AttnArgs {
   int kv_len;
   float scale;
   const void* rel_bias;     // T [H][rel_buckets] or nullptr
+  // attn_mma_kernel: the same bias laid out by distance: [H][bias_off + 4] floats, entry bias_off - d
+  // for causal distance d = position - key in [0, bias_off], zeros after it
+  const float* bias_by_key;
+  int bias_off;
   const int* bucket_lut;    // [n_pages * page_size <= ATTN_LDS_DIST] bucket of each causal distance
   int rel_buckets;
 };
 
-// dynamic LDS (floats): q [RG][DH] | s [RG][KB] | o [16][RPP][DH] | m, l, f [3][RG] | acc [RG][DH]
-template <typename T, int DH>
-static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArgs a) {
+// THREADS (256, 512 or 1024) sets the key block: THREADS / LPK keys per pass, so a launch takes the
+// smallest workgroup whose block covers the contexts it expects; CROSS compiles the cross-attention
+// addressing (fixed keys, no mask, no bias) apart from the paged one.
+// The kernel is a chain of latencies, so everything the first key block needs from memory leaves
+// in one go before anything waits: the rows' positions and the page-table entries (cached reads),
+// then the K and V rows (threads whose key lies beyond the context re-read the block's first key,
+// whose page entry every thread holds, and get probability 0), then the queries and the bias tables on their way to LDS.  The next block's page entries are
+// asked for a block ahead, its keys as soon as the scores have used the current ones, its values
+// after the last P*V pass.
+// dynamic LDS (floats): q [RG][DH] | s [RG][KB] | o [THREADS/64][RPP][DH] | m, l, f [3][RG] | acc [RG][DH]
+template <typename T, int DH, int THREADS, bool CROSS>
+static __global__ __launch_bounds__(THREADS) void attn_kernel(const AttnArgs a) {
   extern __shared__ float lds[];
   __shared__ int s_pos[MAX_ROWS];
-  __shared__ int s_pt[ATTN_LDS_PAGES];
   __shared__ float s_bias[4 * 64];                 // rel_bias rows of this kv head's query heads
   __shared__ unsigned char s_bucket[ATTN_LDS_DIST];
   typedef AttnShape<DH> SH;
-  constexpr int KB = SH::KB, LPK = SH::LPK, DP = SH::DP, KPT = SH::KPT, RPP = SH::RPP;
+  constexpr int LPK = SH::LPK, KB = THREADS / LPK, DP = SH::DP, KPT = SH::KPT, RPP = SH::RPP;
   constexpr int OCT = DH / 8;                      // 8-element slices of a V row
-  constexpr int NW = ATTN_THREADS / 64;
-  static_assert((ATTN_THREADS / OCT) * KPT == KB, "P*V mapping must cover the key block");
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int NW = THREADS / 64;
+  static_assert((THREADS / OCT) * KPT == KB, "P*V mapping must cover the key block");
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int hkv = blockIdx.x;
   // rows are independent: blockIdx.y takes rows [r0, r0 + R) of the launch
   const int split = (a.nsplit > 1) ? (int)blockIdx.y % a.nsplit : 0;
@@ -101,80 +113,96 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
   const int r0 = (int)blockIdx.z * a.R + rs;      // first row within the launch
   const int* page_table = a.page_table + (size_t)(a.seq0 + blockIdx.z) * a.pt_stride;
   const int G = a.H / a.Hkv, RG = R * G;
+  const int kl_s = tid / LPK, part = tid % LPK;    // score phase: key within block, slice
+  const int oct = tid % OCT, grp = tid / OCT;      // P*V phase: V slice, key group (KPT keys)
+  const int page_shift = __ffs(a.page_size) - 1, page_mask = a.page_size - 1;
+  const int key_cap = CROSS ? a.kv_len : a.n_pages * a.page_size;   // keys that exist in memory
+  const int k_begin = split * a.split_keys;
 
-  if (tid < MAX_ROWS) s_pos[tid] = (tid < R) ? (a.cross ? 0 : a.row_pos[r0 + tid]) : -1;
-  if (!a.cross) for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += ATTN_THREADS) s_pt[i] = page_table[i];
-  // relative-position bias: table rows and distance -> bucket map into LDS, so
-  // the score loop has no global loads
-  const bool use_bias = !a.cross && a.rel_bias != nullptr;
-  if (use_bias) {
-    for (int i = tid; i < G * a.rel_buckets; i += ATTN_THREADS)
-      s_bias[i] = Store<T>::ld(static_cast<const T*>(a.rel_bias) + (size_t)(hkv * G) * a.rel_buckets + i);
-    const int n_dist = min(ATTN_LDS_DIST, a.n_pages * a.page_size);
-    for (int i = tid; i < n_dist; i += ATTN_THREADS) s_bucket[i] = (unsigned char)a.bucket_lut[i];
-  }
+  // ---- (1) positions and page entries ----
+  int my_pos = -1;                                 // lane r of every wavefront: the causal limit of row r
+  if (lane < R) my_pos = CROSS ? 0 : a.row_pos[r0 + lane];
+  int pg0 = 0, pgk = 0, pgv[KPT];                 // page of the block's first key, of this thread's K key and V keys
+  auto load_pages = [&](int k0) {
+    if (CROSS) return;
+    pg0 = page_table[k0 >> page_shift];
+    pgk = page_table[min(k0 + kl_s, key_cap - 1) >> page_shift];
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) pgv[u] = page_table[min(k0 + grp * KPT + u, key_cap - 1) >> page_shift];
+  };
+  auto row_ptr = [&](int key, int page, int which) -> const T* {   // which: 0 = K, 1 = V
+    if (CROSS) return static_cast<const T*>(which ? a.cv : a.ck) + ((size_t)hkv * a.kv_len + key) * DH;
+    return static_cast<const T*>(a.kv_pool) +
+           ((((size_t)page * 2 + which) * a.Hkv + hkv) * a.page_size + (key & page_mask)) * DH;
+  };
+  // ---- (2) K and V rows of a block: unconditional 16-byte loads (a branch per load would serialise them) ----
+  float kreg[DP];
+  float vreg[KPT][8];                              // keys grp * KPT + u
+  int kv_len = a.kv_len;                           // keys this workgroup attends to end here
+  auto issue_k = [&](int k0) {
+    const bool ok = k0 + kl_s < kv_len;
+    const T* kp = row_ptr(ok ? k0 + kl_s : k0, ok ? pgk : pg0, 0) + part * DP;
+#pragma unroll
+    for (int e = 0; e < DP; e += 8) {
+      float v[8];
+      load8<T>(kp + e, v);
+#pragma unroll
+      for (int f = 0; f < 8; ++f) kreg[e + f] = v[f];
+    }
+  };
+  auto issue_v = [&](int k0) {
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+      const bool ok = k0 + grp * KPT + u < kv_len;
+      load8<T>(row_ptr(ok ? k0 + grp * KPT + u : k0, ok ? pgv[u] : pg0, 1) + oct * 8, vreg[u]);
+    }
+  };
+#pragma unroll
+  for (int u = 0; u < KPT; ++u) pgv[u] = 0;
+  load_pages(k_begin);
+  if (!CROSS) kv_len = wave_max(my_pos) + 1;
+  const int kv_all = kv_len;                       // the context; kv_len: where this key range ends
+  if (a.nsplit > 1) kv_len = min(kv_len, k_begin + a.split_keys);
+  issue_k(k_begin);
+  issue_v(k_begin);
+
+  // ---- (3) queries and tables into LDS ----
   float* q_s = lds;                                // [RG][DH]
   float* s_s = q_s + RG * DH;                      // [RG][KB]
-  float* o_s = s_s + RG * KB;                      // [16][RPP][DH]
+  float* o_s = s_s + RG * KB;                      // [NW][RPP][DH]
   float* m_s = o_s + NW * RPP * DH;                // [RG] running max
   float* l_s = m_s + RG;                           // [RG] running denominator
   float* f_s = l_s + RG;                           // [RG] rescale factor of this pass
   float* acc_s = f_s + RG;                         // [RG][DH] running output
-
+  if (tid < MAX_ROWS) s_pos[tid] = my_pos;
   const T* qg = static_cast<const T*>(a.q);
-  for (int i = tid; i < RG * DH; i += ATTN_THREADS) {
+  for (int i = tid; i < RG * DH; i += THREADS) {
     const int rg = i / DH, d = i % DH, r = rg / G, h = hkv * G + rg % G;
     q_s[i] = Store<T>::ld(qg + (size_t)(r0 + r) * a.H * DH + h * DH + d);
     acc_s[i] = 0.0f;
   }
   if (tid < RG) { m_s[tid] = -INFINITY; l_s[tid] = 0.0f; }
-  __syncthreads();
-  int kv_len = a.kv_len;
-  if (!a.cross) {
-    int mx = -1;
-    for (int r = 0; r < R; ++r) mx = max(mx, s_pos[r]);
-    kv_len = mx + 1;
+  // relative-position bias: table rows and distance -> bucket map (the distances this context
+  // can hold) into LDS, so the score loop has no global loads
+  const bool use_bias = !CROSS && a.rel_bias != nullptr;
+  if (use_bias) {
+    for (int i = tid; i < G * a.rel_buckets; i += THREADS)
+      s_bias[i] = Store<T>::ld(static_cast<const T*>(a.rel_bias) + (size_t)(hkv * G) * a.rel_buckets + i);
+    const int n_dist = min(ATTN_LDS_DIST, kv_all);
+    for (int i = tid; i < n_dist; i += THREADS) s_bucket[i] = (unsigned char)a.bucket_lut[i];
   }
-  const int page_shift = __ffs(a.page_size) - 1, page_mask = a.page_size - 1;
-  const T* cross_k = a.cross ? static_cast<const T*>(a.ck) + (size_t)hkv * a.kv_len * DH : nullptr;
-  const T* cross_v = a.cross ? static_cast<const T*>(a.cv) + (size_t)hkv * a.kv_len * DH : nullptr;
-  auto row_ptr = [&](int key, int which) -> const T* {   // which: 0 = K, 1 = V
-    if (a.cross) return (which ? cross_v : cross_k) + (size_t)key * DH;
-    const int page = s_pt[key >> page_shift], slot = key & page_mask;
-    return static_cast<const T*>(a.kv_pool) +
-           ((((size_t)page * 2 + which) * a.Hkv + hkv) * a.page_size + slot) * DH;
-  };
-  const int kl_s = tid / LPK, part = tid % LPK;    // score phase: key within block, slice
-  const int oct = tid % OCT, grp = tid / OCT;      // P*V phase: V slice, key group (KPT keys)
-
-  const int k_begin = split * a.split_keys;
   if (a.nsplit > 1 && k_begin >= kv_len) {       // nothing in this key range yet: an empty partial
     float* pp = a.partial + ((((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
     if (tid < RG) { pp[(size_t)tid * (DH + 2) + DH] = -INFINITY; pp[(size_t)tid * (DH + 2) + DH + 1] = 0.0f; }
     return;
   }
-  if (a.nsplit > 1) kv_len = min(kv_len, k_begin + a.split_keys);
-  for (int k0 = (a.nsplit > 1) ? k_begin : 0; k0 < kv_len; k0 += KB) {
+  __syncthreads();
+
+  for (int k0 = k_begin; k0 < kv_len; k0 += KB) {
     const int nkeys = min(KB, kv_len - k0);
-    // ---- issue every global load of this block.  Loads are unconditional
-    //      (out-of-range keys re-read the last valid one and get probability 0):
-    //      a branch per load would serialise them. ----
-    float kreg[DP];
+    const bool more = k0 + KB < kv_len;
+    if (more) load_pages(k0 + KB);
     const bool key_ok = kl_s < nkeys;
-    {
-      const T* kp = row_ptr(k0 + min(kl_s, nkeys - 1), 0) + part * DP;
-#pragma unroll
-      for (int e = 0; e < DP; e += 8) {
-        float v[8];
-        load8<T>(kp + e, v);
-#pragma unroll
-        for (int f = 0; f < 8; ++f) kreg[e + f] = v[f];
-      }
-    }
-    float vreg[KPT][8];                            // keys grp * KPT + u
-#pragma unroll
-    for (int u = 0; u < KPT; ++u)
-      load8<T>(row_ptr(k0 + min(grp * KPT + u, nkeys - 1), 1) + oct * 8, vreg[u]);
 
     // ---- scores ----
     for (int rg = 0; rg < RG; ++rg) {
@@ -193,13 +221,14 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
       if (part == 0) {
         const int r = rg / G, pos = s_pos[r], key = k0 + kl_s;
         float sc = -INFINITY;
-        if (key_ok && pos >= 0 && (a.cross || key <= pos)) {
+        if (key_ok && pos >= 0 && (CROSS || key <= pos)) {
           sc = a.scale * dot;
           if (use_bias) sc += s_bias[(rg % G) * a.rel_buckets + (int)s_bucket[pos - key]];
         }
         s_s[rg * KB + kl_s] = sc;
       }
     }
+    if (more) issue_k(k0 + KB);
     __syncthreads();
 
     // ---- online softmax: one wavefront per row ----
@@ -261,8 +290,9 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
           for (int e = 0; e < 8; ++e) o[e] = t[e];
         }
       }
+      if (more && rb + RPP >= RG) issue_v(k0 + KB);
       __syncthreads();
-      for (int i = tid; i < nr * DH; i += ATTN_THREADS) {      // wavefronts = key ranges, ascending
+      for (int i = tid; i < nr * DH; i += THREADS) {           // wavefronts = key ranges, ascending
         float t = 0.0f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) t += o_s[w * RPP * DH + i];
@@ -275,24 +305,26 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
 
   if (a.nsplit > 1) {            // leave the partial result of this key range for the merge
     float* pp = a.partial + ((((size_t)blockIdx.z * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
-    for (int i = tid; i < RG * DH; i += ATTN_THREADS) pp[(size_t)(i / DH) * (DH + 2) + i % DH] = acc_s[i];
+    for (int i = tid; i < RG * DH; i += THREADS) pp[(size_t)(i / DH) * (DH + 2) + i % DH] = acc_s[i];
     if (tid < RG) { pp[(size_t)tid * (DH + 2) + DH] = m_s[tid]; pp[(size_t)tid * (DH + 2) + DH + 1] = l_s[tid]; }
     return;
   }
   T* og = static_cast<T*>(a.out);
-  for (int i = tid; i < RG * DH; i += ATTN_THREADS) {
+  for (int i = tid; i < RG * DH; i += THREADS) {
     const int rg = i / DH, d = i % DH, r = rg / G, h = hkv * G + rg % G;
     const float L = l_s[rg];
     Store<T>::st(og + (size_t)(r0 + r) * a.H * DH + h * DH + d, (L > 0.0f) ? acc_s[i] / L : 0.0f);
   }
 }
 
-// Long contexts, bf16: the same key-range workgroups as attn_kernel with nsplit > 1, but the
-// two products run on the matrix cores, because with thousands of keys the vector ALUs, not
-// the loads, bound attn_kernel (gamma+1 rows x 4 query heads per kv head: about 1.3 M
-// multiply-adds per 256 keys).  A workgroup has four wavefronts that never synchronise inside
-// the key loop; each walks every fourth 32-key step of the range with its own running maximum,
-// denominator and output, all in registers:
+// bf16 attention on the matrix cores.  attn_kernel is a chain of a few hundred vector
+// instructions per wavefront, and a wavefront issues one every four cycles at best: at decode
+// sizes that chain, not memory, is most of its time.  Here the two products are MFMAs and the
+// operands go from the cache rows straight into their fragments, so a 32-key step is a few dozen
+// instructions.  A workgroup has NW (4 or 8) wavefronts that never synchronise inside the key
+// loop; each walks every NW-th 32-key step of its key range with its own running maximum,
+// denominator and output, all in registers (more wavefronts than that lose more at the merge
+// than they gain on the steps):
 //   S^T = K Q^T   16x16x32 MFMA, A = 16 keys x 32 features straight from the cache rows,
 //                 B = the query rows (rows x heads of the kv head, zero-padded to 16 or 32),
 //                 kept in registers for the whole kernel.  Which features a lane holds is free
@@ -305,9 +337,20 @@ static __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(const AttnArg
 //                 16-byte loads and reads the fragments back transposed, 2 bytes at a time;
 //                 B = the probabilities the lane
 //                 already holds, each as the sum of two bf16 numbers (two MFMAs).
-// The wavefronts' results are merged through LDS and left in `partial` for attn_merge_kernel
-// exactly as attn_kernel leaves them.  Every row's arithmetic is independent of the other rows.
-// dynamic LDS: max(4 x 32 x (d_head + 8) bf16 staging, 4 x RG x (d_head + 2) floats for the merge).
+// The wavefronts' results are merged through LDS, in wavefront order; a launch without key ranges
+// (nsplit == 1) normalises and writes the output rows, one with key ranges leaves (m, l, O) in
+// `partial` for attn_merge_kernel exactly as attn_kernel does.  Every row's arithmetic is
+// independent of the other rows.  MODE: causal self-attention over the paged cache, the same with
+// the relative-position bias, or cross-attention (the fixed encoder keys, no mask, no bias).
+// The bias of (head, key - position) comes from a table the host lays out by distance
+// (bias_by_key: [head][max_len + 3], entry max_len - 1 - distance, zero-padded), so the four
+// consecutive keys a lane scores per 16-key tile are one 16-byte read, asked for with the step's
+// K and V rows: no tables in LDS, no barrier before the loop.
+// Memory latency: the rows' positions, the first step's page entries and the queries leave
+// together; the K and V rows follow as soon as the positions (hence the context length) are
+// known; page entries of later steps are asked for a step ahead.  No page table in LDS.
+// grid = (kv heads, sequences, row groups or key ranges).
+// dynamic LDS: max(NW x 32 x (d_head + 8) bf16 staging, NW x RG x (d_head + 2) floats for the merge).
 __device__ __forceinline__ bf16x8 ld_frag(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
 __device__ __forceinline__ bf16x8 zero_frag() {
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -318,65 +361,86 @@ __device__ __forceinline__ bf16x8 zero_frag() {
 __device__ __forceinline__ f32x4 mma_bf16(const bf16x8& a, const bf16x8& b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-constexpr int ATTN_LONG_WAVES = 4;
-constexpr float ATTN_LONG_SLACK = 6.0f;      // how far scores may outgrow the softmax reference point before it moves
-constexpr size_t attn_long_lds_bytes(int rg, int dh) {
-  const size_t stage = (size_t)ATTN_LONG_WAVES * 32 * (dh + 8) * 2, merge = (size_t)ATTN_LONG_WAVES * rg * (dh + 2) * 4;
+constexpr float ATTN_MMA_SLACK = 6.0f;       // how far scores may outgrow the softmax reference point before it moves
+constexpr size_t attn_mma_lds_bytes(int rg, int dh, int nw) {
+  const size_t stage = (size_t)nw * 32 * (dh + 8) * 2, merge = (size_t)nw * rg * (dh + 2) * 4;
   return stage > merge ? stage : merge;
 }
 
-template <int DH, int NRT>
-static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kernel(const AttnArgs a) {
+constexpr int ATTN_SELF = 0, ATTN_SELF_BIAS = 1, ATTN_CROSS = 2;
+typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // four floats at any 4-byte boundary
+
+template <int DH, int NRT, int NW, int MODE>
+static __global__ __launch_bounds__(64 * NW) void attn_mma_kernel(const AttnArgs a) {
   extern __shared__ float lds[];
-  __shared__ int s_pos[MAX_ROWS];
-  __shared__ int s_pt[ATTN_LDS_PAGES];
+  constexpr bool CROSS = MODE == ATTN_CROSS, BIAS = MODE == ATTN_SELF_BIAS;
   constexpr int KSQ = DH / 32;                     // k-steps of the score product
   constexpr int DT = DH / 16;                      // 16-feature tiles of the output
-  constexpr int NW = ATTN_LONG_WAVES;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j = lane & 15, kq = lane >> 4;
   const int hkv = blockIdx.x;
-  const int seq = blockIdx.y;                       // key ranges in z, the slowest index: the fullest ranges start first
-  const int split = (int)blockIdx.z % a.nsplit;
-  const int rs = ((int)blockIdx.z / a.nsplit) * a.rows_per_wg;
+  const int seq = blockIdx.y;
+  // z: the key ranges of a launch that has them (it has one row group), else the row groups
+  const int split = (a.nsplit > 1) ? (int)blockIdx.z : 0;
+  const int rs = (a.nsplit > 1) ? 0 : (int)blockIdx.z * a.rows_per_wg;
   const int R = min(a.rows_per_wg, a.R - rs);
   const int r0 = seq * a.R + rs;
+  const int G = a.G, RG = R * G;
   const int* page_table = a.page_table + (size_t)(a.seq0 + seq) * a.pt_stride;
-  const int G = a.H / a.Hkv, RG = R * G;
-  if (tid < MAX_ROWS) s_pos[tid] = (tid < R) ? a.row_pos[r0 + tid] : -1;
-  for (int i = tid; i < min(a.n_pages, ATTN_LDS_PAGES); i += 64 * NW) s_pt[i] = page_table[i];
-  __syncthreads();
-  int kv_len = 0;
-  for (int r = 0; r < R; ++r) kv_len = max(kv_len, s_pos[r] + 1);
-  const int k_begin = split * a.split_keys;
-  float* pp = a.partial + ((((size_t)seq * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
-  if (k_begin >= kv_len) {                          // nothing in this key range yet: an empty partial
-    if (tid < RG) { pp[(size_t)tid * (DH + 2) + DH] = -INFINITY; pp[(size_t)tid * (DH + 2) + DH + 1] = 0.0f; }
-    return;
-  }
-  kv_len = min(kv_len, k_begin + a.split_keys);
   const int page_shift = __ffs(a.page_size) - 1, page_mask = a.page_size - 1;
-  const bf16* pool = static_cast<const bf16*>(a.kv_pool);
-  auto row_ptr = [&](int key, int which) -> const bf16* {
-    const int page = s_pt[key >> page_shift], slot = key & page_mask;
-    return pool + ((((size_t)page * 2 + which) * a.Hkv + hkv) * a.page_size + slot) * DH;
-  };
+  const int last_page = a.n_pages - 1;
+  const int k_begin = split * a.split_keys;
+  const int kb0 = k_begin + wave * 32;
 
+  // ---- positions, the first step's page entries, the queries: one round of loads ----
+  int my_pos = -1;                                  // lane r: the causal limit of row r
+  if (!CROSS && lane < R) my_pos = a.row_pos[r0 + lane];
+  int pg[2] = {0, 0};                               // pages of keys kb .. kb + 15 and kb + 16 .. kb + 31 of the step to load
+  auto ask_pages = [&](int kb, int (&out)[2]) {
+    if (CROSS) return;
+    out[0] = page_table[min(kb >> page_shift, last_page)];
+    out[1] = page_table[min((kb + 16) >> page_shift, last_page)];
+  };
+  ask_pages(kb0, pg);
   // query rows of this lane: rg = rt * 16 + j; features (4 s + kq) * 8 .. + 8 in k-step s
   bf16x8 qf[NRT][KSQ];
-  int pos[NRT];
+  int pos[NRT], gq[NRT];
+  const float* brow[NRT];                           // BIAS: this lane's head in bias_by_key
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
     const int rg = rt * 16 + j;
     const bool ok = rg < RG;
     const int rgc = ok ? rg : 0;
-    pos[rt] = ok ? s_pos[rgc / G] : -1;
-    const bf16* qp = static_cast<const bf16*>(a.q) + (size_t)(r0 + rgc / G) * a.H * DH + (size_t)(hkv * G + rgc % G) * DH + kq * 8;
+    const int rr = (rgc * a.g_mul) >> 16;           // rgc / G
+    gq[rt] = rgc - rr * G;
+    pos[rt] = ok ? (CROSS ? 0x7fffffff : a.row_pos[r0 + rr]) : -1;
+    brow[rt] = BIAS ? a.bias_by_key + (size_t)(hkv * G + gq[rt]) * (a.bias_off + 4) : nullptr;
+    const bf16* qp = static_cast<const bf16*>(a.q) + (size_t)(r0 + rr) * a.H * DH + (size_t)(hkv * G + gq[rt]) * DH + kq * 8;
 #pragma unroll
     for (int s = 0; s < KSQ; ++s) qf[rt][s] = ok ? ld_frag(qp + s * 32) : zero_frag();
   }
+  int kv_len = a.kv_len;
   int pos_min = 0x7fffffff;                         // a step whose keys all lie at or below it needs no mask
-  for (int r = 0; r < R; ++r) pos_min = min(pos_min, s_pos[r]);
+  if (!CROSS) {
+    kv_len = wave_max(my_pos) + 1;
+    pos_min = wave_min(lane < R ? my_pos : 0x7fffffff);
+  }
+  float* pp = a.partial + ((((size_t)seq * a.Hkv + hkv) * a.nsplit + split) * ATTN_MAX_RG + (size_t)rs * G) * (DH + 2);
+  if (a.nsplit > 1) {
+    if (k_begin >= kv_len) {                        // nothing in this key range yet: an empty partial
+      if (tid < RG) { pp[(size_t)tid * (DH + 2) + DH] = -INFINITY; pp[(size_t)tid * (DH + 2) + DH + 1] = 0.0f; }
+      return;
+    }
+    kv_len = min(kv_len, k_begin + a.split_keys);
+  }
+  int pg_last = 0;                                  // page of the last key: what loads past the range re-read
+  if (!CROSS) pg_last = page_table[min(max(kv_len - 1, 0) >> page_shift, last_page)];
+  auto row_ptr = [&](int key, int page, int which) -> const bf16* {   // which: 0 = K, 1 = V
+    if (CROSS) return static_cast<const bf16*>(which ? a.cv : a.ck) + ((size_t)hkv * a.kv_len + key) * DH;
+    return static_cast<const bf16*>(a.kv_pool) + ((((size_t)page * 2 + which) * a.Hkv + hkv) * a.page_size + (key & page_mask)) * DH;
+  };
+
   float m_run[NRT], l_run[NRT];
   f32x4 o[DT][NRT];
 #pragma unroll
@@ -397,13 +461,19 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
   bf16x8 kf[2][KSQ];
   bf16x8 vr[DH / 16];
   // A step's 32 keys start at a multiple of 32 and pages hold a multiple of 16 keys, so keys 0..15
-  // of the step are consecutive slots of one page and keys 16..31 of one page: two table lookups
-  // per step and operand instead of one per load.  (Past the range kb is clamped and every lane
-  // re-reads key kb itself, slot 0 of the first half.)
-  auto load_k = [&](int kb) {                       // always issued
-    kb = min(kb, kv_len - 1);
-    const int nk = min(32, kv_len - kb);
-    const bf16* half[2] = {row_ptr(kb, 0), row_ptr(min(kb + 16, kv_len - 1), 0)};
+  // of the step are consecutive slots of one page and keys 16..31 of one page: two page entries
+  // per step.  (Past the range kb is clamped and every lane re-reads the last key itself.)
+  auto halves = [&](int kb, int which, const bf16* (&half)[2], int& nk) {
+    const bool in = kb < kv_len;
+    const int kc = in ? kb : max(kv_len - 1, 0);
+    nk = max(min(32, kv_len - kc), 1);
+    const bool in1 = kb + 16 < kv_len;
+    half[0] = row_ptr(kc, in ? pg[0] : pg_last, which);
+    half[1] = row_ptr(in1 ? kb + 16 : max(kv_len - 1, 0), in1 ? pg[1] : pg_last, which);
+  };
+  auto load_k = [&](int kb) {
+    const bf16* half[2]; int nk;
+    halves(kb, 0, half, nk);
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       const int kk = min(kt * 16 + j, nk - 1);
@@ -413,20 +483,35 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
     }
   };
   auto load_v = [&](int kb) {                       // load c: VKPL keys, each row read by DH/8 consecutive lanes
-    kb = min(kb, kv_len - 1);
-    const int nk = min(32, kv_len - kb);
-    const bf16* half[2] = {row_ptr(kb, 1), row_ptr(min(kb + 16, kv_len - 1), 1)};
+    const bf16* half[2]; int nk;
+    halves(kb, 1, half, nk);
 #pragma unroll
     for (int c = 0; c < DH / 16; ++c) {
       const int kk = min(c * VKPL + vkey, nk - 1);
       vr[c] = ld_frag(((kk < 16) ? half[0] + kk * DH : half[1] + (kk - 16) * DH) + vpiece * 8);
     }
   };
-  const int kb0 = k_begin + wave * 32;
-  load_k(kb0); load_v(kb0);                         // out-of-range keys re-read the last valid one and get probability 0
+  // bias of this lane's keys kb + kt*16 + kq*4 + 0..3 for row rt: table entries (key - pos) + bias_off ..,
+  // clamped where every one of them is masked anyway (key > pos)
+  f32x4 bz[2][NRT];
+  auto load_bias = [&](int kb) {
+    if (!BIAS) return;
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        const int i0 = min(kb + kt * 16 + kq * 4 - pos[rt] + a.bias_off, a.bias_off);
+        bz[kt][rt] = *reinterpret_cast<const f32x4_a4*>(brow[rt] + i0);
+      }
+  };
+  if (kb0 < kv_len) { load_k(kb0); load_v(kb0); load_bias(kb0); }   // a wavefront without keys loads nothing
+  ask_pages(kb0 + NW * 32, pg);
+
   for (int kb = kb0; kb < kv_len; kb += NW * 32) {
     const int nkeys = min(32, kv_len - kb);
     const int kb_next = kb + NW * 32;
+    int pgn[2] = {0, 0};
+    ask_pages(kb_next + NW * 32, pgn);
     // ---- V tile -> LDS, transposed; then its registers take the next step's tile ----
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");     // the reads of the previous step are done
 #pragma unroll
@@ -443,6 +528,13 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
         for (int s = 0; s < KSQ; ++s) sc[kt][rt] = mma_bf16(kf[kt][s], qf[rt][s], sc[kt][rt]);
       }
     load_k(kb_next);
+    pg[0] = pgn[0]; pg[1] = pgn[1];
+    f32x4 bias[2][NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) bias[kt][rt] = BIAS ? bz[kt][rt] : f32x4{0.f, 0.f, 0.f, 0.f};
+    load_bias(kb_next);                              // (its index clamp keeps reads past the range in bounds)
     float p[2][NRT][4];
     float f[NRT];
     bool rescale = false;
@@ -456,6 +548,7 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             p[kt][rt][r] = a.scale * sc[kt][rt][r];
+            if (BIAS) p[kt][rt][r] += bias[kt][rt][r];
             mx = fmaxf(mx, p[kt][rt][r]);
           }
       } else {
@@ -465,15 +558,17 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
           for (int r = 0; r < 4; ++r) {
             const int kl = kt * 16 + kq * 4 + r;
             const bool ok = kl < nkeys && kb + kl <= pos[rt];
-            p[kt][rt][r] = ok ? a.scale * sc[kt][rt][r] : -INFINITY;
+            float v = a.scale * sc[kt][rt][r];
+            if (BIAS) v += bias[kt][rt][r];
+            p[kt][rt][r] = ok ? v : -INFINITY;
             mx = fmaxf(mx, p[kt][rt][r]);
           }
       }
       mx = lane_combine<16>(mx, OpMaxF());
       mx = lane_combine<32>(mx, OpMaxF());
       // the reference point m_run only moves when the scores outgrow it by more than
-      // ATTN_LONG_SLACK: probabilities stay below e^slack, and most steps need no rescaling
-      const float m_new = (mx > m_run[rt] + ATTN_LONG_SLACK || m_run[rt] == -INFINITY) ? fmaxf(m_run[rt], mx) : m_run[rt];
+      // ATTN_MMA_SLACK: probabilities stay below e^slack, and most steps need no rescaling
+      const float m_new = (mx > m_run[rt] + ATTN_MMA_SLACK || m_run[rt] == -INFINITY) ? fmaxf(m_run[rt], mx) : m_run[rt];
       f[rt] = (m_new == m_run[rt]) ? 1.0f : ((m_run[rt] == -INFINITY) ? 0.0f : __expf(m_run[rt] - m_new));
       rescale = rescale || (f[rt] != 1.0f);
       float sum = 0.0f;
@@ -540,21 +635,44 @@ static __global__ __launch_bounds__(64 * ATTN_LONG_WAVES, 2) void attn_long_kern
     }
   }
   __syncthreads();
-  for (int i = tid; i < RG * (DH + 2); i += 64 * NW) {
-    const int rg = i / (DH + 2), d = i % (DH + 2);
+  if (a.nsplit > 1) {
+    for (int i = tid; i < RG * (DH + 2); i += 64 * NW) {
+      const int rg = i / (DH + 2), d = i % (DH + 2);
+      float m = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) m = fmaxf(m, lds[((size_t)w * RG + rg) * (DH + 2) + DH]);
+      float out = m;                                   // d == DH: the maximum itself
+      if (d != DH) {
+        out = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {                 // wavefronts in order; d == DH + 1 sums the denominators
+          const float mw = lds[((size_t)w * RG + rg) * (DH + 2) + DH];
+          if (mw != -INFINITY) out += lds[((size_t)w * RG + rg) * (DH + 2) + d] * __expf(mw - m);
+        }
+      }
+      pp[i] = out;
+    }
+    return;
+  }
+  bf16* og = static_cast<bf16*>(a.out);
+  for (int i = tid; i < RG * DH; i += 64 * NW) {
+    const int rg = i / DH, d = i % DH;
     float m = -INFINITY;
 #pragma unroll
     for (int w = 0; w < NW; ++w) m = fmaxf(m, lds[((size_t)w * RG + rg) * (DH + 2) + DH]);
-    float out = m;                                   // d == DH: the maximum itself
-    if (d != DH) {
-      out = 0.0f;
+    float L = 0.0f, acc = 0.0f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) {                 // wavefronts in order; d == DH + 1 sums the denominators
-        const float mw = lds[((size_t)w * RG + rg) * (DH + 2) + DH];
-        if (mw != -INFINITY) out += lds[((size_t)w * RG + rg) * (DH + 2) + d] * __expf(mw - m);
+    for (int w = 0; w < NW; ++w) {                     // wavefronts in order
+      const float* row = lds + ((size_t)w * RG + rg) * (DH + 2);
+      const float mw = row[DH];
+      if (mw != -INFINITY) {
+        const float e = __expf(mw - m);
+        L += row[DH + 1] * e;
+        acc += row[d] * e;
       }
     }
-    pp[i] = out;
+    const int rr = (rg * a.g_mul) >> 16, gg = rg - rr * G;
+    og[(size_t)(r0 + rr) * a.H * DH + (size_t)(hkv * G + gg) * DH + d] = (bf16)((L > 0.0f) ? acc / L : 0.0f);
   }
 }
 

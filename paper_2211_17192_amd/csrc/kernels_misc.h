@@ -184,6 +184,19 @@ static __global__ __launch_bounds__(512) void stream_read_kernel(const f32x4* __
   if (acc.x + acc.y + acc.z + acc.w == 1.2345e-31f) *sink = acc.x;
 }
 
+// Relative-position bias by causal distance: out[h][max_len - 1 - d] = rel_bias[h][bucket_lut[d]] for
+// d in [0, max_len), three zeros after it (rows of max_len + 3 floats): consecutive keys of one query
+// position are consecutive entries.
+template <typename T>
+static __global__ void bias_by_key_kernel(const T* __restrict__ rel_bias, const int* __restrict__ bucket_lut, int rel_buckets,
+                                          int max_len, int n_heads, float* __restrict__ out) {
+  const int row = max_len + 3;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_heads * row) return;
+  const int h = i / row, e = i % row;
+  out[i] = (e < max_len) ? Store<T>::ld(rel_bias + (size_t)h * rel_buckets + bucket_lut[max_len - 1 - e]) : 0.0f;
+}
+
 static __global__ void fill_u32_kernel(unsigned int* p, unsigned int v, size_t n) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

@@ -58,6 +58,7 @@ struct Model {
   int nq = 0, nkv = 0, n_pages = 0, page_size = 0;
   void *tok_emb = nullptr, *pos_emb = nullptr, *head = nullptr, *lnfg = nullptr, *lnfb = nullptr, *rel_bias = nullptr;
   int* bucket_lut = nullptr;
+  float* bias_by_key = nullptr; // T5DEC: rel_bias by causal distance, [n_heads][max_len + 3] (attn_mma_kernel)
   float* rope = nullptr;
   std::vector<LayerW> L;
   int batch = 1;               // sequences; each owns n_pages pages of every layer's pool
@@ -120,6 +121,7 @@ void plan_model(Arena& A, Model& m, const sd_model_cfg& c, int page_size, int ba
   if (c.arch == SD_ARCH_T5DEC) {
     m.rel_bias = A.take((size_t)c.n_heads * c.rel_buckets * e);
     m.bucket_lut = static_cast<int*>(A.take((size_t)c.max_len * sizeof(int)));
+    m.bias_by_key = static_cast<float*>(A.take((size_t)c.n_heads * (c.max_len + 3) * sizeof(float)));
   }
   if (c.arch == SD_ARCH_GQA) m.rope = static_cast<float*>(A.take((size_t)c.max_len * c.d_head * sizeof(float)));
   m.L.assign(c.n_layers, LayerW());
@@ -377,33 +379,76 @@ void launch_gemm(hipStream_t s, int pro, int epi, const GemmArgs& a) {
 #undef SD_CASE
 }
 
-size_t attn_lds_bytes(int RG, int DH) {
-  return (size_t)(RG * DH + RG * attn_block_keys(DH) + (ATTN_THREADS / 64) * attn_rows_per_pass(DH) * DH +
+size_t attn_lds_bytes(int RG, int DH, int threads) {
+  return (size_t)(RG * DH + RG * attn_block_keys(DH, threads) + (threads / 64) * attn_rows_per_pass(DH) * DH +
                   3 * RG + RG * DH) * sizeof(float);
+}
+
+// Threads per workgroup of attn_kernel: the smallest size whose key block covers `keys`.
+int attn_threads(int DH, int keys) {
+  for (int t : {256, 512})
+    if (attn_block_keys(DH, t) >= keys) return t;
+  return 1024;
+}
+
+template <typename T, int DH>
+void launch_attn_kernel(hipStream_t s, const AttnArgs& a, dim3 grid, int threads, size_t lds) {
+#define SD_ATTN(TH)                                                                                  \
+  if (threads == TH) {                                                                               \
+    if (a.cross) hipLaunchKernelGGL((attn_kernel<T, DH, TH, true>), grid, dim3(TH), lds, s, a);      \
+    else hipLaunchKernelGGL((attn_kernel<T, DH, TH, false>), grid, dim3(TH), lds, s, a);             \
+    return;                                                                                          \
+  }
+  SD_ATTN(256) SD_ATTN(512) SD_ATTN(1024)
+#undef SD_ATTN
+}
+
+// The matrix-core kernel: four wavefronts per workgroup, eight when the expected context is more than
+// eight 32-key steps (measured at 512 encoder keys: 6.5 us against 6.8 with four and 7.7 with sixteen).
+int attn_mma_waves(int keys) { return (keys + 31) / 32 > 8 ? 8 : 4; }
+template <int DH, int NRT>
+void launch_attn_mma(hipStream_t s, const AttnArgs& a, dim3 grid, int nw, size_t lds) {
+  const int mode = a.cross ? ATTN_CROSS : (a.bias_by_key != nullptr ? ATTN_SELF_BIAS : ATTN_SELF);
+#define SD_MMA(NW_, MODE_)                                                                                \
+  if (nw == NW_ && mode == MODE_) {                                                                       \
+    hipLaunchKernelGGL((attn_mma_kernel<DH, NRT, NW_, MODE_>), grid, dim3(64 * NW_), lds, s, a);          \
+    return;                                                                                               \
+  }
+  SD_MMA(4, ATTN_SELF) SD_MMA(4, ATTN_SELF_BIAS) SD_MMA(4, ATTN_CROSS)
+  SD_MMA(8, ATTN_SELF) SD_MMA(8, ATTN_SELF_BIAS) SD_MMA(8, ATTN_CROSS)
+#undef SD_MMA
 }
 
 template <typename T>
 void launch_attn(hipStream_t s, const Model& m, AttnArgs a, int nseq) {
   const int G = a.H / a.Hkv, DH = m.cfg.d_head;
+  a.G = G; a.g_mul = 65536 / G + 1;
   // few kv heads leave most CUs idle: split the (independent) rows over more workgroups
   a.rows_per_wg = (nseq * a.Hkv * ((a.R + 1) / 2) <= g_num_cus) ? std::min(2, a.R) : a.R;
   if (a.cross || m.attn_nsplit <= 1) { a.nsplit = 1; a.split_keys = 0; a.partial = nullptr; }
   else { a.nsplit = m.attn_nsplit; a.split_keys = m.attn_split_keys; a.partial = m.attn_partial; }
   if (a.nsplit > 1) a.rows_per_wg = a.R;          // the key ranges already spread the work
-  const size_t lds = attn_lds_bytes(a.rows_per_wg * G, DH);
-  const dim3 grid(a.Hkv, ((a.R + a.rows_per_wg - 1) / a.rows_per_wg) * a.nsplit, nseq), block(ATTN_THREADS);
-  // long bf16 contexts without a position bias: the matrix-core variant of the key-range workgroups
-  if (std::is_same<T, bf16>::value && a.nsplit > 1 && a.rel_bias == nullptr && (DH == 64 || DH == 128)) {
+  // The workgroup is sized for the context: all of the encoder's keys in one block for cross-attention,
+  // half of max_len for self-attention (a sequence that grows to max_len spends half its life below
+  // that; longer contexts take more blocks).  Fixed per model, so every forward of a model, plain or
+  // (gamma+1)-row, adds a row's keys in the same order.
+  const int threads = a.cross ? attn_threads(DH, a.kv_len) : (a.nsplit > 1 ? 1024 : attn_threads(DH, (m.cfg.max_len + 1) / 2));
+  const size_t lds = attn_lds_bytes(a.rows_per_wg * G, DH, threads);
+  const dim3 grid(a.Hkv, ((a.R + a.rows_per_wg - 1) / a.rows_per_wg) * a.nsplit, nseq);
+  // bf16 with d_head 64 or 128: the matrix-core kernel (key ranges: four wavefronts per range, as
+  // the ranges already spread the work)
+  if (std::is_same<T, bf16>::value && (DH == 64 || DH == 128)) {
     const int RG = a.rows_per_wg * G;
-    const size_t ll = attn_long_lds_bytes(RG, DH);
-    const dim3 lb(64 * ATTN_LONG_WAVES), lg(grid.x, grid.z, grid.y);     // key ranges in z: the fullest ranges start first
-    if (DH == 64 && RG <= 16) hipLaunchKernelGGL((attn_long_kernel<64, 1>), lg, lb, ll, s, a);
-    else if (DH == 64) hipLaunchKernelGGL((attn_long_kernel<64, 2>), lg, lb, ll, s, a);
-    else if (RG <= 16) hipLaunchKernelGGL((attn_long_kernel<128, 1>), lg, lb, ll, s, a);
-    else hipLaunchKernelGGL((attn_long_kernel<128, 2>), lg, lb, ll, s, a);
-  } else if (DH == 32) hipLaunchKernelGGL((attn_kernel<T, 32>), grid, block, lds, s, a);
-  else if (DH == 64) hipLaunchKernelGGL((attn_kernel<T, 64>), grid, block, lds, s, a);
-  else hipLaunchKernelGGL((attn_kernel<T, 128>), grid, block, lds, s, a);
+    const int nw = (a.nsplit > 1) ? 4 : attn_mma_waves(a.cross ? a.kv_len : (m.cfg.max_len + 1) / 2);
+    const size_t ll = attn_mma_lds_bytes(RG, DH, nw);
+    const dim3 lg(grid.x, grid.z, grid.y);          // key ranges in z, the slowest index: the fullest ranges start first
+    if (DH == 64 && RG <= 16) launch_attn_mma<64, 1>(s, a, lg, nw, ll);
+    else if (DH == 64) launch_attn_mma<64, 2>(s, a, lg, nw, ll);
+    else if (RG <= 16) launch_attn_mma<128, 1>(s, a, lg, nw, ll);
+    else launch_attn_mma<128, 2>(s, a, lg, nw, ll);
+  } else if (DH == 32) launch_attn_kernel<T, 32>(s, a, grid, threads, lds);
+  else if (DH == 64) launch_attn_kernel<T, 64>(s, a, grid, threads, lds);
+  else launch_attn_kernel<T, 128>(s, a, grid, threads, lds);
   if (a.nsplit > 1) {
     const dim3 mg(a.Hkv, a.R * G, nseq);
     if (DH == 32) hipLaunchKernelGGL((attn_merge_kernel<T, 32>), mg, dim3(32), 0, s, a);
@@ -415,19 +460,53 @@ void launch_attn(hipStream_t s, const Model& m, AttnArgs a, int nseq) {
 // The attention kernel keeps up to ATTN_MAX_RG query rows in more than 64 KB of LDS.
 // Each instantiation gets the most it can ask for, ATTN_MAX_RG query rows at its own d_head (the
 // reduction buffer [16 wavefronts][rows per pass][d_head] makes d_head 64 the largest).
-constexpr size_t ATTN_STATIC_LDS = MAX_ROWS * 4 + ATTN_LDS_PAGES * 4 + 4 * 64 * 4 + ATTN_LDS_DIST;   // the kernel's __shared__ arrays
+constexpr size_t ATTN_STATIC_LDS = MAX_ROWS * 4 + 4 * 64 * 4 + ATTN_LDS_DIST;   // the kernel's __shared__ arrays
 constexpr size_t LDS_PER_CU = 160 * 1024;
+template <typename T, int DH, int TH>
+hipError_t allow_attn_lds_t() {
+  const size_t bytes = attn_lds_bytes(ATTN_MAX_RG, DH, TH);
+  if (bytes + ATTN_STATIC_LDS > LDS_PER_CU) return hipErrorInvalidValue;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, DH, TH, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, DH, TH, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  return e;
+}
 template <typename T, int DH>
 hipError_t allow_attn_lds() {
-  const size_t bytes = attn_lds_bytes(ATTN_MAX_RG, DH);
-  if (bytes + ATTN_STATIC_LDS > LDS_PER_CU) return hipErrorInvalidValue;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<T, DH>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  hipError_t e = allow_attn_lds_t<T, DH, 256>();
+  if (e == hipSuccess) e = allow_attn_lds_t<T, DH, 512>();
+  if (e == hipSuccess) e = allow_attn_lds_t<T, DH, 1024>();
+  return e;
+}
+// The matrix-core kernel with eight wavefronts, 24 query rows and d_head 128 merges through 100 KB of LDS.
+template <int DH, int NRT, int NW, int MODE>
+hipError_t allow_mma_lds() {
+  const size_t bytes = attn_mma_lds_bytes(NRT == 1 ? 16 : ATTN_MAX_RG, DH, NW);
+  static_assert(attn_mma_lds_bytes(ATTN_MAX_RG, 128, 8) <= LDS_PER_CU, "matrix-core attention: LDS budget");
+  if (bytes <= 64 * 1024) return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mma_kernel<DH, NRT, NW, MODE>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+template <int DH, int NRT, int NW>
+hipError_t allow_mma_lds_modes() {
+  hipError_t e = allow_mma_lds<DH, NRT, NW, ATTN_SELF>();
+  if (e == hipSuccess) e = allow_mma_lds<DH, NRT, NW, ATTN_SELF_BIAS>();
+  if (e == hipSuccess) e = allow_mma_lds<DH, NRT, NW, ATTN_CROSS>();
+  return e;
+}
+template <int DH>
+hipError_t allow_mma_lds_dh() {
+  hipError_t e = allow_mma_lds_modes<DH, 1, 4>();
+  if (e == hipSuccess) e = allow_mma_lds_modes<DH, 1, 8>();
+  if (e == hipSuccess) e = allow_mma_lds_modes<DH, 2, 4>();
+  if (e == hipSuccess) e = allow_mma_lds_modes<DH, 2, 8>();
+  return e;
 }
 template <typename T>
 hipError_t allow_big_lds() {
   hipError_t e = allow_attn_lds<T, 32>();
   if (e == hipSuccess) e = allow_attn_lds<T, 64>();
   if (e == hipSuccess) e = allow_attn_lds<T, 128>();
+  if (e == hipSuccess) e = allow_mma_lds_dh<64>();
+  if (e == hipSuccess) e = allow_mma_lds_dh<128>();
   return e;
 }
 
@@ -557,8 +636,9 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
         a.row_pos = q.row_pos; a.R = rw.rps; a.H = f.n_heads; a.Hkv = f.n_kv_heads; a.cross = 0; a.kv_len = 0;
         a.scale = (f.arch == SD_ARCH_T5DEC) ? 1.0f : 1.0f / sqrtf((float)f.d_head);
         a.rel_bias = m.rel_bias; a.bucket_lut = m.bucket_lut; a.rel_buckets = f.rel_buckets;
+        a.bias_by_key = m.bias_by_key; a.bias_off = f.max_len - 1;
         a.seq0 = rw.seq0; a.pt_stride = m.n_pages;
-        if (cross) { a.cross = 1; a.ck = l.cross_k; a.cv = l.cross_v; a.kv_len = f.enc_len; a.scale = 1.0f; a.rel_bias = nullptr; }
+        if (cross) { a.cross = 1; a.ck = l.cross_k; a.cv = l.cross_v; a.kv_len = f.enc_len; a.scale = 1.0f; a.rel_bias = nullptr; a.bias_by_key = nullptr; }
         // long contexts end in the merge kernel, which can leave its output in fragment order for
         // the batched O projection (no re-tile)
         if (!cross && m.attn_nsplit > 1 && n_groups > 1 && n_groups <= GEMM_WIDE_RT) { a.out_frag = m.xfrag2; produced_frag = true; }
@@ -777,6 +857,10 @@ sd_status load_model(hipStream_t s, Model& m, const sd_tensor* w, int n, std::st
       lut[rel] = b;
     }
     if (hipMemcpy(m.bucket_lut, lut.data(), lut.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess) { err = "bucket table upload"; return SD_EHIP; }
+    const int row = f.max_len + 3;                  // after rel_bias on the same stream
+    hipLaunchKernelGGL((bias_by_key_kernel<T>), dim3((unsigned)((f.n_heads * row + 255) / 256)), dim3(256), 0, s,
+                       static_cast<const T*>(m.rel_bias), m.bucket_lut, f.rel_buckets, f.max_len, f.n_heads, m.bias_by_key);
+    if (hipGetLastError() != hipSuccess) { err = "bias table"; return SD_EHIP; }
   }
   if (f.arch == SD_ARCH_GQA) {
     std::vector<float> cs((size_t)f.max_len * f.d_head);
@@ -852,8 +936,6 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
   if ((rt->max_gamma + 1) * (p_cfg->n_heads / p_cfg->n_kv_heads) > ATTN_MAX_RG ||
       2 * (q_cfg->n_heads / q_cfg->n_kv_heads) > ATTN_MAX_RG)
     return fail(nullptr, SD_EINVAL, "(max_gamma+1) x (query heads per kv head) exceeds the attention kernel's limit");
-  if ((std::max(p_cfg->max_len, q_cfg->max_len) + rt->page_size - 1) / rt->page_size > ATTN_LDS_PAGES)
-    return fail(nullptr, SD_EINVAL, "max_len / page_size exceeds the attention kernel's page-table cache");
   if (!rt->workspace || (reinterpret_cast<uintptr_t>(rt->workspace) & 255)) return fail(nullptr, SD_EINVAL, "workspace must be 256-byte aligned");
   const size_t need = sd_workspace_bytes(p_cfg, q_cfg, rt);
   if (rt->workspace_bytes < need) return fail(nullptr, SD_ENOMEM, "workspace too small: need " + std::to_string(need));
