@@ -53,8 +53,12 @@ enum { SD_ATTN_MAX_ROWS_X_GROUP = 24 };  /* the attention kernels keep (query ro
 enum {
   SD_FLAG_GRAPH   = 1,  /* replay each iteration as one hipGraph (draft loop, verify, accept) */
   SD_FLAG_PROFILE = 2,  /* record HIP events around the draft / verify / accept phases */
-  SD_FLAG_BETA    = 4   /* also compute beta_i = sum_x min(p_i(x), q_i(x)) of every guess (section 3.1)
+  SD_FLAG_BETA    = 4,  /* also compute beta_i = sum_x min(p_i(x), q_i(x)) of every guess (section 3.1)
                            in each sd_step: one more small launch; feeds sd_stats.beta_sum */
+  SD_FLAG_SCATTER_PAGES = 8  /* at load only: every sequence's page table lists its KV-cache pages back to
+                           front instead of in order.  Results are identical; it exists to show that
+                           every kernel finds its pages through the table.  sd_set_flags leaves it as
+                           it was at load. */
 };
 
 /*
@@ -226,7 +230,8 @@ const char* sd_last_error(const sd_ctx* ctx);
  * after sd_step_baseline: [batch, vocab].  host_out: host, n floats (n <= rows*vocab). */
 sd_status sd_debug_logits(sd_ctx* ctx, int32_t which, float* host_out, size_t n);
 sd_status sd_get_stats(sd_ctx* ctx, sd_stats* out);
-/* Replace the flags given at load for the following calls (captured graphs are rebuilt). */
+/* Replace the flags given at load for the following calls (captured graphs are rebuilt).
+ * SD_FLAG_SCATTER_PAGES keeps the value it had at load whatever is passed here. */
 sd_status sd_set_flags(sd_ctx* ctx, int32_t flags);
 /* Sampling options for the following sd_step / sd_step_baseline calls (host
  * struct, copied).  SD_EINVAL unless 0 < lenience <= 1, top_k >= 0,

@@ -349,6 +349,10 @@ static __global__ __launch_bounds__(THREADS) void attn_kernel(const AttnArgs a) 
 // Memory latency: the rows' positions, the first step's page entries and the queries leave
 // together; the K and V rows follow as soon as the positions (hence the context length) are
 // known; page entries of later steps are asked for a step ahead.  No page table in LDS.
+// (Computing a key's address without the table when a sequence's pages lie in order, and loading
+// the first step's rows before the context length is known - clamped to the cache's extent, rows
+// past the context zeroed on their way through LDS - was tried: 0.3 us faster at 120 keys, 0.3 us
+// slower at 60, where two of four wavefronts then pull never-written rows from cold memory.)
 // grid = (kv heads, sequences, row groups or key ranges).
 // dynamic LDS: max(NW x 32 x (d_head + 8) bf16 staging, NW x RG x (d_head + 2) floats for the merge).
 __device__ __forceinline__ bf16x8 ld_frag(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
@@ -373,7 +377,7 @@ typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // fou
 template <int DH, int NRT, int NW, int MODE>
 static __global__ __launch_bounds__(64 * NW) void attn_mma_kernel(const AttnArgs a) {
   extern __shared__ float lds[];
-  constexpr bool CROSS = MODE == ATTN_CROSS, BIAS = MODE == ATTN_SELF_BIAS;
+  constexpr bool CROSS = MODE == ATTN_CROSS, BIAS = MODE == ATTN_SELF_BIAS, TABLE = !CROSS;   // TABLE: paged keys
   constexpr int KSQ = DH / 32;                     // k-steps of the score product
   constexpr int DT = DH / 16;                      // 16-feature tiles of the output
   const int tid = threadIdx.x, lane = tid & 63;
@@ -387,7 +391,7 @@ static __global__ __launch_bounds__(64 * NW) void attn_mma_kernel(const AttnArgs
   const int R = min(a.rows_per_wg, a.R - rs);
   const int r0 = seq * a.R + rs;
   const int G = a.G, RG = R * G;
-  const int* page_table = a.page_table + (size_t)(a.seq0 + seq) * a.pt_stride;
+  const int* page_table = TABLE ? a.page_table + (size_t)(a.seq0 + seq) * a.pt_stride : nullptr;
   const int page_shift = __ffs(a.page_size) - 1, page_mask = a.page_size - 1;
   const int last_page = a.n_pages - 1;
   const int k_begin = split * a.split_keys;
@@ -396,9 +400,9 @@ static __global__ __launch_bounds__(64 * NW) void attn_mma_kernel(const AttnArgs
   // ---- positions, the first step's page entries, the queries: one round of loads ----
   int my_pos = -1;                                  // lane r: the causal limit of row r
   if (!CROSS && lane < R) my_pos = a.row_pos[r0 + lane];
-  int pg[2] = {0, 0};                               // pages of keys kb .. kb + 15 and kb + 16 .. kb + 31 of the step to load
+  int pg[2] = {0, 0};                               // TABLE: pages of keys kb .. kb + 15 and kb + 16 .. kb + 31 of the step to load
   auto ask_pages = [&](int kb, int (&out)[2]) {
-    if (CROSS) return;
+    if (!TABLE) return;
     out[0] = page_table[min(kb >> page_shift, last_page)];
     out[1] = page_table[min((kb + 16) >> page_shift, last_page)];
   };
@@ -420,7 +424,59 @@ static __global__ __launch_bounds__(64 * NW) void attn_mma_kernel(const AttnArgs
 #pragma unroll
     for (int s = 0; s < KSQ; ++s) qf[rt][s] = ok ? ld_frag(qp + s * 32) : zero_frag();
   }
+  auto row_ptr = [&](int key, int page, int which) -> const bf16* {   // which: 0 = K, 1 = V
+    if (CROSS) return static_cast<const bf16*>(which ? a.cv : a.ck) + ((size_t)hkv * a.kv_len + key) * DH;
+    return static_cast<const bf16*>(a.kv_pool) + ((((size_t)page * 2 + which) * a.Hkv + hkv) * a.page_size + (key & page_mask)) * DH;
+  };
+  // The loads of a step are issued one step ahead, into the registers the previous step has
+  // just finished with (V after its transposition at the top of the step, K after the score
+  // product), so a wavefront's load latency overlaps a whole step of its own arithmetic.
+  bf16x8 kf[2][KSQ];
+  bf16x8 vr[DH / 16];
+  constexpr int VKPL = 64 / (DH / 8);               // keys one V load of the wavefront covers
+  const int vpiece = lane % (DH / 8), vkey = lane / (DH / 8);
   int kv_len = a.kv_len;
+  int pg_last = 0;                                  // TABLE: page of the last key, what loads past the range re-read
+  // TABLE: a step's 32 keys start at a multiple of 32 and pages hold a multiple of 16 keys, so keys
+  // 0..15 of the step are consecutive slots of one page and keys 16..31 of one page: two page
+  // entries per step.  (Past the range kb is clamped and every lane re-reads the last key itself.)
+  auto halves = [&](int kb, int which, const bf16* (&half)[2], int& nk) {
+    const bool in = kb < kv_len;
+    const int kc = in ? kb : max(kv_len - 1, 0);
+    nk = max(min(32, kv_len - kc), 1);
+    const bool in1 = kb + 16 < kv_len;
+    half[0] = row_ptr(kc, in ? pg[0] : pg_last, which);
+    half[1] = row_ptr(in1 ? kb + 16 : max(kv_len - 1, 0), in1 ? pg[1] : pg_last, which);
+  };
+  auto load_k = [&](int kb) {
+    const bf16* half[2] = {nullptr, nullptr}; int nk = 0;
+    if (TABLE) halves(kb, 0, half, nk);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      const bf16* kp;
+      if (TABLE) {
+        const int kk = min(kt * 16 + j, nk - 1);
+        kp = ((kk < 16) ? half[0] + kk * DH : half[1] + (kk - 16) * DH) + kq * 8;
+      } else {
+        kp = row_ptr(min(kb + kt * 16 + j, a.kv_len - 1), 0, 0) + kq * 8;
+      }
+#pragma unroll
+      for (int s = 0; s < KSQ; ++s) kf[kt][s] = ld_frag(kp + s * 32);      // the four quarters read 64 contiguous bytes
+    }
+  };
+  auto load_v = [&](int kb) {                       // load c: VKPL keys, each row read by DH/8 consecutive lanes
+    const bf16* half[2] = {nullptr, nullptr}; int nk = 0;
+    if (TABLE) halves(kb, 1, half, nk);
+#pragma unroll
+    for (int c = 0; c < DH / 16; ++c) {
+      if (TABLE) {
+        const int kk = min(c * VKPL + vkey, nk - 1);
+        vr[c] = ld_frag(((kk < 16) ? half[0] + kk * DH : half[1] + (kk - 16) * DH) + vpiece * 8);
+      } else {
+        vr[c] = ld_frag(row_ptr(min(kb + c * VKPL + vkey, a.kv_len - 1), 0, 1) + vpiece * 8);
+      }
+    }
+  };
   int pos_min = 0x7fffffff;                         // a step whose keys all lie at or below it needs no mask
   if (!CROSS) {
     kv_len = wave_max(my_pos) + 1;
@@ -434,12 +490,7 @@ static __global__ __launch_bounds__(64 * NW) void attn_mma_kernel(const AttnArgs
     }
     kv_len = min(kv_len, k_begin + a.split_keys);
   }
-  int pg_last = 0;                                  // page of the last key: what loads past the range re-read
-  if (!CROSS) pg_last = page_table[min(max(kv_len - 1, 0) >> page_shift, last_page)];
-  auto row_ptr = [&](int key, int page, int which) -> const bf16* {   // which: 0 = K, 1 = V
-    if (CROSS) return static_cast<const bf16*>(which ? a.cv : a.ck) + ((size_t)hkv * a.kv_len + key) * DH;
-    return static_cast<const bf16*>(a.kv_pool) + ((((size_t)page * 2 + which) * a.Hkv + hkv) * a.page_size + (key & page_mask)) * DH;
-  };
+  if (TABLE) pg_last = page_table[min(max(kv_len - 1, 0) >> page_shift, last_page)];
 
   float m_run[NRT], l_run[NRT];
   f32x4 o[DT][NRT];
@@ -451,46 +502,8 @@ static __global__ __launch_bounds__(64 * NW) void attn_mma_kernel(const AttnArgs
   }
   // V tile of the step, row-major with padded rows: [32 keys][DH + 8] bf16.  The 16-byte writes of
   // a load and the 2-byte reads of a fragment (16 features x 4 key groups) are both conflict-free.
-  constexpr int VRS = DH + 8, VKPL = 64 / (DH / 8);
+  constexpr int VRS = DH + 8;
   unsigned short* vt = reinterpret_cast<unsigned short*>(lds) + (size_t)wave * 32 * VRS;
-  const int vpiece = lane % (DH / 8), vkey = lane / (DH / 8);
-
-  // The loads of a step are issued one step ahead, into the registers the previous step has
-  // just finished with (V after its transposition at the top of the step, K after the score
-  // product), so a wavefront's load latency overlaps a whole step of its own arithmetic.
-  bf16x8 kf[2][KSQ];
-  bf16x8 vr[DH / 16];
-  // A step's 32 keys start at a multiple of 32 and pages hold a multiple of 16 keys, so keys 0..15
-  // of the step are consecutive slots of one page and keys 16..31 of one page: two page entries
-  // per step.  (Past the range kb is clamped and every lane re-reads the last key itself.)
-  auto halves = [&](int kb, int which, const bf16* (&half)[2], int& nk) {
-    const bool in = kb < kv_len;
-    const int kc = in ? kb : max(kv_len - 1, 0);
-    nk = max(min(32, kv_len - kc), 1);
-    const bool in1 = kb + 16 < kv_len;
-    half[0] = row_ptr(kc, in ? pg[0] : pg_last, which);
-    half[1] = row_ptr(in1 ? kb + 16 : max(kv_len - 1, 0), in1 ? pg[1] : pg_last, which);
-  };
-  auto load_k = [&](int kb) {
-    const bf16* half[2]; int nk;
-    halves(kb, 0, half, nk);
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      const int kk = min(kt * 16 + j, nk - 1);
-      const bf16* kp = ((kk < 16) ? half[0] + kk * DH : half[1] + (kk - 16) * DH) + kq * 8;
-#pragma unroll
-      for (int s = 0; s < KSQ; ++s) kf[kt][s] = ld_frag(kp + s * 32);      // the four quarters read 64 contiguous bytes
-    }
-  };
-  auto load_v = [&](int kb) {                       // load c: VKPL keys, each row read by DH/8 consecutive lanes
-    const bf16* half[2]; int nk;
-    halves(kb, 1, half, nk);
-#pragma unroll
-    for (int c = 0; c < DH / 16; ++c) {
-      const int kk = min(c * VKPL + vkey, nk - 1);
-      vr[c] = ld_frag(((kk < 16) ? half[0] + kk * DH : half[1] + (kk - 16) * DH) + vpiece * 8);
-    }
-  };
   // bias of this lane's keys kb + kt*16 + kq*4 + 0..3 for row rt: table entries (key - pos) + bias_off ..,
   // clamped where every one of them is masked anyway (key > pos)
   f32x4 bz[2][NRT];
@@ -504,7 +517,8 @@ static __global__ __launch_bounds__(64 * NW) void attn_mma_kernel(const AttnArgs
         bz[kt][rt] = *reinterpret_cast<const f32x4_a4*>(brow[rt] + i0);
       }
   };
-  if (kb0 < kv_len) { load_k(kb0); load_v(kb0); load_bias(kb0); }   // a wavefront without keys loads nothing
+  if (kb0 < kv_len) { load_k(kb0); load_v(kb0); }   // a wavefront without keys loads nothing
+  if (kb0 < kv_len) load_bias(kb0);
   ask_pages(kb0 + NW * 32, pg);
 
   for (int kb = kb0; kb < kv_len; kb += NW * 32) {

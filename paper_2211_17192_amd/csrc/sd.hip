@@ -64,6 +64,7 @@ struct Model {
   int batch = 1;               // sequences; each owns n_pages pages of every layer's pool
   int rows_cap = MAX_ROWS;     // activation rows: one group of MAX_ROWS rows per sequence at most
   int* page_table = nullptr;   // [batch][n_pages]
+  bool pages_in_order = true;  // sequence b's table is b * n_pages + 0, 1, 2, ...; false (SD_FLAG_SCATTER_PAGES): back to front
   int *row_seq = nullptr, *logit_row = nullptr;   // [rows_cap], written by the embedding kernel
   void* xfrag = nullptr;       // activations of one wide GEMM in fragment order
   float* wide_partial = nullptr;   // partial tiles of the K chunks of one split GEMM
@@ -839,8 +840,11 @@ sd_status load_model(hipStream_t s, Model& m, const sd_tensor* w, int n, std::st
   }
 #undef PUT
   // host-built tables
-  std::vector<int> pt((size_t)m.batch * m.n_pages);         // sequence b owns pages b * n_pages .. of every pool
-  for (size_t i = 0; i < pt.size(); ++i) pt[i] = (int)i;
+  // sequence b owns pages b * n_pages .. of every pool: in order, or (m.pages_in_order false) back to front
+  std::vector<int> pt((size_t)m.batch * m.n_pages);
+  for (int b = 0; b < m.batch; ++b)
+    for (int i = 0; i < m.n_pages; ++i)
+      pt[(size_t)b * m.n_pages + i] = b * m.n_pages + (m.pages_in_order ? i : m.n_pages - 1 - i);
   if (hipMemcpy(m.page_table, pt.data(), pt.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess) { err = "page table upload"; return SD_EHIP; }
   if (f.arch == SD_ARCH_T5DEC) {
     // causal distance -> bucket: one distance per bucket in the first half,
@@ -972,6 +976,7 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
       allow_wide_lds<bf16>() != hipSuccess || allow_wide_lds<float>() != hipSuccess)
     return bail(SD_EHIP, "cannot raise the LDS limit");
   std::string err;
+  c->p.pages_in_order = c->q.pages_in_order = (rt->flags & SD_FLAG_SCATTER_PAGES) == 0;
   sd_status st = (p_cfg->dtype == SD_BF16) ? load_model<bf16>(c->stream, c->p, p_w, n_p, err)
                                            : load_model<float>(c->stream, c->p, p_w, n_p, err);
   if (st != SD_OK) return bail(st, "Mp: " + err);
@@ -1208,7 +1213,8 @@ extern "C" sd_status sd_debug_logits(sd_ctx* c, int32_t which, float* host_out, 
 
 extern "C" sd_status sd_set_flags(sd_ctx* c, int32_t flags) {
   if (!c) return SD_EINVAL;
-  if (flags & ~(SD_FLAG_GRAPH | SD_FLAG_PROFILE | SD_FLAG_BETA)) return fail(c, SD_EINVAL, "unknown flag");
+  if (flags & ~(SD_FLAG_GRAPH | SD_FLAG_PROFILE | SD_FLAG_BETA | SD_FLAG_SCATTER_PAGES)) return fail(c, SD_EINVAL, "unknown flag");
+  flags = (flags & ~SD_FLAG_SCATTER_PAGES) | (c->rt.flags & SD_FLAG_SCATTER_PAGES);    // the cache layout is fixed at load
   if ((flags ^ c->rt.flags) & SD_FLAG_BETA) {            // the captured iteration changes
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     for (auto& g : c->graphs) if (g) { hipGraphExecDestroy(g); g = nullptr; }

@@ -10,8 +10,17 @@ from paper_2211_17192_amd import synth
 W_STD = {"f32": 0.1, "bf16": 0.06}
 
 
-def small_cfg(arch, dtype):
+def small_cfg(arch, dtype, d_head=32):
+    """d_head 32: two heads of 32 (GQA: four); d_head 64: two heads of 64 (GQA: four query, two KV heads),
+    the head size the bf16 matrix-core attention kernel takes."""
     kw = dict(dtype=dtype, logit_scale=4.0)
+    if d_head == 64:
+        if arch == T.GPT:
+            return synth.model_cfg(T.GPT, 3, 128, 2, 128, 512, 160, **kw)
+        if arch == T.T5DEC:
+            return synth.model_cfg(T.T5DEC, 3, 128, 2, 96, 512, 160, enc_len=72, norm_eps=1e-6, **kw)
+        return synth.model_cfg(T.GQA, 3, 128, 4, 160, 512, 160, d_head=64, n_kv_heads=2, **kw)
+    assert d_head == 32
     if arch == T.GPT:
         return synth.model_cfg(T.GPT, 3, 64, 2, 128, 512, 160, **kw)
     if arch == T.T5DEC:
@@ -19,10 +28,10 @@ def small_cfg(arch, dtype):
     return synth.model_cfg(T.GQA, 3, 128, 4, 160, 512, 160, d_head=32, n_kv_heads=2, **kw)
 
 
-def small_pair(arch, dtype, seed=3, w_std=None):
+def small_pair(arch, dtype, seed=3, w_std=None, d_head=32):
     """(cfg_p, w_p, cfg_q, w_q, enc_p, enc_q): a 3-layer target of the given block type and its
     1-layer noisy copy as the approximation model."""
-    cfg = small_cfg(arch, dtype)
+    cfg = small_cfg(arch, dtype, d_head)
     w = synth.random_weights(cfg, seed, w_std=W_STD[dtype] if w_std is None else w_std)
     cfg_q, w_q = synth.truncated_noisy_copy(cfg, w, 1, seed + 50, 0.02)
     enc_p = enc_q = None

@@ -200,6 +200,68 @@ def test_small_pairs_all_block_types(arch, dtype):
     dec.close()
 
 
+@pytest.mark.parametrize("arch", [T.GPT, T.T5DEC, T.GQA])
+def test_small_bf16_pairs_with_64_wide_heads_take_the_matrix_core_attention(arch):
+    """bf16 with d_head 64 runs self- and cross-attention on the matrix cores at every context
+    length (T5DEC: with the position bias read by distance and 72 encoder keys, i.e. two full
+    32-key steps and a ragged third; GQA: two query heads per KV head).  Same checks as the other
+    small pairs: logits against the oracle's bf16 model and its unrounded model, decisions
+    against the logits, plain greedy decoding identical to speculative greedy decoding."""
+    # unscaled scores over 64-wide heads: at the usual weight scale of 0.06 the oracle's own bf16 and
+    # unrounded T5DEC models are 9e-2 apart, at 0.04 they are 1.4e-2 apart (measured with the oracle alone)
+    cfg_p, w_p, cfg_q, w_q, enc_p, enc_q = small_pair(arch, "bf16", d_head=64, w_std=0.04 if arch == T.T5DEC else None)
+    sp, sq = oracle_models(cfg_p, w_p, cfg_q, w_q, enc_p, enc_q)
+    un = oracle_models(unrounded(cfg_p), w_p, unrounded(cfg_q), w_q, enc_p, enc_q)
+    prompt = [int(t) for t in synth.random_tokens(22, 70, cfg_p["vocab"])]
+    enc = (None if enc_p is None else enc_p.cuda(), None if enc_q is None else enc_q.cuda())
+    dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=7, flags=1)
+    for temperature, gamma, useed in ((1.0, 5, 14), (0.7, 7, 16)):
+        dec.reset(); dec.prefill(prompt, *enc)
+        toks, tol, worst, mean_n = run_pair(dec, sp, sq, prompt, 24, gamma, temperature, useed, "bf16", False, un)
+        print(f"arch {arch} bf16 d_head 64 T={temperature} gamma={gamma}: worst logit error {worst}, tolerated {tol}, mean n {mean_n:.2f}")
+        assert tol["accept"] + tol["draw"] <= 1, tol
+    dec.reset(); dec.prefill(prompt, *enc)
+    plain = [dec.step_baseline(0.0) for _ in range(20)]
+    dec.reset(); dec.prefill(prompt, *enc)
+    spec = []
+    while len(spec) < 20:
+        spec += dec.step(4, 0.0, None, prefix=prompt + spec)[1]
+    assert spec[:20] == plain
+    dec.close()
+
+
+@pytest.mark.parametrize("arch,dtype,d_head", [(T.T5DEC, "bf16", 64), (T.GQA, "bf16", 64), (T.GPT, "bf16", 32), (T.GQA, "f32", 32)])
+def test_scattered_kv_pages_give_identical_results(arch, dtype, d_head):
+    """SD_FLAG_SCATTER_PAGES lists every sequence's cache pages back to front in its page table:
+    the QKV epilogue and both attention kernels must find each page through the table.  Tokens
+    and logits are bit-identical to the in-order layout, over contexts of several pages, for two
+    sequences where the block type allows them."""
+    from paper_2211_17192_amd import binding
+    if arch == T.T5DEC:
+        batch = 1
+    else:
+        batch = 2
+    cfg_p, w_p, cfg_q, w_q, enc_p, enc_q = small_pair(arch, dtype, d_head=d_head, w_std=0.04 if arch == T.T5DEC else None)
+    enc = (None if enc_p is None else enc_p.cuda(), None if enc_q is None else enc_q.cuda())
+    prompts = [synth.random_tokens(31 + b, 45 + 13 * b, cfg_p["vocab"]) for b in range(batch)]
+    gamma = 4
+    urows = synth.uniform_stream(9, 12 * batch * (2 * gamma + 1)).reshape(12, -1)
+    runs = []
+    for flags in (binding.SD_FLAG_GRAPH, binding.SD_FLAG_GRAPH | binding.SD_FLAG_SCATTER_PAGES):
+        dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=flags, batch=batch)
+        for b in range(batch):
+            dec.prefill(prompts[b], *enc, row=b) if batch > 1 else dec.prefill(prompts[b], *enc)
+        out = []
+        for it in range(12):
+            res = dec.step(gamma, 1.0, urows[it].reshape(batch, -1) if batch > 1 else urows[it])
+            out.append((res, dec.logits(0, batch * (gamma + 1)).copy(), dec.logits(1, batch * gamma).copy()))
+        runs.append(out)
+        dec.close()
+    for it, (a, b) in enumerate(zip(*runs)):
+        assert a[0] == b[0], (it, a[0], b[0])
+        assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2]), it
+
+
 def test_one_token_prefix_and_baseline_identity():
     """Decoder that starts from a single start token (the encoder-decoder case):
     the first draft step has a padding row.  Also: argmax speculative decoding
