@@ -99,6 +99,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a 256 MiB device-to-device copy (reference for the profiler's byte counters)")
+    ap.add_argument("--counters-pass", action="store_true",
+                    help="t5xxl: load the pair, run --warmup + --steps iterations at the first of --gammas (and the "
+                         "copy of --calibrate), print a short line and stop: the pass `rocprofv3 --pmc` wraps, which "
+                         "serialises every dispatch and would take many minutes over the whole benchmark")
     ap.add_argument("--ctx", type=int, default=2048, help="gqa8b-batch16: tokens of context per sequence")
     ap.add_argument("--workload", type=str, default="t5xxl", choices=["t5xxl", "gqa8b-batch16", "sampler", "gpt97m"],
                     help="t5xxl: the headline configuration (default); sampler: the isolated accept / resample "
@@ -131,6 +135,25 @@ def main():
     def restart():
         dec.reset()
         dec.prefill([0], enc_p, enc_q)
+
+    if args.counters_pass:
+        gamma = gammas[0]
+        urows = synth.uniform_stream(100 + gamma, 1024 * (2 * gamma + 1)).reshape(1024, -1)
+        restart()
+        tokens = 0
+        for i in range(args.warmup + args.steps):
+            n, _ = dec.step(gamma, TEMPERATURE, urows[i])
+            tokens += n + 1
+            if i % 4 == 0:
+                print(f"counters pass: iteration {i}", file=sys.stderr, flush=True)
+        if args.calibrate:
+            src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+            dst = torch.empty_like(src)
+            for _ in range(4):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+        print(json.dumps({"counters_pass": True, "gamma": gamma, "iterations": args.warmup + args.steps, "tokens": tokens}))
+        return
 
     per_gamma = {}
 
