@@ -375,7 +375,9 @@ constexpr int ATTN_SELF = 0, ATTN_SELF_BIAS = 1, ATTN_CROSS = 2;
 typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // four floats at any 4-byte boundary
 
 template <int DH, int NRT, int NW, int MODE>
-static __global__ __launch_bounds__(64 * NW) void attn_mma_kernel(const AttnArgs a) {
+// (four wavefronts: capped at 128 registers so that two workgroups share a CU, which the long
+// contexts' key ranges need: one workgroup per CU took two rounds there)
+static __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mma_kernel(const AttnArgs a) {
   extern __shared__ float lds[];
   constexpr bool CROSS = MODE == ATTN_CROSS, BIAS = MODE == ATTN_SELF_BIAS, TABLE = !CROSS;   // TABLE: paged keys
   constexpr int KSQ = DH / 32;                     // k-steps of the score product
