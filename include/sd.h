@@ -44,10 +44,10 @@ typedef enum { SD_F32 = 0, SD_BF16 = 1 } sd_dtype;
 enum { SD_ARCH_GPT = 0, SD_ARCH_T5DEC = 1, SD_ARCH_GQA = 2 };
 enum { SD_MAX_GAMMA = 15 };       /* a sequence contributes at most SD_MAX_GAMMA+1 rows to a forward */
 enum { SD_MAX_BATCH = 64 };       /* sequences decoded together */
-enum { SD_ATTN_MAX_ROWS_X_GROUP = 24 };  /* the attention kernels keep (query rows) x (query heads per KV head)
-                                     <= 24 rows per KV head: sd_load_models refuses (max_gamma + 1) x
+enum { SD_ATTN_MAX_ROWS_X_GROUP = 32 };  /* the attention kernels keep (query rows) x (query heads per KV head)
+                                     <= 32 rows per KV head: sd_load_models refuses (max_gamma + 1) x
                                      (n_heads / n_kv_heads) beyond it (SD_EINVAL), e.g. 4 query heads per
-                                     KV head allow max_gamma <= 5 */
+                                     KV head allow max_gamma <= 7 */
 
 /* Flags of sd_runtime_cfg.flags */
 enum {

@@ -33,7 +33,7 @@ namespace sd {
 
 
 constexpr int ATTN_LDS_DIST = 4096;        // causal distances whose bias bucket is cached in LDS
-constexpr int ATTN_MAX_RG = 24;            // query rows x heads per kv head that fit in LDS
+constexpr int ATTN_MAX_RG = 32;            // query rows x heads per kv head: two 16-row MFMA tiles; 150 KB of LDS in attn_kernel at d_head 64
 
 // LPK lanes per key and DP head-dim elements per lane in the score phase (a workgroup of THREADS
 // threads takes THREADS / LPK keys per block); KPT consecutive keys per thread in the P*V phase;

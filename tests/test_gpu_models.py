@@ -721,19 +721,20 @@ def test_long_context_spans_several_key_blocks(d_head, ctx):
 
 
 def test_fp32_long_context_with_the_most_rows_per_kv_head():
-    """d_head 64 with 4 query heads per KV head at gamma = 5 in a long (key-range) context: 24
-    (row, head) pairs per KV head in one workgroup, the attention kernel's largest LDS request
-    (its reduction buffer is biggest at d_head 64).  fp32, against the oracle."""
+    """d_head 64 with 4 query heads per KV head at gamma = 7 in a long (key-range) context: 32
+    (row, head) pairs per KV head in one workgroup, the most the kernels take and the attention
+    kernel's largest LDS request (its reduction buffer is biggest at d_head 64).  fp32, against
+    the oracle."""
     cfg = synth.model_cfg(T.GQA, 2, 8 * 64, 8, 256, 512, 1100 + 64, d_head=64, n_kv_heads=2, dtype="f32", logit_scale=4.0)
     w = synth.random_weights(cfg, 9, w_std=0.1)
     cfg_q, w_q = synth.truncated_noisy_copy(cfg, w, 1, 59, 0.02)
-    gamma = 5
+    gamma = 7
     dec = make_decoder(cfg, w, cfg_q, w_q, max_gamma=gamma, flags=1)
     sp, sq = oracle_models(cfg, w, cfg_q, w_q)
     prompt = synth.random_tokens(73, 1100, cfg["vocab"])
     dec.prefill(prompt)
     toks, tol, worst, _ = run_pair(dec, sp, sq, prompt, 10, gamma, 1.0, 43, "f32", False)
-    print(f"fp32 d_head 64, 8/2 heads, gamma 5, context 1100: worst logit error {worst}, tolerated {tol}")
+    print(f"fp32 d_head 64, 8/2 heads, gamma 7, context 1100: worst logit error {worst}, tolerated {tol}")
     assert tol["accept"] + tol["draw"] <= 1
     dec.close()
 
@@ -771,14 +772,14 @@ def test_single_row_prefill_does_not_clear_the_other_rows_stale_draft_caches():
 
 @pytest.mark.parametrize("d_head,n_heads,n_kv,gamma,ctx,batch", [(128, 8, 2, 4, 1500, 2), (64, 4, 2, 3, 1100, 2),
                                                                  (64, 8, 2, 5, 1200, 2), (128, 2, 2, 3, 1300, 2),
-                                                                 (64, 4, 2, 4, 1100, 5)])
+                                                                 (64, 4, 2, 4, 1100, 5), (128, 8, 2, 7, 1200, 2)])
 def test_long_context_bf16_matrix_core_attention(d_head, n_heads, n_kv, gamma, ctx, batch):
     """bf16 models with contexts beyond 1024 positions take the matrix-core attention kernel
     (key ranges over workgroups, four wavefronts per range, merge).  (gamma+1) x (query heads per
-    kv head) = 20, 8, 24 (the most the kernels take) and 4 rows per kv head; two sequences of
+    kv head) = 20, 8, 24, 4, 10 and 32 (the most the kernels take); two sequences of
     different length, so ranges are full, ragged and empty; against the oracle.  The same
     sequence decoded alone must give bit-identical logits: a row does not see its neighbours.
-    The last case has five sequences (25 verify rows in two slabs): the batched GEMMs, whose O
+    The fifth case has five sequences (25 verify rows in two slabs): the batched GEMMs, whose O
     projection reads the merge kernel's output in fragment order."""
     cfg = synth.model_cfg(T.GQA, 2, n_heads * d_head, n_heads, 256, 512, ctx + 64, d_head=d_head, n_kv_heads=n_kv,
                           dtype="bf16", logit_scale=4.0)
