@@ -402,42 +402,107 @@ __device__ __forceinline__ int icdf_regs(const float4 (&vp)[SAMPLE_REG_F4], cons
 
 // ---------------------------------------------------------------------------
 // Draw one token from one logits row: x_i ~ q_i of the draft loop, or the
-// plain-decoding draw t ~ p.  One workgroup.
+// plain-decoding draw t ~ p.
 //   mode 0: store the token as guess number `slot` (st->x[slot])
 //   mode 1: commit it (standard decoding): len += 1
+// Several sequences: sequence b reads the row at logits + b * seq_stride (floats) and uses
+// prm[b], st[b].
 // ---------------------------------------------------------------------------
-// Several sequences: grid = sequences; sequence b reads the row at logits + b * seq_stride
-// (floats) and uses prm[b], st[b].
-static __global__ __launch_bounds__(SAMPLE_THREADS) void sample_row_kernel(
+// The draw is spread over SAMPLE_SPLIT workgroups per row.  One workgroup is bound by its own
+// instruction stream (32 exponentials per thread, twice, and the fp64 weights: 8.5 us on one CU for
+// a 32128-entry row), so here every workgroup finds the row's maximum itself (a cheap pass over the
+// whole row), then takes one register slice of the row: chunks w * 16 .. w * 16 + 15 for workgroup
+// w, one wavefront per 256-entry chunk as in icdf_regs.  The chunk totals go to `tot`
+// ([sequence][SAMPLE_MAX_CHUNKS] doubles); the workgroup that arrives last (ticket: one counter
+// per sequence, SAMPLE_COUNTER_STRIDE words apart, zero before and after) scans them and walks
+// the chunk that holds u * total.  The weights are exp((z - m) / T) without the division by
+// their sum: both sides of "cumulative weight > u * total" carry the same factor.
+// Argmax sampling, top-k / nucleus and rows that do not fit the registers are left to workgroup 0,
+// which then does the whole row (statistics and draw from registers, one read of the row); the others leave at once.  grid = (SAMPLE_SPLIT, sequences).
+constexpr int SAMPLE_SPLIT = SAMPLE_REG_F4;
+
+__device__ __forceinline__ void commit_draw(SeqState* st, int mode, int slot, int tok) {
+  if (mode == 0) {
+    st->x[slot] = tok;
+  } else {
+    st->prev_tok = st->last_tok;
+    st->last_tok = tok;
+    st->len += 1;
+    st->n = 0;
+    st->out[0] = tok;
+  }
+}
+
+static __global__ __launch_bounds__(SAMPLE_THREADS) void sample_row_split_kernel(
     const float* __restrict__ logits, int V, const StepParams* __restrict__ prm, int uniform_idx,
-    SeqState* __restrict__ st, int mode, int slot, size_t seq_stride) {
+    SeqState* __restrict__ st, int mode, int slot, size_t seq_stride, double* __restrict__ tot,
+    unsigned int* __restrict__ ticket) {
   __shared__ SampleSmem sm;
-  logits += (size_t)blockIdx.x * seq_stride;
-  prm += blockIdx.x;
-  st += blockIdx.x;
+  const int w = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  logits += (size_t)blockIdx.y * seq_stride;
+  prm += blockIdx.y;
+  st += blockIdx.y;
+  tot += (size_t)blockIdx.y * SAMPLE_MAX_CHUNKS;
+  ticket += (size_t)blockIdx.y * SAMPLE_COUNTER_STRIDE;
   const float T = prm->temperature;
   const bool greedy = (T == 0.0f);
   const float invT = greedy ? 1.0f : 1.0f / T;
-  int tok;
-  if (row_fits_regs(logits, V)) {            // one read of the row: statistics and draw from registers
+  const bool filtered = prm->top_k > 0 || (prm->top_p > 0.0f && prm->top_p < 1.0f);
+  if (greedy || filtered || !row_fits_regs(logits, V)) {      // uniform over the grid's workgroups of this row
+    if (w != 0) return;
+    int tok;
+    if (row_fits_regs(logits, V)) {
+      float4 v[SAMPLE_REG_F4];
+      load_row_regs(logits, V, v);
+      const RowStat rs = row_stats_regs(v, invT, greedy, sm, prm->top_k, prm->top_p, V);
+      tok = greedy ? rs.arg : icdf_regs(v, rs, v, rs, false, invT, V, prm->uniforms[uniform_idx], sm);
+    } else {
+      const RowStat rs = row_stats(logits, V, invT, greedy, sm);
+      tok = greedy ? rs.arg : icdf_row(logits, rs, nullptr, rs, invT, V, prm->uniforms[uniform_idx], sm);
+    }
+    if (tid == 0) commit_draw(st, mode, slot, tok);
+    return;
+  }
+  const float4* z4 = reinterpret_cast<const float4*>(logits);
+  const int n4 = V >> 2, nchunks = (V + SAMPLE_CHUNK - 1) / SAMPLE_CHUNK;
+  const float4 pad = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+  // the row's maximum, and this workgroup's slice (float4 number w * 1024 + tid: lane-slice `lane` of chunk w * 16 + wave)
+  float m = -INFINITY;
+  float4 mine = pad;
+  {
     float4 v[SAMPLE_REG_F4];
     load_row_regs(logits, V, v);
-    const RowStat rs = row_stats_regs(v, invT, greedy, sm, prm->top_k, prm->top_p, V);
-    tok = greedy ? rs.arg : icdf_regs(v, rs, v, rs, false, invT, V, prm->uniforms[uniform_idx], sm);
-  } else {
-    const RowStat rs = row_stats(logits, V, invT, greedy, sm);
-    tok = greedy ? rs.arg : icdf_row(logits, rs, nullptr, rs, invT, V, prm->uniforms[uniform_idx], sm);
-  }
-  if (threadIdx.x == 0) {
-    if (mode == 0) {
-      st->x[slot] = tok;
-    } else {
-      st->prev_tok = st->last_tok;
-      st->last_tok = tok;
-      st->len += 1;
-      st->n = 0;
-      st->out[0] = tok;
+#pragma unroll
+    for (int it = 0; it < SAMPLE_REG_F4; ++it) {
+      m = fmaxf(m, fmaxf(fmaxf(v[it].x, v[it].y), fmaxf(v[it].z, v[it].w)));
+      if (it == w) mine = v[it];
     }
+  }
+  m = block_reduce(m, sm.redf, OpMaxF(), -INFINITY);
+  const int c = w * (SAMPLE_THREADS / 64) + wave;
+  {
+    const double t = wave_sum(((double)exp_scaled(mine.x, m, invT, -INFINITY) + (double)exp_scaled(mine.y, m, invT, -INFINITY)) +
+                              ((double)exp_scaled(mine.z, m, invT, -INFINITY) + (double)exp_scaled(mine.w, m, invT, -INFINITY)));
+    if (lane == 0 && c < nchunks) tot[c] = t;
+  }
+  if (!last_block_arrives(ticket, SAMPLE_SPLIT, &sm.flag)) return;
+  for (int i = tid; i < nchunks; i += SAMPLE_THREADS) sm.ctot[i] = tot[i];
+  __syncthreads();
+  const float u = prm->uniforms[uniform_idx];
+  if (wave == 0) scan_chunk_totals(nchunks, u, sm);
+  __syncthreads();
+  if (wave == 0) {
+    const double total = sm.total;
+    const int chunk = sm.chunk;
+    const bool fallback = chunk < 0;            // threshold not reached by round-off
+    const int cc = fallback ? (-1 - chunk) : chunk;
+    const int i4 = cc * (SAMPLE_CHUNK / 4) + lane;
+    const float4 t4 = z4[min(i4, n4 - 1)];
+    const float4 z = (i4 < n4) ? t4 : pad;
+    const double wv[4] = {(double)exp_scaled(z.x, m, invT, -INFINITY), (double)exp_scaled(z.y, m, invT, -INFINITY),
+                          (double)exp_scaled(z.z, m, invT, -INFINITY), (double)exp_scaled(z.w, m, invT, -INFINITY)};
+    const int tok = pick_in_chunk(wv, i4 * 4, V, fallback, (double)u * total, sm.before);
+    if (lane == 0) commit_draw(st, mode, slot, tok);
   }
 }
 

@@ -190,6 +190,8 @@ struct sd_ctx {
   float *p_logits = nullptr, *q_logits = nullptr;
   RowStat* d_stats = nullptr;
   unsigned int* d_counter = nullptr;
+  double* d_draw_tot = nullptr;          // sample_row_split_kernel: chunk totals [batch][SAMPLE_MAX_CHUNKS]
+  unsigned int* d_draw_ticket = nullptr; // and its tickets, SAMPLE_COUNTER_STRIDE words per sequence
   SeqState* h_state = nullptr;       // pinned
   StepParams* h_params = nullptr;    // pinned
   int batch = 1;
@@ -238,6 +240,8 @@ void plan_ctx(Arena& A, sd_ctx& c, const sd_model_cfg& pc, const sd_model_cfg& q
   c.q_logits = static_cast<float*>(A.take(B * rt.max_gamma * pc.vocab * sizeof(float)));         // [seq][gamma][V]
   c.d_stats = static_cast<RowStat*>(A.take(B * (2 * SD_MAX_GAMMA + 1) * sizeof(RowStat)));
   c.d_counter = static_cast<unsigned int*>(A.take(B * SAMPLE_COUNTER_STRIDE * sizeof(unsigned int)));
+  c.d_draw_tot = static_cast<double*>(A.take(B * SAMPLE_MAX_CHUNKS * sizeof(double)));
+  c.d_draw_ticket = static_cast<unsigned int*>(A.take(B * SAMPLE_COUNTER_STRIDE * sizeof(unsigned int)));
   c.hist_stride = pc.max_len;
   c.d_hist = static_cast<int*>(A.take(B * (size_t)pc.max_len * sizeof(int)));
 }
@@ -715,6 +719,12 @@ void cross_kv(sd_ctx* c, Model& m, const void* enc) {
       }
 }
 
+// One draw per sequence from the row at logits + b * seq_stride (mode 0: guess number `slot`; 1: commit).
+void launch_draw(sd_ctx* c, const float* logits, int uniform_idx, int mode, int slot, size_t seq_stride) {
+  hipLaunchKernelGGL(sample_row_split_kernel, dim3(SAMPLE_SPLIT, c->batch), dim3(SAMPLE_THREADS), 0, c->stream, logits,
+                     c->p.cfg.vocab, c->d_params, uniform_idx, c->d_state, mode, slot, seq_stride, c->d_draw_tot, c->d_draw_ticket);
+}
+
 // The launch sequence of one run of Algorithm 1 for every sequence (everything between the
 // upload of the step parameters and the download of the states).
 void enqueue_step(sd_ctx* c, int gamma, bool profile) {
@@ -731,8 +741,7 @@ void enqueue_step(sd_ctx* c, int gamma, bool profile) {
                          c->draft_row_of, c->draft_rows, V, c->d_state, i, c->q_logits + (size_t)i * V, (size_t)gamma * V);
     else if (i == 0) forward_any(c, c->q, Rows{ROWS_DRAFT_FIRST, 0, 2, 0, 0, B, gamma}, c->q_logits);
     else forward_any(c, c->q, Rows{ROWS_DRAFT_NEXT, i, 1, 0, 0, B, gamma}, c->q_logits);
-    hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, s, c->q_logits + (size_t)i * V, V,
-                       c->d_params, i, c->d_state, 0, i, (size_t)gamma * V);
+    launch_draw(c, c->q_logits + (size_t)i * V, i, 0, i, (size_t)gamma * V);
   }
   if (profile) hipEventRecord(c->ev[1], s);
   // p_1..p_{gamma+1} in one forward
@@ -760,8 +769,7 @@ void enqueue_step(sd_ctx* c, int gamma, bool profile) {
 void enqueue_baseline(sd_ctx* c) {
   const int V = c->p.cfg.vocab, B = c->batch;
   forward_any(c, c->p, Rows{ROWS_BASELINE, 0, 1, 0, 0, B, 0}, c->p_logits);
-  hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
-                     c->d_params, 0, c->d_state, 1, 0, (size_t)V);
+  launch_draw(c, c->p_logits, 0, 1, 0, (size_t)V);
   if (c->copy_match > 0) hipLaunchKernelGGL(hist_append_kernel, dim3(B), dim3(32), 0, c->stream, c->d_hist, c->hist_stride, c->d_state, 0);
 }
 
@@ -986,6 +994,7 @@ extern "C" sd_status sd_load_models(sd_ctx** out, const sd_model_cfg* p_cfg, con
   {
     const size_t n = B * SAMPLE_COUNTER_STRIDE;
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->d_counter, 0u, n);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->d_draw_ticket, 0u, n);
   }
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e == hipSuccess) e = hipGetLastError();
@@ -1301,12 +1310,10 @@ extern "C" sd_status sd_measure_cost(sd_ctx* c, int32_t reps, double* mq_us, dou
     const sd_status cs = capture_graph(c, &ge, [&] {
       if (which == 0) {      // a draft step that is not the first of an iteration: guess x_1 in, q_2 and x_2 out
         forward_any(c, c->q, Rows{ROWS_DRAFT_NEXT, 1, 1, 0, 0, B, 2}, c->q_logits);     // rows [seq][2][V], second of each
-        hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->q_logits + (size_t)V, V,
-                           c->d_params, 1, c->d_state, 0, 1, (size_t)2 * V);
+        launch_draw(c, c->q_logits + (size_t)V, 1, 0, 1, (size_t)2 * V);
       } else {               // standard decoding's forward and draw; the draw lands in a guess slot, nothing is committed
         forward_any(c, c->p, Rows{ROWS_BASELINE, 0, 1, 0, 0, B, 0}, c->p_logits);
-        hipLaunchKernelGGL(sample_row_kernel, dim3(B), dim3(SAMPLE_THREADS), 0, c->stream, c->p_logits, V,
-                           c->d_params, 0, c->d_state, 0, 1, (size_t)V);
+        launch_draw(c, c->p_logits, 0, 0, 1, (size_t)V);
       }
     });
     if (cs != SD_OK) return cs;
