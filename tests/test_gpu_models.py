@@ -470,7 +470,8 @@ def test_lenient_decoding_and_beta_statistics_match_oracle(temperature, lenience
 
 
 def test_gamma_autotuner_and_cost_measurement_leave_decoding_untouched():
-    """sd_measure_cost / sd_autotune_gamma between iterations: positive times, gamma equal to
+    """sd_measure_cost / sd_autotune_gamma / sd_time_forward / sd_time_stream_read between
+    iterations: positive times (a forward with launches left out is shorter), gamma equal to
     sd_choose_gamma on the reported alpha and c, alpha equal to accepted / tested, and the
     tokens decoded afterwards are the ones a context that never measured produces."""
     from paper_2211_17192_amd import binding
@@ -492,6 +493,16 @@ def test_gamma_autotuner_and_cost_measurement_leave_decoding_untouched():
                 assert tuned["c"] > 0.0
                 g, v = binding.choose_gamma(tuned["alpha"], tuned["c"], 5)
                 assert (g, v) == (tuned["gamma"], tuned["improvement"])
+                # the other measurement entries: a forward with and without a launch, the pure read
+                full = dec.time_forward(0, 6, 0, reps=3)
+                less = dec.time_forward(0, 6, binding.SD_OP["ffn_in"] | binding.SD_OP["attn"], reps=3)
+                assert 0.0 < less < full < 1e5
+                assert dec.time_forward(1, 1, 0, reps=3) > 0.0
+                assert dec.stream_read_GBps(0, reps=2) > 0.0 and dec.stream_read_GBps(1, reps=2) > 0.0
+                with pytest.raises(Exception):
+                    dec.time_forward(2, 1, 0)
+                with pytest.raises(Exception):
+                    dec.time_forward(0, 1, 1 << 20)
             n, t = dec.step(5, 1.0, urows[it])
             toks += t
         outs.append(toks)
