@@ -985,28 +985,29 @@ static __global__ __launch_bounds__(256) void gemm_split_finish_kernel(const Gem
 // the activation fragments passing through LDS as in gemm_split_kernel; every wavefront keeps
 // gemm_kernel's sums: the k-steps of a chunk go into `acc` in order, and at a chunk's end `acc`
 // is added to the running total, chunks in order -- the additions gemm_kernel's epilogue
-// makes -- so the results stay bit-identical.  One workgroup per CU has to cover the memory
-// latency alone, so a pass is GEMM_GATED_SUB k-steps deep: a weight register is reloaded for the
-// next pass right after its multiply (no second copy), and the running totals live in LDS to
-// make room.  Epilogue out of registers: norm factor (from rows_to_fragments_kernel),
-// activation, product.  grid = ceil(tiles / 4);
-// dynamic LDS = SUB * nrt fragments + 4 x 2 x GEMM_WIDE_RT x 256 floats.
+// makes -- so the results stay bit-identical.  One workgroup per CU, one wavefront per SIMD: nothing
+// hides a stall, so the number of slabs is a template parameter (no branch inside a pass), the
+// activation fragments of k-step u + 1 are read from LDS while k-step u is multiplied, a weight
+// register is reloaded for the next pass right after its multiply (no second copy), and running
+// totals and accumulators both live in registers (a wavefront alone on its SIMD has 512).
+// Epilogue out of registers: norm factor (from rows_to_fragments_kernel), activation, product.
+// grid = ceil(tiles / 4); dynamic LDS = SUB * NRT fragments.
 constexpr int GEMM_GATED_NW = 4;
 template <typename T> __host__ __device__ constexpr size_t gemm_gated_lds_bytes(int nrt) {
-  return (size_t)SplitShape<T>::SUB * nrt * 64 * 8 * sizeof(T) + (size_t)GEMM_GATED_NW * 2 * GEMM_WIDE_RT * 256 * sizeof(float);
+  return (size_t)SplitShape<T>::SUB * nrt * 64 * 8 * sizeof(T);
 }
 // EPI == EPI_LOGITS: the same walk for the LM head; a wavefront's two streams are the tiles 2 t and
 // 2 t + 1 of the one weight matrix, the epilogue scales and routes the rows (out_row).
-template <typename T, int EPI>
+template <typename T, int EPI, int NRT>
 static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_kernel(const GemmArgs a) {
   typedef typename Mma<T>::Frag Frag;
   extern __shared__ float lds[];
   constexpr int SUB = SplitShape<T>::SUB, RT = GEMM_WIDE_RT, NW = GEMM_GATED_NW, NT = 64 * NW;
+  constexpr int nrt = NRT;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, kq = lane >> 4;
-  const int KS = a.K >> 5, ntiles = a.N >> 4, nrt = a.nrt, kpw = a.ksteps_per_wave;
-  f32x4* tot = reinterpret_cast<f32x4*>(lds) + (size_t)wave * 2 * RT * 64 + lane;   // [2][RT] x 64 lanes, this lane's
-  Frag* xs = reinterpret_cast<Frag*>(lds + NW * 2 * RT * 256);                      // [SUB][nrt][64 lanes]
+  const int KS = a.K >> 5, ntiles = a.N >> 4, kpw = a.ksteps_per_wave;
+  Frag* xs = reinterpret_cast<Frag*>(lds);                        // [SUB][NRT][64 lanes]
   // work item = pair of streams: (gate, up) of tile `item`, or tiles 2 item and 2 item + 1
   const int nitems = (EPI == EPI_GATED) ? ntiles : (ntiles + 1) / 2;
   const int item = (int)blockIdx.x * NW + wave, itemc = min(item, nitems - 1);
@@ -1016,20 +1017,21 @@ static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_ker
   wbase[1] = static_cast<const T*>((EPI == EPI_GATED) ? a.W2 : a.W) + ((size_t)tile1 * KS) * 512 + lane * 8;
   const Frag* xf = reinterpret_cast<const Frag*>(a.X);            // [KS][RT][64 lanes]
 
-  f32x4 acc[2][RT];
+  f32x4 acc[2][NRT], tot[2][NRT];
 #pragma unroll
   for (int st = 0; st < 2; ++st)
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) { acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f}; tot[(st * RT + rt) * 64] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int rt = 0; rt < NRT; ++rt) { acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f}; tot[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
   Frag wf[2][SUB];
-  constexpr int XPT = (SUB * RT * 64 + NT - 1) / NT;
+  // this thread's share of a pass's activation fragments: fragment i = tid + NT m is (k-step
+  // i / (NRT * 64), slab and lane i % (NRT * 64)); the split is the same for every pass
+  constexpr int NFRAG = SUB * NRT * 64, XPT = (NFRAG + NT - 1) / NT;
   Frag xr[XPT];
-  const int nfrag = SUB * nrt * 64;
   auto load_x = [&](int ksb) {                       // unconditional, clamped: no branch around loads
 #pragma unroll
     for (int m = 0; m < XPT; ++m) {
-      const int i = min(tid + NT * m, nfrag - 1);
-      const int u = i / (nrt * 64), rem = i - u * (nrt * 64);
+      const int i = min(tid + NT * m, NFRAG - 1);
+      const int u = i / (NRT * 64), rem = i - u * (NRT * 64);       // (a division by a constant)
       xr[m] = xf[(size_t)min(ksb + u, KS - 1) * (RT * 64) + rem];
     }
   };
@@ -1046,34 +1048,55 @@ static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_ker
     __syncthreads();                                 // the previous pass has been multiplied
 #pragma unroll
     for (int m = 0; m < XPT; ++m)
-      if (tid + NT * m < nfrag) xs[tid + NT * m] = xr[m];
+      if (NFRAG % NT == 0 || tid + NT * m < NFRAG) xs[tid + NT * m] = xr[m];
     __syncthreads();
     load_x(next);
+    if (len == SUB) {                                // (uniform) a whole pass, straight-line
+      constexpr int NB = (NRT <= 5) ? 2 : 1;         // six slabs: no registers left for a second set of fragments
+      Frag fb[NB][NRT];
 #pragma unroll
-    for (int u = 0; u < SUB; ++u) {
-      if (u < len) {                                 // uniform
+      for (int rt = 0; rt < NRT; ++rt) fb[0][rt] = xs[rt * 64 + lane];
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          if (rt < nrt) {
-            const Frag fb = xs[(u * nrt + rt) * 64 + lane];
+      for (int u = 0; u < SUB; ++u) {
+        if (NB == 2 && u + 1 < SUB) {
+#pragma unroll
+          for (int rt = 0; rt < NRT; ++rt) fb[(u + 1) & 1][rt] = xs[((u + 1) * NRT + rt) * 64 + lane];
+        }
+        if (NB == 1 && u > 0) {
+#pragma unroll
+          for (int rt = 0; rt < NRT; ++rt) fb[0][rt] = xs[(u * NRT + rt) * 64 + lane];
+        }
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+          acc[0][rt] = Mma<T>::mma(wf[0][u], fb[u & (NB - 1)][rt], acc[0][rt]);
+          acc[1][rt] = Mma<T>::mma(wf[1][u], fb[u & (NB - 1)][rt], acc[1][rt]);
+        }
+        // this register's next k-step is on its way while the rest of the pass is multiplied
+        wf[0][u] = Mma<T>::load_stream(wbase[0] + (size_t)min(next + u, KS - 1) * 512);
+        wf[1][u] = Mma<T>::load_stream(wbase[1] + (size_t)min(next + u, KS - 1) * 512);
+      }
+    } else {                                         // the short pass at a chunk's end
+#pragma unroll
+      for (int u = 0; u < SUB; ++u) {
+        if (u < len) {                               // uniform
+#pragma unroll
+          for (int rt = 0; rt < NRT; ++rt) {
+            const Frag fb = xs[(u * NRT + rt) * 64 + lane];
             acc[0][rt] = Mma<T>::mma(wf[0][u], fb, acc[0][rt]);
             acc[1][rt] = Mma<T>::mma(wf[1][u], fb, acc[1][rt]);
           }
         }
+        wf[0][u] = Mma<T>::load_stream(wbase[0] + (size_t)min(next + u, KS - 1) * 512);
+        wf[1][u] = Mma<T>::load_stream(wbase[1] + (size_t)min(next + u, KS - 1) * 512);
       }
-      // this register's next k-step is on its way while the rest of the pass is multiplied
-      wf[0][u] = Mma<T>::load_stream(wbase[0] + (size_t)min(next + u, KS - 1) * 512);
-      wf[1][u] = Mma<T>::load_stream(wbase[1] + (size_t)min(next + u, KS - 1) * 512);
     }
     if (next == KS || next % kpw == 0) {             // the chunk is complete: add it, chunks in order
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          f32x4 t = tot[(st * RT + rt) * 64];
+        for (int rt = 0; rt < NRT; ++rt) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) t[r] += acc[st][rt][r];
-          tot[(st * RT + rt) * 64] = t;
+          for (int r = 0; r < 4; ++r) tot[st][rt][r] += acc[st][rt][r];
           acc[st][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
       ++chunks_done;
@@ -1084,13 +1107,13 @@ static __global__ __launch_bounds__(64 * GEMM_GATED_NW) void gemm_gated_wide_ker
   // accumulator layout: lane holds features 4 kq + r, r = 0..3, of row j
   const int n0 = tile0 * 16 + kq * 4;
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    if (rt < nrt) {
+  for (int rt = 0; rt < NRT; ++rt) {
+    {
       const int rows = (rt == nrt - 1) ? a.R_last : a.R;
       if (j < rows) {
         const int row = rt * 16 + j;
         const float r1 = a.rs_in[row];
-        f32x4 t0 = tot[rt * 64], t1 = tot[(RT + rt) * 64];
+        f32x4 t0 = tot[0][rt], t1 = tot[1][rt];
         for (int c = chunks_done; c < a.nchunk; ++c)      // chunks beyond K are empty in gemm_kernel too: it adds their zeros
 #pragma unroll
           for (int r = 0; r < 4; ++r) { t0[r] += 0.0f; t1[r] += 0.0f; }

@@ -327,8 +327,15 @@ void launch_gemm_gated_wide(hipStream_t s, GemmArgs a) {
   const int S = pick_waves(KS);                  // the chunks whose sums the one-slab kernel adds
   a.ksteps_per_wave = (KS + S - 1) / S;
   a.nchunk = S;
-  hipLaunchKernelGGL((gemm_gated_wide_kernel<T, EPI>), dim3((tiles + GEMM_GATED_NW - 1) / GEMM_GATED_NW), dim3(64 * GEMM_GATED_NW),
-                     gemm_gated_lds_bytes<T>(a.nrt), s, a);
+  const dim3 grid((tiles + GEMM_GATED_NW - 1) / GEMM_GATED_NW), block(64 * GEMM_GATED_NW);
+  const size_t lds = gemm_gated_lds_bytes<T>(a.nrt);       // at most 48 KB: within the default limit
+  static_assert(gemm_gated_lds_bytes<T>(GEMM_WIDE_RT) <= 64 * 1024, "gated wide kernel: dynamic LDS");
+  switch (a.nrt) {                                         // the slab count is a template parameter of the kernel
+#define SD_NRT(N_) case N_: hipLaunchKernelGGL((gemm_gated_wide_kernel<T, EPI, N_>), grid, block, lds, s, a); break
+    SD_NRT(1); SD_NRT(2); SD_NRT(3); SD_NRT(4); SD_NRT(5); SD_NRT(6);
+#undef SD_NRT
+    default: break;                                        // (callers pass 1 .. GEMM_WIDE_RT)
+  }
 }
 
 // Which products take the split design (activations in fragment order, RMSNorm or no norm).
@@ -340,17 +347,14 @@ inline bool split_ok(int pro, int epi) {
 template <typename T>
 void launch_gemm_split(hipStream_t s, int pro, int epi, const GemmArgs& a, float* partial) {
 #define SD_CASE(P, E) if (pro == P && epi == E) return launch_gemm_split_t<T, P, E>(s, a, partial)
-  SD_CASE(PRO_POST, EPI_QKV); SD_CASE(PRO_NONE, EPI_RESID); SD_CASE(PRO_POST, EPI_GATED);
+  SD_CASE(PRO_POST, EPI_QKV); SD_CASE(PRO_NONE, EPI_RESID);     // (split_ok() admits no others)
 #undef SD_CASE
 }
 
 // The wide kernel's LDS exceeds the default 64 KB limit of dynamic LDS.
 template <typename T>
 hipError_t allow_wide_lds() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_gated_wide_kernel<T, EPI_GATED>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_gated_lds_bytes<T>(GEMM_WIDE_RT));
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_gated_wide_kernel<T, EPI_LOGITS>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_gated_lds_bytes<T>(GEMM_WIDE_RT));
+  hipError_t e = hipSuccess;
 #define SD_CASE(P, E)                                                                                          \
   if (e == hipSuccess)                                                                                         \
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide_kernel<T, P, E>),                         \
