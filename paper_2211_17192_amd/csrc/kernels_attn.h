@@ -334,7 +334,8 @@ static __global__ __launch_bounds__(THREADS) void attn_kernel(const AttnArgs a) 
 //                 exchanges per step only.
 //   O^T = V^T P   A = 16 features x 32 keys: V is key-major in the cache, so every wavefront
 //                 copies its 32 x d_head tile into a private LDS region with fully coalesced
-//                 16-byte loads and reads the fragments back transposed, 2 bytes at a time;
+//                 16-byte loads and reads the fragments back with gfx950's transposing LDS read
+//                 (ds_read_b64_tr_b16: two per 16-feature tile instead of eight 2-byte reads);
 //                 B = the probabilities the lane
 //                 already holds, each as the sum of two bf16 numbers (two MFMAs).
 // The wavefronts' results are merged through LDS, in wavefront order; a launch without key ranges
@@ -502,8 +503,8 @@ static __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mma_kern
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) o[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  // V tile of the step, row-major with padded rows: [32 keys][DH + 8] bf16.  The 16-byte writes of
-  // a load and the 2-byte reads of a fragment (16 features x 4 key groups) are both conflict-free.
+  // V tile of the step, row-major with padded rows: [32 keys][DH + 8] bf16 (rows stay 8-byte aligned,
+  // which the transposing reads of a fragment need).
   constexpr int VRS = DH + 8;
   unsigned short* vt = reinterpret_cast<unsigned short*>(lds) + (size_t)wave * 32 * VRS;
   // bias of this lane's keys kb + kt*16 + kq*4 + 0..3 for row rt: table entries (key - pos) + bias_off ..,
@@ -621,10 +622,17 @@ static __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mma_kern
     }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
-      u16x8 vb;                                      // V[key (e/4) 16 + 4 kq + e%4][feature dt 16 + j]
-#pragma unroll
-      for (int e = 0; e < 8; ++e) vb[e] = vt[((e >> 2) * 16 + kq * 4 + (e & 3)) * VRS + dt * 16 + j];
+      // vf[e] = V[key (e/4) 16 + 4 kq + e%4][feature dt 16 + j]: two transposing LDS reads.  In each
+      // block of 16 lanes, lane s hands in the address of four consecutive 16-bit elements D[s][0..3]
+      // and lane i gets back D[i/4 + 4 e][i%4], e = 0..3; with lane s pointing at
+      // V[key0 + s/4][dt 16 + 4 (s%4) ..], lane j receives keys key0 .. key0 + 3 of feature dt 16 + j.
+      typedef short s16x4 __attribute__((ext_vector_type(4)));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+      const unsigned short* vp = vt + (kq * 4 + (j >> 2)) * VRS + dt * 16 + 4 * (j & 3);
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)vp);
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 16 * VRS));
+      const s16x8 vb = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       const bf16x8 vf = __builtin_bit_cast(bf16x8, vb);
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt) {
