@@ -134,6 +134,17 @@ template <> struct Mma<float> {
   }
 };
 
+// The 8 elements of a fragment as floats (what load8 gives for the same 8 elements).
+template <typename T> __device__ __forceinline__ void frag_to_floats(const typename Mma<T>::Frag& f, float (&o)[8]);
+template <> __device__ __forceinline__ void frag_to_floats<bf16>(const bf16x8& f, float (&o)[8]) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (float)f[e];
+}
+template <> __device__ __forceinline__ void frag_to_floats<float>(const Mma<float>::Frag& f, float (&o)[8]) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = f.v[e];
+}
+
 // The same row must come out bit-identical from every kernel that can compute it (one slab or
 // several), so the arithmetic of the epilogues and of the LayerNorm prologue is written once and
 // with floating-point contraction off: left to itself the compiler fuses a multiply and an add
@@ -204,38 +215,7 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   const int e_row = (tid >> 4) & 15, e_f = tid & 15;  // epilogue role of this thread
   const int e_rowc = min(e_row, a.R - 1);             // clamped: loads stay in bounds
 
-  // ---- PRO_LN: statistics of the fp32 rows, reduced across the workgroup ----
   float mu = 0.0f, rstd = 1.0f;
-  if (PRO == PRO_LN) {
-    const float* x = static_cast<const float*>(a.X) + (size_t)min(j, a.R - 1) * a.K + kq * 8;
-    float s = 0.0f;
-#pragma unroll 4
-    for (int ks = ks0; ks < ks1; ++ks) {
-      float v[8]; load8<float>(x + ks * 32, v);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) s += v[e];
-    }
-    s = lane_combine<16>(s, OpSumF()); s = lane_combine<32>(s, OpSumF());
-    if (kq == 0) stat[wave * 16 + j] = s;
-    __syncthreads();
-    float t = 0.0f;
-    for (int w = 0; w < S; ++w) t += stat[w * 16 + j];
-    mu = t / (float)a.K;
-    __syncthreads();
-    float s2 = 0.0f;
-#pragma unroll 4
-    for (int ks = ks0; ks < ks1; ++ks) {
-      float v[8]; load8<float>(x + ks * 32, v);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) s2 = add_square(s2, v[e] - mu);
-    }
-    s2 = lane_combine<16>(s2, OpSumF()); s2 = lane_combine<32>(s2, OpSumF());
-    if (kq == 0) stat[wave * 16 + j] = s2;
-    __syncthreads();
-    float t2 = 0.0f;
-    for (int w = 0; w < S; ++w) t2 += stat[w * 16 + j];
-    rstd = 1.0f / sqrtf(t2 / (float)a.K + a.eps);
-  }
 
   typedef typename Mma<T>::Frag Frag;
   struct Buf { Frag fa[ND][U]; Frag fb[U]; };
@@ -263,7 +243,9 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
   // chunk g of this workgroup's work list: tile blockIdx.x + (g / nchunks) * gridDim.x,
   // k-steps ks0 + (g % nchunks) * U ... of this wave's K-slice
   const int ks_last = max(ks1 - 1, 0);
-  auto load_chunk = [&](Buf& b, int g) {
+  // (WHAT: 1 = the weights, 2 = the activations, 3 = both, interleaved per k-step)
+  auto load_chunk_part = [&](Buf& b, int g, auto what) {
+    constexpr int WHAT = decltype(what)::value;
     const int ti = g / nchunks, c = g - ti * nchunks;
     const size_t tile = (size_t)blockIdx.x + (size_t)ti * gridDim.x;
     const T* w0 = static_cast<const T*>(a.W) + (tile * KS) * 512 + lane * 8;
@@ -272,11 +254,14 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
     for (int u = 0; u < U; ++u) {
       const int ks = ks0 + c * U + u;
       const int ksc = min(ks, ks_last);
-      b.fa[0][u] = Mma<T>::load_stream(w0 + (size_t)ksc * 512);
-      if (ND == 2) b.fa[ND - 1][u] = Mma<T>::load_stream(w1 + (size_t)ksc * 512);
-      b.fb[u] = make_b(ksc, ks < ks1);
+      if (WHAT & 1) {
+        b.fa[0][u] = Mma<T>::load_stream(w0 + (size_t)ksc * 512);
+        if (ND == 2) b.fa[ND - 1][u] = Mma<T>::load_stream(w1 + (size_t)ksc * 512);
+      }
+      if (WHAT & 2) b.fb[u] = make_b(ksc, ks < ks1);
     }
   };
+  auto load_chunk = [&](Buf& b, int g) { load_chunk_part(b, g, std::integral_constant<int, 3>()); };
 
   const int G = my_tiles * nchunks;
   Buf b0, b1;
@@ -301,7 +286,98 @@ static __global__ __launch_bounds__(512) void gemm_kernel(const GemmArgs a) {
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(blk + 4 * i),
                                        (__attribute__((address_space(3))) void*)(ssb + (4 * i + wave) * 256), 16, 0, 0);
   }
-  if (G > 0) load_chunk(b0, 0);
+  // A LayerNorm model's rows cannot be normalised before their statistics are known, but the first
+  // chunk's weights depend on nothing: they are asked for first and arrive while the statistics
+  // (two passes over the rows, two barriers) are computed.
+  if (PRO == PRO_LN) {
+    if (G > 0) load_chunk_part(b0, 0, std::integral_constant<int, 1>());
+    // ---- statistics of the fp32 rows, reduced across the workgroup ----
+    if (sizeof(T) == 2 && nchunks == 1) {            // (fp32 fragments are twice the registers: general path)
+      // A wavefront's whole K-slice is one chunk (small d_model): the rows' elements, gains and
+      // offsets are fetched ONCE, with the weights, and both passes of the statistics and the
+      // normalised fragments come out of registers -- the same additions in the same order as
+      // the general path below, without its two further trips to memory.
+      const float* x = static_cast<const float*>(a.X) + (size_t)jr * a.K + kq * 8;
+      float xv[U][8];
+      typename Mma<T>::Frag gv[U], bv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int k = min(ks0 + u, ks_last) * 32;
+        load8<float>(x + k, xv[u]);
+        gv[u] = Mma<T>::load(static_cast<const T*>(a.gain) + k + kq * 8);
+        bv[u] = Mma<T>::load(static_cast<const T*>(a.beta) + k + kq * 8);
+      }
+      float s = 0.0f;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ks0 + u < ks1) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) s += xv[u][e];
+        }
+      s = lane_combine<16>(s, OpSumF()); s = lane_combine<32>(s, OpSumF());
+      if (kq == 0) stat[wave * 16 + j] = s;
+      __syncthreads();
+      float t = 0.0f;
+      for (int w = 0; w < S; ++w) t += stat[w * 16 + j];
+      mu = t / (float)a.K;
+      __syncthreads();
+      float s2 = 0.0f;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ks0 + u < ks1) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) s2 = add_square(s2, xv[u][e] - mu);
+        }
+      s2 = lane_combine<16>(s2, OpSumF()); s2 = lane_combine<32>(s2, OpSumF());
+      if (kq == 0) stat[wave * 16 + j] = s2;
+      __syncthreads();
+      float t2 = 0.0f;
+      for (int w = 0; w < S; ++w) t2 += stat[w * 16 + j];
+      rstd = 1.0f / sqrtf(t2 / (float)a.K + a.eps);
+      if (G > 0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float v[8], g[8], bb[8];
+          frag_to_floats<T>(gv[u], g); frag_to_floats<T>(bv[u], bb);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = ln_apply(xv[u][e], mu, rstd, g[e], bb[e]);
+          b0.fb[u] = Mma<T>::select((ks0 + u < ks1) && row_ok, Mma<T>::from_floats(v));
+        }
+      }
+    } else {
+      const float* x = static_cast<const float*>(a.X) + (size_t)min(j, a.R - 1) * a.K + kq * 8;
+      float s = 0.0f;
+#pragma unroll 4
+      for (int ks = ks0; ks < ks1; ++ks) {
+        float v[8]; load8<float>(x + ks * 32, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += v[e];
+      }
+      s = lane_combine<16>(s, OpSumF()); s = lane_combine<32>(s, OpSumF());
+      if (kq == 0) stat[wave * 16 + j] = s;
+      __syncthreads();
+      float t = 0.0f;
+      for (int w = 0; w < S; ++w) t += stat[w * 16 + j];
+      mu = t / (float)a.K;
+      __syncthreads();
+      float s2 = 0.0f;
+#pragma unroll 4
+      for (int ks = ks0; ks < ks1; ++ks) {
+        float v[8]; load8<float>(x + ks * 32, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s2 = add_square(s2, v[e] - mu);
+      }
+      s2 = lane_combine<16>(s2, OpSumF()); s2 = lane_combine<32>(s2, OpSumF());
+      if (kq == 0) stat[wave * 16 + j] = s2;
+      __syncthreads();
+      float t2 = 0.0f;
+      for (int w = 0; w < S; ++w) t2 += stat[w * 16 + j];
+      rstd = 1.0f / sqrtf(t2 / (float)a.K + a.eps);
+      if (G > 0) load_chunk_part(b0, 0, std::integral_constant<int, 2>());
+    }
+  } else if (G > 0) {
+    load_chunk(b0, 0);
+  }
   int e_pos = -1;
   size_t e_kvbase = 0;                            // EPI_QKV: cache offset of this row's page / slot
   if (EPI == EPI_QKV && epi_thread) {
