@@ -55,10 +55,14 @@ enum {
   SD_FLAG_PROFILE = 2,  /* record HIP events around the draft / verify / accept phases */
   SD_FLAG_BETA    = 4,  /* also compute beta_i = sum_x min(p_i(x), q_i(x)) of every guess (section 3.1)
                            in each sd_step: one more small launch; feeds sd_stats.beta_sum */
-  SD_FLAG_SCATTER_PAGES = 8  /* at load only: every sequence's page table lists its KV-cache pages back to
+  SD_FLAG_SCATTER_PAGES = 8, /* at load only: every sequence's page table lists its KV-cache pages back to
                            front instead of in order.  Results are identical; it exists to show that
                            every kernel finds its pages through the table.  sd_set_flags leaves it as
                            it was at load. */
+  SD_FLAG_SEPARATE_CROSS_Q = 16 /* small T5-type models (bf16, heads of 64, d_model <= 512, at most 16 rows)
+                           let the cross-attention kernel compute its own queries, one launch less
+                           per layer; with this flag the query projection stays a launch of its own.
+                           Results are identical; it exists so that a test can show that. */
 };
 
 /*

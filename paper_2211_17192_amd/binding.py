@@ -22,7 +22,7 @@ lib = C.CDLL(LIB_PATH)
 SD_OK, SD_EINVAL, SD_ESTATE, SD_ERANGE, SD_ENOMEM, SD_EHIP = range(6)
 SD_F32, SD_BF16 = 0, 1
 SD_MAX_GAMMA = 15
-SD_FLAG_GRAPH, SD_FLAG_PROFILE, SD_FLAG_BETA, SD_FLAG_SCATTER_PAGES = 1, 2, 4, 8
+SD_FLAG_GRAPH, SD_FLAG_PROFILE, SD_FLAG_BETA, SD_FLAG_SCATTER_PAGES, SD_FLAG_SEPARATE_CROSS_Q = 1, 2, 4, 8, 16
 STATUS_NAMES = ["SD_OK", "SD_EINVAL", "SD_ESTATE", "SD_ERANGE", "SD_ENOMEM", "SD_EHIP"]
 
 

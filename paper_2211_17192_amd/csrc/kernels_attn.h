@@ -80,6 +80,14 @@ struct AttnArgs {
   int bias_off;
   const int* bucket_lut;    // [n_pages * page_size <= ATTN_LDS_DIST] bucket of each causal distance
   int rel_buckets;
+  // attn_mma_kernel, mode ATTN_CROSS_PROJ: the kernel computes its head's queries itself from the
+  // RMSNorm input of the cross-attention block, exactly as gemm_kernel<bf16, PRO_POST, EPI_STORE>
+  // would (`q` is not read): pj_w = the projection's weights in MFMA tile order, pj_x = the rows
+  // times the norm's gain [R][pj_K], pj_ss = [pj_npart][16] partial sums of squares of the rows,
+  // pj_q_off = where in dynamic LDS (in floats) the 16 x d_head query rows go
+  const void* pj_w; const void* pj_x; const float* pj_ss;
+  int pj_K, pj_npart, pj_q_off;
+  float pj_eps;
 };
 
 // THREADS (256, 512 or 1024) sets the key block: THREADS / LPK keys per pass, so a launch takes the
@@ -372,7 +380,19 @@ constexpr size_t attn_mma_lds_bytes(int rg, int dh, int nw) {
   return stage > merge ? stage : merge;
 }
 
-constexpr int ATTN_SELF = 0, ATTN_SELF_BIAS = 1, ATTN_CROSS = 2;
+constexpr int ATTN_SELF = 0, ATTN_SELF_BIAS = 1, ATTN_CROSS = 2, ATTN_CROSS_PROJ = 3;
+// ATTN_CROSS_PROJ (d_head 64, one row tile, one query head per kv head, K <= 512): cross-attention of a
+// small model whose query projection is done here instead of in a launch of its own.  A head's 64
+// query features are 4 tiles x K/32 k-steps of weights, 64 KB at K = 512: the wavefronts fetch them
+// with the first keys and values, multiply them exactly as gemm_kernel would -- four K-slices per
+// tile, chunks of four k-steps with the k-steps past a slice masked, the slices' partial tiles added
+// in order, the row's 1/rms from the partial sums of squares in gemm_kernel's order, rounding to
+// bf16 -- and hand the rows to the score product through LDS.  Bit-identical to the two launches.
+constexpr int ATTN_PJ_S = 4, ATTN_PJ_U = 4;            // gemm_kernel's wavefronts and chunk at K <= 512
+constexpr size_t attn_mma_proj_lds_bytes(int rg, int nw) {
+  const size_t base = attn_mma_lds_bytes(rg, 64, nw), part = (size_t)4 * ATTN_PJ_S * 256 * 4;
+  return ((base > part ? base : part) + 15) / 16 * 16 + 16 * 64 * 2;
+}
 typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // four floats at any 4-byte boundary
 
 template <int DH, int NRT, int NW, int MODE>
@@ -380,7 +400,8 @@ template <int DH, int NRT, int NW, int MODE>
 // contexts' key ranges need: one workgroup per CU took two rounds there)
 static __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mma_kernel(const AttnArgs a) {
   extern __shared__ float lds[];
-  constexpr bool CROSS = MODE == ATTN_CROSS, BIAS = MODE == ATTN_SELF_BIAS, TABLE = !CROSS;   // TABLE: paged keys
+  constexpr bool PROJ = MODE == ATTN_CROSS_PROJ;
+  constexpr bool CROSS = MODE == ATTN_CROSS || PROJ, BIAS = MODE == ATTN_SELF_BIAS, TABLE = !CROSS;   // TABLE: paged keys
   constexpr int KSQ = DH / 32;                     // k-steps of the score product
   constexpr int DT = DH / 16;                      // 16-feature tiles of the output
   const int tid = threadIdx.x, lane = tid & 63;
@@ -410,6 +431,31 @@ static __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mma_kern
     out[1] = page_table[min((kb + 16) >> page_shift, last_page)];
   };
   ask_pages(kb0, pg);
+  // ---- PROJ: the loads of the query projection leave first ----
+  constexpr int PJ_PER_WAVE = PROJ ? (DH / 16) * ATTN_PJ_S / NW : 1;      // (tile, K-slice) units per wavefront
+  bf16x8 pj_w[PJ_PER_WAVE][ATTN_PJ_U], pj_b[PJ_PER_WAVE][ATTN_PJ_U];
+  float pj_ss[16];
+  const int pj_KS = PROJ ? a.pj_K >> 5 : 0, pj_kpw = (pj_KS + ATTN_PJ_S - 1) / ATTN_PJ_S;
+  if (PROJ) {
+    const bf16* W = static_cast<const bf16*>(a.pj_w);
+    const bf16* xb = static_cast<const bf16*>(a.pj_x) + (size_t)(r0 + min(j, R - 1)) * a.pj_K + kq * 8;
+#pragma unroll
+    for (int i = 0; i < PJ_PER_WAVE; ++i) {
+      const int u = wave + NW * i, tile = hkv * (DH / 16) + (u >> 2), w = u & 3;
+      const int ks0 = min(pj_KS, w * pj_kpw), ks1 = min(pj_KS, ks0 + pj_kpw), ks_last = max(ks1 - 1, 0);
+#pragma unroll
+      for (int uu = 0; uu < ATTN_PJ_U; ++uu) {
+        const int ksc = min(ks0 + uu, ks_last);
+        pj_w[i][uu] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(W + ((size_t)tile * pj_KS + ksc) * 512 + lane * 8));
+        pj_b[i][uu] = ld_frag(xb + ksc * 32);
+      }
+    }
+    if (tid < 256) {                                // thread (row, f) of the projection's epilogue: partials f, f + 16, ..
+      const int rowc = r0 + min(tid >> 4, R - 1), f = tid & 15;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) pj_ss[u] = a.pj_ss[min(f + 16 * u, a.pj_npart - 1) * 16 + rowc];
+    }
+  }
   // query rows of this lane: rg = rt * 16 + j; features (4 s + kq) * 8 .. + 8 in k-step s
   bf16x8 qf[NRT][KSQ];
   int pos[NRT], gq[NRT];
@@ -425,7 +471,7 @@ static __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mma_kern
     brow[rt] = BIAS ? a.bias_by_key + (size_t)(hkv * G + gq[rt]) * (a.bias_off + 4) : nullptr;
     const bf16* qp = static_cast<const bf16*>(a.q) + (size_t)(r0 + rr) * a.H * DH + (size_t)(hkv * G + gq[rt]) * DH + kq * 8;
 #pragma unroll
-    for (int s = 0; s < KSQ; ++s) qf[rt][s] = ok ? ld_frag(qp + s * 32) : zero_frag();
+    for (int s = 0; s < KSQ; ++s) qf[rt][s] = (ok && !PROJ) ? ld_frag(qp + s * 32) : zero_frag();
   }
   auto row_ptr = [&](int key, int page, int which) -> const bf16* {   // which: 0 = K, 1 = V
     if (CROSS) return static_cast<const bf16*>(which ? a.cv : a.ck) + ((size_t)hkv * a.kv_len + key) * DH;
@@ -523,6 +569,55 @@ static __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mma_kern
   if (kb0 < kv_len) { load_k(kb0); load_v(kb0); }   // a wavefront without keys loads nothing
   if (kb0 < kv_len) load_bias(kb0);
   ask_pages(kb0 + NW * 32, pg);
+  if (PROJ) {
+    // ---- the projection itself, while the first keys and values are on their way ----
+    float* pj_part = lds;                            // [4 tiles][4 slices][256]; the staging region is not in use yet
+    unsigned short* pj_q = reinterpret_cast<unsigned short*>(lds + a.pj_q_off);     // [16 rows][DH] bf16
+#pragma unroll
+    for (int i = 0; i < PJ_PER_WAVE; ++i) {
+      const int u = wave + NW * i, w = u & 3;
+      const int ks0 = min(pj_KS, w * pj_kpw), ks1 = min(pj_KS, ks0 + pj_kpw);
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int uu = 0; uu < ATTN_PJ_U; ++uu) {
+        const bool valid = (ks0 + uu < ks1) && (j < R);
+        acc = mma_bf16(pj_w[i][uu], valid ? pj_b[i][uu] : zero_frag(), acc);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) pj_part[u * 256 + j * 16 + kq * 4 + r] = acc[r];     // u = tile * 4 + slice
+    }
+    __syncthreads();
+    if (tid < 256) {
+      const int row = tid >> 4, f = tid & 15;
+      float q = 0.0f;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) q += (f + 16 * u < a.pj_npart) ? pj_ss[u] : 0.0f;
+      q = lane_combine<1>(q, OpSumF()); q = lane_combine<2>(q, OpSumF());
+      q = lane_combine<4>(q, OpSumF()); q = lane_combine<8>(q, OpSumF());
+      q = row_first(q);
+      const float rs_row = 1.0f / sqrtf(q / (float)a.pj_K + a.pj_eps);
+#pragma unroll
+      for (int t = 0; t < DH / 16; ++t) {
+        float y = 0.0f;
+#pragma unroll
+        for (int w = 0; w < ATTN_PJ_S; ++w) y += pj_part[(t * ATTN_PJ_S + w) * 256 + tid];
+        y *= rs_row;
+        y += 0.0f;                                   // (gemm_kernel adds its absent bias as zero)
+        const bf16 yb = (bf16)y;
+        pj_q[row * DH + t * 16 + f] = __builtin_bit_cast(unsigned short, yb);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      const int rg = rt * 16 + j;                    // (one query head per kv head: row group = row)
+#pragma unroll
+      for (int s = 0; s < KSQ; ++s)
+        qf[rt][s] = (rg < RG) ? *reinterpret_cast<const bf16x8*>(pj_q + rg * DH + s * 32 + kq * 8) : zero_frag();
+    }
+    // (pj_part was last read before the barrier above, so the staging region is free; pj_q lies beyond
+    // everything the rest of the kernel writes)
+  }
 
   for (int kb = kb0; kb < kv_len; kb += NW * 32) {
     const int nkeys = min(32, kv_len - kb);

@@ -417,7 +417,14 @@ void launch_attn_kernel(hipStream_t s, const AttnArgs& a, dim3 grid, int threads
 int attn_mma_waves(int keys) { return (keys + 31) / 32 > 8 ? 8 : 4; }
 template <int DH, int NRT>
 void launch_attn_mma(hipStream_t s, const AttnArgs& a, dim3 grid, int nw, size_t lds) {
-  const int mode = a.cross ? ATTN_CROSS : (a.bias_by_key != nullptr ? ATTN_SELF_BIAS : ATTN_SELF);
+  const int mode = a.cross ? (a.pj_w != nullptr ? ATTN_CROSS_PROJ : ATTN_CROSS) : (a.bias_by_key != nullptr ? ATTN_SELF_BIAS : ATTN_SELF);
+  if constexpr (DH == 64 && NRT == 1) {
+    if (mode == ATTN_CROSS_PROJ) {
+      if (nw == 4) hipLaunchKernelGGL((attn_mma_kernel<64, 1, 4, ATTN_CROSS_PROJ>), grid, dim3(256), lds, s, a);
+      else hipLaunchKernelGGL((attn_mma_kernel<64, 1, 8, ATTN_CROSS_PROJ>), grid, dim3(512), lds, s, a);
+      return;
+    }
+  }
 #define SD_MMA(NW_, MODE_)                                                                                \
   if (nw == NW_ && mode == MODE_) {                                                                       \
     hipLaunchKernelGGL((attn_mma_kernel<DH, NRT, NW_, MODE_>), grid, dim3(64 * NW_), lds, s, a);          \
@@ -449,7 +456,12 @@ void launch_attn(hipStream_t s, const Model& m, AttnArgs a, int nseq) {
   if (std::is_same<T, bf16>::value && (DH == 64 || DH == 128)) {
     const int RG = a.rows_per_wg * G;
     const int nw = (a.nsplit > 1) ? 4 : attn_mma_waves(a.cross ? a.kv_len : (m.cfg.max_len + 1) / 2);
-    const size_t ll = attn_mma_lds_bytes(RG, DH, nw);
+    if (a.pj_w != nullptr && !(a.cross && DH == 64 && RG <= 16 && G == 1)) a.pj_w = nullptr;   // (callers check; never project elsewhere)
+    size_t ll = attn_mma_lds_bytes(RG, DH, nw);
+    if (a.pj_w != nullptr) {
+      ll = attn_mma_proj_lds_bytes(RG, nw);
+      a.pj_q_off = (int)((ll - 16 * 64 * 2) / 4);
+    }
     const dim3 lg(grid.x, grid.z, grid.y);          // key ranges in z, the slowest index: the fullest ranges start first
     if (DH == 64 && RG <= 16) launch_attn_mma<64, 1>(s, a, lg, nw, ll);
     else if (DH == 64) launch_attn_mma<64, 2>(s, a, lg, nw, ll);
@@ -637,6 +649,13 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
       a.rope = m.rope;
       if (m.batch > 1) { a.row_seq = q.row_seq; a.pt_stride = m.n_pages; }
     });
+    // Small models: the cross-attention kernel computes its own queries (ATTN_CROSS_PROJ), one launch
+    // less per layer.  The conditions are the kernel's: bf16, heads of 64, one query head per kv head,
+    // one slab of rows, K = d_model <= 512 (gemm_kernel then runs four wavefronts with chunks of four
+    // k-steps, which the kernel reproduces).
+    const bool fuse_cross_q = f.arch == SD_ARCH_T5DEC && std::is_same<T, bf16>::value && f.d_head == 64 &&
+                              f.n_heads == f.n_kv_heads && n_groups == 1 && d <= 512 && d % 32 == 0 &&
+                              !(c->rt.flags & SD_FLAG_SEPARATE_CROSS_Q);
     auto attention = [&](bool cross) {
       {
         const Grp q = group(0);                     // one launch over all sequences (grid.z)
@@ -648,6 +667,9 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
         a.bias_by_key = m.bias_by_key; a.bias_off = f.max_len - 1;
         a.seq0 = rw.seq0; a.pt_stride = m.n_pages;
         if (cross) { a.cross = 1; a.ck = l.cross_k; a.cv = l.cross_v; a.kv_len = f.enc_len; a.scale = 1.0f; a.rel_bias = nullptr; a.bias_by_key = nullptr; }
+        if (cross && fuse_cross_q && !(skip & SD_OP_CROSS_Q)) {
+          a.pj_w = l.cq; a.pj_x = q.xg; a.pj_ss = q.ss; a.pj_K = d; a.pj_npart = n_part; a.pj_eps = f.norm_eps;
+        }
         // long contexts end in the merge kernel, which can leave its output in fragment order for
         // the batched O projection (no re-tile)
         if (!cross && m.attn_nsplit > 1 && n_groups > 1 && n_groups <= GEMM_WIDE_RT) { a.out_frag = m.xfrag2; produced_frag = true; }
@@ -661,7 +683,7 @@ void forward(sd_ctx* c, Model& m, const Rows& rw, float* logits) {
     else n_part = d / 16;
     frag_in = nullptr;
     if (f.arch == SD_ARCH_T5DEC) {
-      for (int g = 0; g < n_groups && !(skip & SD_OP_CROSS_Q); ++g) {
+      for (int g = 0; g < n_groups && !(skip & SD_OP_CROSS_Q) && !fuse_cross_q; ++g) {
         const Grp q = group(g);
         GemmArgs cq{};
         normed(cq, q, l.lncg, nullptr);
@@ -1226,11 +1248,12 @@ extern "C" sd_status sd_debug_logits(sd_ctx* c, int32_t which, float* host_out, 
 
 extern "C" sd_status sd_set_flags(sd_ctx* c, int32_t flags) {
   if (!c) return SD_EINVAL;
-  if (flags & ~(SD_FLAG_GRAPH | SD_FLAG_PROFILE | SD_FLAG_BETA | SD_FLAG_SCATTER_PAGES)) return fail(c, SD_EINVAL, "unknown flag");
+  if (flags & ~(SD_FLAG_GRAPH | SD_FLAG_PROFILE | SD_FLAG_BETA | SD_FLAG_SCATTER_PAGES | SD_FLAG_SEPARATE_CROSS_Q)) return fail(c, SD_EINVAL, "unknown flag");
   flags = (flags & ~SD_FLAG_SCATTER_PAGES) | (c->rt.flags & SD_FLAG_SCATTER_PAGES);    // the cache layout is fixed at load
-  if ((flags ^ c->rt.flags) & SD_FLAG_BETA) {            // the captured iteration changes
+  if ((flags ^ c->rt.flags) & (SD_FLAG_BETA | SD_FLAG_SEPARATE_CROSS_Q)) {            // the captured iteration changes
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     for (auto& g : c->graphs) if (g) { hipGraphExecDestroy(g); g = nullptr; }
+    if (c->graph_baseline) { hipGraphExecDestroy(c->graph_baseline); c->graph_baseline = nullptr; }
   }
   c->rt.flags = flags;
   return SD_OK;

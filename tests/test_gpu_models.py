@@ -262,6 +262,33 @@ def test_scattered_kv_pages_give_identical_results(arch, dtype, d_head):
         assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2]), it
 
 
+def test_cross_attention_that_projects_its_own_queries_is_bit_identical():
+    """Small T5-type bf16 pairs (heads of 64, d_model <= 512) run the cross-attention's query
+    projection inside the attention kernel; SD_FLAG_SEPARATE_CROSS_Q keeps it a launch of its own.
+    Tokens and logits of both models must agree bit for bit: prefill rows, the two-row first draft
+    step, one-row draft steps and the (gamma+1)-row verify forward all pass through it."""
+    from paper_2211_17192_amd import binding
+    cfg_p, w_p, cfg_q, w_q, enc_p, enc_q = small_pair(T.T5DEC, "bf16", d_head=64, w_std=0.04)
+    prompt = synth.random_tokens(77, 23, cfg_p["vocab"])
+    gamma = 5
+    urows = synth.uniform_stream(19, 10 * (2 * gamma + 1)).reshape(10, -1)
+    runs = []
+    for flags in (binding.SD_FLAG_GRAPH, binding.SD_FLAG_GRAPH | binding.SD_FLAG_SEPARATE_CROSS_Q):
+        dec = make_decoder(cfg_p, w_p, cfg_q, w_q, max_gamma=gamma, flags=flags)
+        dec.prefill(prompt, enc_p.cuda(), enc_q.cuda())
+        out = []
+        for it in range(10):
+            res = dec.step(gamma, 1.0, urows[it])
+            out.append((res, dec.logits(0, gamma + 1).copy(), dec.logits(1, gamma).copy()))
+        out.append((dec.step_baseline(1.0, 0.37), dec.logits(2, 1).copy(), None))
+        runs.append(out)
+        dec.close()
+    for it, (a, b) in enumerate(zip(*runs)):
+        assert a[0] == b[0], (it, a[0], b[0])
+        assert np.array_equal(a[1], b[1]), it
+        assert a[2] is None or np.array_equal(a[2], b[2]), it
+
+
 def test_one_token_prefix_and_baseline_identity():
     """Decoder that starts from a single start token (the encoder-decoder case):
     the first draft step has a padding row.  Also: argmax speculative decoding
