@@ -333,7 +333,10 @@ sd_status sd_time_ffn_in(sd_ctx* ctx, int32_t rows, int32_t reps, double* us_per
  *              scoring of r - 1 guesses, section 2.3), rows <= max_gamma + 1;
  *              1 = Mq, rows 1 (a draft step) or 2 (the first draft step of an iteration)
  *   skip_ops : SD_OP_* bits: the launches of these kinds are not recorded (their outputs keep
- *              whatever the last forward left, so the remaining launches do the same work)
+ *              whatever the last forward left, so the remaining launches do the same work).
+ *              Where the cross-attention launch computes its own queries (small T5-type models,
+ *              see SD_FLAG_SEPARATE_CROSS_Q), SD_OP_CROSS_Q leaves that part of the launch out
+ *              and SD_OP_CROSS_ATTN the whole launch.
  *   reps     : graph replays between the two HIP events, 1..1000
  *   us_per_forward : host output, microseconds per replay.
  * Writes cache rows beyond the committed sequence and the logits buffers only; commits nothing.
